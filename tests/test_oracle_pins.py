@@ -1,0 +1,289 @@
+"""Pins of the CPU oracle against things other than itself: brute-force loops,
+closed forms, library routines on special cases, and invariants.  Each test
+names the passage of the paper whose reading it pins."""
+import math
+
+import numpy as np
+import pytest
+import scipy.stats
+import torch
+
+from oracle import arkv_oracle as O
+
+
+def bf16(x):
+    return torch.tensor(np.asarray(x, dtype=np.float32)).to(torch.bfloat16).to(torch.float32).numpy()
+
+
+# ---------------------------------------------------------------- eq. 2 ----
+def test_window_attention_bruteforce_tiny():
+    """Sec. IV-C eq. 2: pure-Python causal softmax of the last W queries."""
+    rng = np.random.default_rng(1)
+    Hq, Hkv, W, T, d = 4, 2, 3, 9, 5
+    G = Hq // Hkv
+    q = bf16(rng.standard_normal((Hq, W, d)))
+    k = bf16(rng.standard_normal((Hkv, T, d)))
+    scale = 0.37
+    a = O.window_attention(q, k, scale, G)
+    for h in range(Hq):
+        for i in range(W):
+            last = T - W + i
+            logits = [scale * sum(float(q[h, i, c]) * float(k[h // G, j, c]) for c in range(d))
+                      for j in range(last + 1)]
+            m = max(logits)
+            den = sum(math.exp(l - m) for l in logits)
+            for j in range(T):
+                want = math.exp(logits[j] - m) / den if j <= last else 0.0
+                assert a[h, i, j] == pytest.approx(want, rel=1e-12, abs=1e-15)
+    assert np.allclose(a.sum(axis=2), 1.0)
+
+
+def test_window_attention_matches_library_sdpa():
+    """Special case that reduces to a library routine: causal SDPA rows."""
+    rng = np.random.default_rng(2)
+    Hq, Hkv, W, T, d = 8, 2, 4, 40, 16
+    G = Hq // Hkv
+    q_all = bf16(rng.standard_normal((Hq, T, d)))
+    k = bf16(rng.standard_normal((Hkv, T, d)))
+    v = np.eye(T)[None].repeat(Hkv, 0)            # identity values: output row == attention row
+    kk = np.repeat(k, G, axis=0)
+    vv = np.repeat(v, G, axis=0)
+    out = torch.nn.functional.scaled_dot_product_attention(
+        torch.tensor(q_all, dtype=torch.float64)[None], torch.tensor(kk, dtype=torch.float64)[None],
+        torch.tensor(vv, dtype=torch.float64)[None], is_causal=True, scale=0.2)[0].numpy()
+    a = O.window_attention(q_all[:, T - W:], k, 0.2, G)
+    assert np.allclose(a, out[:, T - W:, :], rtol=1e-10, atol=1e-13)
+
+
+# ------------------------------------------------------------ eqs. 3-5 ----
+def test_statistics_uniform_closed_form():
+    """q = 0 makes every visible row uniform: H = ln n, V = 0, Kurt := 0."""
+    Hq, Hkv, W, T, d = 4, 2, 4, 36, 8
+    a = O.window_attention(np.zeros((Hq, W, d)), bf16(np.random.default_rng(0).standard_normal((Hkv, T, d))),
+                           1.0, 2)
+    H, V, K, p = O.layer_statistics(a, W)
+    n = T - W
+    assert H == pytest.approx(math.log(n), rel=1e-12)
+    assert V == pytest.approx(0.0, abs=1e-30)
+    assert K == 0.0 or V < 1e-30
+    assert p.sum() == pytest.approx(1.0)
+
+
+def test_statistics_one_hot_closed_form():
+    """All mass on one non-window key: H = 0, V = (n-1)/n^2, Kurt = (n^2-3n+3)/(n-1)."""
+    Hq, W, T = 3, 4, 24
+    n = T - W
+    a = np.zeros((Hq, W, T)); a[:, :, 5] = 0.7; a[:, :, T - 1] = 0.3   # window mass must be ignored
+    H, V, K, p = O.layer_statistics(a, W)
+    assert H == pytest.approx(0.0, abs=1e-15)
+    assert V == pytest.approx((n - 1) / n ** 2, rel=1e-12)
+    assert K == pytest.approx((n * n - 3 * n + 3) / (n - 1), rel=1e-12)
+
+
+@pytest.mark.parametrize("f", [0.25, 0.5, 0.1])
+def test_statistics_two_level_closed_form(f):
+    """A fraction f of the keys shares the mass equally:
+    H = ln(fn), V = (1-f)/(f n^2), Kurt = (1 - 3f(1-f)) / (f(1-f))."""
+    Hq, W, n = 2, 4, 40
+    T = n + W
+    m = int(round(f * n)); f = m / n
+    a = np.zeros((Hq, W, T))
+    a[0, :, 3:3 + m] = 0.02          # heads contribute unequally; only the aggregate matters
+    a[1, :, 3:3 + m] = 0.01
+    H, V, K, _ = O.layer_statistics(a, W)
+    assert H == pytest.approx(math.log(f * n), rel=1e-12)
+    assert V == pytest.approx((1 - f) / (f * n * n), rel=1e-12)
+    assert K == pytest.approx((1 - 3 * f * (1 - f)) / (f * (1 - f)), rel=1e-10)
+
+
+def test_statistics_against_scipy_and_bruteforce():
+    rng = np.random.default_rng(3)
+    Hq, W, T = 4, 5, 60
+    a = rng.random((Hq, W, T)) ** 4
+    H, V, K, p = O.layer_statistics(a, W)
+    n = T - W
+    # brute force
+    c = [sum(a[h, i, j] for h in range(Hq) for i in range(W)) for j in range(n)]
+    Z = sum(c); pp = [x / Z for x in c]
+    Hb = -sum(x * math.log(x) for x in pp if x > 0)
+    mean = sum(pp) / n
+    m2 = sum((x - mean) ** 2 for x in pp) / n
+    m4 = sum((x - mean) ** 4 for x in pp) / n
+    assert H == pytest.approx(Hb, rel=1e-12)
+    assert V == pytest.approx(m2, rel=1e-12)
+    assert K == pytest.approx(m4 / m2 ** 2, rel=1e-12)
+    # library routines
+    assert H == pytest.approx(scipy.stats.entropy(p), rel=1e-12)
+    assert V == pytest.approx(np.var(p), rel=1e-12)
+    assert K == pytest.approx(scipy.stats.kurtosis(p, fisher=False, bias=True), rel=1e-10)
+    # kurtosis does not change under rescaling of p
+    assert K == pytest.approx(scipy.stats.kurtosis(n * p, fisher=False, bias=True), rel=1e-10)
+
+
+# ------------------------------------------------------------ eqs. 6-8 ----
+def test_oq_score_closed_form_with_paper_taus():
+    t1, t2, t3 = O.PAPER_TAU
+    q = O.oq_score(2.0 ** t1, 3.0 ** t2, 5.0 ** t3)
+    assert q == pytest.approx(30.0, rel=1e-12)
+    # log-linearity, via logs instead of powers
+    H, V, K = 6.3, 2.5e-7, 40.0
+    assert math.log(O.oq_score(H, V, K)) == pytest.approx(
+        math.log(H) / t1 + math.log(V) / t2 + math.log(K) / t3, rel=1e-12)
+
+
+def test_oq_ratio_invariants():
+    q = np.array([0.2, 0.5, 0.1, 0.5])
+    rho = O.oq_ratio(q)
+    assert rho.max() == 1.0 and (rho > 0).all() and (rho <= 1).all()
+    assert np.argmax(rho) in (1, 3) and rho[0] == pytest.approx(0.4)
+    assert (O.oq_ratio(np.full(5, 0.3)) == 1.0).all()
+    assert (O.oq_ratio(np.zeros(3)) == 1.0).all()      # degenerate reading
+
+
+@pytest.mark.parametrize("N,W", [(128, 32), (2048, 32), (8192, 32), (16384, 32), (40, 8)])
+def test_budget_counts_invariants(N, W):
+    for rho in [0.0, 0.1, 0.37, 0.5, 0.75, 0.9, 1.0]:
+        n_o, n_q, b = O.budget_counts(rho, N, W)
+        assert n_o + n_q == b and n_o >= 0 and n_q >= 0
+        assert b == min(math.floor(0.75 * (N - W)), N - W - 1)
+        assert n_o + W <= N and b + W < N
+        if rho == 1.0:
+            assert n_q == 0          # evict-only baseline
+        if rho == 0.0:
+            assert n_o == 0          # everything outside the window quantised
+    # Table VII plausibility: quantised share of the budget for a mid rho
+    n_o, n_q, b = O.budget_counts(0.6, 2048, 32)
+    assert 0.10 < n_q / 2048 < 0.20
+    # C1..C4 sizes of the scope table
+    assert O.budget_counts(0.5, 128, 32)[2] == 72
+    assert O.budget_counts(0.5, 2048, 32)[2] == 1512
+    assert O.budget_counts(0.5, 8192, 32)[2] == 6120
+    assert O.budget_counts(0.5, 16384, 32)[2] == 12264
+
+
+# --------------------------------------------------------------- eq. 9 ----
+def test_hh_score_bruteforce_and_constant():
+    rng = np.random.default_rng(4)
+    n_tok, n_samp = 7, 12
+    samples = rng.random((n_tok, n_samp)) * 0.01
+    s1 = samples.sum(1); s2 = (samples ** 2).sum(1)
+    S = O.hh_score(s1, s2, np.full(n_tok, n_samp), gamma=263.81)
+    for j in range(n_tok):
+        mu = sum(samples[j]) / n_samp
+        var = sum((x - mu) ** 2 for x in samples[j]) / n_samp
+        assert S[j] == pytest.approx(mu + 263.81 * var, rel=1e-9)
+    # constant attention: variance 0, S = mu
+    Sc = O.hh_score(np.full(3, 0.5 * 8), np.full(3, 0.25 * 8), np.full(3, 8))
+    assert np.allclose(Sc, 0.5)
+    # fp32 mode agrees with fp64 to fp32 accuracy and is fp32-typed
+    S32 = O.hh_score(s1, s2, np.full(n_tok, n_samp), exact32=True)
+    assert S32.dtype == np.float32 and np.allclose(S32, S, rtol=1e-5)
+
+
+def test_sample_count_closed_form():
+    T, W, G = 100, 8, 4
+    # prompt token outside the window after the prompt: W queries x G heads
+    assert O.sample_count(10, T - 1, T, W, G) == G * W
+    # window token at T-3: seen by queries T-3, T-2, T-1
+    assert O.sample_count(T - 3, T - 1, T, W, G) == G * 3
+    # after 5 decode steps (P = T+4)
+    assert O.sample_count(10, T + 4, T, W, G) == G * (W + 5)
+    assert O.sample_count(T + 2, T + 4, T, W, G) == G * 3
+
+
+def test_prefill_accumulators_bruteforce():
+    rng = np.random.default_rng(5)
+    Hq, G, W, T = 4, 2, 3, 10
+    a = rng.random((Hq, W, T))
+    s1, s2 = O.prefill_accumulators(a, G)
+    for g in range(Hq // G):
+        for j in range(T):
+            v1 = sum(a[g * G + hh, i, j] for hh in range(G) for i in range(W))
+            v2 = sum(a[g * G + hh, i, j] ** 2 for hh in range(G) for i in range(W))
+            assert s1[g, j] == pytest.approx(v1) and s2[g, j] == pytest.approx(v2)
+
+
+# -------------------------------------------------------------- eq. 10 ----
+def test_tailor_assign_bruteforce_sort():
+    rng = np.random.default_rng(6)
+    for trial in range(20):
+        n = int(rng.integers(5, 60))
+        S = np.round(rng.random(n), 1).astype(np.float32)       # many ties
+        pos = rng.permutation(1000)[:n]
+        state = rng.integers(0, 2, n).astype(np.int8)
+        b = int(rng.integers(0, n + 3)); n_o = int(rng.integers(0, b + 1))
+        new = O.tailor_assign(S, pos, state, n_o, b)
+        order = sorted(range(n), key=lambda i: (-float(S[i]), int(pos[i])))
+        for r, i in enumerate(order):
+            target = O.STATE_O if r < n_o else (O.STATE_Q if r < b else O.STATE_E)
+            assert new[i] == max(int(state[i]), target)
+        assert (new != O.STATE_E).sum() == min(b, n)
+        assert ((new == O.STATE_O) <= (state == O.STATE_O)).all()       # never promoted
+        assert (new == O.STATE_O).sum() <= n_o
+
+
+# ------------------------------------------------------------ quantiser ----
+@pytest.mark.parametrize("bits", [4, 2])
+def test_quantiser_properties(bits):
+    rng = np.random.default_rng(7)
+    qmax = (1 << bits) - 1
+    x = bf16(rng.standard_normal((500, 32)) * rng.choice([1e-3, 1.0, 10.0, 80.0], (500, 1)))
+    x[::7, 3] *= 10
+    codes, sc, zr = O.quantize_groups(x, bits)
+    scf = sc.astype(np.float64); zf = zr.astype(np.float64)
+    assert codes.max() <= qmax
+    assert (zf <= x.min(1)).all()                                   # grid starts at or below min
+    assert (zf + qmax * scf >= x.max(1) * (1 - 1e-7)).all()         # and reaches max
+    deq = codes * scf[:, None] + zf[:, None]
+    assert (np.abs(deq - x) <= scf[:, None] / 2 * (1 + 1e-5) + 1e-30).all()   # half-step bound
+    assert (codes[np.arange(500), x.argmin(1)] == 0).all()
+    assert (codes[np.arange(500), x.argmax(1)] == qmax).all()
+    # bf16 minima in the fp16 normal range are exact in fp16
+    assert (zf == x.min(1)).all()
+    # idempotence: the dequantised row quantises to the same codes
+    deq32 = deq.astype(np.float32)
+    c2, s2, z2 = O.quantize_groups(deq32, bits)
+    same_grid = (s2 == sc) & (z2 == zr)
+    assert same_grid.mean() > 0.9 and (c2[same_grid] == codes[same_grid]).all()
+
+
+def test_quantiser_constant_group_and_directed_rounding():
+    x = np.full((1, 32), 1.5, dtype=np.float32)
+    c, s, z = O.quantize_groups(x, 4)
+    assert (c == 0).all() and s[0] == 0 and z[0] == np.float16(1.5)
+    assert O.dequantize_row(c[0], s, z).tolist() == [1.5] * 32
+    # a minimum that fp16 would round upwards must be stepped down
+    mn = np.float32(-(1 + 2.0 ** -11 + 2.0 ** -13))     # rounds to -1.0 in fp16 (towards zero = up)
+    x = np.linspace(mn, 1.0, 32).astype(np.float32); x[0] = mn
+    c, s, z = O.quantize_groups(x[None], 4)
+    assert np.float32(z[0]) <= mn and np.float32(z[0]) + 15 * np.float32(s[0]) >= 1.0
+    assert c[0, 0] == 0 and c[0, -1] == 15
+
+
+def test_pack_unpack_layout():
+    codes = np.arange(16, dtype=np.uint8) % 16
+    p4 = O.pack_codes(codes, 4)
+    assert p4[0] == (0 | (1 << 4)) and p4[1] == (2 | (3 << 4))
+    c2 = np.array([1, 2, 3, 0, 3, 3, 0, 1], dtype=np.uint8)
+    p2 = O.pack_codes(c2, 2)
+    assert p2[0] == (1 | (2 << 2) | (3 << 4) | (0 << 6)) and p2[1] == (3 | (3 << 2) | (0 << 4) | (1 << 6))
+    assert (O.unpack_codes(p4, 4) == codes).all() and (O.unpack_codes(p2, 2) == c2).all()
+
+
+# ------------------------------------------------------ decode attention ----
+def test_attend_bruteforce_and_special_cases():
+    rng = np.random.default_rng(8)
+    n, d = 6, 4
+    q = rng.standard_normal(d); K = rng.standard_normal((n, d)); V = rng.standard_normal((n, d))
+    out, p = O.attend(q, K, V, 0.5)
+    logits = [0.5 * sum(q[c] * K[j, c] for c in range(d)) for j in range(n)]
+    den = sum(math.exp(l) for l in logits)
+    for c in range(d):
+        assert out[c] == pytest.approx(sum(math.exp(logits[j]) / den * V[j, c] for j in range(n)))
+    # one live token: output is its value row
+    out1, p1 = O.attend(q, K[:1], V[:1], 0.5)
+    assert np.allclose(out1, V[0]) and p1[0] == 1.0
+    # order of the cache slots does not matter
+    perm = rng.permutation(n)
+    out2, _ = O.attend(q, K[perm], V[perm], 0.5)
+    assert np.allclose(out, out2)
