@@ -1,0 +1,158 @@
+/*
+ * libarkv - ARKV per-layer KV-cache management around decode attention, for AMD MI355X (gfx950).
+ *
+ * C ABI.  Every pointer argument says whether it is HOST or DEVICE memory.  Tensors are dense,
+ * row-major, in the index order written in brackets; "bf16" is the 16-bit brain float stored as
+ * uint16_t.  hip_stream is a hipStream_t passed as void* (NULL = the default stream).  One cache
+ * object must be driven from one stream at a time.  Every call returns 0 on success or a negative
+ * ARKV_E* code; nothing throws.  Calls that take a stream are asynchronous on it unless stated.
+ *
+ * Notation (the paper's): L layers, B sequences, H_q query heads, H_kv KV heads, G = H_q / H_kv,
+ * d head dimension, T prompt length, N cache limit in tokens per (sequence, kv-head), W protected
+ * window.  A "unit" is one (layer, sequence, kv-head); units never interact during decode.
+ */
+#ifndef ARKV_H
+#define ARKV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ARKV_OK            0
+#define ARKV_EINVAL       -1   /* bad argument (null pointer, shape, range) */
+#define ARKV_ESTATE       -2   /* call out of order (decode before commit, commit twice, ...) */
+#define ARKV_ENOMEM       -3   /* device or host allocation failed */
+#define ARKV_EHIP         -4   /* a HIP runtime call failed; arkv_last_hip_error() has its text */
+#define ARKV_EUNSUPPORTED -5   /* valid but not built (head_dim, group size, bit width) */
+
+/* Token states (Sec. IV-B "Problem Formulation": full precision, quantized, evicted). */
+#define ARKV_STATE_ORIGINAL  0
+#define ARKV_STATE_QUANTIZED 1
+#define ARKV_STATE_EVICTED   2
+
+typedef struct arkv_cache arkv_cache;   /* opaque; the library owns all cache device memory */
+
+/* Hyper-parameters (Sec. V "Main Results" gives the tuned values used as defaults). */
+typedef struct {
+  int32_t n_layers;         /* L */
+  int32_t batch;            /* B */
+  int32_t n_q_heads;        /* H_q, multiple of n_kv_heads; G in {1,2,4,8} */
+  int32_t n_kv_heads;       /* H_kv */
+  int32_t head_dim;         /* d: 64 or 128 */
+  int32_t capacity_tokens;  /* N: cache limit per (sequence, kv-head), same for all layers (eq. 8 text) */
+  int32_t window;           /* W: last W tokens always Original (eq. 10, last line); default 32 */
+  float   alpha;            /* slack factor of Top-b, b = floor(alpha (N-W)) (eq. 10); default 0.75 */
+  float   gamma;            /* weight of the variance in the heavy-hitter score (eq. 9); default 263.81 */
+  float   tau[3];           /* temperatures of the OQ score (eq. 6); default 7.774, 5.407, 5.528 */
+  int32_t quant_bits;       /* bits per channel of a Quantized token: 4 or 2 */
+  int32_t group_size;       /* channels per scale/zero pair: 32 */
+} arkv_config;
+
+/* Fills *cfg with the paper's tuned hyper-parameters, 4-bit groups of 32, and zero shapes. HOST. */
+int arkv_config_default(arkv_config* cfg);
+
+/* Allocates the pools of all layers on the current device (per unit: N bf16 K and V rows, b packed
+ * rows, per-slot position / score accumulators / pending logits) and returns the cache in *out.
+ * Synchronous.  ARKV_EINVAL: null pointers, non-positive shapes, W >= N - 1, alpha outside (0,1],
+ * gamma < 0, group_size != 32.  ARKV_EUNSUPPORTED: head_dim not in {64,128}, G not in {1,2,4,8},
+ * quant_bits not in {2,4}. */
+int arkv_cache_create(const arkv_config* cfg, arkv_cache** out);
+
+/* Frees everything.  Synchronises the device first.  NULL is accepted. */
+int arkv_cache_destroy(arkv_cache* cache);
+
+/* Forgets the contents of one layer (layer >= 0) or of all layers (layer = -1) so that the prompt
+ * of a new request can be scored and committed; keeps the memory. */
+int arkv_cache_reset(arkv_cache* cache, int32_t layer);
+
+/* Prefill scorer of one layer (Sec. IV-C, eqs. 2-5; Sec. IV-E eq. 9 for the accumulators).
+ *   q_win  DEVICE bf16 [B][H_q][W][d]   queries of the last W prompt positions
+ *   k      DEVICE bf16 [B][H_kv][T][d]  keys of the whole prompt (already position-encoded)
+ *   stats  DEVICE float [B][3]          out: entropy, variance, kurtosis of the aggregated key
+ *                                        distribution over keys [0, T-W), per sequence
+ * Window query i (position T-W+i) attends causally to keys 0..T-W+i with
+ * softmax(softmax_scale * q.k); the layer statistics use keys < T-W only.  As a side effect the
+ * per-(kv-head, token) sums of attention and squared attention over the window are kept inside the
+ * cache for arkv_prefill_commit.  May allocate scratch on first use or when T grows.
+ * ARKV_EINVAL: T <= W, bad layer.  ARKV_ESTATE: layer already committed. */
+int arkv_prefill_stats(arkv_cache* cache, int32_t layer, const void* q_win, const void* k, int32_t T,
+                       float softmax_scale, float* stats, void* hip_stream);
+
+/* OQ score and ratio (eqs. 6-7).  HOST, pure.  stats [L][B][3] -> rho [L][B]:
+ * q = H^(1/tau1) V^(1/tau2) Kurt^(1/tau3), rho = q / max over the layers of the same sequence;
+ * if every q of a sequence is 0, every rho of it is 1. */
+int arkv_oq_ratio(const float* stats, int32_t n_layers, int32_t batch, const float tau[3], float* rho);
+
+/* Token counts a tailor keeps (Alg. 1 "Assign origin budget", eq. 10).  HOST, pure.
+ * b = min(floor(alpha (N-W)), N-W-1); n_o = min(floor(rho (N-W)), b); n_q = b - n_o. */
+int arkv_budget_counts(const arkv_config* cfg, float rho, int32_t* n_o, int32_t* n_q, int32_t* b);
+
+/* Loads one layer's prompt into the cache and fixes the layer's budgets (Alg. 1, prefill phase).
+ *   k, v  DEVICE bf16 [B][H_kv][T][d]  (the same k that was scored)
+ *   rho   HOST float [B]               OQ ratio of this layer for every sequence
+ * If T >= N the first tailor runs here on the window scores (Top-b, Top-B_o, quantise, evict).
+ * The caller's k, v are not referenced after the stream has passed this call.
+ * ARKV_ESTATE: arkv_prefill_stats has not run for this layer with the same T, or already committed. */
+int arkv_prefill_commit(arkv_cache* cache, int32_t layer, const void* k, const void* v, int32_t T,
+                        const float* rho, void* hip_stream);
+
+/* One decode step of one layer for the whole batch (Alg. 1, decoding phase + reconstruction).
+ *   q             DEVICE bf16 [B][H_q][d]
+ *   k_new, v_new  DEVICE bf16 [B][H_kv][d]   the token being generated (position T + step)
+ *   out           DEVICE bf16 [B][H_q][d]    softmax(scale q.K~) V~ over every live token,
+ *                                             K~/V~ = bf16 row (Original) or code*scale+zero (Quantized)
+ * Appends the token as Original, attends (the new token included), adds each token's attention
+ * probabilities to its running sums (eq. 9), and when the number of live tokens has reached N
+ * runs the tailor (eq. 10): ranks tokens older than the W most recent by S = mean + gamma*variance,
+ * keeps the top b, the top n_o of them in bf16 (a Quantized token is never promoted), quantises the
+ * others in place, evicts the rest.  Never allocates, never synchronises. */
+int arkv_decode_step(arkv_cache* cache, int32_t layer, const void* q, const void* k_new,
+                     const void* v_new, float softmax_scale, void* out, void* hip_stream);
+
+/* The same for n consecutive, independent layers in one set of launches (benchmarks, graph capture).
+ *   q [n][B][H_q][d], k_new/v_new [n][B][H_kv][d], out [n][B][H_q][d]  DEVICE bf16
+ *   softmax_scale HOST float [n]
+ * All n layers must be in the same state (same prompt length, same number of steps taken). */
+int arkv_decode_step_layers(arkv_cache* cache, int32_t layer_begin, int32_t n, const void* q,
+                            const void* k_new, const void* v_new, const float* softmax_scale,
+                            void* out, void* hip_stream);
+
+/* ---- observability and parity hooks: HOST outputs, synchronise the cache's last stream ---- */
+
+/* Per unit of one layer, arrays [B][H_kv]: Original / Quantized token counts and live bytes
+ * n_o*4d + n_q*2*(d*bits/8 + 4*d/32) (the left side of eq. 1 for that unit). */
+int arkv_cache_counters(arkv_cache* cache, int32_t layer, int32_t* n_original, int32_t* n_quantized,
+                        int64_t* live_bytes);
+
+/* Contents of one layer, per unit, tokens sorted by position.  max_tokens >= N.  Any output pointer
+ * may be NULL.  n_live [U]; pos, state [U][max_tokens]; s1, s2 [U][max_tokens] running sums of
+ * attention and squared attention; rows_k, rows_v bf16 [U][max_tokens][d] (Original tokens, else 0);
+ * codes_k, codes_v uint8 [U][max_tokens][d*bits/8] in canonical packing (channel c of a 4-bit row in
+ * byte c/2 bits 4(c%2)..; of a 2-bit row in byte c/4 bits 2(c%4)..); scale_*, zero_* fp16 bits
+ * [U][max_tokens][d/32] (Quantized tokens, else 0).  U = B*H_kv. */
+int arkv_cache_export(arkv_cache* cache, int32_t layer, int32_t max_tokens, int32_t* n_live,
+                      int32_t* pos, uint8_t* state, float* s1, float* s2,
+                      uint16_t* rows_k, uint16_t* rows_v, uint8_t* codes_k, uint8_t* codes_v,
+                      uint16_t* scale_k, uint16_t* zero_k, uint16_t* scale_v, uint16_t* zero_v);
+
+/* Scores the latest tailor of this layer ranked on: per unit, count [U] eligible tokens with their
+ * position and fp32 score S [U][max_tokens] in no particular order (count = -1: no tailor yet). */
+int arkv_debug_last_tailor_scores(arkv_cache* cache, int32_t layer, int32_t max_tokens,
+                                  int32_t* count, int32_t* pos, float* score);
+
+/* fp32 attention output of the latest decode step of this layer, before rounding to bf16. [B][H_q][d] */
+int arkv_debug_last_out_f32(arkv_cache* cache, int32_t layer, float* out);
+
+/* Number of tailors run so far on this layer and the current number of live tokens per unit. */
+int arkv_cache_progress(arkv_cache* cache, int32_t layer, int32_t* n_tailors, int32_t* n_live,
+                        int32_t* position);
+
+const char* arkv_strerror(int code);        /* static text for an ARKV_E* code */
+const char* arkv_last_hip_error(void);      /* text of the HIP error behind the latest ARKV_EHIP */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ARKV_H */

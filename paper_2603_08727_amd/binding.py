@@ -1,0 +1,239 @@
+"""ctypes binding of libarkv's C ABI (include/arkv.h): argument marshalling only.
+
+Functions have the names of the C entry points.  Device tensors are torch tensors (bf16 / fp32,
+contiguous, on the GPU); the binding passes their data pointers and the current torch stream.
+There is no fallback: if the shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libarkv.so")
+
+OK, EINVAL, ESTATE, ENOMEM, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+STATE_ORIGINAL, STATE_QUANTIZED, STATE_EVICTED = 0, 1, 2
+
+EXPORTED = [
+    "arkv_config_default", "arkv_cache_create", "arkv_cache_destroy", "arkv_cache_reset",
+    "arkv_prefill_stats", "arkv_oq_ratio", "arkv_budget_counts", "arkv_prefill_commit",
+    "arkv_decode_step", "arkv_decode_step_layers", "arkv_cache_counters", "arkv_cache_export",
+    "arkv_debug_last_tailor_scores", "arkv_debug_last_out_f32", "arkv_cache_progress",
+    "arkv_strerror", "arkv_last_hip_error",
+]
+
+
+class arkv_config(C.Structure):
+    _fields_ = [
+        ("n_layers", C.c_int32), ("batch", C.c_int32), ("n_q_heads", C.c_int32),
+        ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("capacity_tokens", C.c_int32),
+        ("window", C.c_int32), ("alpha", C.c_float), ("gamma", C.c_float), ("tau", C.c_float * 3),
+        ("quant_bits", C.c_int32), ("group_size", C.c_int32),
+    ]
+
+
+class ArkvError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        msg = f"{where}: {strerror(code)} ({code})"
+        if code == EHIP:
+            msg += ": " + last_hip_error()
+        super().__init__(msg)
+
+
+_lib = None
+
+
+def load():
+    """Loads libarkv.so once.  Raises if it has not been built (python -m paper_2603_08727_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with __graft_entry__.build(); "
+                           "there is no CPU fallback for the HIP path")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, f32 = C.c_void_p, C.c_int32, C.c_float
+    P = C.POINTER
+    sig = {
+        "arkv_config_default": (C.c_int, [P(arkv_config)]),
+        "arkv_cache_create": (C.c_int, [P(arkv_config), P(vp)]),
+        "arkv_cache_destroy": (C.c_int, [vp]),
+        "arkv_cache_reset": (C.c_int, [vp, i32]),
+        "arkv_prefill_stats": (C.c_int, [vp, i32, vp, vp, i32, f32, vp, vp]),
+        "arkv_oq_ratio": (C.c_int, [vp, i32, i32, vp, vp]),
+        "arkv_budget_counts": (C.c_int, [P(arkv_config), f32, P(i32), P(i32), P(i32)]),
+        "arkv_prefill_commit": (C.c_int, [vp, i32, vp, vp, i32, vp, vp]),
+        "arkv_decode_step": (C.c_int, [vp, i32, vp, vp, vp, f32, vp, vp]),
+        "arkv_decode_step_layers": (C.c_int, [vp, i32, i32, vp, vp, vp, vp, vp, vp]),
+        "arkv_cache_counters": (C.c_int, [vp, i32, vp, vp, vp]),
+        "arkv_cache_export": (C.c_int, [vp, i32, i32] + [vp] * 13),
+        "arkv_debug_last_tailor_scores": (C.c_int, [vp, i32, i32, vp, vp, vp]),
+        "arkv_debug_last_out_f32": (C.c_int, [vp, i32, vp]),
+        "arkv_cache_progress": (C.c_int, [vp, i32, P(i32), P(i32), P(i32)]),
+        "arkv_strerror": (C.c_char_p, [C.c_int]),
+        "arkv_last_hip_error": (C.c_char_p, []),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load().arkv_strerror(code).decode()
+
+
+def last_hip_error() -> str:
+    return load().arkv_last_hip_error().decode()
+
+
+def _check(code, where):
+    if code != OK:
+        raise ArkvError(code, where)
+
+
+def _np_ptr(a):
+    return a.ctypes.data_as(C.c_void_p) if a is not None else None
+
+
+def _dev_ptr(t, dtype=None):
+    import torch
+    assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous GPU tensors"
+    if dtype is not None:
+        assert t.dtype == dtype, f"expected {dtype}, got {t.dtype}"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+# ---- entry points, same names as the C ABI ---------------------------------------------------
+
+def arkv_config_default(**overrides) -> arkv_config:
+    cfg = arkv_config()
+    _check(load().arkv_config_default(C.byref(cfg)), "arkv_config_default")
+    for k, v in overrides.items():
+        if k == "tau":
+            cfg.tau = (C.c_float * 3)(*v)
+        else:
+            setattr(cfg, k, v)
+    return cfg
+
+
+def arkv_cache_create(cfg: arkv_config):
+    h = C.c_void_p()
+    _check(load().arkv_cache_create(C.byref(cfg), C.byref(h)), "arkv_cache_create")
+    return h
+
+
+def arkv_cache_destroy(cache):
+    _check(load().arkv_cache_destroy(cache), "arkv_cache_destroy")
+
+
+def arkv_cache_reset(cache, layer=-1):
+    _check(load().arkv_cache_reset(cache, layer), "arkv_cache_reset")
+
+
+def arkv_prefill_stats(cache, layer, q_win, k, T, softmax_scale, stats):
+    import torch
+    _check(load().arkv_prefill_stats(cache, layer, _dev_ptr(q_win, torch.bfloat16), _dev_ptr(k, torch.bfloat16),
+                                     T, softmax_scale, _dev_ptr(stats, torch.float32), _stream()),
+           "arkv_prefill_stats")
+
+
+def arkv_oq_ratio(stats: np.ndarray, tau) -> np.ndarray:
+    stats = np.ascontiguousarray(stats, dtype=np.float32)
+    L, B, three = stats.shape
+    assert three == 3
+    rho = np.empty((L, B), dtype=np.float32)
+    t = np.asarray(tau, dtype=np.float32)
+    _check(load().arkv_oq_ratio(_np_ptr(stats), L, B, _np_ptr(t), _np_ptr(rho)), "arkv_oq_ratio")
+    return rho
+
+
+def arkv_budget_counts(cfg: arkv_config, rho: float):
+    a, b, c = C.c_int32(), C.c_int32(), C.c_int32()
+    _check(load().arkv_budget_counts(C.byref(cfg), rho, C.byref(a), C.byref(b), C.byref(c)), "arkv_budget_counts")
+    return a.value, b.value, c.value
+
+
+def arkv_prefill_commit(cache, layer, k, v, T, rho):
+    import torch
+    rho = np.ascontiguousarray(rho, dtype=np.float32)
+    _check(load().arkv_prefill_commit(cache, layer, _dev_ptr(k, torch.bfloat16), _dev_ptr(v, torch.bfloat16), T,
+                                      _np_ptr(rho), _stream()), "arkv_prefill_commit")
+
+
+def arkv_decode_step(cache, layer, q, k_new, v_new, softmax_scale, out):
+    import torch
+    bf = torch.bfloat16
+    _check(load().arkv_decode_step(cache, layer, _dev_ptr(q, bf), _dev_ptr(k_new, bf), _dev_ptr(v_new, bf),
+                                   softmax_scale, _dev_ptr(out, bf), _stream()), "arkv_decode_step")
+
+
+def arkv_decode_step_layers(cache, layer_begin, n, q, k_new, v_new, softmax_scale, out):
+    import torch
+    bf = torch.bfloat16
+    sc = np.ascontiguousarray(softmax_scale, dtype=np.float32)
+    assert sc.shape == (n,)
+    _check(load().arkv_decode_step_layers(cache, layer_begin, n, _dev_ptr(q, bf), _dev_ptr(k_new, bf),
+                                          _dev_ptr(v_new, bf), _np_ptr(sc), _dev_ptr(out, bf), _stream()),
+           "arkv_decode_step_layers")
+
+
+def arkv_cache_counters(cache, layer, n_units):
+    no = np.empty(n_units, dtype=np.int32); nq = np.empty(n_units, dtype=np.int32)
+    lb = np.empty(n_units, dtype=np.int64)
+    _check(load().arkv_cache_counters(cache, layer, _np_ptr(no), _np_ptr(nq), _np_ptr(lb)), "arkv_cache_counters")
+    return no, nq, lb
+
+
+def arkv_cache_progress(cache, layer):
+    a, b, c = C.c_int32(), C.c_int32(), C.c_int32()
+    _check(load().arkv_cache_progress(cache, layer, C.byref(a), C.byref(b), C.byref(c)), "arkv_cache_progress")
+    return a.value, b.value, c.value
+
+
+def arkv_cache_export(cache, layer, cfg: arkv_config, rows=True, codes=True):
+    """Returns a dict of NumPy arrays, tokens of every unit sorted by position (see arkv.h)."""
+    U = cfg.batch * cfg.n_kv_heads
+    MT, d = cfg.capacity_tokens, cfg.head_dim
+    CB, NG = d * cfg.quant_bits // 8, d // 32
+    out = dict(
+        n_live=np.zeros(U, np.int32), pos=np.full((U, MT), -1, np.int32), state=np.full((U, MT), 255, np.uint8),
+        s1=np.zeros((U, MT), np.float32), s2=np.zeros((U, MT), np.float32),
+        rows_k=np.zeros((U, MT, d), np.uint16) if rows else None,
+        rows_v=np.zeros((U, MT, d), np.uint16) if rows else None,
+        codes_k=np.zeros((U, MT, CB), np.uint8) if codes else None,
+        codes_v=np.zeros((U, MT, CB), np.uint8) if codes else None,
+        scale_k=np.zeros((U, MT, NG), np.uint16) if codes else None,
+        zero_k=np.zeros((U, MT, NG), np.uint16) if codes else None,
+        scale_v=np.zeros((U, MT, NG), np.uint16) if codes else None,
+        zero_v=np.zeros((U, MT, NG), np.uint16) if codes else None,
+    )
+    order = ["n_live", "pos", "state", "s1", "s2", "rows_k", "rows_v", "codes_k", "codes_v",
+             "scale_k", "zero_k", "scale_v", "zero_v"]
+    _check(load().arkv_cache_export(cache, layer, MT, *[_np_ptr(out[k]) for k in order]), "arkv_cache_export")
+    return out
+
+
+def arkv_debug_last_tailor_scores(cache, layer, n_units, max_tokens):
+    cnt = np.empty(n_units, np.int32)
+    pos = np.empty((n_units, max_tokens), np.int32)
+    sc = np.empty((n_units, max_tokens), np.float32)
+    _check(load().arkv_debug_last_tailor_scores(cache, layer, max_tokens, _np_ptr(cnt), _np_ptr(pos), _np_ptr(sc)),
+           "arkv_debug_last_tailor_scores")
+    return cnt, pos, sc
+
+
+def arkv_debug_last_out_f32(cache, layer, shape):
+    out = np.empty(shape, np.float32)
+    _check(load().arkv_debug_last_out_f32(cache, layer, _np_ptr(out)), "arkv_debug_last_out_f32")
+    return out

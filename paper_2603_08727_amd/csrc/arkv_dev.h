@@ -1,0 +1,105 @@
+// Shared declarations of libarkv's host code and gfx950 kernels: data layout in HBM and launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace arkv {
+
+constexpr int kGroup = 32;        // channels per (scale, zero) pair
+constexpr int kMaxSplits = 32;    // split-K factor of the decode attention, upper bound
+constexpr int kMaxLayersPerLaunch = 64;
+
+// Cache memory of ALL layers.  Every array is [L*U][...] with U = B*H_kv units per layer, so that a
+// launch over several layers is just a launch over more units.  "O pool": bf16 rows of Original
+// tokens, slots [0, cnt.x) dense.  "Q pool": packed rows of Quantized tokens, slots [0, cnt.y) dense.
+// A tailor compacts both pools in place; between tailors tokens are only appended to the O pool.
+struct Pools {
+  int U;                // units per layer
+  int capO, capQ;       // slots per unit: N and b
+  int D, G, bits;
+  // O pool
+  uint16_t* ok;         // [LU][capO][D] bf16 keys
+  uint16_t* ov;         // [LU][capO][D] bf16 values
+  int32_t*  opos;       // [LU][capO] position of the token in the sequence
+  float2*   oacc;       // [LU][capO] (s1, s2): running sums of attention and attention^2 (eq. 9)
+  float*    olg;        // [LU][capO][G] logits of the latest step (base-2 units), pending for oacc
+  // Q pool
+  uint8_t*  qkc;        // [LU][capQ][D*bits/8] key codes, canonical packing
+  uint8_t*  qvc;        // [LU][capQ][D*bits/8]
+  uint32_t* qkm;        // [LU][capQ][D/32] (fp16 scale | fp16 zero << 16)
+  uint32_t* qvm;        // [LU][capQ][D/32]
+  int32_t*  qpos;       // [LU][capQ]
+  float2*   qacc;       // [LU][capQ]
+  float*    qlg;        // [LU][capQ][G]
+  // per unit
+  int2*     cnt;        // [LU] (tokens in O pool, tokens in Q pool)
+  float2*   fin;        // [2][LU][G] (row max in base-2 units, 1/denominator) of the latest two steps
+  size_t    fin_stride; // LU*G
+  float*    part;       // [LU][kMaxSplits][G][D+2] split-K partials: acc[D], max, sum
+  float*    outf;       // [LU][G][D] fp32 output of the latest step (parity hook)
+  int32_t*  n_o;        // [LU] Original target of the unit's layer/sequence
+  // tailor scratch
+  uint64_t* keys;       // [LU][capO+capQ] selection keys of the latest tailor (0 = not eligible)
+  uint64_t* thr;        // [LU][2] keys of rank n_o and rank b
+  int32_t*  plan;       // [LU][kPlanHdr + 2*capO + 3*capQ... ] see arkv_tailor.hip
+  int       plan_stride;
+};
+
+constexpr int kPlanHdr = 16;
+// plan header fields (int32 each)
+enum { PL_CO_NEW = 0, PL_CQ_NEW, PL_N_DEM, PL_N_QMOV, PL_N_OMOV, PL_N_ELIG, PL_CO_OLD, PL_CQ_OLD };
+
+struct DecodeLaunch {
+  const uint16_t* q;      // [n][B][Hq][D]
+  const uint16_t* k_new;  // [n][B][Hkv][D]
+  const uint16_t* v_new;
+  uint16_t* out;          // [n][B][Hq][D]
+  int unit_begin;         // first global unit (= layer_begin * U)
+  int n_units;            // n * U
+  int units_per_layer;
+  int splits;
+  int position;           // P of the token being appended
+  int has_pending;        // 1: olg/qlg hold logits of the previous step not yet added to (s1,s2)
+  int parity;             // fin[parity] belongs to the previous step; this step writes fin[parity^1]
+  float scale2[kMaxLayersPerLaunch];  // softmax scale * log2(e), per launched layer
+};
+
+struct TailorLaunch {
+  int unit_begin, n_units;
+  int position;       // P of the latest token
+  int t_prefill;      // T
+  int window;
+  int b;              // survivors outside the window
+  float gamma;
+  int has_pending, parity;
+};
+
+struct CommitLaunch {
+  const uint16_t* k;  // [B][Hkv][T][D]
+  const uint16_t* v;
+  const float2* pre;  // [U][T] window sums (s1, s2) from the prefill scorer
+  int unit_begin, n_units;
+  int T, window, b;
+  float gamma;
+  int select;         // 1: T >= N, run the first tailor; 0: copy everything as Original
+};
+
+struct PrefillLaunch {
+  const uint16_t* q_win;  // [B][Hq][W][D]
+  const uint16_t* k;      // [B][Hkv][T][D]
+  float2* pre;            // [U][T]  out: (s1, s2)
+  float2* rowstat;        // [U][chunks][G*W] (row max base-2, row sum) partials
+  float* stats;           // [B][3]
+  int B, Hkv, G, W, D, T;
+  int chunk;              // keys per workgroup
+  int n_chunks;
+  float scale2;
+};
+
+hipError_t launch_decode(const Pools& P, const DecodeLaunch& a, hipStream_t s);
+hipError_t launch_flush_scores(const Pools& P, int unit_begin, int n_units, int parity, hipStream_t s);
+hipError_t launch_tailor(const Pools& P, const TailorLaunch& a, hipStream_t s);
+hipError_t launch_commit(const Pools& P, const CommitLaunch& a, uint64_t* commit_keys /*[U][T]*/, hipStream_t s);
+hipError_t launch_prefill_stats(const PrefillLaunch& a, float* rowc /*[U][MP] scratch*/, hipStream_t s);
+
+}  // namespace arkv

@@ -1,0 +1,509 @@
+// libarkv host side: the C ABI of include/arkv.h, argument checks, memory, count policy and the
+// order of kernel launches.  No arithmetic of the method runs here except the scalar OQ-ratio /
+// budget formulas (eqs. 6-8), which the paper defines on per-layer scalars.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "arkv.h"
+#include "arkv_dev.h"
+
+using namespace arkv;
+
+static thread_local std::string g_hip_error;
+
+static int hip_fail(hipError_t e, const char* what) {
+  g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+  (void)hipGetLastError();
+  return ARKV_EHIP;
+}
+#define HIP_TRY(expr)                                   \
+  do {                                                  \
+    hipError_t e_ = (expr);                             \
+    if (e_ != hipSuccess) return hip_fail(e_, #expr);   \
+  } while (0)
+
+struct LayerState {
+  bool scored = false, committed = false, pending = false;
+  int scored_T = 0, T = 0, P = -1, live = 0, parity = 0, n_tailors = 0;
+  int last_tailor = 0;          // 0 none, 1 at commit (keys in commit scratch), 2 during decode
+  float2* pre = nullptr;        // [U][T] window sums from the prefill scorer
+  size_t pre_cap = 0;
+  std::vector<int32_t> n_o;     // [B] Original target per sequence
+};
+
+struct arkv_cache {
+  arkv_config cfg;
+  Pools P;
+  int L = 0, U = 0, b = 0;
+  std::vector<LayerState> layers;
+  std::vector<void*> allocs;
+  // grow-only scratch shared by all layers (calls on one cache are stream-ordered)
+  float2* rowstat = nullptr; size_t rowstat_cap = 0;
+  float* rowc = nullptr; size_t rowc_cap = 0;
+  uint64_t* ckeys = nullptr; size_t ckeys_cap = 0;
+  int ckeys_layer = -1, ckeys_T = 0;
+  hipStream_t last_stream = nullptr;
+};
+
+static int validate(const arkv_config* c) {
+  if (!c) return ARKV_EINVAL;
+  if (c->n_layers <= 0 || c->batch <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0)
+    return ARKV_EINVAL;
+  if (c->n_q_heads % c->n_kv_heads != 0) return ARKV_EINVAL;
+  if (c->window < 1 || c->capacity_tokens < 3 || c->window >= c->capacity_tokens - 1) return ARKV_EINVAL;
+  if (!(c->alpha > 0.0f && c->alpha <= 1.0f) || !(c->gamma >= 0.0f)) return ARKV_EINVAL;
+  for (int i = 0; i < 3; ++i)
+    if (!(c->tau[i] > 0.0f)) return ARKV_EINVAL;
+  if (c->group_size != kGroup) return ARKV_EINVAL;
+  const int G = c->n_q_heads / c->n_kv_heads;
+  if (c->head_dim != 64 && c->head_dim != 128) return ARKV_EUNSUPPORTED;
+  if (G != 1 && G != 2 && G != 4 && G != 8) return ARKV_EUNSUPPORTED;
+  if (c->quant_bits != 2 && c->quant_bits != 4) return ARKV_EUNSUPPORTED;
+  if (G * c->window > 256) return ARKV_EUNSUPPORTED;
+  return ARKV_OK;
+}
+
+static int survivors_b(const arkv_config* c) {
+  const int nw = c->capacity_tokens - c->window;
+  int b = (int)floor((double)c->alpha * (double)nw);
+  b = std::min(b, nw - 1);
+  return std::max(b, 0);
+}
+
+template <typename T>
+static int dev_alloc(arkv_cache* c, T** p, size_t count) {
+  void* q = nullptr;
+  hipError_t e = hipMalloc(&q, std::max<size_t>(count, 1) * sizeof(T));
+  if (e != hipSuccess) {
+    hip_fail(e, "hipMalloc");
+    return e == hipErrorOutOfMemory ? ARKV_ENOMEM : ARKV_EHIP;
+  }
+  c->allocs.push_back(q);
+  *p = static_cast<T*>(q);
+  return ARKV_OK;
+}
+
+template <typename T>
+static int grow(T** p, size_t* cap, size_t count) {
+  if (count <= *cap) return ARKV_OK;
+  if (*p) HIP_TRY(hipFree(*p));
+  *p = nullptr; *cap = 0;
+  void* q = nullptr;
+  hipError_t e = hipMalloc(&q, count * sizeof(T));
+  if (e != hipSuccess) { hip_fail(e, "hipMalloc"); return e == hipErrorOutOfMemory ? ARKV_ENOMEM : ARKV_EHIP; }
+  *p = static_cast<T*>(q); *cap = count;
+  return ARKV_OK;
+}
+
+static int flush_and_sync(arkv_cache* c, int layer) {
+  LayerState& ls = c->layers[(size_t)layer];
+  if (ls.pending) {
+    HIP_TRY(launch_flush_scores(c->P, layer * c->U, c->U, ls.parity, c->last_stream));
+    ls.pending = false;
+  }
+  HIP_TRY(hipStreamSynchronize(c->last_stream));
+  return ARKV_OK;
+}
+
+template <typename T>
+static int fetch(std::vector<T>& h, const T* dev, size_t count) {
+  h.resize(count);
+  HIP_TRY(hipMemcpy(h.data(), dev, count * sizeof(T), hipMemcpyDeviceToHost));
+  return ARKV_OK;
+}
+
+extern "C" {
+
+int arkv_config_default(arkv_config* cfg) {
+  if (!cfg) return ARKV_EINVAL;
+  memset(cfg, 0, sizeof(*cfg));
+  cfg->window = 32;
+  cfg->alpha = 0.75f;
+  cfg->gamma = 263.81f;
+  cfg->tau[0] = 7.774f; cfg->tau[1] = 5.407f; cfg->tau[2] = 5.528f;
+  cfg->quant_bits = 4;
+  cfg->group_size = 32;
+  return ARKV_OK;
+}
+
+int arkv_budget_counts(const arkv_config* cfg, float rho, int32_t* n_o, int32_t* n_q, int32_t* b) {
+  if (!cfg || !n_o || !n_q || !b) return ARKV_EINVAL;
+  if (cfg->window < 1 || cfg->window >= cfg->capacity_tokens - 1) return ARKV_EINVAL;
+  if (!(cfg->alpha > 0.0f && cfg->alpha <= 1.0f) || !(rho >= 0.0f && rho <= 1.0f)) return ARKV_EINVAL;
+  const int bb = survivors_b(cfg);
+  const int no = std::min((int)floor((double)rho * (double)(cfg->capacity_tokens - cfg->window)), bb);
+  *n_o = no; *n_q = bb - no; *b = bb;
+  return ARKV_OK;
+}
+
+int arkv_oq_ratio(const float* stats, int32_t n_layers, int32_t batch, const float tau[3], float* rho) {
+  if (!stats || !tau || !rho || n_layers <= 0 || batch <= 0) return ARKV_EINVAL;
+  for (int i = 0; i < 3; ++i)
+    if (!(tau[i] > 0.0f)) return ARKV_EINVAL;
+  std::vector<double> q((size_t)n_layers);
+  for (int s = 0; s < batch; ++s) {
+    double mx = 0.0;
+    for (int l = 0; l < n_layers; ++l) {
+      const float* st = stats + ((size_t)l * batch + s) * 3;
+      if (!(st[0] >= 0.0f) || !(st[1] >= 0.0f) || !(st[2] >= 0.0f)) return ARKV_EINVAL;   // also rejects NaN
+      q[l] = pow((double)st[0], 1.0 / (double)tau[0]) * pow((double)st[1], 1.0 / (double)tau[1]) *
+             pow((double)st[2], 1.0 / (double)tau[2]);
+      mx = std::max(mx, q[l]);
+    }
+    for (int l = 0; l < n_layers; ++l) rho[(size_t)l * batch + s] = mx > 0.0 ? (float)(q[l] / mx) : 1.0f;
+  }
+  return ARKV_OK;
+}
+
+int arkv_cache_create(const arkv_config* cfg, arkv_cache** out) {
+  if (!out) return ARKV_EINVAL;
+  *out = nullptr;
+  int rc = validate(cfg);
+  if (rc != ARKV_OK) return rc;
+  arkv_cache* c = new (std::nothrow) arkv_cache();
+  if (!c) return ARKV_ENOMEM;
+  c->cfg = *cfg;
+  c->L = cfg->n_layers;
+  c->U = cfg->batch * cfg->n_kv_heads;
+  c->b = survivors_b(cfg);
+  c->layers.resize((size_t)c->L);
+  for (auto& ls : c->layers) ls.n_o.assign((size_t)cfg->batch, 0);
+  Pools& P = c->P;
+  memset(&P, 0, sizeof(P));
+  P.U = c->U;
+  P.capO = cfg->capacity_tokens;
+  P.capQ = std::max(c->b, 1);
+  P.D = cfg->head_dim;
+  P.G = cfg->n_q_heads / cfg->n_kv_heads;
+  P.bits = cfg->quant_bits;
+  const size_t LU = (size_t)c->L * c->U, D = (size_t)P.D, G = (size_t)P.G;
+  const size_t CB = D * P.bits / 8, NG = D / kGroup;
+  P.fin_stride = LU * G;
+  P.plan_stride = kPlanHdr + 3 * P.capO + 2 * P.capQ;
+#define A(field, count) if ((rc = dev_alloc(c, &P.field, (count))) != ARKV_OK) { arkv_cache_destroy(c); return rc; }
+  A(ok, LU * P.capO * D) A(ov, LU * P.capO * D)
+  A(opos, LU * P.capO) A(oacc, LU * P.capO) A(olg, LU * P.capO * G)
+  A(qkc, LU * P.capQ * CB) A(qvc, LU * P.capQ * CB)
+  A(qkm, LU * P.capQ * NG) A(qvm, LU * P.capQ * NG)
+  A(qpos, LU * P.capQ) A(qacc, LU * P.capQ) A(qlg, LU * P.capQ * G)
+  A(cnt, LU) A(fin, 2 * LU * G) A(part, LU * kMaxSplits * G * (D + 2)) A(outf, LU * G * D) A(n_o, LU)
+  A(keys, LU * (size_t)(P.capO + P.capQ)) A(thr, LU * 2) A(plan, LU * (size_t)P.plan_stride)
+#undef A
+  hipError_t e = hipMemset(P.cnt, 0, LU * sizeof(int2));
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e != hipSuccess) { arkv_cache_destroy(c); return hip_fail(e, "hipMemset"); }
+  *out = c;
+  return ARKV_OK;
+}
+
+int arkv_cache_destroy(arkv_cache* c) {
+  if (!c) return ARKV_OK;
+  (void)hipDeviceSynchronize();
+  for (void* p : c->allocs) (void)hipFree(p);
+  for (auto& ls : c->layers)
+    if (ls.pre) (void)hipFree(ls.pre);
+  if (c->rowstat) (void)hipFree(c->rowstat);
+  if (c->rowc) (void)hipFree(c->rowc);
+  if (c->ckeys) (void)hipFree(c->ckeys);
+  delete c;
+  return ARKV_OK;
+}
+
+int arkv_cache_reset(arkv_cache* c, int32_t layer) {
+  if (!c || layer < -1 || layer >= c->L) return ARKV_EINVAL;
+  for (int l = 0; l < c->L; ++l) {
+    if (layer >= 0 && l != layer) continue;
+    LayerState& s = c->layers[(size_t)l];
+    s.scored = s.committed = s.pending = false;
+    s.scored_T = s.T = s.live = s.parity = s.n_tailors = s.last_tailor = 0;
+    s.P = -1;
+  }
+  return ARKV_OK;
+}
+
+int arkv_prefill_stats(arkv_cache* c, int32_t layer, const void* q_win, const void* k, int32_t T,
+                       float softmax_scale, float* stats, void* hip_stream) {
+  if (!c || !q_win || !k || !stats || layer < 0 || layer >= c->L) return ARKV_EINVAL;
+  if (T <= c->cfg.window || !(softmax_scale > 0.0f)) return ARKV_EINVAL;
+  LayerState& ls = c->layers[(size_t)layer];
+  if (ls.committed) return ARKV_ESTATE;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int U = c->U, G = c->P.G, W = c->cfg.window;
+  int rc;
+  if ((rc = grow(&ls.pre, &ls.pre_cap, (size_t)U * T)) != ARKV_OK) return rc;
+  int chunk = 1024;
+  while (chunk > 128 && (size_t)((T + chunk - 1) / chunk) * U < 1024) chunk >>= 1;
+  const int n_chunks = (T + chunk - 1) / chunk;
+  int MP = 32;
+  while (MP < G * W) MP *= 2;
+  if ((rc = grow(&c->rowstat, &c->rowstat_cap, (size_t)U * n_chunks * MP)) != ARKV_OK) return rc;
+  if ((rc = grow(&c->rowc, &c->rowc_cap, (size_t)U * MP)) != ARKV_OK) return rc;
+  PrefillLaunch a;
+  a.q_win = static_cast<const uint16_t*>(q_win);
+  a.k = static_cast<const uint16_t*>(k);
+  a.pre = ls.pre; a.rowstat = c->rowstat; a.stats = stats;
+  a.B = c->cfg.batch; a.Hkv = c->cfg.n_kv_heads; a.G = G; a.W = W; a.D = c->P.D; a.T = T;
+  a.chunk = chunk; a.n_chunks = n_chunks;
+  a.scale2 = softmax_scale * 1.4426950408889634f;
+  HIP_TRY(launch_prefill_stats(a, c->rowc, s));
+  ls.scored = true; ls.scored_T = T;
+  c->last_stream = s;
+  return ARKV_OK;
+}
+
+int arkv_prefill_commit(arkv_cache* c, int32_t layer, const void* k, const void* v, int32_t T,
+                        const float* rho, void* hip_stream) {
+  if (!c || !k || !v || !rho || layer < 0 || layer >= c->L) return ARKV_EINVAL;
+  LayerState& ls = c->layers[(size_t)layer];
+  if (ls.committed || !ls.scored || ls.scored_T != T) return ARKV_ESTATE;
+  const arkv_config& cfg = c->cfg;
+  const int N = cfg.capacity_tokens, W = cfg.window, U = c->U;
+  std::vector<int32_t> no_units((size_t)U);
+  for (int s = 0; s < cfg.batch; ++s) {
+    int32_t no, nq, bb;
+    int rc = arkv_budget_counts(&cfg, rho[s], &no, &nq, &bb);
+    if (rc != ARKV_OK) return rc;
+    ls.n_o[(size_t)s] = no;
+    for (int g = 0; g < cfg.n_kv_heads; ++g) no_units[(size_t)s * cfg.n_kv_heads + g] = no;
+  }
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  HIP_TRY(hipStreamSynchronize(st));
+  HIP_TRY(hipMemcpy(c->P.n_o + (size_t)layer * U, no_units.data(), (size_t)U * sizeof(int32_t), hipMemcpyHostToDevice));
+  CommitLaunch a;
+  a.k = static_cast<const uint16_t*>(k);
+  a.v = static_cast<const uint16_t*>(v);
+  a.pre = ls.pre;
+  a.unit_begin = layer * U; a.n_units = U;
+  a.T = T; a.window = W; a.b = c->b; a.gamma = cfg.gamma;
+  a.select = T >= N ? 1 : 0;
+  if (a.select) {
+    int rc = grow(&c->ckeys, &c->ckeys_cap, (size_t)U * T);
+    if (rc != ARKV_OK) return rc;
+    c->ckeys_layer = layer; c->ckeys_T = T;
+  }
+  HIP_TRY(launch_commit(c->P, a, c->ckeys, st));
+  ls.committed = true; ls.T = T; ls.P = T - 1; ls.pending = false; ls.parity = 0;
+  if (a.select) {
+    ls.live = std::min(c->b, T - W) + W;
+    ls.n_tailors = 1; ls.last_tailor = 1;
+  } else {
+    ls.live = T; ls.n_tailors = 0; ls.last_tailor = 0;
+  }
+  c->last_stream = st;
+  return ARKV_OK;
+}
+
+int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const void* q, const void* k_new,
+                            const void* v_new, const float* softmax_scale, void* out, void* hip_stream) {
+  if (!c || !q || !k_new || !v_new || !softmax_scale || !out) return ARKV_EINVAL;
+  if (n < 1 || n > kMaxLayersPerLaunch || layer_begin < 0 || layer_begin + n > c->L) return ARKV_EINVAL;
+  LayerState& l0 = c->layers[(size_t)layer_begin];
+  for (int i = 0; i < n; ++i) {
+    const LayerState& li = c->layers[(size_t)(layer_begin + i)];
+    if (!li.committed) return ARKV_ESTATE;
+    if (li.T != l0.T || li.P != l0.P || li.live != l0.live || li.pending != l0.pending || li.parity != l0.parity)
+      return ARKV_ESTATE;
+    if (!(softmax_scale[i] > 0.0f)) return ARKV_EINVAL;
+  }
+  const arkv_config& cfg = c->cfg;
+  const int N = cfg.capacity_tokens, W = cfg.window, U = c->U;
+  if (l0.live >= N) return ARKV_ESTATE;   // cannot happen: a tailor always frees a slot
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  DecodeLaunch a;
+  a.q = static_cast<const uint16_t*>(q);
+  a.k_new = static_cast<const uint16_t*>(k_new);
+  a.v_new = static_cast<const uint16_t*>(v_new);
+  a.out = static_cast<uint16_t*>(out);
+  a.unit_begin = layer_begin * U; a.n_units = n * U; a.units_per_layer = U;
+  int splits = (1024 + a.n_units - 1) / a.n_units;
+  splits = std::min(splits, std::max(1, l0.live / 64));
+  a.splits = std::max(1, std::min(splits, kMaxSplits));
+  a.position = l0.P + 1;
+  a.has_pending = l0.pending ? 1 : 0;
+  a.parity = l0.parity;
+  for (int i = 0; i < n; ++i) a.scale2[i] = softmax_scale[i] * 1.4426950408889634f;
+  HIP_TRY(launch_decode(c->P, a, st));
+  const int P = l0.P + 1, live = l0.live + 1, parity = l0.parity ^ 1;
+  bool tailor = live >= N;
+  int live_after = live;
+  if (tailor) {
+    TailorLaunch t;
+    t.unit_begin = a.unit_begin; t.n_units = a.n_units;
+    t.position = P; t.t_prefill = l0.T; t.window = W; t.b = c->b; t.gamma = cfg.gamma;
+    t.has_pending = 1; t.parity = parity;
+    HIP_TRY(launch_tailor(c->P, t, st));
+    const int wcount = std::min(W, P + 1);
+    live_after = std::min(c->b, live - wcount) + wcount;
+  }
+  for (int i = 0; i < n; ++i) {
+    LayerState& li = c->layers[(size_t)(layer_begin + i)];
+    li.P = P; li.live = live_after; li.parity = parity; li.pending = !tailor;
+    if (tailor) { li.n_tailors += 1; li.last_tailor = 2; }
+  }
+  c->last_stream = st;
+  return ARKV_OK;
+}
+
+int arkv_decode_step(arkv_cache* c, int32_t layer, const void* q, const void* k_new, const void* v_new,
+                     float softmax_scale, void* out, void* hip_stream) {
+  return arkv_decode_step_layers(c, layer, 1, q, k_new, v_new, &softmax_scale, out, hip_stream);
+}
+
+// ---- observability ---------------------------------------------------------------------------
+
+int arkv_cache_counters(arkv_cache* c, int32_t layer, int32_t* n_original, int32_t* n_quantized,
+                        int64_t* live_bytes) {
+  if (!c || layer < 0 || layer >= c->L) return ARKV_EINVAL;
+  if (!c->layers[(size_t)layer].committed) return ARKV_ESTATE;
+  HIP_TRY(hipStreamSynchronize(c->last_stream));
+  std::vector<int2> cnt;
+  int rc = fetch(cnt, c->P.cnt + (size_t)layer * c->U, (size_t)c->U);
+  if (rc != ARKV_OK) return rc;
+  const int64_t d = c->P.D, co = 4 * d, cq = 2 * (d * c->P.bits / 8 + (d / kGroup) * 4);
+  for (int u = 0; u < c->U; ++u) {
+    if (n_original) n_original[u] = cnt[(size_t)u].x;
+    if (n_quantized) n_quantized[u] = cnt[(size_t)u].y;
+    if (live_bytes) live_bytes[u] = cnt[(size_t)u].x * co + cnt[(size_t)u].y * cq;
+  }
+  return ARKV_OK;
+}
+
+int arkv_cache_progress(arkv_cache* c, int32_t layer, int32_t* n_tailors, int32_t* n_live, int32_t* position) {
+  if (!c || layer < 0 || layer >= c->L) return ARKV_EINVAL;
+  const LayerState& ls = c->layers[(size_t)layer];
+  if (n_tailors) *n_tailors = ls.n_tailors;
+  if (n_live) *n_live = ls.live;
+  if (position) *position = ls.P;
+  return ARKV_OK;
+}
+
+int arkv_cache_export(arkv_cache* c, int32_t layer, int32_t max_tokens, int32_t* n_live, int32_t* pos,
+                      uint8_t* state, float* s1, float* s2, uint16_t* rows_k, uint16_t* rows_v,
+                      uint8_t* codes_k, uint8_t* codes_v, uint16_t* scale_k, uint16_t* zero_k,
+                      uint16_t* scale_v, uint16_t* zero_v) {
+  if (!c || layer < 0 || layer >= c->L || max_tokens < c->cfg.capacity_tokens) return ARKV_EINVAL;
+  if (!c->layers[(size_t)layer].committed) return ARKV_ESTATE;
+  int rc = flush_and_sync(c, layer);
+  if (rc != ARKV_OK) return rc;
+  const Pools& P = c->P;
+  const size_t U = (size_t)c->U, off = (size_t)layer * U, D = (size_t)P.D;
+  const size_t CB = D * P.bits / 8, NG = D / kGroup, cO = (size_t)P.capO, cQ = (size_t)P.capQ;
+  std::vector<int2> cnt;
+  std::vector<int32_t> opos, qpos;
+  std::vector<float2> oacc, qacc;
+  std::vector<uint16_t> ok, ov;
+  std::vector<uint8_t> qkc, qvc;
+  std::vector<uint32_t> qkm, qvm;
+  if ((rc = fetch(cnt, P.cnt + off, U)) || (rc = fetch(opos, P.opos + off * cO, U * cO)) ||
+      (rc = fetch(qpos, P.qpos + off * cQ, U * cQ)) || (rc = fetch(oacc, P.oacc + off * cO, U * cO)) ||
+      (rc = fetch(qacc, P.qacc + off * cQ, U * cQ)))
+    return rc;
+  if (rows_k && (rc = fetch(ok, P.ok + off * cO * D, U * cO * D))) return rc;
+  if (rows_v && (rc = fetch(ov, P.ov + off * cO * D, U * cO * D))) return rc;
+  if (codes_k && (rc = fetch(qkc, P.qkc + off * cQ * CB, U * cQ * CB))) return rc;
+  if (codes_v && (rc = fetch(qvc, P.qvc + off * cQ * CB, U * cQ * CB))) return rc;
+  if ((scale_k || zero_k) && (rc = fetch(qkm, P.qkm + off * cQ * NG, U * cQ * NG))) return rc;
+  if ((scale_v || zero_v) && (rc = fetch(qvm, P.qvm + off * cQ * NG, U * cQ * NG))) return rc;
+  const size_t MT = (size_t)max_tokens;
+  struct Ent { int32_t pos; int32_t slot; uint8_t st; };
+  std::vector<Ent> ents;
+  for (size_t u = 0; u < U; ++u) {
+    ents.clear();
+    for (int i = 0; i < cnt[u].x; ++i) ents.push_back({opos[u * cO + i], i, ARKV_STATE_ORIGINAL});
+    for (int i = 0; i < cnt[u].y; ++i) ents.push_back({qpos[u * cQ + i], i, ARKV_STATE_QUANTIZED});
+    std::sort(ents.begin(), ents.end(), [](const Ent& a, const Ent& b) { return a.pos < b.pos; });
+    if (ents.size() > MT) return ARKV_EINVAL;
+    if (n_live) n_live[u] = (int32_t)ents.size();
+    for (size_t t = 0; t < ents.size(); ++t) {
+      const Ent& e = ents[t];
+      const size_t o = u * MT + t;
+      const bool isq = e.st == ARKV_STATE_QUANTIZED;
+      const size_t so = u * cO + (size_t)e.slot, sq = u * cQ + (size_t)e.slot;
+      if (pos) pos[o] = e.pos;
+      if (state) state[o] = e.st;
+      if (s1) s1[o] = isq ? qacc[sq].x : oacc[so].x;
+      if (s2) s2[o] = isq ? qacc[sq].y : oacc[so].y;
+      if (rows_k) { if (isq) memset(rows_k + o * D, 0, D * 2); else memcpy(rows_k + o * D, &ok[so * D], D * 2); }
+      if (rows_v) { if (isq) memset(rows_v + o * D, 0, D * 2); else memcpy(rows_v + o * D, &ov[so * D], D * 2); }
+      if (codes_k) { if (isq) memcpy(codes_k + o * CB, &qkc[sq * CB], CB); else memset(codes_k + o * CB, 0, CB); }
+      if (codes_v) { if (isq) memcpy(codes_v + o * CB, &qvc[sq * CB], CB); else memset(codes_v + o * CB, 0, CB); }
+      for (size_t g = 0; g < NG; ++g) {
+        if (scale_k) scale_k[o * NG + g] = isq ? (uint16_t)(qkm[sq * NG + g] & 0xffffu) : 0;
+        if (zero_k) zero_k[o * NG + g] = isq ? (uint16_t)(qkm[sq * NG + g] >> 16) : 0;
+        if (scale_v) scale_v[o * NG + g] = isq ? (uint16_t)(qvm[sq * NG + g] & 0xffffu) : 0;
+        if (zero_v) zero_v[o * NG + g] = isq ? (uint16_t)(qvm[sq * NG + g] >> 16) : 0;
+      }
+    }
+  }
+  return ARKV_OK;
+}
+
+int arkv_debug_last_tailor_scores(arkv_cache* c, int32_t layer, int32_t max_tokens, int32_t* count,
+                                  int32_t* pos, float* score) {
+  if (!c || layer < 0 || layer >= c->L || !count || max_tokens < 1) return ARKV_EINVAL;
+  const LayerState& ls = c->layers[(size_t)layer];
+  const size_t U = (size_t)c->U;
+  if (ls.last_tailor == 0) {
+    for (size_t u = 0; u < U; ++u) count[u] = -1;
+    return ARKV_OK;
+  }
+  HIP_TRY(hipStreamSynchronize(c->last_stream));
+  std::vector<uint64_t> keys;
+  size_t per;
+  int rc;
+  if (ls.last_tailor == 1) {
+    if (c->ckeys_layer != layer) return ARKV_ESTATE;   // scratch reused by another layer's commit
+    per = (size_t)c->ckeys_T;
+    rc = fetch(keys, (const uint64_t*)c->ckeys, U * per);
+  } else {
+    per = (size_t)(c->P.capO + c->P.capQ);
+    rc = fetch(keys, (const uint64_t*)c->P.keys + (size_t)layer * U * per, U * per);
+  }
+  if (rc != ARKV_OK) return rc;
+  for (size_t u = 0; u < U; ++u) {
+    int n = 0;
+    for (size_t i = 0; i < per; ++i) {
+      const uint64_t k = keys[u * per + i];
+      if (!k) continue;
+      if (n >= max_tokens) return ARKV_EINVAL;
+      const uint32_t sb = (uint32_t)(k >> 32);
+      float S;
+      memcpy(&S, &sb, 4);
+      if (pos) pos[u * (size_t)max_tokens + n] = (int32_t)(0xFFFFFFFFu - (uint32_t)(k & 0xFFFFFFFFu));
+      if (score) score[u * (size_t)max_tokens + n] = S;
+      ++n;
+    }
+    count[u] = n;
+  }
+  return ARKV_OK;
+}
+
+int arkv_debug_last_out_f32(arkv_cache* c, int32_t layer, float* out) {
+  if (!c || !out || layer < 0 || layer >= c->L) return ARKV_EINVAL;
+  HIP_TRY(hipStreamSynchronize(c->last_stream));
+  const size_t n = (size_t)c->U * c->P.G * c->P.D;
+  HIP_TRY(hipMemcpy(out, c->P.outf + (size_t)layer * n, n * sizeof(float), hipMemcpyDeviceToHost));
+  return ARKV_OK;
+}
+
+const char* arkv_strerror(int code) {
+  switch (code) {
+    case ARKV_OK: return "ok";
+    case ARKV_EINVAL: return "invalid argument";
+    case ARKV_ESTATE: return "call out of order for this layer";
+    case ARKV_ENOMEM: return "out of memory";
+    case ARKV_EHIP: return "HIP runtime error (see arkv_last_hip_error)";
+    case ARKV_EUNSUPPORTED: return "configuration not supported by this build";
+  }
+  return "unknown error code";
+}
+
+const char* arkv_last_hip_error(void) { return g_hip_error.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,266 @@
+// Prefill scorer (Sec. IV-C eqs. 2-5, and the first samples of the eq. 9 moments).
+//
+// Per unit (sequence, kv-head) the last W queries of the G heads of the group form M = G*W query
+// rows; their logits against all T keys are a dense [T x d] x [d x M] contraction -> MFMA
+// (v_mfma_f32_32x32x16_bf16, keys on the M side so that a lane owns ONE query row and the softmax
+// statistics of a row are in-register reductions).  The causal softmax needs each row's max and
+// sum before any probability exists, so the keys are streamed twice:
+//   k_prefill_rows     per (key chunk, unit): row max / row sum partials
+//   k_prefill_rowfinal per unit: c_r = max_r + log2(sum_r)
+//   k_prefill_cols     per (key chunk, unit): p = 2^(x - c_r); per key sum_r p and sum_r p^2 -> pre
+//   k_prefill_stats    per sequence: p_k over keys < T-W aggregated over all heads, entropy,
+//                      variance, kurtosis (fp64 reductions)
+#include "arkv_dev.h"
+
+namespace arkv {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr float kNegBigP = -1.0e30f;
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_p(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL,
+                                                               0xf, 0xf, true));
+}
+// sum over the 32 lanes that share lane/32
+__device__ __forceinline__ float sum32(float x) {
+  x += dpp_p<0xB1>(x);
+  x += dpp_p<0x4E>(x);
+  x += dpp_p<0x141>(x);
+  x += dpp_p<0x140>(x);
+  x += __shfl_xor(x, 16);
+  return x;
+}
+
+// Stage the unit's query rows in LDS: row r at byte r*(2D+16), rows >= M zero.
+template <int D>
+__device__ __forceinline__ void stage_q(unsigned char* sm, const uint16_t* q, int M, int MP) {
+  constexpr int RB = 2 * D + 16;
+  constexpr int VPR = D / 8;  // uint4 per row
+  for (int i = threadIdx.x; i < MP * VPR; i += 256) {
+    const int r = i / VPR, c = i % VPR;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (r < M) v = *reinterpret_cast<const uint4*>(q + (size_t)r * D + c * 8);
+    *reinterpret_cast<uint4*>(sm + (size_t)r * RB + c * 16) = v;
+  }
+}
+
+// Logits of one 32-key tile against row tile rt: C[i] at key j0 + 8(i/4) + 4(lane/32) + i%4, row rt*32 + lane%32.
+template <int D>
+__device__ __forceinline__ f32x16 tile_logits(const uint4 (&kf)[D / 16], const unsigned char* sm, int rt, int lane) {
+  constexpr int RB = 2 * D + 16;
+  f32x16 C = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  const unsigned char* qrow = sm + (size_t)(rt * 32 + (lane & 31)) * RB + (lane >> 5) * 16;
+#pragma unroll
+  for (int kk = 0; kk < D / 16; ++kk) {
+    const uint4 qb = *reinterpret_cast<const uint4*>(qrow + kk * 32);
+    C = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[kk]), __builtin_bit_cast(bf16x8, qb), C, 0, 0, 0);
+  }
+  return C;
+}
+
+template <int D>
+__device__ __forceinline__ void load_keys(uint4 (&kf)[D / 16], const uint16_t* k, int j0, int T, int lane) {
+  int key = j0 + (lane & 31);
+  if (key > T - 1) key = T - 1;
+  const uint16_t* p = k + (size_t)key * D + (lane >> 5) * 8;
+#pragma unroll
+  for (int kk = 0; kk < D / 16; ++kk) kf[kk] = *reinterpret_cast<const uint4*>(p + kk * 16);
+}
+
+template <int D, int RT>
+__global__ __launch_bounds__(256) void k_prefill_rows(PrefillLaunch L) {
+  extern __shared__ __align__(16) unsigned char sm[];
+  const int chunk = blockIdx.x, u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int M = L.G * L.W, MP = RT * 32, T = L.T;
+  stage_q<D>(sm, L.q_win + (size_t)u * M * D, M, MP);
+  __syncthreads();
+  const uint16_t* k = L.k + (size_t)u * T * D;
+  float m[RT], l[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) { m[rt] = kNegBigP; l[rt] = 0.f; }
+  const int jbeg = chunk * L.chunk, jend = min(jbeg + L.chunk, T);
+  for (int j0 = jbeg + w * 32; j0 < jend; j0 += 128) {
+    uint4 kf[D / 16];
+    load_keys<D>(kf, k, j0, T, lane);
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const f32x16 C = tile_logits<D>(kf, sm, rt, lane);
+      const int r = rt * 32 + (lane & 31);
+      const int last = r < M ? T - L.W + (r % L.W) : -1;   // last visible key of this row
+      float x[16];
+      float mt = kNegBigP;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int j = j0 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+        x[i] = j <= last ? C[i] * L.scale2 : kNegBigP;
+        mt = fmaxf(mt, x[i]);
+      }
+      const float mn = fmaxf(m[rt], mt);
+      float s = l[rt] * exp2f(m[rt] - mn);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s += x[i] > 0.5f * kNegBigP ? exp2f(x[i] - mn) : 0.f;
+      m[rt] = mn; l[rt] = s;
+    }
+  }
+  // merge the two lane halves, then the four waves
+  float* red = reinterpret_cast<float*>(sm);   // reuse after everyone is done with the queries
+  __syncthreads();
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const float mo = __shfl_xor(m[rt], 32), lo = __shfl_xor(l[rt], 32);
+    const float mn = fmaxf(m[rt], mo);
+    l[rt] = l[rt] * exp2f(m[rt] - mn) + lo * exp2f(mo - mn);
+    m[rt] = mn;
+    if (lane < 32) { red[(w * MP + rt * 32 + lane) * 2] = m[rt]; red[(w * MP + rt * 32 + lane) * 2 + 1] = l[rt]; }
+  }
+  __syncthreads();
+  for (int r = tid; r < MP; r += 256) {
+    float mn = kNegBigP;
+    for (int i = 0; i < 4; ++i) mn = fmaxf(mn, red[(i * MP + r) * 2]);
+    float s = 0.f;
+    for (int i = 0; i < 4; ++i) s += red[(i * MP + r) * 2 + 1] * exp2f(red[(i * MP + r) * 2] - mn);
+    L.rowstat[((size_t)u * L.n_chunks + chunk) * MP + r] = make_float2(mn, s);
+  }
+}
+
+__global__ void k_prefill_rowfinal(PrefillLaunch L, int MP, float* rowc) {
+  const int u = blockIdx.x;
+  for (int r = threadIdx.x; r < MP; r += blockDim.x) {
+    float mn = kNegBigP;
+    for (int c = 0; c < L.n_chunks; ++c) mn = fmaxf(mn, L.rowstat[((size_t)u * L.n_chunks + c) * MP + r].x);
+    float s = 0.f;
+    for (int c = 0; c < L.n_chunks; ++c) {
+      const float2 t = L.rowstat[((size_t)u * L.n_chunks + c) * MP + r];
+      s += t.y * exp2f(t.x - mn);
+    }
+    rowc[(size_t)u * MP + r] = s > 0.f ? mn + log2f(s) : 0.f;
+  }
+}
+
+template <int D, int RT>
+__global__ __launch_bounds__(256) void k_prefill_cols(PrefillLaunch L, const float* rowc) {
+  extern __shared__ __align__(16) unsigned char sm[];
+  const int chunk = blockIdx.x, u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int M = L.G * L.W, MP = RT * 32, T = L.T;
+  stage_q<D>(sm, L.q_win + (size_t)u * M * D, M, MP);
+  __syncthreads();
+  const uint16_t* k = L.k + (size_t)u * T * D;
+  float cr[RT];
+  int last[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int r = rt * 32 + (lane & 31);
+    cr[rt] = rowc[(size_t)u * MP + r];
+    last[rt] = r < M ? T - L.W + (r % L.W) : -1;
+  }
+  const int jbeg = chunk * L.chunk, jend = min(jbeg + L.chunk, T);
+  float2* pre = L.pre + (size_t)u * T;
+  for (int j0 = jbeg + w * 32; j0 < jend; j0 += 128) {
+    uint4 kf[D / 16];
+    load_keys<D>(kf, k, j0, T, lane);
+    float a1[16], a2[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { a1[i] = 0.f; a2[i] = 0.f; }
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const f32x16 C = tile_logits<D>(kf, sm, rt, lane);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int j = j0 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+        const float p = j <= last[rt] ? exp2f(C[i] * L.scale2 - cr[rt]) : 0.f;
+        a1[i] += p;
+        a2[i] = fmaf(p, p, a2[i]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { a1[i] = sum32(a1[i]); a2[i] = sum32(a2[i]); }
+    if ((lane & 31) == 0) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int j = j0 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+        if (j < T) pre[j] = make_float2(a1[i], a2[i]);
+      }
+    }
+  }
+}
+
+__device__ __forceinline__ double block_sum_d(double v, double* sm) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  const int w = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sm[w] = v;
+  __syncthreads();
+  double t = 0;
+  for (int i = 0; i < (int)(blockDim.x >> 6); ++i) t += sm[i];
+  return t;
+}
+
+// One workgroup per sequence: aggregated key distribution over ALL heads and its three statistics.
+__global__ __launch_bounds__(1024) void k_prefill_stats(PrefillLaunch L) {
+  __shared__ double sm[16];
+  const int b = blockIdx.x, n = L.T - L.W;
+  const float2* pre = L.pre + (size_t)b * L.Hkv * L.T;
+  double z = 0;
+  for (int j = threadIdx.x; j < n; j += 1024) {
+    double c = 0;
+    for (int g = 0; g < L.Hkv; ++g) c += (double)pre[(size_t)g * L.T + j].x;
+    z += c;
+  }
+  const double Z = block_sum_d(z, sm);
+  const double pbar = 1.0 / (double)n;
+  double h = 0, m2 = 0, m4 = 0;
+  for (int j = threadIdx.x; j < n; j += 1024) {
+    double c = 0;
+    for (int g = 0; g < L.Hkv; ++g) c += (double)pre[(size_t)g * L.T + j].x;
+    const double p = c / Z;
+    if (p > 0) h -= p * log(p);
+    const double d = p - pbar, d2 = d * d;
+    m2 += d2; m4 += d2 * d2;
+  }
+  h = block_sum_d(h, sm);
+  m2 = block_sum_d(m2, sm) / (double)n;
+  m4 = block_sum_d(m4, sm) / (double)n;
+  if (threadIdx.x == 0) {
+    L.stats[b * 3 + 0] = (float)h;
+    L.stats[b * 3 + 1] = (float)m2;
+    L.stats[b * 3 + 2] = m2 > 0 ? (float)(m4 / (m2 * m2)) : 0.f;
+  }
+}
+
+template <int D, int RT>
+static hipError_t launch_prefill_t(const PrefillLaunch& a, float* rowc, hipStream_t s) {
+  const int U = a.B * a.Hkv, MP = RT * 32;
+  const size_t shm = (size_t)MP * (2 * D + 16);
+  if (shm > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_prefill_rows<D, RT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_prefill_cols<D, RT>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
+    if (e != hipSuccess) return e;
+  }
+  dim3 grid(a.n_chunks, U);
+  hipLaunchKernelGGL((k_prefill_rows<D, RT>), grid, dim3(256), shm, s, a);
+  hipLaunchKernelGGL(k_prefill_rowfinal, dim3(U), dim3(256), 0, s, a, MP, rowc);
+  hipLaunchKernelGGL((k_prefill_cols<D, RT>), grid, dim3(256), shm, s, a, (const float*)rowc);
+  hipLaunchKernelGGL(k_prefill_stats, dim3(a.B), dim3(1024), 0, s, a);
+  return hipGetLastError();
+}
+
+// rowc: scratch [U][MP] floats
+hipError_t launch_prefill_stats(const PrefillLaunch& a, float* rowc, hipStream_t s) {
+  const int M = a.G * a.W;
+  int RT = 1;
+  while (RT * 32 < M) RT *= 2;
+  if (RT > 8) return hipErrorInvalidValue;
+#define ARKV_PF(D_, RT_) if (a.D == D_ && RT == RT_) return launch_prefill_t<D_, RT_>(a, rowc, s);
+  ARKV_PF(128, 1) ARKV_PF(128, 2) ARKV_PF(128, 4) ARKV_PF(128, 8)
+  ARKV_PF(64, 1) ARKV_PF(64, 2) ARKV_PF(64, 4) ARKV_PF(64, 8)
+#undef ARKV_PF
+  return hipErrorInvalidValue;
+}
+
+}  // namespace arkv

@@ -1,0 +1,215 @@
+"""Shared plumbing of the GPU parity tests: runs the HIP path (through the C ABI binding) and the
+CPU oracle side by side on the same synthetic inputs and compares them."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import arkv_oracle as O
+from paper_2603_08727_amd import binding as A
+from paper_2603_08727_amd import synth
+
+TOL = 2e-3                  # attention outputs, scores, statistics (fp32 accumulation)
+
+
+def rel_err(x, ref):
+    """max |x - ref| / max |ref| over one tensor (element-wise relative error is meaningless for
+    values that cancel to ~0)."""
+    x = np.asarray(x, dtype=np.float64); ref = np.asarray(ref, dtype=np.float64)
+    den = np.abs(ref).max()
+    return float(np.abs(x - ref).max() / den) if den > 0 else float(np.abs(x).max())
+
+
+def bf16_round(x32: np.ndarray) -> np.ndarray:
+    """fp32 -> bf16 bits, round to nearest even (for checking the library's final rounding)."""
+    u = np.asarray(x32, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = u + 0x7FFF + ((u >> 16) & 1)
+    return (u >> 16).astype(np.uint16)
+
+
+def make_cfg(wl: synth.Workload):
+    return A.arkv_config_default(
+        n_layers=wl.n_layers, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
+        head_dim=wl.head_dim, capacity_tokens=wl.capacity, window=wl.window, alpha=wl.alpha,
+        gamma=wl.gamma, tau=wl.tau, quant_bits=wl.bits)
+
+
+class SideBySide:
+    """One workload on both sides.  Scores the prompt, commits, then steps in lock-step: whenever the
+    GPU ran a tailor, the oracle's tailor of the same step ranks on the GPU's fp32 scores, so that
+    states / codes / scales can be compared bit for bit; everything floating point is compared at TOL."""
+
+    def __init__(self, wl: synth.Workload, rho_override=None, device="cuda"):
+        self.wl = wl
+        self.dev = device
+        self.cfg = make_cfg(wl)
+        self.cache = A.arkv_cache_create(self.cfg)
+        self.U = wl.batch * wl.n_kv_heads
+        self.rho_override = rho_override
+        self.oracles = {}        # (layer, b) -> SequenceCacheOracle
+        self.scales = [synth.softmax_scale(wl, l) for l in range(wl.n_layers)]
+        self.stats_gpu = None
+        self.stats_ref = None
+        self.max_err = dict(out=0.0, s1=0.0, s2=0.0, S=0.0, stats=0.0)
+
+    def close(self):
+        A.arkv_cache_destroy(self.cache)
+
+    # ---- prefill ---------------------------------------------------------------------------------
+    def prefill(self):
+        wl = self.wl
+        L, B = wl.n_layers, wl.batch
+        stats = torch.zeros((L, B, 3), dtype=torch.float32, device=self.dev)
+        self.inputs = []
+        ref_stats = np.zeros((L, B, 3))
+        ref_acc = {}
+        for l in range(L):
+            k, v, qw = synth.prefill_inputs(wl, l)          # CPU draw, copied to the GPU
+            self.inputs.append((k, v, qw))
+            kd, qd = k.to(self.dev), qw.to(self.dev)
+            A.arkv_prefill_stats(self.cache, l, qd, kd, wl.prefill, self.scales[l], stats[l])
+            for b in range(B):
+                a = O.window_attention(synth.to_numpy_f32(qw[b]), synth.to_numpy_f32(k[b]), self.scales[l], wl.group)
+                H, V, K, _ = O.layer_statistics(a, wl.window)
+                ref_stats[l, b] = (H, V, K)
+                ref_acc[(l, b)] = O.prefill_accumulators(a, wl.group)
+        torch.cuda.synchronize()
+        self.stats_gpu = stats.cpu().numpy()
+        self.stats_ref = ref_stats
+        err = np.abs(self.stats_gpu - ref_stats) / np.maximum(np.abs(ref_stats), 1e-300)
+        self.max_err["stats"] = float(err.max())
+        # OQ ratio: the library's host routine on the GPU statistics, the oracle's on its own
+        self.rho_gpu = A.arkv_oq_ratio(self.stats_gpu, wl.tau)
+        q = np.array([[O.oq_score(*ref_stats[l, b], tau=wl.tau) for b in range(B)] for l in range(L)])
+        self.rho_ref = np.stack([O.oq_ratio(q[:, b]) for b in range(B)], axis=1)
+        self.ref_acc = ref_acc
+
+    def commit(self):
+        wl = self.wl
+        for l in range(wl.n_layers):
+            k, v, _ = self.inputs[l]
+            rho = self.rho_gpu[l] if self.rho_override is None else np.full(wl.batch, self.rho_override, np.float32)
+            A.arkv_prefill_commit(self.cache, l, k.to(self.dev), v.to(self.dev), wl.prefill, rho)
+            over = self._gpu_scores(l) if wl.prefill >= wl.capacity else None
+            for b in range(wl.batch):
+                oc = O.SequenceCacheOracle(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.capacity, W=wl.window,
+                                           alpha=float(np.float32(wl.alpha)), gamma=float(np.float32(wl.gamma)),
+                                           bits=wl.bits)
+                s1, s2 = self.ref_acc[(l, b)]
+                if over is not None:
+                    self._check_scores(oc, l, b, over, commit=(s1, s2))
+                oc.commit(synth.to_numpy_f32(k[b]), synth.to_numpy_f32(v[b]), s1, s2, float(rho[b]),
+                          S_override=None if over is None else over[b * wl.n_kv_heads:(b + 1) * wl.n_kv_heads])
+                self.oracles[(l, b)] = oc
+            self.compare_state(l)
+
+    def _gpu_scores(self, layer):
+        """Per unit: dict position -> fp32 score of the tailor the GPU just ran."""
+        mt = max(self.wl.prefill, self.wl.capacity)
+        cnt, pos, sc = A.arkv_debug_last_tailor_scores(self.cache, layer, self.U, mt)
+        assert (cnt >= 0).all()
+        return [dict(zip(pos[u, :cnt[u]].tolist(), sc[u, :cnt[u]])) for u in range(self.U)]
+
+    def _check_scores(self, oc, l, b, over, commit=None):
+        """GPU scores vs the oracle's own fp64 scores of the same eligible tokens (TOL)."""
+        wl = self.wl
+        for g in range(wl.n_kv_heads):
+            d = over[b * wl.n_kv_heads + g]
+            if commit is not None:
+                T = wl.prefill
+                posr = np.arange(T - wl.window)
+                n = O.sample_count(posr, T - 1, T, wl.window, wl.group)
+                Sref = O.hh_score(commit[0][g][:T - wl.window], commit[1][g][:T - wl.window], n, oc.gamma)
+            else:
+                u = oc.units[g]
+                el = u.pos < oc.P + 1 - wl.window
+                posr = u.pos[el]
+                Sref = oc.scores(g)[el]
+            assert set(d.keys()) == set(posr.tolist())
+            Sg = np.array([d[int(p)] for p in posr])
+            assert (Sg >= 0).all()
+            self.max_err["S"] = max(self.max_err["S"], rel_err(Sg, Sref))
+
+    # ---- decode ----------------------------------------------------------------------------------
+    def decode(self, steps=None, check_every=1):
+        wl = self.wl
+        S = wl.decode_steps if steps is None else steps
+        ins = [synth.decode_inputs(wl, l, S) for l in range(wl.n_layers)]
+        dins = [tuple(t.to(self.dev) for t in x) for x in ins]
+        out = torch.empty((wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.bfloat16, device=self.dev)
+        for t in range(S):
+            for l in range(wl.n_layers):
+                q, kn, vn = dins[l]
+                nt0 = A.arkv_cache_progress(self.cache, l)[0]
+                A.arkv_decode_step(self.cache, l, q[t], kn[t], vn[t], self.scales[l], out)
+                fired = A.arkv_cache_progress(self.cache, l)[0] > nt0
+                outf = A.arkv_debug_last_out_f32(self.cache, l, (wl.batch, wl.n_q_heads, wl.head_dim))
+                assert np.array_equal(out.cpu().view(torch.int16).numpy().view(np.uint16), bf16_round(outf))
+                over = self._gpu_scores(l) if fired else None
+                for b in range(wl.batch):
+                    oc = self.oracles[(l, b)]
+                    qn, knn, vnn = (synth.to_numpy_f32(x[t, b]) for x in ins[l])
+                    if fired:
+                        # scores the oracle itself would rank on, before it adopts the GPU's
+                        probe = _clone_for_scores(oc, qn, knn, vnn, self.scales[l])
+                        self._check_scores(probe, l, b, over)
+                    ref, ofired = oc.decode_step(qn, knn, vnn, self.scales[l],
+                                                 S_override=None if over is None else
+                                                 over[b * wl.n_kv_heads:(b + 1) * wl.n_kv_heads])
+                    assert ofired == fired
+                    for h in range(wl.n_q_heads):
+                        self.max_err["out"] = max(self.max_err["out"], rel_err(outf[b, h], ref[h]))
+                if fired or t % check_every == 0 or t == S - 1:
+                    self.compare_state(l)
+
+    # ---- state comparison ------------------------------------------------------------------------
+    def compare_state(self, layer):
+        wl = self.wl
+        ex = A.arkv_cache_export(self.cache, layer, self.cfg)
+        no, nq, lb = A.arkv_cache_counters(self.cache, layer, self.U)
+        for b in range(wl.batch):
+            oc = self.oracles[(layer, b)]
+            for g in range(wl.n_kv_heads):
+                u = b * wl.n_kv_heads + g
+                ou = oc.units[g]
+                order = np.argsort(ou.pos)
+                n = len(order)
+                assert ex["n_live"][u] == n, (ex["n_live"][u], n)
+                assert np.array_equal(ex["pos"][u, :n], ou.pos[order])              # bit-exact: who survived
+                assert np.array_equal(ex["state"][u, :n], ou.state[order].astype(np.uint8))   # and in which state
+                assert (no[u], nq[u]) == oc.counts(g) and lb[u] == oc.live_bytes(g)
+                assert lb[u] <= wl.capacity * 4 * wl.head_dim                      # eq. 1, per unit
+                self.max_err["s1"] = max(self.max_err["s1"], rel_err(ex["s1"][u, :n], ou.s1[order]))
+                self.max_err["s2"] = max(self.max_err["s2"], rel_err(ex["s2"][u, :n], ou.s2[order]))
+                for t_, j in enumerate(order):
+                    p = int(ou.pos[j])
+                    if ou.state[j] == O.STATE_O:
+                        raw = ou.raw[j]
+                        assert np.array_equal(ex["rows_k"][u, t_], bf16_round(raw[0]))
+                        assert np.array_equal(ex["rows_v"][u, t_], bf16_round(raw[1]))
+                    else:
+                        e = ou.q[p]
+                        assert np.array_equal(ex["codes_k"][u, t_], O.pack_codes(e["k_codes"], wl.bits))
+                        assert np.array_equal(ex["codes_v"][u, t_], O.pack_codes(e["v_codes"], wl.bits))
+                        assert np.array_equal(ex["scale_k"][u, t_], e["k_scale"].view(np.uint16))
+                        assert np.array_equal(ex["zero_k"][u, t_], e["k_zero"].view(np.uint16))
+                        assert np.array_equal(ex["scale_v"][u, t_], e["v_scale"].view(np.uint16))
+                        assert np.array_equal(ex["zero_v"][u, t_], e["v_zero"].view(np.uint16))
+
+    def assert_within_tol(self, stats=True):
+        for k, v in self.max_err.items():
+            if k == "stats" and not stats:
+                continue
+            assert v <= TOL, (k, v, self.max_err)
+
+
+def _clone_for_scores(oc, q, kn, vn, scale):
+    """Copy of an oracle cache advanced by one step WITHOUT tailoring, to read the scores the
+    tailor of that step would rank on."""
+    import copy
+    c = copy.deepcopy(oc)
+    N = c.N
+    c.N = 10 ** 9
+    c.decode_step(q, kn, vn, scale)
+    c.N = N
+    return c

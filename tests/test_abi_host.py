@@ -1,0 +1,84 @@
+"""CPU-side checks of the C-ABI library: it loads, exports what include/arkv.h declares, rejects bad
+arguments before touching a GPU, and its host-only entry points agree with the oracle."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import arkv_oracle as O
+from paper_2603_08727_amd import binding as A
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "arkv.h")).read()
+    declared = set(re.findall(r"\b(arkv_[a-z0-9_]+)\s*\(", hdr))
+    assert declared, "no declarations found"
+    lib = A.load()
+    for name in declared:
+        assert hasattr(lib, name), f"{name} declared in arkv.h but not exported"
+    assert declared == set(A.EXPORTED)
+
+
+def test_strerror_and_defaults():
+    assert A.strerror(0) == "ok" and "invalid" in A.strerror(A.EINVAL)
+    cfg = A.arkv_config_default()
+    assert cfg.window == 32 and cfg.alpha == 0.75 and cfg.quant_bits == 4 and cfg.group_size == 32
+    assert [round(x, 3) for x in cfg.tau] == [7.774, 5.407, 5.528] and round(cfg.gamma, 2) == 263.81
+
+
+def _cfg(**kw):
+    base = dict(n_layers=1, batch=1, n_q_heads=8, n_kv_heads=2, head_dim=64, capacity_tokens=128)
+    base.update(kw)
+    return A.arkv_config_default(**base)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(n_layers=0), A.EINVAL), (dict(n_q_heads=7), A.EINVAL), (dict(window=127), A.EINVAL),
+    (dict(alpha=0.0), A.EINVAL), (dict(alpha=1.5), A.EINVAL), (dict(gamma=-1.0), A.EINVAL),
+    (dict(group_size=64), A.EINVAL), (dict(head_dim=96), A.EUNSUPPORTED),
+    (dict(quant_bits=3), A.EUNSUPPORTED), (dict(n_q_heads=6, n_kv_heads=2), A.EUNSUPPORTED),
+    (dict(tau=(1.0, 0.0, 1.0)), A.EINVAL),
+])
+def test_create_rejects_bad_config_without_gpu(kw, code):
+    with pytest.raises(A.ArkvError) as e:
+        A.arkv_cache_create(_cfg(**kw))
+    assert e.value.code == code
+
+
+def test_null_handles_are_errors_not_crashes():
+    lib = A.load()
+    assert lib.arkv_cache_destroy(None) == A.OK
+    assert lib.arkv_decode_step(None, 0, None, None, None, 1.0, None, None) == A.EINVAL
+    assert lib.arkv_prefill_stats(None, 0, None, None, 10, 1.0, None, None) == A.EINVAL
+    assert lib.arkv_cache_create(None, None) == A.EINVAL
+
+
+@pytest.mark.parametrize("N,W,alpha", [(128, 32, 0.75), (2048, 32, 0.75), (8192, 32, 0.75), (16384, 32, 0.75),
+                                       (40, 8, 0.5), (100, 4, 1.0), (64, 16, 0.9)])
+def test_budget_counts_match_oracle(N, W, alpha):
+    cfg = _cfg(capacity_tokens=N, window=W, alpha=alpha)
+    for rho in np.linspace(0, 1, 41, dtype=np.float32):
+        got = A.arkv_budget_counts(cfg, float(rho))
+        want = O.budget_counts(float(rho), N, W, float(np.float32(alpha)))
+        assert got == want
+
+
+def test_oq_ratio_matches_oracle():
+    rng = np.random.default_rng(0)
+    L, B = 7, 3
+    stats = np.stack([rng.uniform(3, 9, (L, B)), 10 ** rng.uniform(-9, -5, (L, B)), rng.uniform(3, 500, (L, B))],
+                     axis=-1).astype(np.float32)
+    stats[2, 1] = (5.0, 0.0, 0.0)            # a uniform layer: q = 0
+    stats[:, 2] = (np.log(100.0), 0.0, 0.0)  # a sequence where every layer is uniform: all rho = 1
+    tau = np.float32(O.PAPER_TAU)
+    rho = A.arkv_oq_ratio(stats, tau)
+    for b in range(B):
+        q = [O.oq_score(*stats[l, b].astype(np.float64), tau=tau.astype(np.float64)) for l in range(L)]
+        assert np.allclose(rho[:, b], O.oq_ratio(q), rtol=1e-6)
+    assert (rho[:, 2] == 1).all() and rho[2, 1] == 0 and rho.max() == 1
+    bad = stats.copy(); bad[0, 0, 1] = np.nan
+    with pytest.raises(A.ArkvError):
+        A.arkv_oq_ratio(bad, tau)

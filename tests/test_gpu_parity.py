@@ -1,0 +1,72 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, element by element on
+the same seeded inputs.  Integer results (positions, states, codes, fp16 scale/zero bits, counts,
+bf16 rows) must be identical; floating-point results within 2e-3 (helpers.TOL)."""
+import numpy as np
+import pytest
+
+from paper_2603_08727_amd import synth
+from helpers import SideBySide
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(wl, rho=None, steps=None, check_every=4, stats=True):
+    sb = SideBySide(wl, rho_override=rho)
+    try:
+        sb.prefill()
+        sb.commit()
+        sb.decode(steps, check_every=check_every)
+        print(wl.name, {k: f"{v:.2e}" for k, v in sb.max_err.items()}, flush=True)
+        sb.assert_within_tol(stats=stats)
+        # the OQ ratios computed from GPU statistics agree with the oracle's
+        assert np.abs(sb.rho_gpu - sb.rho_ref).max() <= 2e-3
+        return sb
+    finally:
+        sb.close()
+
+
+def test_c1_small_lockstep():
+    """Config 1 exactly: 1 layer, 8/2 heads, d=64, T=512, N=128, 64 steps, 4-bit."""
+    sb = _run(synth.C1, check_every=1)
+    assert sb.oracles[(0, 0)].n_tailors == 1 + 64 // 24
+
+
+def test_below_budget_no_tailor():
+    wl = synth.C1.scaled(name="below", prefill=100, budget_frac=3.0, decode_steps=40)
+    sb = _run(wl)
+    assert sb.oracles[(0, 0)].n_tailors == 0
+
+
+def test_fills_up_during_decode():
+    wl = synth.C1.scaled(name="fills", prefill=100, budget_frac=1.2, decode_steps=50)   # N = 120
+    sb = _run(wl, check_every=1)
+    assert sb.oracles[(0, 0)].n_tailors >= 1
+
+
+@pytest.mark.parametrize("rho", [0.0, 1.0, 0.3])
+def test_c1_forced_ratio(rho):
+    _run(synth.C1.scaled(name=f"c1_rho{rho}", decode_steps=30), rho=rho)
+
+
+def test_llama_shape_scaled_4bit():
+    """Config 2's shape (d=128, 32/8 heads) at reduced length, 2 layers so the OQ ratios differ."""
+    wl = synth.C2.scaled(name="c2_scaled", n_layers=2, prefill=1000, budget_frac=0.25, decode_steps=70)
+    _run(wl)
+
+
+def test_qwen_shape_scaled_batched_temperature():
+    wl = synth.C3.scaled(name="c3_scaled", n_layers=2, batch=2, prefill=777, budget_frac=0.26, decode_steps=60)
+    _run(wl)
+
+
+def test_long_context_shape_scaled_2bit():
+    wl = synth.C4.scaled(name="c4_scaled", n_layers=1, prefill=2048, budget_frac=0.125, decode_steps=40,
+                         heavy_frac=0.01)
+    _run(wl)
+
+
+@pytest.mark.parametrize("hq,hkv,d,bits", [(8, 1, 64, 4), (2, 2, 128, 2), (4, 2, 64, 2), (8, 8, 128, 4)])
+def test_group_sizes(hq, hkv, d, bits):
+    wl = synth.C1.scaled(name=f"g{hq // hkv}_d{d}_b{bits}", n_q_heads=hq, n_kv_heads=hkv, head_dim=d, bits=bits,
+                         prefill=300, budget_frac=0.3, decode_steps=30)
+    _run(wl)
