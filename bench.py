@@ -1,0 +1,262 @@
+#!/usr/bin/env python3
+"""Benchmark of the ARKV decode hot path on one MI355X.
+
+Workload (config.workload): benchmark configs[2], the configuration the metric is quoted on
+(32K context): Qwen3-8B-shaped cache, 36 layers, 32 q / 8 kv heads, d=128, batch 4, prompt 32768,
+budget 25 % (N = 8192), 4-bit groups of 32.  Synthetic inputs, drawn on the GPU (synth.py).
+
+A "step" is one decode step of the whole model: one arkv_decode_step call per layer (append,
+attend, score update, tailor when due), cycling through all 36 layer caches (2.8 GB of distinct
+cache memory per step, so the 256 MB last-level cache cannot hold it).  The prompt is scored
+(arkv_prefill_stats), the OQ ratios computed (arkv_oq_ratio) and every layer committed
+(arkv_prefill_commit, first tailor) before the timed region; those phases are timed separately and
+reported under "prefill".
+
+value = layer-batch decode steps per second = n_layers * steps / seconds.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def kv_bytes_per_token(d, bits):
+    c_o = 4 * d
+    c_q = 2 * (d * bits // 8 + (d // 32) * 4)
+    return c_o, c_q
+
+
+def algorithmic_bytes_attend(n_o, n_q, d, G, bits):
+    """Bytes the method itself must move for one unit in one decode step: every live K and V row
+    once, each token's (s1, s2) read and written, the unit's queries and outputs, the appended row."""
+    c_o, c_q = kv_bytes_per_token(d, bits)
+    n_live = n_o + n_q
+    return n_o * c_o + n_q * c_q + 16 * n_live + 2 * G * d * 2 + c_o
+
+
+def cpu_baseline(wl, k, v, qw, dq, scale, rho, seconds_budget=25.0):
+    """The oracle as it stands on one sequence of one layer: commit + a few decode steps, timed on
+    the host; scaled to layer-batch steps per second by the batch size."""
+    import numpy as np
+    from oracle import arkv_oracle as O
+    from paper_2603_08727_amd import synth
+    k0, v0, qw0 = (synth.to_numpy_f32(t) for t in (k, v, qw))
+    t0 = time.perf_counter()
+    a = O.window_attention(qw0, k0, scale, wl.group)
+    stats = O.layer_statistics(a, wl.window)[:3]
+    s1, s2 = O.prefill_accumulators(a, wl.group)
+    del a
+    t_score = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    oc = O.SequenceCacheOracle(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.capacity, W=wl.window,
+                               alpha=wl.alpha, gamma=wl.gamma, bits=wl.bits)
+    oc.commit(k0, v0, s1, s2, float(rho))
+    t_commit = time.perf_counter() - t0
+    q, kn, vn = (synth.to_numpy_f32(t) for t in dq)
+    n = 0
+    t0 = time.perf_counter()
+    while n < q.shape[0] and (n < 4 or time.perf_counter() - t0 < seconds_budget):
+        oc.decode_step(q[n], kn[n], vn[n], scale)
+        n += 1
+    t_dec = (time.perf_counter() - t0) / n
+    try:
+        import threadpoolctl
+        threads = max((p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()), default=1)
+    except Exception:
+        threads = os.cpu_count() or 1
+    return {
+        "value": 1.0 / (t_dec * wl.batch), "unit": "steps/s", "cores": int(threads), "kind": "oracle",
+        "sample": f"layer 0, sequence 0 of {wl.batch}: {n} decode steps after commit "
+                  f"({t_dec * 1e3:.1f} ms per sequence-step; x{wl.batch} sequences per layer-batch); "
+                  f"prompt scoring {t_score:.2f} s and commit {t_commit:.2f} s for that sequence, untimed in value",
+        "nproc": os.cpu_count(),
+    }, stats
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="c3_qwen3_8b_32k_b4")
+    ap.add_argument("--layers", type=int, default=None, help="override the number of layers (debug)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-steps", type=int, default=8)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures ONE GPU (units of the cache never interact across GPUs; "
+              "see DESIGN.md 'How it would shard'); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2603_08727_amd import binding as A
+    from paper_2603_08727_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda"
+    wl = synth.CONFIGS[args.workload]
+    if args.layers:
+        wl = wl.scaled(n_layers=args.layers)
+    L, B, Hq, Hkv, d, T, W = wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.prefill, wl.window
+    G, U = wl.group, wl.batch * wl.n_kv_heads
+    total_steps = args.warmup + args.steps + args.profile_steps + 8
+    cfg = A.arkv_config_default(n_layers=L, batch=B, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d,
+                                capacity_tokens=wl.capacity, window=W, alpha=wl.alpha, gamma=wl.gamma,
+                                tau=wl.tau, quant_bits=wl.bits)
+    cache = A.arkv_cache_create(cfg)
+    scales = [synth.softmax_scale(wl, l) for l in range(L)]
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    # ---- prefill scorer, all layers -------------------------------------------------------------
+    stats = torch.zeros((L, B, 3), dtype=torch.float32, device=dev)
+    t_stats = 0.0
+    sample = None
+    for l in range(L):
+        k, v, qw = synth.prefill_inputs(wl, l, device=dev)
+        if l == 0:
+            sample = (k[0].cpu(), v[0].cpu(), qw[0].cpu())
+        e0, e1 = ev(), ev()
+        e0.record()
+        A.arkv_prefill_stats(cache, l, qw, k, T, scales[l], stats[l])
+        e1.record()
+        torch.cuda.synchronize()
+        t_stats += e0.elapsed_time(e1)
+        del k, v, qw
+    stats_h = stats.cpu().numpy()
+    rho = A.arkv_oq_ratio(stats_h, wl.tau)
+    # ---- commit ---------------------------------------------------------------------------------
+    t_commit = 0.0
+    for l in range(L):
+        k, v, qw = synth.prefill_inputs(wl, l, device=dev)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        A.arkv_prefill_commit(cache, l, k, v, T, rho[l])
+        torch.cuda.synchronize()
+        t_commit += (time.perf_counter() - t0) * 1e3
+        del k, v, qw
+    # ---- decode inputs [S][L][B][H][d] ------------------------------------------------------------
+    per_layer = [synth.decode_inputs(wl, l, total_steps, device=dev) for l in range(L)]
+    q_all = torch.stack([p[0] for p in per_layer], dim=1).contiguous()
+    kn_all = torch.stack([p[1] for p in per_layer], dim=1).contiguous()
+    vn_all = torch.stack([p[2] for p in per_layer], dim=1).contiguous()
+    dq_sample = tuple(p[:, 0].cpu() for p in per_layer[0])
+    del per_layer
+    out = torch.empty((L, B, Hq, d), dtype=torch.bfloat16, device=dev)
+    step_i = 0
+
+    def one_step():
+        nonlocal step_i
+        t = step_i
+        for l in range(L):
+            A.arkv_decode_step(cache, l, q_all[t, l], kn_all[t, l], vn_all[t, l], scales[l], out[l])
+        step_i += 1
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    no0 = np.zeros(L); nq0 = np.zeros(L)
+    for l in range(L):
+        a_, b_, _ = A.arkv_cache_counters(cache, l, U)
+        no0[l], nq0[l] = a_.sum(), b_.sum()
+    tailors0 = sum(A.arkv_cache_progress(cache, l)[0] for l in range(L))
+    # ---- timed region -----------------------------------------------------------------------------
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    tailors1 = sum(A.arkv_cache_progress(cache, l)[0] for l in range(L))
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = L * args.steps / elapsed
+
+    # ---- dominant kernel: live duration by HIP events on the launch stream -------------------------
+    A.arkv_debug_time_attend(cache, True)
+    no_p = np.zeros(L); nq_p = np.zeros(L)
+    for l in range(L):
+        a_, b_, _ = A.arkv_cache_counters(cache, l, U)
+        no_p[l], nq_p[l] = a_.sum(), b_.sum()
+    for _ in range(args.profile_steps):
+        one_step()
+    att_ms, att_n = A.arkv_debug_attend_time(cache)
+    A.arkv_debug_time_attend(cache, False)
+    # tokens per launch during the profiled steps: counts before + half the appended tokens
+    mean_no = (no_p.mean() + U * args.profile_steps / 2.0) / U
+    mean_nq = nq_p.mean() / U
+    bytes_per_launch = U * algorithmic_bytes_attend(mean_no, mean_nq, d, G, wl.bits)
+    att_us = att_ms * 1e3 / max(att_n, 1)
+    achieved = bytes_per_launch / (att_us * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": "k_decode_attend", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "avg_kernel_us": round(att_us, 2), "launches_timed": int(att_n),
+                "algorithmic_bytes_per_launch": int(bytes_per_launch),
+                "tokens_per_unit": {"original": round(float(mean_no), 1), "quantized": round(float(mean_nq), 1)}}
+    # whole-step view: algorithmic bytes of a layer-batch call over its wall time in the timed region
+    mean_no_t = (no0.mean() + U * args.steps / 2.0) / U
+    mean_nq_t = nq0.mean() / U
+    step_bytes = U * algorithmic_bytes_attend(mean_no_t, mean_nq_t, d, G, wl.bits)
+    call_us = elapsed * 1e6 / (L * args.steps)
+
+    # ---- variant: all layers in one launch ----------------------------------------------------------
+    variants = {}
+    if L <= 64:
+        sc = np.array(scales, dtype=np.float32)
+        for _ in range(2):
+            A.arkv_decode_step_layers(cache, 0, L, q_all[step_i], kn_all[step_i], vn_all[step_i], sc, out); step_i += 1
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        nv = 4
+        for _ in range(nv):
+            A.arkv_decode_step_layers(cache, 0, L, q_all[step_i], kn_all[step_i], vn_all[step_i], sc, out); step_i += 1
+        torch.cuda.synchronize()
+        tv = time.perf_counter() - t0
+        variants["all_layers_one_launch"] = {"steps_per_s_per_layer_batch": round(L * nv / tv, 1),
+                                             "achieved_GBps": round(L * step_bytes * nv / tv / 1e9, 1)}
+
+    result = {
+        "metric": "decode steps/sec per layer-batch at 32K ctx", "value": round(value, 1), "unit": "steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 accumulate over bf16 / int%d rows" % wl.bits, "data": "synthetic",
+        "config": {"workload": wl.name, "n_layers": L, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
+                   "head_dim": d, "context": T, "capacity_tokens": wl.capacity, "quant_bits": wl.bits,
+                   "window": W, "launch": "one arkv_decode_step per layer"},
+        "roofline": roofline,
+        "step": {"us_per_layer_batch_call": round(call_us, 2),
+                 "achieved_GBps_whole_call": round(step_bytes / (call_us * 1e-6) / 1e9, 1),
+                 "frac_of_hbm_peak_whole_call": round(step_bytes / (call_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                 "tailors_in_timed_region": int(tailors1 - tailors0)},
+        "prefill": {"scorer_ms_per_layer": round(t_stats / L, 3),
+                    "scorer_TFLOPs": round(2.0 * W * Hq * T * d * B / (t_stats / L * 1e-3) / 1e12, 1),
+                    "scorer_frac_of_bf16_mfma_peak": round(2.0 * W * Hq * T * d * B / (t_stats / L * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                    "scorer_GBps_keys_once": round((B * Hkv * T * d * 2) / (t_stats / L * 1e-3) / 1e9, 1),
+                    "commit_ms_per_layer": round(t_commit / L, 3),
+                    "rho_min_mean_max": [round(float(rho.min()), 3), round(float(rho.mean()), 3), round(float(rho.max()), 3)]},
+        "variants": variants,
+    }
+    if not args.no_cpu_baseline:
+        cb, ref_stats = cpu_baseline(wl, *sample, dq_sample, scales[0], rho[0, 0])
+        result["cpu_baseline"] = cb
+        got = stats_h[0, 0]
+        result["prefill"]["stats_rel_err_vs_oracle_layer0_seq0"] = [
+            float(abs(got[i] - ref_stats[i]) / max(abs(ref_stats[i]), 1e-300)) for i in range(3)]
+    A.arkv_cache_destroy(cache)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

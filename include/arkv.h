@@ -149,6 +149,13 @@ int arkv_debug_last_out_f32(arkv_cache* cache, int32_t layer, float* out);
 int arkv_cache_progress(arkv_cache* cache, int32_t layer, int32_t* n_tailors, int32_t* n_live,
                         int32_t* position);
 
+/* Measurement hook.  enable != 0: every later decode step brackets its attention kernel with HIP
+ * events on the call's stream (a few microseconds of extra gap per step; off by default).
+ * arkv_debug_attend_time synchronises, returns the summed duration in milliseconds and the number of
+ * attention-kernel launches since the hook was enabled, and clears both. */
+int arkv_debug_time_attend(arkv_cache* cache, int32_t enable);
+int arkv_debug_attend_time(arkv_cache* cache, double* total_ms, int64_t* launches);
+
 const char* arkv_strerror(int code);        /* static text for an ARKV_E* code */
 const char* arkv_last_hip_error(void);      /* text of the HIP error behind the latest ARKV_EHIP */
 

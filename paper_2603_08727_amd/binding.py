@@ -22,7 +22,7 @@ EXPORTED = [
     "arkv_prefill_stats", "arkv_oq_ratio", "arkv_budget_counts", "arkv_prefill_commit",
     "arkv_decode_step", "arkv_decode_step_layers", "arkv_cache_counters", "arkv_cache_export",
     "arkv_debug_last_tailor_scores", "arkv_debug_last_out_f32", "arkv_cache_progress",
-    "arkv_strerror", "arkv_last_hip_error",
+    "arkv_debug_time_attend", "arkv_debug_attend_time", "arkv_strerror", "arkv_last_hip_error",
 ]
 
 
@@ -74,6 +74,8 @@ def load():
         "arkv_debug_last_tailor_scores": (C.c_int, [vp, i32, i32, vp, vp, vp]),
         "arkv_debug_last_out_f32": (C.c_int, [vp, i32, vp]),
         "arkv_cache_progress": (C.c_int, [vp, i32, P(i32), P(i32), P(i32)]),
+        "arkv_debug_time_attend": (C.c_int, [vp, i32]),
+        "arkv_debug_attend_time": (C.c_int, [vp, P(C.c_double), P(C.c_int64)]),
         "arkv_strerror": (C.c_char_p, [C.c_int]),
         "arkv_last_hip_error": (C.c_char_p, []),
     }
@@ -237,3 +239,13 @@ def arkv_debug_last_out_f32(cache, layer, shape):
     out = np.empty(shape, np.float32)
     _check(load().arkv_debug_last_out_f32(cache, layer, _np_ptr(out)), "arkv_debug_last_out_f32")
     return out
+
+
+def arkv_debug_time_attend(cache, enable: bool):
+    _check(load().arkv_debug_time_attend(cache, 1 if enable else 0), "arkv_debug_time_attend")
+
+
+def arkv_debug_attend_time(cache):
+    ms, n = C.c_double(), C.c_int64()
+    _check(load().arkv_debug_attend_time(cache, C.byref(ms), C.byref(n)), "arkv_debug_attend_time")
+    return ms.value, n.value

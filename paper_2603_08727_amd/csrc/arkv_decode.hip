@@ -382,32 +382,35 @@ __global__ __launch_bounds__(256) void k_flush_scores(Pools P, int unit_begin, i
 }
 
 template <int D, int G, int BITS>
-static hipError_t launch_decode_t(const Pools& P, const DecodeLaunch& a, hipStream_t s) {
+static hipError_t launch_decode_t(const Pools& P, const DecodeLaunch& a, hipStream_t s, hipEvent_t ev0,
+                                  hipEvent_t ev1) {
   dim3 grid(a.splits, a.n_units);
+  if (ev0) (void)hipEventRecord(ev0, s);
   hipLaunchKernelGGL((k_decode_attend<D, G, BITS>), grid, dim3(256), 0, s, P, a);
+  if (ev1) (void)hipEventRecord(ev1, s);
   hipLaunchKernelGGL((k_decode_combine<D, G>), dim3(a.n_units), dim3(256), 0, s, P, a);
   return hipGetLastError();
 }
 
 template <int D, int G>
-static hipError_t launch_decode_b(const Pools& P, const DecodeLaunch& a, hipStream_t s) {
-  return P.bits == 4 ? launch_decode_t<D, G, 4>(P, a, s) : launch_decode_t<D, G, 2>(P, a, s);
+static hipError_t launch_decode_b(const Pools& P, const DecodeLaunch& a, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
+  return P.bits == 4 ? launch_decode_t<D, G, 4>(P, a, s, e0, e1) : launch_decode_t<D, G, 2>(P, a, s, e0, e1);
 }
 
 template <int D>
-static hipError_t launch_decode_g(const Pools& P, const DecodeLaunch& a, hipStream_t s) {
+static hipError_t launch_decode_g(const Pools& P, const DecodeLaunch& a, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
   switch (P.G) {
-    case 1: return launch_decode_b<D, 1>(P, a, s);
-    case 2: return launch_decode_b<D, 2>(P, a, s);
-    case 4: return launch_decode_b<D, 4>(P, a, s);
-    case 8: return launch_decode_b<D, 8>(P, a, s);
+    case 1: return launch_decode_b<D, 1>(P, a, s, e0, e1);
+    case 2: return launch_decode_b<D, 2>(P, a, s, e0, e1);
+    case 4: return launch_decode_b<D, 4>(P, a, s, e0, e1);
+    case 8: return launch_decode_b<D, 8>(P, a, s, e0, e1);
   }
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_decode(const Pools& P, const DecodeLaunch& a, hipStream_t s) {
-  if (P.D == 128) return launch_decode_g<128>(P, a, s);
-  if (P.D == 64) return launch_decode_g<64>(P, a, s);
+hipError_t launch_decode(const Pools& P, const DecodeLaunch& a, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
+  if (P.D == 128) return launch_decode_g<128>(P, a, s, e0, e1);
+  if (P.D == 64) return launch_decode_g<64>(P, a, s, e0, e1);
   return hipErrorInvalidValue;
 }
 

@@ -49,6 +49,10 @@ struct arkv_cache {
   uint64_t* ckeys = nullptr; size_t ckeys_cap = 0;
   int ckeys_layer = -1, ckeys_T = 0;
   hipStream_t last_stream = nullptr;
+  // measurement hook: events around the attention kernel
+  bool timing = false;
+  std::vector<hipEvent_t> ev_pool;   // pairs, reused after every read
+  size_t ev_used = 0;
 };
 
 static int validate(const arkv_config* c) {
@@ -211,6 +215,7 @@ int arkv_cache_destroy(arkv_cache* c) {
   if (c->rowstat) (void)hipFree(c->rowstat);
   if (c->rowc) (void)hipFree(c->rowc);
   if (c->ckeys) (void)hipFree(c->ckeys);
+  for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
   delete c;
   return ARKV_OK;
 }
@@ -328,7 +333,19 @@ int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const
   a.has_pending = l0.pending ? 1 : 0;
   a.parity = l0.parity;
   for (int i = 0; i < n; ++i) a.scale2[i] = softmax_scale[i] * 1.4426950408889634f;
-  HIP_TRY(launch_decode(c->P, a, st));
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (c->timing) {
+    if (c->ev_used + 2 > c->ev_pool.size()) {
+      for (int i = 0; i < 2; ++i) {
+        hipEvent_t e;
+        HIP_TRY(hipEventCreate(&e));
+        c->ev_pool.push_back(e);
+      }
+    }
+    e0 = c->ev_pool[c->ev_used]; e1 = c->ev_pool[c->ev_used + 1];
+    c->ev_used += 2;
+  }
+  HIP_TRY(launch_decode(c->P, a, st, e0, e1));
   const int P = l0.P + 1, live = l0.live + 1, parity = l0.parity ^ 1;
   bool tailor = live >= N;
   int live_after = live;
@@ -489,6 +506,28 @@ int arkv_debug_last_out_f32(arkv_cache* c, int32_t layer, float* out) {
   HIP_TRY(hipStreamSynchronize(c->last_stream));
   const size_t n = (size_t)c->U * c->P.G * c->P.D;
   HIP_TRY(hipMemcpy(out, c->P.outf + (size_t)layer * n, n * sizeof(float), hipMemcpyDeviceToHost));
+  return ARKV_OK;
+}
+
+int arkv_debug_time_attend(arkv_cache* c, int32_t enable) {
+  if (!c) return ARKV_EINVAL;
+  c->timing = enable != 0;
+  c->ev_used = 0;
+  return ARKV_OK;
+}
+
+int arkv_debug_attend_time(arkv_cache* c, double* total_ms, int64_t* launches) {
+  if (!c || !total_ms || !launches) return ARKV_EINVAL;
+  HIP_TRY(hipStreamSynchronize(c->last_stream));
+  double tot = 0.0;
+  for (size_t i = 0; i + 1 < c->ev_used; i += 2) {
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, c->ev_pool[i], c->ev_pool[i + 1]));
+    tot += (double)ms;
+  }
+  *total_ms = tot;
+  *launches = (int64_t)(c->ev_used / 2);
+  c->ev_used = 0;
   return ARKV_OK;
 }
 
