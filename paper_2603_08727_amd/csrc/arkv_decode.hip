@@ -2,8 +2,9 @@
 //   k_decode_attend : append + split-K attention of one query per head over the bf16 pool and the
 //                     packed low-bit pool (dequantisation inside the QK and PV loops) + the score
 //                     update of the PREVIOUS step (its probabilities need that step's final
-//                     softmax denominator, which only exists after the split-K combine)
-//   k_decode_combine: merges the split-K partials, writes the output and the step's (max, 1/sum)
+//                     softmax denominator, which only exists after the split-K merge) + the merge
+//                     itself, done by the last workgroup of a unit to finish
+//   k_decode_combine: the merge as a kernel of its own (used when the fused merge is switched off)
 //   k_flush_scores  : adds the pending probabilities to (s1, s2) when something needs them now
 //                     (tailor, export)
 #include <hip/hip_fp16.h>
@@ -14,19 +15,29 @@ namespace arkv {
 
 constexpr float kNegBig = -1.0e30f;
 
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
 template <int CTRL>
 __device__ __forceinline__ float dpp_mov(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL,
                                                                0xf, 0xf, true));
 }
 
-// Sum over the LPR consecutive lanes that share a row (LPR = 8 or 16, aligned); every lane gets the sum.
-template <int LPR>
-__device__ __forceinline__ float group_sum(float x) {
-  x += dpp_mov<0xB1>(x);                 // quad_perm [1,0,3,2]
-  x += dpp_mov<0x4E>(x);                 // quad_perm [2,3,0,1]
-  x += dpp_mov<0x141>(x);                // row_half_mirror: lane i <- 7-i
-  if (LPR >= 16) x += dpp_mov<0x140>(x); // row_mirror: lane i <- 15-i
+// DPP controls: 0xB1 quad_perm [1,0,3,2], 0x4E quad_perm [2,3,0,1], 0x141 row_half_mirror, 0x140 row_mirror.
+// Applied in this order they reduce over the 16 lanes of a DPP row and leave the result in every lane.
+__device__ __forceinline__ float row_sum16(float x) {
+  x += dpp_mov<0xB1>(x);
+  x += dpp_mov<0x4E>(x);
+  x += dpp_mov<0x141>(x);
+  x += dpp_mov<0x140>(x);
+  return x;
+}
+__device__ __forceinline__ float row_max16(float x) {
+  x = fmaxf(x, dpp_mov<0xB1>(x));
+  x = fmaxf(x, dpp_mov<0x4E>(x));
+  x = fmaxf(x, dpp_mov<0x141>(x));
+  x = fmaxf(x, dpp_mov<0x140>(x));
   return x;
 }
 
@@ -72,69 +83,40 @@ __host__ __device__ inline void split_range(int cO, int cQ, int wq, int S, int s
   ao = mapO(v0); bo = mapO(v1); aq = mapQ(v0); bq = mapQ(v1);
 }
 
-template <int G>
-struct Softmax {
-  float m[G], l[G], a[G][8];
-};
-
-// One tile of UNR rows per lane group: logits, online softmax update, PV accumulation.
-template <int LPR, int G, int UNR>
-__device__ __forceinline__ void consume(Softmax<G>& st, const float (&qf)[G][8], const float (&kf)[UNR][8],
-                                        const float (&vf)[UNR][8], const bool (&ok)[UNR], float scale2,
-                                        float (&lg)[UNR][G]) {
-#pragma unroll
-  for (int u = 0; u < UNR; ++u) {
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-      float d = 0.f;
-#pragma unroll
-      for (int c = 0; c < 8; ++c) d = fmaf(qf[h][c], kf[u][c], d);
-      d = group_sum<LPR>(d);
-      lg[u][h] = ok[u] ? d * scale2 : kNegBig;
-    }
-  }
-#pragma unroll
-  for (int h = 0; h < G; ++h) {
-    float mt = lg[0][h];
-#pragma unroll
-    for (int u = 1; u < UNR; ++u) mt = fmaxf(mt, lg[u][h]);
-    const float mn = fmaxf(st.m[h], mt);
-    const float corr = exp2f(st.m[h] - mn);
-    st.m[h] = mn;
-    st.l[h] *= corr;
-#pragma unroll
-    for (int c = 0; c < 8; ++c) st.a[h][c] *= corr;
-#pragma unroll
-    for (int u = 0; u < UNR; ++u) {
-      const float p = ok[u] ? exp2f(lg[u][h] - mn) : 0.f;
-      st.l[h] += p;
-#pragma unroll
-      for (int c = 0; c < 8; ++c) st.a[h][c] = fmaf(p, vf[u][c], st.a[h][c]);
-    }
-  }
-}
-
-template <int G>
-__device__ __forceinline__ void merge(Softmax<G>& x, const Softmax<G>& y) {
-#pragma unroll
-  for (int h = 0; h < G; ++h) {
-    const float M = fmaxf(x.m[h], y.m[h]);
-    const float cx = exp2f(x.m[h] - M), cy = exp2f(y.m[h] - M);
-    x.m[h] = M;
-    x.l[h] = x.l[h] * cx + y.l[h] * cy;
-#pragma unroll
-    for (int c = 0; c < 8; ++c) x.a[h][c] = x.a[h][c] * cx + y.a[h][c] * cy;
-  }
-}
-
-template <int G>
-__device__ __forceinline__ void store_logits(float* dst, const float (&lg)[G]) {
-  if constexpr (G == 4) {
-    *reinterpret_cast<float4*>(dst) = make_float4(lg[0], lg[1], lg[2], lg[3]);
+// 8 packed codes -> 8 bf16 values 128 + code, element order [c0,c4,c1,c5,c2,c6,c3,c7]
+// (bf16 0x4300 is 128.0 with a 7-bit mantissa, so OR-ing a code < 128 into it adds the code exactly).
+template <int BITS>
+__device__ __forceinline__ uint4 codes_to_bf16_biased(uint32_t cw) {
+  uint4 r;
+  if (BITS == 4) {
+    r.x = (cw & 0x000F000Fu) | 0x43004300u;
+    r.y = ((cw >> 4) & 0x000F000Fu) | 0x43004300u;
+    r.z = ((cw >> 8) & 0x000F000Fu) | 0x43004300u;
+    r.w = ((cw >> 12) & 0x000F000Fu) | 0x43004300u;
   } else {
-#pragma unroll
-    for (int h = 0; h < G; ++h) dst[h] = lg[h];
+    const uint32_t y = (cw & 0xFFu) | ((cw & 0xFF00u) << 8);
+    r.x = (y & 0x00030003u) | 0x43004300u;
+    r.y = ((y >> 2) & 0x00030003u) | 0x43004300u;
+    r.z = ((y >> 4) & 0x00030003u) | 0x43004300u;
+    r.w = ((y >> 6) & 0x00030003u) | 0x43004300u;
   }
+  return r;
+}
+
+// bf16 pairs (c0,c1)(c2,c3)(c4,c5)(c6,c7) -> (c0,c4)(c1,c5)(c2,c6)(c3,c7)
+__device__ __forceinline__ uint4 permute_for_codes(const uint4& q) {
+  uint4 r;
+  r.x = (q.x & 0xFFFFu) | (q.z << 16);
+  r.y = (q.x >> 16) | (q.z & 0xFFFF0000u);
+  r.z = (q.y & 0xFFFFu) | (q.w << 16);
+  r.w = (q.y >> 16) | (q.w & 0xFFFF0000u);
+  return r;
+}
+
+// D[m][n] += sum_k A[m][k] B[k][n], 16x16x32 bf16.  Lane l holds A[l%16][8(l/16)..+7],
+// B[8(l/16)..+7][l%16] and D[4(l/16)..+3][l%16].
+__device__ __forceinline__ f32x4 mfma16(const uint4& a, const uint4& b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
 // (s1, s2) += sum_h p_h, sum_h p_h^2 with p_h = 2^(lg_h - m_h) / Z_h, slots [a, b), one thread per slot.
@@ -164,19 +146,75 @@ __device__ __forceinline__ void apply_pending(float2* acc, const float* lg, int 
   }
 }
 
+// Merge of a unit's split-K partials: output row, the step's (max, 1/sum) per head, token count.
+template <int D, int G>
+__device__ __forceinline__ void combine_splits(const Pools& P, const DecodeLaunch& L, int lu, int gu, int tid) {
+  __shared__ float cw[kMaxSplits][G];
+  __shared__ float cInv[G];
+  const volatile float* part = P.part + (size_t)gu * P.max_splits * G * (D + 2);
+  const int S = L.splits;
+  if (tid < G) {
+    float M = kNegBig;
+    for (int s = 0; s < S; ++s) M = fmaxf(M, part[((size_t)s * G + tid) * (D + 2) + D]);
+    float l = 0.f;
+    for (int s = 0; s < S; ++s) {
+      const float w_ = exp2f(part[((size_t)s * G + tid) * (D + 2) + D] - M);
+      cw[s][tid] = w_;
+      l = fmaf(part[((size_t)s * G + tid) * (D + 2) + D + 1], w_, l);
+    }
+    cInv[tid] = 1.0f / l;
+    P.fin[(size_t)(L.parity ^ 1) * P.fin_stride + (size_t)gu * G + tid] = make_float2(M, 1.0f / l);
+  }
+  __syncthreads();
+  for (int idx = tid; idx < G * D; idx += 256) {
+    const int h = idx / D, c = idx % D;
+    float a0 = 0.f, a1 = 0.f;
+    int s = 0;
+    for (; s + 1 < S; s += 2) {
+      a0 = fmaf(part[((size_t)s * G + h) * (D + 2) + c], cw[s][h], a0);
+      a1 = fmaf(part[((size_t)(s + 1) * G + h) * (D + 2) + c], cw[s + 1][h], a1);
+    }
+    if (s < S) a0 = fmaf(part[((size_t)s * G + h) * (D + 2) + c], cw[s][h], a0);
+    const float o = (a0 + a1) * cInv[h];
+    P.outf[((size_t)gu * G + h) * D + c] = o;
+    L.out[((size_t)lu * G + h) * D + c] = float_to_bf16_rne(o);
+  }
+  if (tid == 0) P.cnt[gu].x += 1;
+}
+
+// Attention of one query per head over this split's share of a unit's cache.
+//
+// A wave works on tiles of 16 tokens.  QK^T of a tile is D/32 MFMAs (A = the unit's G query rows padded
+// to 16, B = 16 key rows loaded from HBM straight into operand layout); lane (token t = lane%16, block
+// b = lane/16) then owns the logits of token t for heads 4b..4b+3.  Probabilities go through a small
+// LDS buffer to the value layout (lane = 8 channels of one of 64/(D/8) rows), where PV runs on the
+// vector ALU.  The softmax reference maximum is only moved when a logit exceeds it by more than 8
+// (base-2 units), which is rare, so the accumulators are almost never rescaled.  Packed rows: codes are
+// OR-ed into bf16 "128 + code" operands, one MFMA per quantisation group, and scale / zero / the 128
+// offset are applied to the per-group dot products.
 template <int D, int G, int BITS>
 __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) {
-  constexpr int LPR = D / 8;        // lanes per row
-  constexpr int R = 64 / LPR;       // rows per wave per load
-  constexpr int UNR = 4;
-  constexpr int TILE = 4 * R * UNR; // rows per workgroup iteration
-  constexpr int CB = D * BITS / 8;  // code bytes per row
+  constexpr int KK = D / 32;           // MFMA k-steps = quantisation groups per row
+  constexpr int LPR = D / 8;           // lanes per value row
+  constexpr int R = 64 / LPR;          // value rows per wave load
+  constexpr int NV = 16 / R;           // value loads per tile
+  constexpr int HB = (G + 3) / 4;      // lane blocks holding real heads
+  constexpr int HPL = G < 4 ? G : 4;   // heads per lane
+  constexpr int CB = D * BITS / 8;     // code bytes per row
   constexpr int NG = D / kGroup;
+  constexpr int CW = BITS;             // code bytes per 8 channels
   const int s = blockIdx.x, lu = blockIdx.y;
   const int gu = L.unit_begin + lu;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int rg = lane / LPR, sub = lane % LPR;
+  const int tok = lane & 15, blk = lane >> 4;
+  const int vrow = lane / LPR, sub = lane % LPR;
+  const bool active = blk < HB;
   const float scale2 = L.scale2[lu / L.units_per_layer];
+
+  __shared__ float pbuf[4][16][G < 4 ? 4 : G];
+  __shared__ float sm_a[4][G][D];
+  __shared__ float sm_m[4][G], sm_l[4][G];
+  __shared__ int s_last;
 
   const int2 cnt = P.cnt[gu];
   const int cO = cnt.x, cQ = cnt.y;
@@ -190,141 +228,293 @@ __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) 
   float2* oacc = P.oacc + (size_t)gu * P.capO;
   float2* qacc = P.qacc + (size_t)gu * P.capQ;
 
-  // ---- phase 1: fold the previous step's probabilities into (s1, s2) for the rows this split owns
-  if (L.has_pending) {
-    float pm[G], pinv[G];
-    const float2* f = P.fin + (size_t)L.parity * P.fin_stride + (size_t)gu * G;
+  // previous step's softmax statistics of the heads this lane owns (for the deferred score update)
+  float pm[HPL], pinv[HPL];
 #pragma unroll
-    for (int h = 0; h < G; ++h) { pm[h] = f[h].x; pinv[h] = f[h].y; }
-    apply_pending<G>(oacc, olg, ao, bo, pm, pinv, tid, 256);
-    apply_pending<G>(qacc, qlg, aq, bq, pm, pinv, tid, 256);
-    __syncthreads();   // the main loop overwrites these logits from other threads
+  for (int i = 0; i < HPL; ++i) { pm[i] = 0.f; pinv[i] = 0.f; }
+  if (L.has_pending && active) {
+    const float2* f = P.fin + (size_t)L.parity * P.fin_stride + (size_t)gu * G + 4 * blk;
+#pragma unroll
+    for (int i = 0; i < HPL; ++i) { pm[i] = f[i].x; pinv[i] = f[i].y; }
   }
 
-  // ---- query of this unit's G heads: the 8 channels this lane owns
-  float qf[G][8];
+  // query operand: lane holds head lane%16 (zero beyond G), channels 32kk + 8(lane/16) .. +7
+  uint4 qa[KK];
   {
-    const uint16_t* q = L.q + ((size_t)lu * G) * D + sub * 8;
+    const uint16_t* q = L.q + ((size_t)lu * G + (tok < G ? tok : 0)) * D + 8 * blk;
 #pragma unroll
-    for (int h = 0; h < G; ++h) unpack_bf16x8(*reinterpret_cast<const uint4*>(q + (size_t)h * D), qf[h]);
-  }
-  Softmax<G> st;
-#pragma unroll
-  for (int h = 0; h < G; ++h) {
-    st.m[h] = kNegBig; st.l[h] = 0.f;
-#pragma unroll
-    for (int c = 0; c < 8; ++c) st.a[h][c] = 0.f;
-  }
-
-  // ---- Original rows
-  for (int r0 = ao; r0 < bo; r0 += TILE) {
-    uint4 kr[UNR], vr[UNR];
-    bool ok[UNR];
-    int row[UNR];
-#pragma unroll
-    for (int u = 0; u < UNR; ++u) {
-      row[u] = r0 + (u * 4 + w) * R + rg;
-      ok[u] = row[u] < bo;
-      const int rr = ok[u] ? row[u] : bo - 1;
-      kr[u] = *reinterpret_cast<const uint4*>(ok_ + (size_t)rr * D + sub * 8);
-      vr[u] = *reinterpret_cast<const uint4*>(ov_ + (size_t)rr * D + sub * 8);
-    }
-    float kf[UNR][8], vf[UNR][8], lg[UNR][G];
-#pragma unroll
-    for (int u = 0; u < UNR; ++u) { unpack_bf16x8(kr[u], kf[u]); unpack_bf16x8(vr[u], vf[u]); }
-    consume<LPR, G, UNR>(st, qf, kf, vf, ok, scale2, lg);
-    if (sub == 0) {
-#pragma unroll
-      for (int u = 0; u < UNR; ++u)
-        if (ok[u]) store_logits<G>(olg + (size_t)row[u] * G, lg[u]);
+    for (int kk = 0; kk < KK; ++kk) {
+      const uint4 v = *reinterpret_cast<const uint4*>(q + 32 * kk);
+      qa[kk] = tok < G ? v : make_uint4(0, 0, 0, 0);
     }
   }
 
-  // ---- Quantized rows: dequantise in registers
-  {
+  float Mreg[HPL], lsum[HPL], acc[G][8];
+#pragma unroll
+  for (int i = 0; i < HPL; ++i) { Mreg[i] = kNegBig; lsum[i] = 0.f; }
+#pragma unroll
+  for (int h = 0; h < G; ++h)
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[h][c] = 0.f;
+
+  // logits x[] of this lane's token -> reference-max check, probabilities, PV with the tile's value rows
+  auto softmax_pv = [&](const float (&x)[HPL], const float (&vf)[NV][8]) {
+    bool need = false;
+#pragma unroll
+    for (int i = 0; i < HPL; ++i) need |= active && (x[i] > Mreg[i] + 8.0f);
+    if (__any(need)) {
+      float f[HPL];
+#pragma unroll
+      for (int i = 0; i < HPL; ++i) {
+        const float nm = fmaxf(Mreg[i], row_max16(x[i]));
+        f[i] = exp2f(Mreg[i] - nm);
+        Mreg[i] = nm;
+        lsum[i] *= f[i];
+      }
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        const float fh = __builtin_bit_cast(
+            float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, f[h % 4]), 16 * (h / 4)));
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[h][c] *= fh;
+      }
+    }
+    float p[HPL];
+#pragma unroll
+    for (int i = 0; i < HPL; ++i) { p[i] = exp2f(x[i] - Mreg[i]); lsum[i] += p[i]; }
+    if (active) {
+#pragma unroll
+      for (int i = 0; i < HPL; ++i) pbuf[w][tok][4 * blk + i] = p[i];
+    }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const float* pp = &pbuf[w][R * j + vrow][0];
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        const float ph = pp[h];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[h][c] = fmaf(ph, vf[j][c], acc[h][c]);
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+  };
+
+  // deferred score update of the lane's token + store of its new logits
+  auto scores_and_logits = [&](bool valid, const float (&x)[HPL], const float (&lgold)[HPL], float2 accold,
+                               float* lgdst, float2* accdst) {
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < HPL; ++i) {
+      const float po = exp2f(lgold[i] - pm[i]) * pinv[i];
+      s1 += po;
+      s2 = fmaf(po, po, s2);
+    }
+    if (HB > 1) { s1 += __shfl_xor(s1, 16); s2 += __shfl_xor(s2, 16); }
+    if (valid && active) {
+      if (L.has_pending && blk == 0) *accdst = make_float2(accold.x + s1, accold.y + s2);
+      if constexpr (HPL == 4) {
+        *reinterpret_cast<float4*>(lgdst) = make_float4(x[0], x[1], x[2], x[3]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < HPL; ++i) lgdst[i] = x[i];
+      }
+    }
+  };
+
+  // ---------------- Original rows ----------------
+  struct OTile { uint4 kb[KK]; uint4 vr[NV]; float lgold[HPL]; float2 accold; };
+  auto load_o = [&](OTile& t, int row0) {
+    const int rk = min(row0 + tok, bo - 1);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk)
+      t.kb[kk] = *reinterpret_cast<const uint4*>(ok_ + (size_t)rk * D + 32 * kk + 8 * blk);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int rv = min(row0 + R * j + vrow, bo - 1);
+      t.vr[j] = *reinterpret_cast<const uint4*>(ov_ + (size_t)rv * D + sub * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < HPL; ++i) t.lgold[i] = 0.f;
+    t.accold = make_float2(0.f, 0.f);
+    if (L.has_pending && active) {
+      if constexpr (HPL == 4) {
+        const float4 v = *reinterpret_cast<const float4*>(olg + (size_t)rk * G + 4 * blk);
+        t.lgold[0] = v.x; t.lgold[1] = v.y; t.lgold[2] = v.z; t.lgold[3] = v.w;
+      } else {
+#pragma unroll
+        for (int i = 0; i < HPL; ++i) t.lgold[i] = olg[(size_t)rk * G + i];
+      }
+      if (blk == 0) t.accold = oacc[rk];
+    }
+  };
+  auto compute_o = [&](const OTile& t, int row0) {
+    f32x4 C = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) C = mfma16(qa[kk], t.kb[kk], C);
+    const bool valid = row0 + tok < bo;
+    float x[HPL];
+#pragma unroll
+    for (int i = 0; i < HPL; ++i) x[i] = (valid && active) ? C[i] * scale2 : kNegBig;
+    const int rk = min(row0 + tok, bo - 1);
+    scores_and_logits(valid, x, t.lgold, t.accold, olg + (size_t)rk * G + 4 * blk, oacc + rk);
+    float vf[NV][8];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) unpack_bf16x8(t.vr[j], vf[j]);
+    softmax_pv(x, vf);
+  };
+  if (ao < bo) {
+    OTile cur, nxt;
+    int row0 = ao + 16 * w;
+    if (row0 < bo) load_o(cur, row0);
+    for (; row0 < bo; row0 += 64) {
+      const bool more = row0 + 64 < bo;
+      if (more) load_o(nxt, row0 + 64);
+      compute_o(cur, row0);
+      if (more) cur = nxt;
+    }
+  }
+
+  // ---------------- Quantized rows ----------------
+  if (aq < bq) {
     const uint8_t* kc = P.qkc + (size_t)gu * P.capQ * CB;
     const uint8_t* vc = P.qvc + (size_t)gu * P.capQ * CB;
     const uint32_t* km = P.qkm + (size_t)gu * P.capQ * NG;
     const uint32_t* vm = P.qvm + (size_t)gu * P.capQ * NG;
-    for (int r0 = aq; r0 < bq; r0 += TILE) {
-      uint32_t kcr[UNR], vcr[UNR], kmr[UNR], vmr[UNR];
-      bool ok[UNR];
-      int row[UNR];
+    // per head and group: sum of the query over the group's channels (MFMA against an all-ones tile)
+    float qs[KK][HPL];
+    uint4 qp[KK];
+    {
+      const uint4 ones = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
 #pragma unroll
-      for (int u = 0; u < UNR; ++u) {
-        row[u] = r0 + (u * 4 + w) * R + rg;
-        ok[u] = row[u] < bq;
-        const int rr = ok[u] ? row[u] : bq - 1;
-        if (BITS == 4) {
-          kcr[u] = *reinterpret_cast<const uint32_t*>(kc + (size_t)rr * CB + sub * 4);
-          vcr[u] = *reinterpret_cast<const uint32_t*>(vc + (size_t)rr * CB + sub * 4);
+      for (int kk = 0; kk < KK; ++kk) {
+        f32x4 C = {0.f, 0.f, 0.f, 0.f};
+        C = mfma16(qa[kk], ones, C);
+#pragma unroll
+        for (int i = 0; i < HPL; ++i) qs[kk][i] = C[i];
+        qp[kk] = permute_for_codes(qa[kk]);
+      }
+    }
+    struct QTile { uint32_t kcw[KK]; uint32_t kmeta[KK]; uint32_t vcw[NV]; uint32_t vmeta[NV]; float lgold[HPL]; float2 accold; };
+    auto load_q = [&](QTile& t, int row0) {
+      const int rk = min(row0 + tok, bq - 1);
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const uint8_t* p = kc + (size_t)rk * CB + kk * (4 * CW) + blk * CW;
+        t.kcw[kk] = BITS == 4 ? *reinterpret_cast<const uint32_t*>(p) : (uint32_t)*reinterpret_cast<const uint16_t*>(p);
+        t.kmeta[kk] = km[(size_t)rk * NG + kk];
+      }
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        const int rv = min(row0 + R * j + vrow, bq - 1);
+        const uint8_t* p = vc + (size_t)rv * CB + sub * CW;
+        t.vcw[j] = BITS == 4 ? *reinterpret_cast<const uint32_t*>(p) : (uint32_t)*reinterpret_cast<const uint16_t*>(p);
+        t.vmeta[j] = vm[(size_t)rv * NG + sub / 4];
+      }
+#pragma unroll
+      for (int i = 0; i < HPL; ++i) t.lgold[i] = 0.f;
+      t.accold = make_float2(0.f, 0.f);
+      if (L.has_pending && active) {
+        if constexpr (HPL == 4) {
+          const float4 v = *reinterpret_cast<const float4*>(qlg + (size_t)rk * G + 4 * blk);
+          t.lgold[0] = v.x; t.lgold[1] = v.y; t.lgold[2] = v.z; t.lgold[3] = v.w;
         } else {
-          kcr[u] = *reinterpret_cast<const uint16_t*>(kc + (size_t)rr * CB + sub * 2);
-          vcr[u] = *reinterpret_cast<const uint16_t*>(vc + (size_t)rr * CB + sub * 2);
+#pragma unroll
+          for (int i = 0; i < HPL; ++i) t.lgold[i] = qlg[(size_t)rk * G + i];
         }
-        kmr[u] = km[(size_t)rr * NG + sub / 4];
-        vmr[u] = vm[(size_t)rr * NG + sub / 4];
+        if (blk == 0) t.accold = qacc[rk];
       }
-      float kf[UNR][8], vf[UNR][8], lg[UNR][G];
+    };
+    auto compute_q = [&](const QTile& t, int row0) {
+      const bool valid = row0 + tok < bq;
+      float x[HPL];
 #pragma unroll
-      for (int u = 0; u < UNR; ++u) { dequant8<BITS>(kcr[u], kmr[u], kf[u]); dequant8<BITS>(vcr[u], vmr[u], vf[u]); }
-      consume<LPR, G, UNR>(st, qf, kf, vf, ok, scale2, lg);
-      if (sub == 0) {
+      for (int i = 0; i < HPL; ++i) x[i] = 0.f;
 #pragma unroll
-        for (int u = 0; u < UNR; ++u)
-          if (ok[u]) store_logits<G>(qlg + (size_t)row[u] * G, lg[u]);
+      for (int kk = 0; kk < KK; ++kk) {
+        f32x4 C = {0.f, 0.f, 0.f, 0.f};
+        C = mfma16(qp[kk], codes_to_bf16_biased<BITS>(t.kcw[kk]), C);
+        const float sc = half_bits_to_float(t.kmeta[kk]), z = half_bits_to_float(t.kmeta[kk] >> 16);
+#pragma unroll
+        for (int i = 0; i < HPL; ++i) x[i] += fmaf(sc, C[i] - 128.0f * qs[kk][i], z * qs[kk][i]);
       }
+#pragma unroll
+      for (int i = 0; i < HPL; ++i) x[i] = (valid && active) ? x[i] * scale2 : kNegBig;
+      const int rk = min(row0 + tok, bq - 1);
+      scores_and_logits(valid, x, t.lgold, t.accold, qlg + (size_t)rk * G + 4 * blk, qacc + rk);
+      float vf[NV][8];
+#pragma unroll
+      for (int j = 0; j < NV; ++j) dequant8<BITS>(t.vcw[j], t.vmeta[j], vf[j]);
+      softmax_pv(x, vf);
+    };
+    QTile cur, nxt;
+    int row0 = aq + 16 * w;
+    if (row0 < bq) load_q(cur, row0);
+    for (; row0 < bq; row0 += 64) {
+      const bool more = row0 + 64 < bq;
+      if (more) load_q(nxt, row0 + 64);
+      compute_q(cur, row0);
+      if (more) cur = nxt;
     }
   }
 
-  // ---- the token being generated: the last split appends it to the O pool and attends to it
-  if (s == L.splits - 1) {
-    const uint16_t* kn = L.k_new + (size_t)lu * D + sub * 8;
-    const uint16_t* vn = L.v_new + (size_t)lu * D + sub * 8;
-    const uint4 kr = *reinterpret_cast<const uint4*>(kn);
-    const uint4 vr = *reinterpret_cast<const uint4*>(vn);
-    float kf[1][8], vf[1][8], lg[1][G];
-    bool ok[1] = {w == 0 && rg == 0};
-    unpack_bf16x8(kr, kf[0]); unpack_bf16x8(vr, vf[0]);
-    consume<LPR, G, 1>(st, qf, kf, vf, ok, scale2, lg);
-    if (ok[0]) {
-      uint16_t* dk = P.ok + ((size_t)gu * P.capO + cO) * D + sub * 8;
-      uint16_t* dv = P.ov + ((size_t)gu * P.capO + cO) * D + sub * 8;
-      *reinterpret_cast<uint4*>(dk) = kr;
-      *reinterpret_cast<uint4*>(dv) = vr;
-      if (sub == 0) {
-        store_logits<G>(olg + (size_t)cO * G, lg[0]);
-        oacc[cO] = make_float2(0.f, 0.f);
-        P.opos[(size_t)gu * P.capO + cO] = L.position;
+  // ---------------- the token being generated (last split, wave 0) ----------------
+  if (s == L.splits - 1 && w == 0) {
+    const uint16_t* kn = L.k_new + (size_t)lu * D;
+    const uint16_t* vn = L.v_new + (size_t)lu * D;
+    uint4 kb[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) kb[kk] = *reinterpret_cast<const uint4*>(kn + 32 * kk + 8 * blk);
+    const uint4 vr = *reinterpret_cast<const uint4*>(vn + sub * 8);
+    f32x4 C = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) C = mfma16(qa[kk], kb[kk], C);
+    const bool valid = tok == 0;
+    float x[HPL];
+#pragma unroll
+    for (int i = 0; i < HPL; ++i) x[i] = (valid && active) ? C[i] * scale2 : kNegBig;
+    float vf[NV][8];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) unpack_bf16x8(vr, vf[j]);
+    softmax_pv(x, vf);
+    uint16_t* dk = P.ok + ((size_t)gu * P.capO + cO) * D;
+    uint16_t* dv = P.ov + ((size_t)gu * P.capO + cO) * D;
+    if (tok == 0) {
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) *reinterpret_cast<uint4*>(dk + 32 * kk + 8 * blk) = kb[kk];
+      if (active) {
+#pragma unroll
+        for (int i = 0; i < HPL; ++i) olg[(size_t)cO * G + 4 * blk + i] = x[i];
       }
+    }
+    if (vrow == 0) *reinterpret_cast<uint4*>(dv + sub * 8) = vr;
+    if (lane == 0) {
+      oacc[cO] = make_float2(0.f, 0.f);
+      P.opos[(size_t)gu * P.capO + cO] = L.position;
     }
   }
 
-  // ---- reduce the row groups of a wave, then the 4 waves, and write this split's partial
+  // ---------------- reduce within the wave, across the 4 waves, write the partial ----------------
 #pragma unroll
-  for (int stride = LPR; stride < 64; stride <<= 1) {
-    Softmax<G> o;
+  for (int i = 0; i < HPL; ++i) lsum[i] = row_sum16(lsum[i]);
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-      o.m[h] = __shfl_xor(st.m[h], stride);
-      o.l[h] = __shfl_xor(st.l[h], stride);
+  for (int stride = LPR; stride < 64; stride <<= 1)
 #pragma unroll
-      for (int c = 0; c < 8; ++c) o.a[h][c] = __shfl_xor(st.a[h][c], stride);
-    }
-    merge<G>(st, o);
+    for (int h = 0; h < G; ++h)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc[h][c] += __shfl_xor(acc[h][c], stride);
+  if (vrow == 0) {
+#pragma unroll
+    for (int h = 0; h < G; ++h)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) sm_a[w][h][sub * 8 + c] = acc[h][c];
   }
-  __shared__ float sm_a[4][G][D];
-  __shared__ float sm_m[4][G], sm_l[4][G];
-  if (rg == 0) {
+  if (tok == 0 && active) {
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-#pragma unroll
-      for (int c = 0; c < 8; ++c) sm_a[w][h][sub * 8 + c] = st.a[h][c];
-      if (sub == 0) { sm_m[w][h] = st.m[h]; sm_l[w][h] = st.l[h]; }
-    }
+    for (int i = 0; i < HPL; ++i) { sm_m[w][4 * blk + i] = Mreg[i]; sm_l[w][4 * blk + i] = lsum[i]; }
   }
   __syncthreads();
-  float* part = P.part + ((size_t)gu * kMaxSplits + s) * G * (D + 2);
+  float* part = P.part + ((size_t)gu * P.max_splits + s) * G * (D + 2);
   for (int idx = tid; idx < G * D; idx += 256) {
     const int h = idx / D, c = idx % D;
     float M = sm_m[0][h];
@@ -333,39 +523,32 @@ __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) 
     float a = 0.f, l = 0.f;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const float cw = exp2f(sm_m[i][h] - M);
-      a = fmaf(sm_a[i][h][c], cw, a);
-      l = fmaf(sm_l[i][h], cw, l);
+      const float cw_ = exp2f(sm_m[i][h] - M);
+      a = fmaf(sm_a[i][h][c], cw_, a);
+      l = fmaf(sm_l[i][h], cw_, l);
     }
     part[h * (D + 2) + c] = a;
     if (c == 0) { part[h * (D + 2) + D] = M; part[h * (D + 2) + D + 1] = l; }
   }
+
+  // ---------------- the last workgroup of the unit to finish merges the splits ----------------
+  if (!L.fuse_combine) return;
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    const unsigned t = atomicAdd(&P.ticket[gu], 1u);
+    s_last = (t == (unsigned)L.splits - 1u);
+    if (s_last) P.ticket[gu] = 0u;
+  }
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  combine_splits<D, G>(P, L, lu, gu, tid);
 }
 
 template <int D, int G>
 __global__ __launch_bounds__(256) void k_decode_combine(Pools P, DecodeLaunch L) {
-  const int lu = blockIdx.x, gu = L.unit_begin + lu, tid = threadIdx.x;
-  const float* part = P.part + (size_t)gu * kMaxSplits * G * (D + 2);
-  const int S = L.splits;
-  for (int idx = tid; idx < G * D; idx += 256) {
-    const int h = idx / D, c = idx % D;
-    const float* ph = part + h * (D + 2);
-    float M = kNegBig;
-    for (int s = 0; s < S; ++s) M = fmaxf(M, ph[(size_t)s * G * (D + 2) + D]);
-    float a = 0.f, l = 0.f;
-    for (int s = 0; s < S; ++s) {
-      const float* p = ph + (size_t)s * G * (D + 2);
-      const float cw = exp2f(p[D] - M);
-      a = fmaf(p[c], cw, a);
-      l = fmaf(p[D + 1], cw, l);
-    }
-    const float inv = 1.0f / l;
-    const float o = a * inv;
-    P.outf[((size_t)gu * G + h) * D + c] = o;
-    L.out[((size_t)lu * G + h) * D + c] = float_to_bf16_rne(o);
-    if (c == 0) P.fin[(size_t)(L.parity ^ 1) * P.fin_stride + (size_t)gu * G + h] = make_float2(M, inv);
-  }
-  if (tid == 0) P.cnt[gu].x += 1;
+  combine_splits<D, G>(P, L, blockIdx.x, L.unit_begin + blockIdx.x, threadIdx.x);
 }
 
 template <int G>
@@ -388,7 +571,7 @@ static hipError_t launch_decode_t(const Pools& P, const DecodeLaunch& a, hipStre
   if (ev0) (void)hipEventRecord(ev0, s);
   hipLaunchKernelGGL((k_decode_attend<D, G, BITS>), grid, dim3(256), 0, s, P, a);
   if (ev1) (void)hipEventRecord(ev1, s);
-  hipLaunchKernelGGL((k_decode_combine<D, G>), dim3(a.n_units), dim3(256), 0, s, P, a);
+  if (!a.fuse_combine) hipLaunchKernelGGL((k_decode_combine<D, G>), dim3(a.n_units), dim3(256), 0, s, P, a);
   return hipGetLastError();
 }
 

@@ -6,7 +6,7 @@
 namespace arkv {
 
 constexpr int kGroup = 32;        // channels per (scale, zero) pair
-constexpr int kMaxSplits = 32;    // split-K factor of the decode attention, upper bound
+constexpr int kMaxSplits = 128;   // split-K factor of the decode attention, upper bound
 constexpr int kMaxLayersPerLaunch = 64;
 
 // Cache memory of ALL layers.  Every array is [L*U][...] with U = B*H_kv units per layer, so that a
@@ -35,7 +35,9 @@ struct Pools {
   int2*     cnt;        // [LU] (tokens in O pool, tokens in Q pool)
   float2*   fin;        // [2][LU][G] (row max in base-2 units, 1/denominator) of the latest two steps
   size_t    fin_stride; // LU*G
-  float*    part;       // [LU][kMaxSplits][G][D+2] split-K partials: acc[D], max, sum
+  float*    part;       // [LU][max_splits][G][D+2] split-K partials: acc[D], max, sum
+  int       max_splits;
+  uint32_t* ticket;     // [LU] split-K arrival counter, 0 between launches
   float*    outf;       // [LU][G][D] fp32 output of the latest step (parity hook)
   int32_t*  n_o;        // [LU] Original target of the unit's layer/sequence
   // tailor scratch
@@ -61,6 +63,7 @@ struct DecodeLaunch {
   int position;           // P of the token being appended
   int has_pending;        // 1: olg/qlg hold logits of the previous step not yet added to (s1,s2)
   int parity;             // fin[parity] belongs to the previous step; this step writes fin[parity^1]
+  int fuse_combine;       // 1: the last workgroup of a unit merges the splits; 0: separate kernel
   float scale2[kMaxLayersPerLaunch];  // softmax scale * log2(e), per launched layer
 };
 

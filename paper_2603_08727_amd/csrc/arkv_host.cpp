@@ -3,6 +3,7 @@
 // budget formulas (eqs. 6-8), which the paper defines on per-layer scalars.
 #include <math.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -50,6 +51,8 @@ struct arkv_cache {
   int ckeys_layer = -1, ckeys_T = 0;
   hipStream_t last_stream = nullptr;
   // measurement hook: events around the attention kernel
+  int wg_target = 768;      // workgroups per decode launch the split-K factor aims at
+  int fuse_combine = 1;
   bool timing = false;
   std::vector<hipEvent_t> ev_pool;   // pairs, reused after every read
   size_t ev_used = 0;
@@ -190,16 +193,20 @@ int arkv_cache_create(const arkv_config* cfg, arkv_cache** out) {
   const size_t CB = D * P.bits / 8, NG = D / kGroup;
   P.fin_stride = LU * G;
   P.plan_stride = kPlanHdr + 3 * P.capO + 2 * P.capQ;
+  if (const char* e = getenv("ARKV_WG_TARGET")) c->wg_target = std::max(1, atoi(e));
+  if (const char* e = getenv("ARKV_FUSE_COMBINE")) c->fuse_combine = atoi(e) != 0;
+  P.max_splits = std::max(1, std::min(kMaxSplits, (c->wg_target + c->U - 1) / c->U));
 #define A(field, count) if ((rc = dev_alloc(c, &P.field, (count))) != ARKV_OK) { arkv_cache_destroy(c); return rc; }
   A(ok, LU * P.capO * D) A(ov, LU * P.capO * D)
   A(opos, LU * P.capO) A(oacc, LU * P.capO) A(olg, LU * P.capO * G)
   A(qkc, LU * P.capQ * CB) A(qvc, LU * P.capQ * CB)
   A(qkm, LU * P.capQ * NG) A(qvm, LU * P.capQ * NG)
   A(qpos, LU * P.capQ) A(qacc, LU * P.capQ) A(qlg, LU * P.capQ * G)
-  A(cnt, LU) A(fin, 2 * LU * G) A(part, LU * kMaxSplits * G * (D + 2)) A(outf, LU * G * D) A(n_o, LU)
+  A(cnt, LU) A(fin, 2 * LU * G) A(part, LU * (size_t)P.max_splits * G * (D + 2)) A(ticket, LU) A(outf, LU * G * D) A(n_o, LU)
   A(keys, LU * (size_t)(P.capO + P.capQ)) A(thr, LU * 2) A(plan, LU * (size_t)P.plan_stride)
 #undef A
   hipError_t e = hipMemset(P.cnt, 0, LU * sizeof(int2));
+  if (e == hipSuccess) e = hipMemset(P.ticket, 0, LU * sizeof(uint32_t));
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) { arkv_cache_destroy(c); return hip_fail(e, "hipMemset"); }
   *out = c;
@@ -326,9 +333,10 @@ int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const
   a.v_new = static_cast<const uint16_t*>(v_new);
   a.out = static_cast<uint16_t*>(out);
   a.unit_begin = layer_begin * U; a.n_units = n * U; a.units_per_layer = U;
-  int splits = (1024 + a.n_units - 1) / a.n_units;
+  int splits = (c->wg_target + a.n_units / 2) / a.n_units;
   splits = std::min(splits, std::max(1, l0.live / 64));
-  a.splits = std::max(1, std::min(splits, kMaxSplits));
+  a.splits = std::max(1, std::min(splits, c->P.max_splits));
+  a.fuse_combine = c->fuse_combine;
   a.position = l0.P + 1;
   a.has_pending = l0.pending ? 1 : 0;
   a.parity = l0.parity;
