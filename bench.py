@@ -91,6 +91,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="c3_qwen3_8b_32k_b4")
     ap.add_argument("--layers", type=int, default=None, help="override the number of layers (debug)")
+    ap.add_argument("--prefill", type=int, default=None, help="override the prompt length (debug)")
+    ap.add_argument("--budget", type=float, default=None, help="override the budget fraction (debug)")
+    ap.add_argument("--rho", type=float, default=None, help="force every layer's OQ ratio (variant runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=8)
     args = ap.parse_args()
@@ -109,6 +112,10 @@ def main():
     wl = synth.CONFIGS[args.workload]
     if args.layers:
         wl = wl.scaled(n_layers=args.layers)
+    if args.prefill:
+        wl = wl.scaled(prefill=args.prefill)
+    if args.budget:
+        wl = wl.scaled(budget_frac=args.budget)
     L, B, Hq, Hkv, d, T, W = wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.prefill, wl.window
     G, U = wl.group, wl.batch * wl.n_kv_heads
     total_steps = args.warmup + args.steps + args.profile_steps + 8
@@ -138,6 +145,8 @@ def main():
         del k, v, qw
     stats_h = stats.cpu().numpy()
     rho = A.arkv_oq_ratio(stats_h, wl.tau)
+    if args.rho is not None:
+        rho = np.full_like(rho, args.rho)
     # ---- commit ---------------------------------------------------------------------------------
     t_commit = 0.0
     for l in range(L):
@@ -158,11 +167,21 @@ def main():
     out = torch.empty((L, B, Hq, d), dtype=torch.bfloat16, device=dev)
     step_i = 0
 
+    # raw pointers once: the timed loop is one C call per layer with no tensor bookkeeping in between
+    lib = A.load()
+    stream = torch.cuda.current_stream().cuda_stream
+    qs_, ks_, os_ = B * Hq * d * 2, B * Hkv * d * 2, B * Hq * d * 2
+    qp, kp, vp, op = q_all.data_ptr(), kn_all.data_ptr(), vn_all.data_ptr(), out.data_ptr()
+    sc_f = [float(x) for x in scales]
+
     def one_step():
         nonlocal step_i
         t = step_i
         for l in range(L):
-            A.arkv_decode_step(cache, l, q_all[t, l], kn_all[t, l], vn_all[t, l], scales[l], out[l])
+            rc = lib.arkv_decode_step(cache, l, qp + (t * L + l) * qs_, kp + (t * L + l) * ks_,
+                                      vp + (t * L + l) * ks_, sc_f[l], op + l * os_, stream)
+            if rc != 0:
+                raise A.ArkvError(rc, "arkv_decode_step")
         step_i += 1
 
     for _ in range(args.warmup):

@@ -12,7 +12,7 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libarkv.so")
+LIB_PATH = os.environ.get("ARKV_LIBRARY") or os.path.join(_HERE, "libarkv.so")
 
 OK, EINVAL, ESTATE, ENOMEM, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 STATE_ORIGINAL, STATE_QUANTIZED, STATE_EVICTED = 0, 1, 2

@@ -13,7 +13,13 @@
 
 namespace arkv {
 
+#ifndef ARKV_EXP
+#define ARKV_EXP 0
+#endif
 constexpr float kNegBig = -1.0e30f;
+
+// 2^x as one v_exp_f32 (arguments here are bounded above and may be hugely negative -> 0)
+__device__ __forceinline__ float fexp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -71,14 +77,14 @@ __device__ __forceinline__ uint16_t float_to_bf16_rne(float x) {
 // by their bytes (bf16 row = 16 units, packed row = wq units) so that splits stream equal bytes.
 __host__ __device__ inline void split_range(int cO, int cQ, int wq, int S, int s, int& ao, int& bo,
                                             int& aq, int& bq) {
-  const long long tot = 16LL * cO + (long long)wq * cQ;
-  const long long v0 = tot * s / S, v1 = tot * (s + 1) / S;
-  auto mapO = [&](long long v) { long long r = (v + 15) / 16; return (int)(r < cO ? r : cO); };
-  auto mapQ = [&](long long v) {
-    long long w = v - 16LL * cO;
-    if (w <= 0) return 0;
-    long long r = (w + wq - 1) / wq;
-    return (int)(r < cQ ? r : cQ);
+  // 16 cO + wq cQ < 2^19 and S <= 128: everything fits 32 bits
+  const unsigned tot = 16u * (unsigned)cO + (unsigned)wq * (unsigned)cQ;
+  const unsigned v0 = tot * (unsigned)s / (unsigned)S, v1 = tot * (unsigned)(s + 1) / (unsigned)S;
+  auto mapO = [&](unsigned v) { const int r = (int)((v + 15u) / 16u); return r < cO ? r : cO; };
+  auto mapQ = [&](unsigned v) {
+    if (v <= 16u * (unsigned)cO) return 0;
+    const int r = (int)((v - 16u * (unsigned)cO + (unsigned)wq - 1u) / (unsigned)wq);
+    return r < cQ ? r : cQ;
   };
   ao = mapO(v0); bo = mapO(v1); aq = mapQ(v0); bq = mapQ(v1);
 }
@@ -149,18 +155,24 @@ __device__ __forceinline__ void apply_pending(float2* acc, const float* lg, int 
 // Merge of a unit's split-K partials: output row, the step's (max, 1/sum) per head, token count.
 template <int D, int G>
 __device__ __forceinline__ void combine_splits(const Pools& P, const DecodeLaunch& L, int lu, int gu, int tid) {
-  __shared__ float cw[kMaxSplits][G];
+  __shared__ float cm[kMaxSplits][G], cl[kMaxSplits][G], cw[kMaxSplits][G];
   __shared__ float cInv[G];
-  const volatile float* part = P.part + (size_t)gu * P.max_splits * G * (D + 2);
+  const float* part = P.part + (size_t)gu * P.max_splits * G * (D + 2);
   const int S = L.splits;
+  for (int i = tid; i < S * G; i += 256) {
+    const int s = i / G, h = i % G;
+    const float2 ml = *reinterpret_cast<const float2*>(part + ((size_t)s * G + h) * (D + 2) + D);
+    cm[s][h] = ml.x; cl[s][h] = ml.y;
+  }
+  __syncthreads();
   if (tid < G) {
     float M = kNegBig;
-    for (int s = 0; s < S; ++s) M = fmaxf(M, part[((size_t)s * G + tid) * (D + 2) + D]);
+    for (int s = 0; s < S; ++s) M = fmaxf(M, cm[s][tid]);
     float l = 0.f;
     for (int s = 0; s < S; ++s) {
-      const float w_ = exp2f(part[((size_t)s * G + tid) * (D + 2) + D] - M);
+      const float w_ = exp2f(cm[s][tid] - M);
       cw[s][tid] = w_;
-      l = fmaf(part[((size_t)s * G + tid) * (D + 2) + D + 1], w_, l);
+      l = fmaf(cl[s][tid], w_, l);
     }
     cInv[tid] = 1.0f / l;
     P.fin[(size_t)(L.parity ^ 1) * P.fin_stride + (size_t)gu * G + tid] = make_float2(M, 1.0f / l);
@@ -168,14 +180,18 @@ __device__ __forceinline__ void combine_splits(const Pools& P, const DecodeLaunc
   __syncthreads();
   for (int idx = tid; idx < G * D; idx += 256) {
     const int h = idx / D, c = idx % D;
-    float a0 = 0.f, a1 = 0.f;
+    const float* ph = part + (size_t)h * (D + 2) + c;
+    float a[4] = {0.f, 0.f, 0.f, 0.f};
     int s = 0;
-    for (; s + 1 < S; s += 2) {
-      a0 = fmaf(part[((size_t)s * G + h) * (D + 2) + c], cw[s][h], a0);
-      a1 = fmaf(part[((size_t)(s + 1) * G + h) * (D + 2) + c], cw[s + 1][h], a1);
+    for (; s + 4 <= S; s += 4) {
+      float v[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v[j] = ph[(size_t)(s + j) * G * (D + 2)];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) a[j] = fmaf(v[j], cw[s + j][h], a[j]);
     }
-    if (s < S) a0 = fmaf(part[((size_t)s * G + h) * (D + 2) + c], cw[s][h], a0);
-    const float o = (a0 + a1) * cInv[h];
+    for (; s < S; ++s) a[0] = fmaf(ph[(size_t)s * G * (D + 2)], cw[s][h], a[0]);
+    const float o = ((a[0] + a[1]) + (a[2] + a[3])) * cInv[h];
     P.outf[((size_t)gu * G + h) * D + c] = o;
     L.out[((size_t)lu * G + h) * D + c] = float_to_bf16_rne(o);
   }
@@ -192,8 +208,14 @@ __device__ __forceinline__ void combine_splits(const Pools& P, const DecodeLaunc
 // (base-2 units), which is rare, so the accumulators are almost never rescaled.  Packed rows: codes are
 // OR-ed into bf16 "128 + code" operands, one MFMA per quantisation group, and scale / zero / the 128
 // offset are applied to the per-group dot products.
+#ifndef ARKV_WAVES
+#define ARKV_WAVES 2
+#endif
+#ifndef ARKV_PIPE
+#define ARKV_PIPE 2
+#endif
 template <int D, int G, int BITS>
-__global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) {
+__global__ __launch_bounds__(256, ARKV_WAVES) void k_decode_attend(Pools P, DecodeLaunch L) {
   constexpr int KK = D / 32;           // MFMA k-steps = quantisation groups per row
   constexpr int LPR = D / 8;           // lanes per value row
   constexpr int R = 64 / LPR;          // value rows per wave load
@@ -211,7 +233,8 @@ __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) 
   const bool active = blk < HB;
   const float scale2 = L.scale2[lu / L.units_per_layer];
 
-  __shared__ float pbuf[4][16][G < 4 ? 4 : G];
+  __shared__ __align__(16) float pbuf[4][16][G < 4 ? 4 : G];
+  __shared__ __align__(16) float pspare[4][16][4];
   __shared__ float sm_a[4][G][D];
   __shared__ float sm_m[4][G], sm_l[4][G];
   __shared__ int s_last;
@@ -258,7 +281,7 @@ __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) 
     for (int c = 0; c < 8; ++c) acc[h][c] = 0.f;
 
   // logits x[] of this lane's token -> reference-max check, probabilities, PV with the tile's value rows
-  auto softmax_pv = [&](const float (&x)[HPL], const float (&vf)[NV][8]) {
+  auto softmax_pv = [&](bool live, const float (&x)[HPL], const float (&vf)[NV][8]) {
     bool need = false;
 #pragma unroll
     for (int i = 0; i < HPL; ++i) need |= active && (x[i] > Mreg[i] + 8.0f);
@@ -267,7 +290,7 @@ __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) 
 #pragma unroll
       for (int i = 0; i < HPL; ++i) {
         const float nm = fmaxf(Mreg[i], row_max16(x[i]));
-        f[i] = exp2f(Mreg[i] - nm);
+        f[i] = fexp2(Mreg[i] - nm);
         Mreg[i] = nm;
         lsum[i] *= f[i];
       }
@@ -281,15 +304,28 @@ __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) 
     }
     float p[HPL];
 #pragma unroll
-    for (int i = 0; i < HPL; ++i) { p[i] = exp2f(x[i] - Mreg[i]); lsum[i] += p[i]; }
-    if (active) {
+    for (int i = 0; i < HPL; ++i) { p[i] = live ? fexp2(x[i] - Mreg[i]) : 0.f; lsum[i] += p[i]; }
+    {
+      // every lane stores (inactive blocks into a spare copy of the buffer): no branch around the LDS op
+      float* dst = active ? &pbuf[w][tok][4 * blk] : &pspare[w][tok][0];
+      if constexpr (HPL == 4) {
+        *reinterpret_cast<float4*>(dst) = make_float4(p[0], p[1], p[2], p[3]);
+      } else {
 #pragma unroll
-      for (int i = 0; i < HPL; ++i) pbuf[w][tok][4 * blk + i] = p[i];
+        for (int i = 0; i < HPL; ++i) dst[i] = p[i];
+      }
     }
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       const float* pp = &pbuf[w][R * j + vrow][0];
+      if (ARKV_EXP & 1) {
+        float t = 0.f;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) t += vf[j][c];
+        acc[0][j] = fmaf(pp[0], t, acc[0][j]);
+        continue;
+      }
 #pragma unroll
       for (int h = 0; h < G; ++h) {
         const float ph = pp[h];
@@ -306,13 +342,17 @@ __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) 
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int i = 0; i < HPL; ++i) {
-      const float po = exp2f(lgold[i] - pm[i]) * pinv[i];
+      float po = fexp2(lgold[i] - pm[i]) * pinv[i];
+      po = L.has_pending ? po : 0.f;
       s1 += po;
       s2 = fmaf(po, po, s2);
     }
     if (HB > 1) { s1 += __shfl_xor(s1, 16); s2 += __shfl_xor(s2, 16); }
-    if (valid && active) {
-      if (L.has_pending && blk == 0) *accdst = make_float2(accold.x + s1, accold.y + s2);
+    // stores are predicated (loads above are not): a skipped store only makes a later wait count
+    // conservative by one, while a shared dump address would serialise every wave of the GPU on one line
+    const bool own = valid && active;
+    if (own && blk == 0) *accdst = make_float2(accold.x + s1, accold.y + s2);
+    if (own) {
       if constexpr (HPL == 4) {
         *reinterpret_cast<float4*>(lgdst) = make_float4(x[0], x[1], x[2], x[3]);
       } else {
@@ -326,53 +366,76 @@ __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) 
   struct OTile { uint4 kb[KK]; uint4 vr[NV]; float lgold[HPL]; float2 accold; };
   auto load_o = [&](OTile& t, int row0) {
     const int rk = min(row0 + tok, bo - 1);
+    {
+      const unsigned off = (unsigned)rk * (2 * D) + 16 * blk;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk)
-      t.kb[kk] = *reinterpret_cast<const uint4*>(ok_ + (size_t)rk * D + 32 * kk + 8 * blk);
+      for (int kk = 0; kk < KK; ++kk)
+        t.kb[kk] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(ok_) + off + 64 * kk);
+    }
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       const int rv = min(row0 + R * j + vrow, bo - 1);
-      t.vr[j] = *reinterpret_cast<const uint4*>(ov_ + (size_t)rv * D + sub * 8);
+      t.vr[j] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(ov_) + (unsigned)rv * (2 * D) + 16 * sub);
     }
+    if (ARKV_EXP & 2) {
 #pragma unroll
-    for (int i = 0; i < HPL; ++i) t.lgold[i] = 0.f;
-    t.accold = make_float2(0.f, 0.f);
-    if (L.has_pending && active) {
+      for (int i = 0; i < HPL; ++i) t.lgold[i] = 0.f;
+      t.accold = make_float2(0.f, 0.f);
+    } else {
+      const float* lp = reinterpret_cast<const float*>(reinterpret_cast<const char*>(olg) +
+                                                       (unsigned)rk * (4 * G) + (active ? 16 * blk : 0));
       if constexpr (HPL == 4) {
-        const float4 v = *reinterpret_cast<const float4*>(olg + (size_t)rk * G + 4 * blk);
+        const float4 v = *reinterpret_cast<const float4*>(lp);
         t.lgold[0] = v.x; t.lgold[1] = v.y; t.lgold[2] = v.z; t.lgold[3] = v.w;
       } else {
 #pragma unroll
-        for (int i = 0; i < HPL; ++i) t.lgold[i] = olg[(size_t)rk * G + i];
+        for (int i = 0; i < HPL; ++i) t.lgold[i] = lp[i];
       }
-      if (blk == 0) t.accold = oacc[rk];
+      t.accold = *reinterpret_cast<const float2*>(reinterpret_cast<const char*>(oacc) + (unsigned)rk * 8);
     }
   };
   auto compute_o = [&](const OTile& t, int row0) {
     f32x4 C = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) C = mfma16(qa[kk], t.kb[kk], C);
+    for (int kk = 0; kk < KK; ++kk) {
+      if (ARKV_EXP & 4) C[0] += __uint_as_float(t.kb[kk].x & 0x3fu); else C = mfma16(qa[kk], t.kb[kk], C);
+    }
     const bool valid = row0 + tok < bo;
     float x[HPL];
 #pragma unroll
     for (int i = 0; i < HPL; ++i) x[i] = (valid && active) ? C[i] * scale2 : kNegBig;
     const int rk = min(row0 + tok, bo - 1);
-    scores_and_logits(valid, x, t.lgold, t.accold, olg + (size_t)rk * G + 4 * blk, oacc + rk);
+    if (!(ARKV_EXP & 2)) scores_and_logits(valid, x, t.lgold, t.accold, olg + (size_t)rk * G + 4 * blk, oacc + rk);
     float vf[NV][8];
 #pragma unroll
     for (int j = 0; j < NV; ++j) unpack_bf16x8(t.vr[j], vf[j]);
-    softmax_pv(x, vf);
+    softmax_pv(valid && active, x, vf);
   };
   if (ao < bo) {
-    OTile cur, nxt;
-    int row0 = ao + 16 * w;
-    if (row0 < bo) load_o(cur, row0);
-    for (; row0 < bo; row0 += 64) {
-      const bool more = row0 + 64 < bo;
-      if (more) load_o(nxt, row0 + 64);
-      compute_o(cur, row0);
-      if (more) cur = nxt;
+    // two tiles in registers: while one is consumed the other is in flight.  Loads past the end of the
+    // range are clamped to its last row and their tiles contribute nothing.
+#if ARKV_PIPE == 1
+    for (int row0 = ao + 16 * w; row0 < bo; row0 += 64) {
+      OTile ta;
+      load_o(ta, row0);
+      compute_o(ta, row0);
     }
+#else
+    OTile ta, tb;
+    int row0 = ao + 16 * w;
+    load_o(ta, row0);
+    for (; row0 + 128 < bo; row0 += 128) {      // this wave still has two more tiles after this one
+      load_o(tb, row0 + 64);
+      compute_o(ta, row0);
+      load_o(ta, row0 + 128);
+      compute_o(tb, row0 + 64);
+    }
+    if (row0 < bo) {                            // one or two tiles left
+      load_o(tb, row0 + 64);
+      compute_o(ta, row0);
+      if (row0 + 64 < bo) compute_o(tb, row0 + 64);
+    }
+#endif
   }
 
   // ---------------- Quantized rows ----------------
@@ -411,18 +474,16 @@ __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) 
         t.vcw[j] = BITS == 4 ? *reinterpret_cast<const uint32_t*>(p) : (uint32_t)*reinterpret_cast<const uint16_t*>(p);
         t.vmeta[j] = vm[(size_t)rv * NG + sub / 4];
       }
-#pragma unroll
-      for (int i = 0; i < HPL; ++i) t.lgold[i] = 0.f;
-      t.accold = make_float2(0.f, 0.f);
-      if (L.has_pending && active) {
+      {
+        const float* lp = qlg + (size_t)rk * G + (active ? 4 * blk : 0);
         if constexpr (HPL == 4) {
-          const float4 v = *reinterpret_cast<const float4*>(qlg + (size_t)rk * G + 4 * blk);
+          const float4 v = *reinterpret_cast<const float4*>(lp);
           t.lgold[0] = v.x; t.lgold[1] = v.y; t.lgold[2] = v.z; t.lgold[3] = v.w;
         } else {
 #pragma unroll
-          for (int i = 0; i < HPL; ++i) t.lgold[i] = qlg[(size_t)rk * G + i];
+          for (int i = 0; i < HPL; ++i) t.lgold[i] = lp[i];
         }
-        if (blk == 0) t.accold = qacc[rk];
+        t.accold = qacc[rk];
       }
     };
     auto compute_q = [&](const QTile& t, int row0) {
@@ -445,17 +506,30 @@ __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) 
       float vf[NV][8];
 #pragma unroll
       for (int j = 0; j < NV; ++j) dequant8<BITS>(t.vcw[j], t.vmeta[j], vf[j]);
-      softmax_pv(x, vf);
+      softmax_pv(valid && active, x, vf);
     };
-    QTile cur, nxt;
-    int row0 = aq + 16 * w;
-    if (row0 < bq) load_q(cur, row0);
-    for (; row0 < bq; row0 += 64) {
-      const bool more = row0 + 64 < bq;
-      if (more) load_q(nxt, row0 + 64);
-      compute_q(cur, row0);
-      if (more) cur = nxt;
+#if ARKV_PIPE == 1
+    for (int row0 = aq + 16 * w; row0 < bq; row0 += 64) {
+      QTile ta;
+      load_q(ta, row0);
+      compute_q(ta, row0);
     }
+#else
+    QTile ta, tb;
+    int row0 = aq + 16 * w;
+    load_q(ta, row0);
+    for (; row0 + 128 < bq; row0 += 128) {
+      load_q(tb, row0 + 64);
+      compute_q(ta, row0);
+      load_q(ta, row0 + 128);
+      compute_q(tb, row0 + 64);
+    }
+    if (row0 < bq) {
+      load_q(tb, row0 + 64);
+      compute_q(ta, row0);
+      if (row0 + 64 < bq) compute_q(tb, row0 + 64);
+    }
+#endif
   }
 
   // ---------------- the token being generated (last split, wave 0) ----------------
@@ -476,7 +550,7 @@ __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) 
     float vf[NV][8];
 #pragma unroll
     for (int j = 0; j < NV; ++j) unpack_bf16x8(vr, vf[j]);
-    softmax_pv(x, vf);
+    softmax_pv(valid && active, x, vf);
     uint16_t* dk = P.ok + ((size_t)gu * P.capO + cO) * D;
     uint16_t* dv = P.ov + ((size_t)gu * P.capO + cO) * D;
     if (tok == 0) {
@@ -523,7 +597,7 @@ __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) 
     float a = 0.f, l = 0.f;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const float cw_ = exp2f(sm_m[i][h] - M);
+      const float cw_ = fexp2(sm_m[i][h] - M);
       a = fmaf(sm_a[i][h][c], cw_, a);
       l = fmaf(sm_l[i][h], cw_, l);
     }

@@ -51,8 +51,8 @@ struct arkv_cache {
   int ckeys_layer = -1, ckeys_T = 0;
   hipStream_t last_stream = nullptr;
   // measurement hook: events around the attention kernel
-  int wg_target = 768;      // workgroups per decode launch the split-K factor aims at
-  int fuse_combine = 1;
+  int wg_target = 512;      // workgroups per decode launch the split-K factor aims at
+  int fuse_combine = 0;     // the fused merge needs device-scope fences in every workgroup: measured slower
   bool timing = false;
   std::vector<hipEvent_t> ev_pool;   // pairs, reused after every read
   size_t ev_used = 0;
@@ -255,7 +255,9 @@ int arkv_prefill_stats(arkv_cache* c, int32_t layer, const void* q_win, const vo
   int MP = 32;
   while (MP < G * W) MP *= 2;
   if ((rc = grow(&c->rowstat, &c->rowstat_cap, (size_t)U * n_chunks * MP)) != ARKV_OK) return rc;
-  if ((rc = grow(&c->rowc, &c->rowc_cap, (size_t)U * MP)) != ARKV_OK) return rc;
+  // row constants [U][MP] floats (MP even, so what follows is 8-byte aligned) + statistics partials
+  const size_t stat_doubles = 4 * (size_t)c->cfg.batch * ((size_t)(T - W + 2047) / 2048);
+  if ((rc = grow(&c->rowc, &c->rowc_cap, (size_t)U * MP + 2 * stat_doubles)) != ARKV_OK) return rc;
   PrefillLaunch a;
   a.q_win = static_cast<const uint16_t*>(q_win);
   a.k = static_cast<const uint16_t*>(k);

@@ -19,6 +19,9 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr float kNegBigP = -1.0e30f;
 
+// 2^x as one v_exp_f32 (arguments are <= 0 up to rounding, or hugely negative -> 0)
+__device__ __forceinline__ float pexp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 template <int CTRL>
 __device__ __forceinline__ float dpp_p(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL,
@@ -82,28 +85,43 @@ __global__ __launch_bounds__(256) void k_prefill_rows(PrefillLaunch L) {
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) { m[rt] = kNegBigP; l[rt] = 0.f; }
   const int jbeg = chunk * L.chunk, jend = min(jbeg + L.chunk, T);
+  int lastv[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int r = rt * 32 + (lane & 31);
+    lastv[rt] = r < M ? T - L.W + (r % L.W) : -1;   // last visible key of this row
+  }
+  uint4 kf[D / 16], kn[D / 16];
+  if (jbeg + w * 32 < jend) load_keys<D>(kf, k, jbeg + w * 32, T, lane);
   for (int j0 = jbeg + w * 32; j0 < jend; j0 += 128) {
-    uint4 kf[D / 16];
-    load_keys<D>(kf, k, j0, T, lane);
+    load_keys<D>(kn, k, j0 + 128, T, lane);            // next tile of this wave (clamped past the end)
+    const bool full = (j0 + 32 <= T - L.W) && (RT * 32 == M);   // no causal mask, no padded rows
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
       const f32x16 C = tile_logits<D>(kf, sm, rt, lane);
-      const int r = rt * 32 + (lane & 31);
-      const int last = r < M ? T - L.W + (r % L.W) : -1;   // last visible key of this row
       float x[16];
       float mt = kNegBigP;
+      if (full) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int j = j0 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-        x[i] = j <= last ? C[i] * L.scale2 : kNegBigP;
-        mt = fmaxf(mt, x[i]);
+        for (int i = 0; i < 16; ++i) { x[i] = C[i] * L.scale2; mt = fmaxf(mt, x[i]); }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int j = j0 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+          x[i] = j <= lastv[rt] ? C[i] * L.scale2 : kNegBigP;
+          mt = fmaxf(mt, x[i]);
+        }
       }
       const float mn = fmaxf(m[rt], mt);
-      float s = l[rt] * exp2f(m[rt] - mn);
+      float s = l[rt] * pexp2(m[rt] - mn);
+      if (mn > 0.5f * kNegBigP) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) s += x[i] > 0.5f * kNegBigP ? exp2f(x[i] - mn) : 0.f;
+        for (int i = 0; i < 16; ++i) s += pexp2(x[i] - mn);   // masked entries: 2^(-1e30 - mn) = 0
+      }
       m[rt] = mn; l[rt] = s;
     }
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) kf[kk] = kn[kk];
   }
   // merge the two lane halves, then the four waves
   float* red = reinterpret_cast<float*>(sm);   // reuse after everyone is done with the queries
@@ -158,21 +176,35 @@ __global__ __launch_bounds__(256) void k_prefill_cols(PrefillLaunch L, const flo
   }
   const int jbeg = chunk * L.chunk, jend = min(jbeg + L.chunk, T);
   float2* pre = L.pre + (size_t)u * T;
+  float ncr[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) ncr[rt] = -cr[rt];
+  uint4 kf[D / 16], kn[D / 16];
+  if (jbeg + w * 32 < jend) load_keys<D>(kf, k, jbeg + w * 32, T, lane);
   for (int j0 = jbeg + w * 32; j0 < jend; j0 += 128) {
-    uint4 kf[D / 16];
-    load_keys<D>(kf, k, j0, T, lane);
+    load_keys<D>(kn, k, j0 + 128, T, lane);
+    const bool full = (j0 + 32 <= T - L.W) && (RT * 32 == M);
     float a1[16], a2[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) { a1[i] = 0.f; a2[i] = 0.f; }
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
       const f32x16 C = tile_logits<D>(kf, sm, rt, lane);
+      if (full) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int j = j0 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-        const float p = j <= last[rt] ? exp2f(C[i] * L.scale2 - cr[rt]) : 0.f;
-        a1[i] += p;
-        a2[i] = fmaf(p, p, a2[i]);
+        for (int i = 0; i < 16; ++i) {
+          const float p = pexp2(fmaf(C[i], L.scale2, ncr[rt]));
+          a1[i] += p;
+          a2[i] = fmaf(p, p, a2[i]);
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int j = j0 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+          const float p = j <= last[rt] ? pexp2(fmaf(C[i], L.scale2, ncr[rt])) : 0.f;
+          a1[i] += p;
+          a2[i] = fmaf(p, p, a2[i]);
+        }
       }
     }
 #pragma unroll
@@ -184,6 +216,8 @@ __global__ __launch_bounds__(256) void k_prefill_cols(PrefillLaunch L, const flo
         if (j < T) pre[j] = make_float2(a1[i], a2[i]);
       }
     }
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) kf[kk] = kn[kk];
   }
 }
 
@@ -198,21 +232,32 @@ __device__ __forceinline__ double block_sum_d(double v, double* sm) {
   return t;
 }
 
-// One workgroup per sequence: aggregated key distribution over ALL heads and its three statistics.
-__global__ __launch_bounds__(1024) void k_prefill_stats(PrefillLaunch L) {
+// Aggregated key distribution over ALL heads of a sequence and its three statistics, in three small
+// deterministic steps: per-chunk sums of c_j, per-chunk sums of -p ln p, (p - 1/n)^2, (p - 1/n)^4, final.
+constexpr int kStatChunk = 2048;   // keys per workgroup
+
+__global__ __launch_bounds__(256) void k_prefill_stats_z(PrefillLaunch L, double* zpart) {
   __shared__ double sm[16];
-  const int b = blockIdx.x, n = L.T - L.W;
+  const int b = blockIdx.y, ch = blockIdx.x, n = L.T - L.W;
   const float2* pre = L.pre + (size_t)b * L.Hkv * L.T;
+  const int j1 = min(n, (ch + 1) * kStatChunk);
   double z = 0;
-  for (int j = threadIdx.x; j < n; j += 1024) {
-    double c = 0;
-    for (int g = 0; g < L.Hkv; ++g) c += (double)pre[(size_t)g * L.T + j].x;
-    z += c;
-  }
-  const double Z = block_sum_d(z, sm);
+  for (int j = ch * kStatChunk + threadIdx.x; j < j1; j += 256)
+    for (int g = 0; g < L.Hkv; ++g) z += (double)pre[(size_t)g * L.T + j].x;
+  z = block_sum_d(z, sm);
+  if (threadIdx.x == 0) zpart[b * gridDim.x + ch] = z;
+}
+
+__global__ __launch_bounds__(256) void k_prefill_stats_m(PrefillLaunch L, const double* zpart, double* mpart) {
+  __shared__ double sm[16];
+  const int b = blockIdx.y, ch = blockIdx.x, n = L.T - L.W, nch = gridDim.x;
+  const float2* pre = L.pre + (size_t)b * L.Hkv * L.T;
+  double Z = 0;
+  for (int i = 0; i < nch; ++i) Z += zpart[b * nch + i];
   const double pbar = 1.0 / (double)n;
+  const int j1 = min(n, (ch + 1) * kStatChunk);
   double h = 0, m2 = 0, m4 = 0;
-  for (int j = threadIdx.x; j < n; j += 1024) {
+  for (int j = ch * kStatChunk + threadIdx.x; j < j1; j += 256) {
     double c = 0;
     for (int g = 0; g < L.Hkv; ++g) c += (double)pre[(size_t)g * L.T + j].x;
     const double p = c / Z;
@@ -220,14 +265,23 @@ __global__ __launch_bounds__(1024) void k_prefill_stats(PrefillLaunch L) {
     const double d = p - pbar, d2 = d * d;
     m2 += d2; m4 += d2 * d2;
   }
-  h = block_sum_d(h, sm);
-  m2 = block_sum_d(m2, sm) / (double)n;
-  m4 = block_sum_d(m4, sm) / (double)n;
+  h = block_sum_d(h, sm); m2 = block_sum_d(m2, sm); m4 = block_sum_d(m4, sm);
   if (threadIdx.x == 0) {
-    L.stats[b * 3 + 0] = (float)h;
-    L.stats[b * 3 + 1] = (float)m2;
-    L.stats[b * 3 + 2] = m2 > 0 ? (float)(m4 / (m2 * m2)) : 0.f;
+    double* o = mpart + ((size_t)b * nch + ch) * 3;
+    o[0] = h; o[1] = m2; o[2] = m4;
   }
+}
+
+__global__ void k_prefill_stats_final(PrefillLaunch L, const double* mpart, int nch) {
+  const int b = blockIdx.x;
+  if (threadIdx.x != 0) return;
+  const int n = L.T - L.W;
+  double h = 0, m2 = 0, m4 = 0;
+  for (int i = 0; i < nch; ++i) { const double* o = mpart + ((size_t)b * nch + i) * 3; h += o[0]; m2 += o[1]; m4 += o[2]; }
+  m2 /= (double)n; m4 /= (double)n;
+  L.stats[b * 3 + 0] = (float)h;
+  L.stats[b * 3 + 1] = (float)m2;
+  L.stats[b * 3 + 2] = m2 > 0 ? (float)(m4 / (m2 * m2)) : 0.f;
 }
 
 template <int D, int RT>
@@ -246,11 +300,16 @@ static hipError_t launch_prefill_t(const PrefillLaunch& a, float* rowc, hipStrea
   hipLaunchKernelGGL((k_prefill_rows<D, RT>), grid, dim3(256), shm, s, a);
   hipLaunchKernelGGL(k_prefill_rowfinal, dim3(U), dim3(256), 0, s, a, MP, rowc);
   hipLaunchKernelGGL((k_prefill_cols<D, RT>), grid, dim3(256), shm, s, a, (const float*)rowc);
-  hipLaunchKernelGGL(k_prefill_stats, dim3(a.B), dim3(1024), 0, s, a);
+  const int nch = (a.T - a.W + kStatChunk - 1) / kStatChunk;
+  double* zpart = reinterpret_cast<double*>(rowc + (size_t)U * MP);      // [B][nch], then [B][nch][3]
+  double* mpart = zpart + (size_t)a.B * nch;
+  hipLaunchKernelGGL(k_prefill_stats_z, dim3(nch, a.B), dim3(256), 0, s, a, zpart);
+  hipLaunchKernelGGL(k_prefill_stats_m, dim3(nch, a.B), dim3(256), 0, s, a, (const double*)zpart, mpart);
+  hipLaunchKernelGGL(k_prefill_stats_final, dim3(a.B), dim3(64), 0, s, a, (const double*)mpart, nch);
   return hipGetLastError();
 }
 
-// rowc: scratch [U][MP] floats
+// rowc: scratch [U][MP] floats followed by 4*B*ceil((T-W)/2048) doubles for the statistics partials
 hipError_t launch_prefill_stats(const PrefillLaunch& a, float* rowc, hipStream_t s) {
   const int M = a.G * a.W;
   int RT = 1;
