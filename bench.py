@@ -96,6 +96,7 @@ def main():
     ap.add_argument("--rho", type=float, default=None, help="force every layer's OQ ratio (variant runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=8)
+    ap.add_argument("--no-tailor-run", action="store_true", help="skip stepping 4 layers up to their next tailor")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures ONE GPU (units of the cache never interact across GPUs; "
@@ -246,6 +247,49 @@ def main():
         variants["all_layers_one_launch"] = {"steps_per_s_per_layer_batch": round(L * nv / tv, 1),
                                              "achieved_GBps": round(L * step_bytes * nv / tv / 1e9, 1)}
 
+    # ---- practical ceiling: plain streaming read of the same number of bytes per launch ---------------
+    ceiling = None
+    try:
+        big = torch.empty(3 << 30, dtype=torch.uint8, device=dev)
+        bpl = max(32768, int(bytes_per_launch) // 32768 * 32768)
+        us = A.arkv_debug_stream_read(big, bpl, 200)
+        ceiling = {"us_per_launch": round(us, 2), "GBps": round(bpl / (us * 1e-6) / 1e9, 1), "bytes_per_launch": bpl}
+        roofline["frac_of_stream_read_ceiling"] = round(achieved / ceiling["GBps"], 4)
+        del big
+    except Exception as e:  # noqa: BLE001 - the ceiling is informative only
+        ceiling = {"error": str(e)}
+
+    # ---- tailor at its natural cadence: step a few layers until the cache is full -----------------------
+    tailor = None
+    if not args.no_tailor_run:
+        nl = min(L, 4)
+        N = wl.capacity
+        live = A.arkv_cache_progress(cache, 0)[1]
+        # all layers are in the same state; bring the first nl to the step that fills the cache
+        plain_ms, tailor_ms, n_plain = 0.0, 0.0, 0
+        t_idx = step_i
+        while live < N - 1:
+            t = t_idx % total_steps
+            for l in range(nl):
+                lib.arkv_decode_step(cache, l, qp + (t * L + l) * qs_, kp + (t * L + l) * ks_,
+                                     vp + (t * L + l) * ks_, sc_f[l], op + l * os_, stream)
+            live += 1; t_idx += 1
+        torch.cuda.synchronize()
+        t = t_idx % total_steps
+        for l in range(nl):
+            e0, e1 = ev(), ev()
+            e0.record()
+            lib.arkv_decode_step(cache, l, qp + (t * L + l) * qs_, kp + (t * L + l) * ks_,
+                                 vp + (t * L + l) * ks_, sc_f[l], op + l * os_, stream)
+            e1.record()
+            torch.cuda.synchronize()
+            tailor_ms += e0.elapsed_time(e1)
+        fired = all(A.arkv_cache_progress(cache, l)[0] == 2 for l in range(nl))
+        cadence = N - (min(int(np.floor(np.float32(wl.alpha) * (N - W))), N - W - 1) + W)
+        tailor = {"layers_stepped": nl, "fired": bool(fired), "step_with_tailor_us": round(tailor_ms * 1e3 / nl, 1),
+                  "cadence_steps": int(cadence),
+                  "amortised_us_per_step": round((tailor_ms * 1e3 / nl - call_us) / max(cadence, 1), 3)}
+
     result = {
         "metric": "decode steps/sec per layer-batch at 32K ctx", "value": round(value, 1), "unit": "steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -266,6 +310,8 @@ def main():
                     "commit_ms_per_layer": round(t_commit / L, 3),
                     "rho_min_mean_max": [round(float(rho.min()), 3), round(float(rho.mean()), 3), round(float(rho.max()), 3)]},
         "variants": variants,
+        "stream_read_ceiling": ceiling,
+        "tailor": tailor,
     }
     if not args.no_cpu_baseline:
         cb, ref_stats = cpu_baseline(wl, *sample, dq_sample, scales[0], rho[0, 0])

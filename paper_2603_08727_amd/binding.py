@@ -22,7 +22,8 @@ EXPORTED = [
     "arkv_prefill_stats", "arkv_oq_ratio", "arkv_budget_counts", "arkv_prefill_commit",
     "arkv_decode_step", "arkv_decode_step_layers", "arkv_cache_counters", "arkv_cache_export",
     "arkv_debug_last_tailor_scores", "arkv_debug_last_out_f32", "arkv_cache_progress",
-    "arkv_debug_time_attend", "arkv_debug_attend_time", "arkv_strerror", "arkv_last_hip_error",
+    "arkv_debug_time_attend", "arkv_debug_attend_time", "arkv_debug_stream_read", "arkv_strerror",
+    "arkv_last_hip_error",
 ]
 
 
@@ -76,6 +77,7 @@ def load():
         "arkv_cache_progress": (C.c_int, [vp, i32, P(i32), P(i32), P(i32)]),
         "arkv_debug_time_attend": (C.c_int, [vp, i32]),
         "arkv_debug_attend_time": (C.c_int, [vp, P(C.c_double), P(C.c_int64)]),
+        "arkv_debug_stream_read": (C.c_int, [vp, C.c_uint64, C.c_uint64, i32, vp, P(C.c_float)]),
         "arkv_strerror": (C.c_char_p, [C.c_int]),
         "arkv_last_hip_error": (C.c_char_p, []),
     }
@@ -249,3 +251,12 @@ def arkv_debug_attend_time(cache):
     ms, n = C.c_double(), C.c_int64()
     _check(load().arkv_debug_attend_time(cache, C.byref(ms), C.byref(n)), "arkv_debug_attend_time")
     return ms.value, n.value
+
+
+def arkv_debug_stream_read(buf, bytes_per_launch: int, launches: int) -> float:
+    """Average microseconds per launch of a plain streaming read over the GPU tensor `buf`."""
+    us = C.c_float()
+    nbytes = buf.numel() * buf.element_size()
+    _check(load().arkv_debug_stream_read(_dev_ptr(buf), nbytes, bytes_per_launch, launches, _stream(), C.byref(us)),
+           "arkv_debug_stream_read")
+    return us.value

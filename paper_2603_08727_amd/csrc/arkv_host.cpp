@@ -541,6 +541,33 @@ int arkv_debug_attend_time(arkv_cache* c, double* total_ms, int64_t* launches) {
   return ARKV_OK;
 }
 
+int arkv_debug_stream_read(const void* buf, uint64_t buf_bytes, uint64_t bytes_per_launch, int32_t launches,
+                           void* hip_stream, float* avg_us) {
+  if (!buf || !avg_us || launches < 1 || bytes_per_launch == 0 || bytes_per_launch % 32768 != 0 ||
+      bytes_per_launch > buf_bytes)
+    return ARKV_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  unsigned* sink = nullptr;
+  HIP_TRY(hipMalloc(reinterpret_cast<void**>(&sink), 2048 * sizeof(unsigned)));
+  hipEvent_t e0, e1;
+  HIP_TRY(hipEventCreate(&e0));
+  HIP_TRY(hipEventCreate(&e1));
+  const uint64_t windows = buf_bytes / bytes_per_launch;
+  for (int pass = 0; pass < 2; ++pass) {          // pass 0 warms up
+    if (pass == 1) HIP_TRY(hipEventRecord(e0, st));
+    const int n = pass == 0 ? std::min(launches, 8) : launches;
+    for (int i = 0; i < n; ++i)
+      HIP_TRY(launch_stream_read(buf, (size_t)((uint64_t)i % windows) * bytes_per_launch, (size_t)bytes_per_launch, sink, st));
+    if (pass == 1) HIP_TRY(hipEventRecord(e1, st));
+  }
+  HIP_TRY(hipEventSynchronize(e1));
+  float ms = 0.f;
+  HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
+  *avg_us = ms * 1000.0f / (float)launches;
+  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); (void)hipFree(sink);
+  return ARKV_OK;
+}
+
 const char* arkv_strerror(int code) {
   switch (code) {
     case ARKV_OK: return "ok";

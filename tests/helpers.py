@@ -181,20 +181,22 @@ class SideBySide:
                 assert lb[u] <= wl.capacity * 4 * wl.head_dim                      # eq. 1, per unit
                 self.max_err["s1"] = max(self.max_err["s1"], rel_err(ex["s1"][u, :n], ou.s1[order]))
                 self.max_err["s2"] = max(self.max_err["s2"], rel_err(ex["s2"][u, :n], ou.s2[order]))
-                for t_, j in enumerate(order):
-                    p = int(ou.pos[j])
-                    if ou.state[j] == O.STATE_O:
-                        raw = ou.raw[j]
-                        assert np.array_equal(ex["rows_k"][u, t_], bf16_round(raw[0]))
-                        assert np.array_equal(ex["rows_v"][u, t_], bf16_round(raw[1]))
-                    else:
-                        e = ou.q[p]
-                        assert np.array_equal(ex["codes_k"][u, t_], O.pack_codes(e["k_codes"], wl.bits))
-                        assert np.array_equal(ex["codes_v"][u, t_], O.pack_codes(e["v_codes"], wl.bits))
-                        assert np.array_equal(ex["scale_k"][u, t_], e["k_scale"].view(np.uint16))
-                        assert np.array_equal(ex["zero_k"][u, t_], e["k_zero"].view(np.uint16))
-                        assert np.array_equal(ex["scale_v"][u, t_], e["v_scale"].view(np.uint16))
-                        assert np.array_equal(ex["zero_v"][u, t_], e["v_zero"].view(np.uint16))
+                st = ou.state[order]
+                is_o = st == O.STATE_O
+                raw = ou.raw[order]
+                assert np.array_equal(ex["rows_k"][u, :n][is_o], bf16_round(raw[is_o, 0]))      # bf16 rows, bit-exact
+                assert np.array_equal(ex["rows_v"][u, :n][is_o], bf16_round(raw[is_o, 1]))
+                qpos = ou.pos[order][~is_o]
+                if len(qpos):
+                    ent = [ou.q[int(p)] for p in qpos]
+                    for name, key, conv in (("codes_k", "k_codes", lambda e: O.pack_codes(e, wl.bits)),
+                                            ("codes_v", "v_codes", lambda e: O.pack_codes(e, wl.bits)),
+                                            ("scale_k", "k_scale", lambda e: e.view(np.uint16)),
+                                            ("zero_k", "k_zero", lambda e: e.view(np.uint16)),
+                                            ("scale_v", "v_scale", lambda e: e.view(np.uint16)),
+                                            ("zero_v", "v_zero", lambda e: e.view(np.uint16))):
+                        want = np.stack([conv(e[key]) for e in ent])
+                        assert np.array_equal(ex[name][u, :n][~is_o], want), name       # codes / fp16 bits, bit-exact
 
     def assert_within_tol(self, stats=True):
         for k, v in self.max_err.items():

@@ -1,0 +1,39 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times (one
+arkv_decode_step per layer, the configuration's whole batch): prompt scoring, commit with the first
+tailor, and a few decode steps of ONE layer of configurations 2, 3 and 4, every unit compared with
+the oracle (states, codes, scales bit-exact; outputs, scores, statistics at 2e-3)."""
+import numpy as np
+import pytest
+
+from paper_2603_08727_amd import synth
+from helpers import SideBySide
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(wl, steps):
+    sb = SideBySide(wl)
+    try:
+        sb.prefill()
+        sb.commit()
+        sb.decode(steps, check_every=steps)
+        print(wl.name, {k: f"{v:.2e}" for k, v in sb.max_err.items()}, flush=True)
+        sb.assert_within_tol()
+        for oc in sb.oracles.values():
+            assert oc.n_tailors == 1
+            for g in range(wl.n_kv_heads):
+                assert len(oc.units[g].pos) == oc.b + wl.window + steps
+    finally:
+        sb.close()
+
+
+def test_c2_llama3_8k_one_layer():
+    _run(synth.C2.scaled(n_layers=1), steps=4)
+
+
+def test_c3_qwen3_32k_batch4_one_layer():
+    _run(synth.C3.scaled(n_layers=1), steps=3)
+
+
+def test_c4_128k_2bit_one_layer():
+    _run(synth.C4.scaled(n_layers=1), steps=3)
