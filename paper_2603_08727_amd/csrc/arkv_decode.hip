@@ -2,9 +2,9 @@
 //   k_decode_attend : append + split-K attention of one query per head over the bf16 pool and the
 //                     packed low-bit pool (dequantisation inside the QK and PV loops) + the score
 //                     update of the PREVIOUS step (its probabilities need that step's final
-//                     softmax denominator, which only exists after the split-K merge) + the merge
-//                     itself, done by the last workgroup of a unit to finish
-//   k_decode_combine: the merge as a kernel of its own (used when the fused merge is switched off)
+//                     softmax denominator, which only exists after the split-K merge)
+//   k_decode_combine: merge of the split-K partials (a fused "last workgroup merges" variant was
+//                     measured 3-6x slower: it needs a device-scope fence in every workgroup)
 //   k_flush_scores  : adds the pending probabilities to (s1, s2) when something needs them now
 //                     (tailor, export)
 #include <hip/hip_fp16.h>
@@ -13,9 +13,6 @@
 
 namespace arkv {
 
-#ifndef ARKV_EXP
-#define ARKV_EXP 0
-#endif
 constexpr float kNegBig = -1.0e30f;
 
 // 2^x as one v_exp_f32 (arguments here are bounded above and may be hugely negative -> 0)
@@ -208,14 +205,8 @@ __device__ __forceinline__ void combine_splits(const Pools& P, const DecodeLaunc
 // (base-2 units), which is rare, so the accumulators are almost never rescaled.  Packed rows: codes are
 // OR-ed into bf16 "128 + code" operands, one MFMA per quantisation group, and scale / zero / the 128
 // offset are applied to the per-group dot products.
-#ifndef ARKV_WAVES
-#define ARKV_WAVES 2
-#endif
-#ifndef ARKV_PIPE
-#define ARKV_PIPE 2
-#endif
 template <int D, int G, int BITS>
-__global__ __launch_bounds__(256, ARKV_WAVES) void k_decode_attend(Pools P, DecodeLaunch L) {
+__global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) {
   constexpr int KK = D / 32;           // MFMA k-steps = quantisation groups per row
   constexpr int LPR = D / 8;           // lanes per value row
   constexpr int R = 64 / LPR;          // value rows per wave load
@@ -237,29 +228,22 @@ __global__ __launch_bounds__(256, ARKV_WAVES) void k_decode_attend(Pools P, Deco
   __shared__ __align__(16) float pspare[4][16][4];
   __shared__ float sm_a[4][G][D];
   __shared__ float sm_m[4][G], sm_l[4][G];
-  __shared__ int s_last;
 
-  const int2 cnt = P.cnt[gu];
-  const int cO = cnt.x, cQ = cnt.y;
+  int cO, cQ;
+  if (L.cnt_known) { cO = L.cnt_o[lu]; cQ = L.cnt_q[lu]; }
+  else { const int2 cnt = P.cnt[gu]; cO = cnt.x; cQ = cnt.y; }
+
+  // logits of the previous step (read by the score workgroups) and of this step (written here)
+  const float* olg_prev = P.olg + ((size_t)L.parity * P.lg_stride_o + (size_t)gu * P.capO) * G;
+  const float* qlg_prev = P.qlg + ((size_t)L.parity * P.lg_stride_q + (size_t)gu * P.capQ) * G;
+  float* olg = P.olg + ((size_t)(L.parity ^ 1) * P.lg_stride_o + (size_t)gu * P.capO) * G;
+  float* qlg = P.qlg + ((size_t)(L.parity ^ 1) * P.lg_stride_q + (size_t)gu * P.capQ) * G;
+
   int ao, bo, aq, bq;
   split_range(cO, cQ, BITS == 4 ? 5 : 3, L.splits, s, ao, bo, aq, bq);
 
   const uint16_t* ok_ = P.ok + (size_t)gu * P.capO * D;
   const uint16_t* ov_ = P.ov + (size_t)gu * P.capO * D;
-  float* olg = P.olg + (size_t)gu * P.capO * G;
-  float* qlg = P.qlg + (size_t)gu * P.capQ * G;
-  float2* oacc = P.oacc + (size_t)gu * P.capO;
-  float2* qacc = P.qacc + (size_t)gu * P.capQ;
-
-  // previous step's softmax statistics of the heads this lane owns (for the deferred score update)
-  float pm[HPL], pinv[HPL];
-#pragma unroll
-  for (int i = 0; i < HPL; ++i) { pm[i] = 0.f; pinv[i] = 0.f; }
-  if (L.has_pending && active) {
-    const float2* f = P.fin + (size_t)L.parity * P.fin_stride + (size_t)gu * G + 4 * blk;
-#pragma unroll
-    for (int i = 0; i < HPL; ++i) { pm[i] = f[i].x; pinv[i] = f[i].y; }
-  }
 
   // query operand: lane holds head lane%16 (zero beyond G), channels 32kk + 8(lane/16) .. +7
   uint4 qa[KK];
@@ -319,13 +303,6 @@ __global__ __launch_bounds__(256, ARKV_WAVES) void k_decode_attend(Pools P, Deco
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       const float* pp = &pbuf[w][R * j + vrow][0];
-      if (ARKV_EXP & 1) {
-        float t = 0.f;
-#pragma unroll
-        for (int c = 0; c < 8; ++c) t += vf[j][c];
-        acc[0][j] = fmaf(pp[0], t, acc[0][j]);
-        continue;
-      }
 #pragma unroll
       for (int h = 0; h < G; ++h) {
         const float ph = pp[h];
@@ -336,34 +313,34 @@ __global__ __launch_bounds__(256, ARKV_WAVES) void k_decode_attend(Pools P, Deco
     __builtin_amdgcn_wave_barrier();
   };
 
-  // deferred score update of the lane's token + store of its new logits
-  auto scores_and_logits = [&](bool valid, const float (&x)[HPL], const float (&lgold)[HPL], float2 accold,
-                               float* lgdst, float2* accdst) {
-    float s1 = 0.f, s2 = 0.f;
-#pragma unroll
-    for (int i = 0; i < HPL; ++i) {
-      float po = fexp2(lgold[i] - pm[i]) * pinv[i];
-      po = L.has_pending ? po : 0.f;
-      s1 += po;
-      s2 = fmaf(po, po, s2);
-    }
-    if (HB > 1) { s1 += __shfl_xor(s1, 16); s2 += __shfl_xor(s2, 16); }
-    // stores are predicated (loads above are not): a skipped store only makes a later wait count
-    // conservative by one, while a shared dump address would serialise every wave of the GPU on one line
-    const bool own = valid && active;
-    if (own && blk == 0) *accdst = make_float2(accold.x + s1, accold.y + s2);
+  // this step's logits of the lane's token (predicated store: a skipped store only makes a later
+  // wait count conservative by one)
+  auto store_logits = [&](bool own, float* dst, const float (&x)[HPL]) {
     if (own) {
       if constexpr (HPL == 4) {
-        *reinterpret_cast<float4*>(lgdst) = make_float4(x[0], x[1], x[2], x[3]);
+        *reinterpret_cast<float4*>(dst) = make_float4(x[0], x[1], x[2], x[3]);
       } else {
 #pragma unroll
-        for (int i = 0; i < HPL; ++i) lgdst[i] = x[i];
+        for (int i = 0; i < HPL; ++i) dst[i] = x[i];
       }
     }
   };
 
+  // ---------------- deferred score update of the rows this split owns ----------------
+  // One thread per token, fully coalesced; reads the previous step's logits (the other buffer of the
+  // ping-pong) and its final (max, 1/sum).  Called once, right after the first tile's loads are issued.
+  auto score_phase = [&]() {
+    if (!L.has_pending) return;
+    float pm[G], pinv[G];
+    const float2* f = P.fin + (size_t)L.parity * P.fin_stride + (size_t)gu * G;
+#pragma unroll
+    for (int h = 0; h < G; ++h) { pm[h] = f[h].x; pinv[h] = f[h].y; }
+    apply_pending<G>(P.oacc + (size_t)gu * P.capO, olg_prev, ao, bo, pm, pinv, tid, 256);
+    apply_pending<G>(P.qacc + (size_t)gu * P.capQ, qlg_prev, aq, bq, pm, pinv, tid, 256);
+  };
+
   // ---------------- Original rows ----------------
-  struct OTile { uint4 kb[KK]; uint4 vr[NV]; float lgold[HPL]; float2 accold; };
+  struct OTile { uint4 kb[KK]; uint4 vr[NV]; };
   auto load_o = [&](OTile& t, int row0) {
     const int rk = min(row0 + tok, bo - 1);
     {
@@ -377,53 +354,30 @@ __global__ __launch_bounds__(256, ARKV_WAVES) void k_decode_attend(Pools P, Deco
       const int rv = min(row0 + R * j + vrow, bo - 1);
       t.vr[j] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(ov_) + (unsigned)rv * (2 * D) + 16 * sub);
     }
-    if (ARKV_EXP & 2) {
-#pragma unroll
-      for (int i = 0; i < HPL; ++i) t.lgold[i] = 0.f;
-      t.accold = make_float2(0.f, 0.f);
-    } else {
-      const float* lp = reinterpret_cast<const float*>(reinterpret_cast<const char*>(olg) +
-                                                       (unsigned)rk * (4 * G) + (active ? 16 * blk : 0));
-      if constexpr (HPL == 4) {
-        const float4 v = *reinterpret_cast<const float4*>(lp);
-        t.lgold[0] = v.x; t.lgold[1] = v.y; t.lgold[2] = v.z; t.lgold[3] = v.w;
-      } else {
-#pragma unroll
-        for (int i = 0; i < HPL; ++i) t.lgold[i] = lp[i];
-      }
-      t.accold = *reinterpret_cast<const float2*>(reinterpret_cast<const char*>(oacc) + (unsigned)rk * 8);
-    }
   };
   auto compute_o = [&](const OTile& t, int row0) {
     f32x4 C = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      if (ARKV_EXP & 4) C[0] += __uint_as_float(t.kb[kk].x & 0x3fu); else C = mfma16(qa[kk], t.kb[kk], C);
-    }
-    const bool valid = row0 + tok < bo;
+    for (int kk = 0; kk < KK; ++kk) C = mfma16(qa[kk], t.kb[kk], C);
+    const bool own = (row0 + tok < bo) && active;
     float x[HPL];
 #pragma unroll
-    for (int i = 0; i < HPL; ++i) x[i] = (valid && active) ? C[i] * scale2 : kNegBig;
-    const int rk = min(row0 + tok, bo - 1);
-    if (!(ARKV_EXP & 2)) scores_and_logits(valid, x, t.lgold, t.accold, olg + (size_t)rk * G + 4 * blk, oacc + rk);
+    for (int i = 0; i < HPL; ++i) x[i] = own ? C[i] * scale2 : kNegBig;
+    store_logits(own, olg + (unsigned)min(row0 + tok, bo - 1) * G + 4 * blk, x);
     float vf[NV][8];
 #pragma unroll
     for (int j = 0; j < NV; ++j) unpack_bf16x8(t.vr[j], vf[j]);
-    softmax_pv(valid && active, x, vf);
+    softmax_pv(own, x, vf);
   };
+  if (ao >= bo) score_phase();
   if (ao < bo) {
     // two tiles in registers: while one is consumed the other is in flight.  Loads past the end of the
-    // range are clamped to its last row and their tiles contribute nothing.
-#if ARKV_PIPE == 1
-    for (int row0 = ao + 16 * w; row0 < bo; row0 += 64) {
-      OTile ta;
-      load_o(ta, row0);
-      compute_o(ta, row0);
-    }
-#else
+    // range are clamped to its last row; every load in the loop is unconditional so that the wait
+    // counts the compiler derives are exact and a prefetch is never drained early.
     OTile ta, tb;
     int row0 = ao + 16 * w;
     load_o(ta, row0);
+    score_phase();                              // overlaps with the first tile's round trip
     for (; row0 + 128 < bo; row0 += 128) {      // this wave still has two more tiles after this one
       load_o(tb, row0 + 64);
       compute_o(ta, row0);
@@ -435,7 +389,6 @@ __global__ __launch_bounds__(256, ARKV_WAVES) void k_decode_attend(Pools P, Deco
       compute_o(ta, row0);
       if (row0 + 64 < bo) compute_o(tb, row0 + 64);
     }
-#endif
   }
 
   // ---------------- Quantized rows ----------------
@@ -458,36 +411,25 @@ __global__ __launch_bounds__(256, ARKV_WAVES) void k_decode_attend(Pools P, Deco
         qp[kk] = permute_for_codes(qa[kk]);
       }
     }
-    struct QTile { uint32_t kcw[KK]; uint32_t kmeta[KK]; uint32_t vcw[NV]; uint32_t vmeta[NV]; float lgold[HPL]; float2 accold; };
+    struct QTile { uint32_t kcw[KK]; uint32_t kmeta[KK]; uint32_t vcw[NV]; uint32_t vmeta[NV]; };
     auto load_q = [&](QTile& t, int row0) {
       const int rk = min(row0 + tok, bq - 1);
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) {
-        const uint8_t* p = kc + (size_t)rk * CB + kk * (4 * CW) + blk * CW;
+        const uint8_t* p = kc + (unsigned)rk * CB + kk * (4 * CW) + blk * CW;
         t.kcw[kk] = BITS == 4 ? *reinterpret_cast<const uint32_t*>(p) : (uint32_t)*reinterpret_cast<const uint16_t*>(p);
-        t.kmeta[kk] = km[(size_t)rk * NG + kk];
+        t.kmeta[kk] = km[(unsigned)rk * NG + kk];
       }
 #pragma unroll
       for (int j = 0; j < NV; ++j) {
         const int rv = min(row0 + R * j + vrow, bq - 1);
-        const uint8_t* p = vc + (size_t)rv * CB + sub * CW;
+        const uint8_t* p = vc + (unsigned)rv * CB + sub * CW;
         t.vcw[j] = BITS == 4 ? *reinterpret_cast<const uint32_t*>(p) : (uint32_t)*reinterpret_cast<const uint16_t*>(p);
-        t.vmeta[j] = vm[(size_t)rv * NG + sub / 4];
-      }
-      {
-        const float* lp = qlg + (size_t)rk * G + (active ? 4 * blk : 0);
-        if constexpr (HPL == 4) {
-          const float4 v = *reinterpret_cast<const float4*>(lp);
-          t.lgold[0] = v.x; t.lgold[1] = v.y; t.lgold[2] = v.z; t.lgold[3] = v.w;
-        } else {
-#pragma unroll
-          for (int i = 0; i < HPL; ++i) t.lgold[i] = lp[i];
-        }
-        t.accold = qacc[rk];
+        t.vmeta[j] = vm[(unsigned)rv * NG + sub / 4];
       }
     };
     auto compute_q = [&](const QTile& t, int row0) {
-      const bool valid = row0 + tok < bq;
+      const bool own = (row0 + tok < bq) && active;
       float x[HPL];
 #pragma unroll
       for (int i = 0; i < HPL; ++i) x[i] = 0.f;
@@ -500,21 +442,13 @@ __global__ __launch_bounds__(256, ARKV_WAVES) void k_decode_attend(Pools P, Deco
         for (int i = 0; i < HPL; ++i) x[i] += fmaf(sc, C[i] - 128.0f * qs[kk][i], z * qs[kk][i]);
       }
 #pragma unroll
-      for (int i = 0; i < HPL; ++i) x[i] = (valid && active) ? x[i] * scale2 : kNegBig;
-      const int rk = min(row0 + tok, bq - 1);
-      scores_and_logits(valid, x, t.lgold, t.accold, qlg + (size_t)rk * G + 4 * blk, qacc + rk);
+      for (int i = 0; i < HPL; ++i) x[i] = own ? x[i] * scale2 : kNegBig;
+      store_logits(own, qlg + (unsigned)min(row0 + tok, bq - 1) * G + 4 * blk, x);
       float vf[NV][8];
 #pragma unroll
       for (int j = 0; j < NV; ++j) dequant8<BITS>(t.vcw[j], t.vmeta[j], vf[j]);
-      softmax_pv(valid && active, x, vf);
+      softmax_pv(own, x, vf);
     };
-#if ARKV_PIPE == 1
-    for (int row0 = aq + 16 * w; row0 < bq; row0 += 64) {
-      QTile ta;
-      load_q(ta, row0);
-      compute_q(ta, row0);
-    }
-#else
     QTile ta, tb;
     int row0 = aq + 16 * w;
     load_q(ta, row0);
@@ -529,7 +463,6 @@ __global__ __launch_bounds__(256, ARKV_WAVES) void k_decode_attend(Pools P, Deco
       compute_q(ta, row0);
       if (row0 + 64 < bq) compute_q(tb, row0 + 64);
     }
-#endif
   }
 
   // ---------------- the token being generated (last split, wave 0) ----------------
@@ -543,14 +476,14 @@ __global__ __launch_bounds__(256, ARKV_WAVES) void k_decode_attend(Pools P, Deco
     f32x4 C = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) C = mfma16(qa[kk], kb[kk], C);
-    const bool valid = tok == 0;
+    const bool own = (tok == 0) && active;
     float x[HPL];
 #pragma unroll
-    for (int i = 0; i < HPL; ++i) x[i] = (valid && active) ? C[i] * scale2 : kNegBig;
+    for (int i = 0; i < HPL; ++i) x[i] = own ? C[i] * scale2 : kNegBig;
     float vf[NV][8];
 #pragma unroll
     for (int j = 0; j < NV; ++j) unpack_bf16x8(vr, vf[j]);
-    softmax_pv(valid && active, x, vf);
+    softmax_pv(own, x, vf);
     uint16_t* dk = P.ok + ((size_t)gu * P.capO + cO) * D;
     uint16_t* dv = P.ov + ((size_t)gu * P.capO + cO) * D;
     if (tok == 0) {
@@ -563,12 +496,12 @@ __global__ __launch_bounds__(256, ARKV_WAVES) void k_decode_attend(Pools P, Deco
     }
     if (vrow == 0) *reinterpret_cast<uint4*>(dv + sub * 8) = vr;
     if (lane == 0) {
-      oacc[cO] = make_float2(0.f, 0.f);
+      P.oacc[(size_t)gu * P.capO + cO] = make_float2(0.f, 0.f);
       P.opos[(size_t)gu * P.capO + cO] = L.position;
     }
   }
 
-  // ---------------- reduce within the wave, across the 4 waves, write the partial ----------------
+  // ---------------- reduce within the wave, across the 4 waves ----------------
 #pragma unroll
   for (int i = 0; i < HPL; ++i) lsum[i] = row_sum16(lsum[i]);
 #pragma unroll
@@ -588,6 +521,8 @@ __global__ __launch_bounds__(256, ARKV_WAVES) void k_decode_attend(Pools P, Deco
     for (int i = 0; i < HPL; ++i) { sm_m[w][4 * blk + i] = Mreg[i]; sm_l[w][4 * blk + i] = lsum[i]; }
   }
   __syncthreads();
+
+  // ---------------- this split's partial ----------------
   float* part = P.part + ((size_t)gu * P.max_splits + s) * G * (D + 2);
   for (int idx = tid; idx < G * D; idx += 256) {
     const int h = idx / D, c = idx % D;
@@ -604,20 +539,6 @@ __global__ __launch_bounds__(256, ARKV_WAVES) void k_decode_attend(Pools P, Deco
     part[h * (D + 2) + c] = a;
     if (c == 0) { part[h * (D + 2) + D] = M; part[h * (D + 2) + D + 1] = l; }
   }
-
-  // ---------------- the last workgroup of the unit to finish merges the splits ----------------
-  if (!L.fuse_combine) return;
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) {
-    const unsigned t = atomicAdd(&P.ticket[gu], 1u);
-    s_last = (t == (unsigned)L.splits - 1u);
-    if (s_last) P.ticket[gu] = 0u;
-  }
-  __syncthreads();
-  if (!s_last) return;
-  __threadfence();
-  combine_splits<D, G>(P, L, lu, gu, tid);
 }
 
 template <int D, int G>
@@ -634,8 +555,8 @@ __global__ __launch_bounds__(256) void k_flush_scores(Pools P, int unit_begin, i
 #pragma unroll
   for (int h = 0; h < G; ++h) { pm[h] = f[h].x; pinv[h] = f[h].y; }
   const int tid = blockIdx.x * 256 + threadIdx.x, nt = gridDim.x * 256;
-  apply_pending<G>(P.oacc + (size_t)gu * P.capO, P.olg + (size_t)gu * P.capO * G, 0, cnt.x, pm, pinv, tid, nt);
-  apply_pending<G>(P.qacc + (size_t)gu * P.capQ, P.qlg + (size_t)gu * P.capQ * G, 0, cnt.y, pm, pinv, tid, nt);
+  apply_pending<G>(P.oacc + (size_t)gu * P.capO, P.olg + ((size_t)parity * P.lg_stride_o + (size_t)gu * P.capO) * G, 0, cnt.x, pm, pinv, tid, nt);
+  apply_pending<G>(P.qacc + (size_t)gu * P.capQ, P.qlg + ((size_t)parity * P.lg_stride_q + (size_t)gu * P.capQ) * G, 0, cnt.y, pm, pinv, tid, nt);
 }
 
 template <int D, int G, int BITS>
@@ -645,7 +566,7 @@ static hipError_t launch_decode_t(const Pools& P, const DecodeLaunch& a, hipStre
   if (ev0) (void)hipEventRecord(ev0, s);
   hipLaunchKernelGGL((k_decode_attend<D, G, BITS>), grid, dim3(256), 0, s, P, a);
   if (ev1) (void)hipEventRecord(ev1, s);
-  if (!a.fuse_combine) hipLaunchKernelGGL((k_decode_combine<D, G>), dim3(a.n_units), dim3(256), 0, s, P, a);
+  hipLaunchKernelGGL((k_decode_combine<D, G>), dim3(a.n_units), dim3(256), 0, s, P, a);
   return hipGetLastError();
 }
 

@@ -8,6 +8,7 @@ namespace arkv {
 constexpr int kGroup = 32;        // channels per (scale, zero) pair
 constexpr int kMaxSplits = 128;   // split-K factor of the decode attention, upper bound
 constexpr int kMaxLayersPerLaunch = 64;
+constexpr int kMaxUnitsKnown = 64;     // launches with at most this many units can carry host-known token counts
 
 // Cache memory of ALL layers.  Every array is [L*U][...] with U = B*H_kv units per layer, so that a
 // launch over several layers is just a launch over more units.  "O pool": bf16 rows of Original
@@ -22,7 +23,7 @@ struct Pools {
   uint16_t* ov;         // [LU][capO][D] bf16 values
   int32_t*  opos;       // [LU][capO] position of the token in the sequence
   float2*   oacc;       // [LU][capO] (s1, s2): running sums of attention and attention^2 (eq. 9)
-  float*    olg;        // [LU][capO][G] logits of the latest step (base-2 units), pending for oacc
+  float*    olg;        // [2][LU][capO][G] logits of the latest two steps (base-2 units), ping-pong by step parity
   // Q pool
   uint8_t*  qkc;        // [LU][capQ][D*bits/8] key codes, canonical packing
   uint8_t*  qvc;        // [LU][capQ][D*bits/8]
@@ -30,14 +31,14 @@ struct Pools {
   uint32_t* qvm;        // [LU][capQ][D/32]
   int32_t*  qpos;       // [LU][capQ]
   float2*   qacc;       // [LU][capQ]
-  float*    qlg;        // [LU][capQ][G]
+  float*    qlg;        // [2][LU][capQ][G]
+  size_t    lg_stride_o, lg_stride_q;   // LU*capO, LU*capQ (slots between the two logits buffers)
   // per unit
   int2*     cnt;        // [LU] (tokens in O pool, tokens in Q pool)
   float2*   fin;        // [2][LU][G] (row max in base-2 units, 1/denominator) of the latest two steps
   size_t    fin_stride; // LU*G
   float*    part;       // [LU][max_splits][G][D+2] split-K partials: acc[D], max, sum
   int       max_splits;
-  uint32_t* ticket;     // [LU] split-K arrival counter, 0 between launches
   float*    outf;       // [LU][G][D] fp32 output of the latest step (parity hook)
   int32_t*  n_o;        // [LU] Original target of the unit's layer/sequence
   // tailor scratch
@@ -61,9 +62,10 @@ struct DecodeLaunch {
   int units_per_layer;
   int splits;
   int position;           // P of the token being appended
-  int has_pending;        // 1: olg/qlg hold logits of the previous step not yet added to (s1,s2)
-  int parity;             // fin[parity] belongs to the previous step; this step writes fin[parity^1]
-  int fuse_combine;       // 1: the last workgroup of a unit merges the splits; 0: separate kernel
+  int has_pending;        // 1: olg/qlg[parity] hold logits of the previous step not yet added to (s1,s2)
+  int parity;             // fin/olg/qlg[parity] belong to the previous step; this step writes [parity^1]
+  int cnt_known;          // 1: cnt_o / cnt_q below are the units' token counts (saves a dependent load)
+  int cnt_o[kMaxUnitsKnown], cnt_q[kMaxUnitsKnown];
   float scale2[kMaxLayersPerLaunch];  // softmax scale * log2(e), per launched layer
 };
 

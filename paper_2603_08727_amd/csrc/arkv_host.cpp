@@ -36,6 +36,10 @@ struct LayerState {
   float2* pre = nullptr;        // [U][T] window sums from the prefill scorer
   size_t pre_cap = 0;
   std::vector<int32_t> n_o;     // [B] Original target per sequence
+  // host mirror of the units' (Original, Quantized) token counts: exact after a commit and while only
+  // appends happen; a decode-time tailor makes the split data dependent and invalidates it
+  bool cnt_valid = false;
+  std::vector<int32_t> cnt_o, cnt_q;   // [U]
 };
 
 struct arkv_cache {
@@ -52,7 +56,6 @@ struct arkv_cache {
   hipStream_t last_stream = nullptr;
   // measurement hook: events around the attention kernel
   int wg_target = 512;      // workgroups per decode launch the split-K factor aims at
-  int fuse_combine = 0;     // the fused merge needs device-scope fences in every workgroup: measured slower
   bool timing = false;
   std::vector<hipEvent_t> ev_pool;   // pairs, reused after every read
   size_t ev_used = 0;
@@ -180,11 +183,16 @@ int arkv_cache_create(const arkv_config* cfg, arkv_cache** out) {
   c->U = cfg->batch * cfg->n_kv_heads;
   c->b = survivors_b(cfg);
   c->layers.resize((size_t)c->L);
-  for (auto& ls : c->layers) ls.n_o.assign((size_t)cfg->batch, 0);
+  for (auto& ls : c->layers) {
+    ls.n_o.assign((size_t)cfg->batch, 0);
+    ls.cnt_o.assign((size_t)c->U, 0);
+    ls.cnt_q.assign((size_t)c->U, 0);
+  }
   Pools& P = c->P;
   memset(&P, 0, sizeof(P));
   P.U = c->U;
-  P.capO = cfg->capacity_tokens;
+  // 17 spare rows per unit: keeps the units' 2^k-byte regions from landing on the same HBM channels
+  P.capO = cfg->capacity_tokens + 17;
   P.capQ = std::max(c->b, 1);
   P.D = cfg->head_dim;
   P.G = cfg->n_q_heads / cfg->n_kv_heads;
@@ -192,21 +200,21 @@ int arkv_cache_create(const arkv_config* cfg, arkv_cache** out) {
   const size_t LU = (size_t)c->L * c->U, D = (size_t)P.D, G = (size_t)P.G;
   const size_t CB = D * P.bits / 8, NG = D / kGroup;
   P.fin_stride = LU * G;
+  P.lg_stride_o = LU * (size_t)P.capO;
+  P.lg_stride_q = LU * (size_t)P.capQ;
   P.plan_stride = kPlanHdr + 3 * P.capO + 2 * P.capQ;
   if (const char* e = getenv("ARKV_WG_TARGET")) c->wg_target = std::max(1, atoi(e));
-  if (const char* e = getenv("ARKV_FUSE_COMBINE")) c->fuse_combine = atoi(e) != 0;
   P.max_splits = std::max(1, std::min(kMaxSplits, (c->wg_target + c->U - 1) / c->U));
 #define A(field, count) if ((rc = dev_alloc(c, &P.field, (count))) != ARKV_OK) { arkv_cache_destroy(c); return rc; }
   A(ok, LU * P.capO * D) A(ov, LU * P.capO * D)
-  A(opos, LU * P.capO) A(oacc, LU * P.capO) A(olg, LU * P.capO * G)
+  A(opos, LU * P.capO) A(oacc, LU * P.capO) A(olg, 2 * LU * P.capO * G)
   A(qkc, LU * P.capQ * CB) A(qvc, LU * P.capQ * CB)
   A(qkm, LU * P.capQ * NG) A(qvm, LU * P.capQ * NG)
-  A(qpos, LU * P.capQ) A(qacc, LU * P.capQ) A(qlg, LU * P.capQ * G)
-  A(cnt, LU) A(fin, 2 * LU * G) A(part, LU * (size_t)P.max_splits * G * (D + 2)) A(ticket, LU) A(outf, LU * G * D) A(n_o, LU)
+  A(qpos, LU * P.capQ) A(qacc, LU * P.capQ) A(qlg, 2 * LU * P.capQ * G)
+  A(cnt, LU) A(fin, 2 * LU * G) A(part, LU * (size_t)P.max_splits * G * (D + 2)) A(outf, LU * G * D) A(n_o, LU)
   A(keys, LU * (size_t)(P.capO + P.capQ)) A(thr, LU * 2) A(plan, LU * (size_t)P.plan_stride)
 #undef A
   hipError_t e = hipMemset(P.cnt, 0, LU * sizeof(int2));
-  if (e == hipSuccess) e = hipMemset(P.ticket, 0, LU * sizeof(uint32_t));
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) { arkv_cache_destroy(c); return hip_fail(e, "hipMemset"); }
   *out = c;
@@ -232,7 +240,7 @@ int arkv_cache_reset(arkv_cache* c, int32_t layer) {
   for (int l = 0; l < c->L; ++l) {
     if (layer >= 0 && l != layer) continue;
     LayerState& s = c->layers[(size_t)l];
-    s.scored = s.committed = s.pending = false;
+    s.scored = s.committed = s.pending = s.cnt_valid = false;
     s.scored_T = s.T = s.live = s.parity = s.n_tailors = s.last_tailor = 0;
     s.P = -1;
   }
@@ -309,6 +317,18 @@ int arkv_prefill_commit(arkv_cache* c, int32_t layer, const void* k, const void*
   } else {
     ls.live = T; ls.n_tailors = 0; ls.last_tailor = 0;
   }
+  // every prompt token starts Original, so the first tailor's split is known without looking at the data
+  for (int u = 0; u < U; ++u) {
+    if (a.select) {
+      const int nel = T - W, keep = std::min(c->b, nel), no = std::min(no_units[(size_t)u], nel);
+      ls.cnt_o[(size_t)u] = W + no;
+      ls.cnt_q[(size_t)u] = keep - no;
+    } else {
+      ls.cnt_o[(size_t)u] = T;
+      ls.cnt_q[(size_t)u] = 0;
+    }
+  }
+  ls.cnt_valid = true;
   c->last_stream = st;
   return ARKV_OK;
 }
@@ -335,10 +355,22 @@ int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const
   a.v_new = static_cast<const uint16_t*>(v_new);
   a.out = static_cast<uint16_t*>(out);
   a.unit_begin = layer_begin * U; a.n_units = n * U; a.units_per_layer = U;
+  // split-K factor: enough workgroups to fill the chip, at least 64 rows each
   int splits = (c->wg_target + a.n_units / 2) / a.n_units;
   splits = std::min(splits, std::max(1, l0.live / 64));
   a.splits = std::max(1, std::min(splits, c->P.max_splits));
-  a.fuse_combine = c->fuse_combine;
+  a.cnt_known = 0;
+  if (a.n_units <= kMaxUnitsKnown) {
+    bool known = true;
+    for (int i = 0; i < n; ++i) known = known && c->layers[(size_t)(layer_begin + i)].cnt_valid;
+    if (known) {
+      a.cnt_known = 1;
+      for (int i = 0; i < n; ++i) {
+        const LayerState& li = c->layers[(size_t)(layer_begin + i)];
+        for (int u = 0; u < U; ++u) { a.cnt_o[i * U + u] = li.cnt_o[(size_t)u]; a.cnt_q[i * U + u] = li.cnt_q[(size_t)u]; }
+      }
+    }
+  }
   a.position = l0.P + 1;
   a.has_pending = l0.pending ? 1 : 0;
   a.parity = l0.parity;
@@ -371,7 +403,8 @@ int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const
   for (int i = 0; i < n; ++i) {
     LayerState& li = c->layers[(size_t)(layer_begin + i)];
     li.P = P; li.live = live_after; li.parity = parity; li.pending = !tailor;
-    if (tailor) { li.n_tailors += 1; li.last_tailor = 2; }
+    for (auto& v : li.cnt_o) v += 1;
+    if (tailor) { li.n_tailors += 1; li.last_tailor = 2; li.cnt_valid = false; }
   }
   c->last_stream = st;
   return ARKV_OK;
