@@ -70,8 +70,8 @@ __device__ __forceinline__ uint16_t float_to_bf16_rne(float x) {
   return (uint16_t)(u >> 16);
 }
 
-// Rows [ao,bo) of the O pool and [aq,bq) of the Q pool that split s of S owns.  Rows are weighted
-// by their bytes (bf16 row = 16 units, packed row = wq units) so that splits stream equal bytes.
+// Rows [ao,bo) of the O pool and [aq,bq) of the Q pool that split s of S owns.  Rows are weighted by
+// their measured cost (bf16 row = 16 units, packed row = wq units) so that splits take equal time.
 __host__ __device__ inline void split_range(int cO, int cQ, int wq, int S, int s, int& ao, int& bo,
                                             int& aq, int& bq) {
   // 16 cO + wq cQ < 2^19 and S <= 128: everything fits 32 bits
@@ -240,7 +240,7 @@ __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) 
   float* qlg = P.qlg + ((size_t)(L.parity ^ 1) * P.lg_stride_q + (size_t)gu * P.capQ) * G;
 
   int ao, bo, aq, bq;
-  split_range(cO, cQ, BITS == 4 ? 5 : 3, L.splits, s, ao, bo, aq, bq);
+  split_range(cO, cQ, L.wq, L.splits, s, ao, bo, aq, bq);
 
   const uint16_t* ok_ = P.ok + (size_t)gu * P.capO * D;
   const uint16_t* ov_ = P.ov + (size_t)gu * P.capO * D;

@@ -64,6 +64,7 @@ struct DecodeLaunch {
   int position;           // P of the token being appended
   int has_pending;        // 1: olg/qlg[parity] hold logits of the previous step not yet added to (s1,s2)
   int parity;             // fin/olg/qlg[parity] belong to the previous step; this step writes [parity^1]
+  int wq;                 // cost of a packed row in sixteenths of a bf16 row (split balancing)
   int cnt_known;          // 1: cnt_o / cnt_q below are the units' token counts (saves a dependent load)
   int cnt_o[kMaxUnitsKnown], cnt_q[kMaxUnitsKnown];
   float scale2[kMaxLayersPerLaunch];  // softmax scale * log2(e), per launched layer

@@ -56,6 +56,7 @@ struct arkv_cache {
   hipStream_t last_stream = nullptr;
   // measurement hook: events around the attention kernel
   int wg_target = 512;      // workgroups per decode launch the split-K factor aims at
+  int wq = 14;              // measured: a packed row costs nearly as much time as a bf16 row in the attention kernel
   bool timing = false;
   std::vector<hipEvent_t> ev_pool;   // pairs, reused after every read
   size_t ev_used = 0;
@@ -204,6 +205,7 @@ int arkv_cache_create(const arkv_config* cfg, arkv_cache** out) {
   P.lg_stride_q = LU * (size_t)P.capQ;
   P.plan_stride = kPlanHdr + 3 * P.capO + 2 * P.capQ;
   if (const char* e = getenv("ARKV_WG_TARGET")) c->wg_target = std::max(1, atoi(e));
+  if (const char* e = getenv("ARKV_WQ")) c->wq = std::max(1, std::min(16, atoi(e)));
   P.max_splits = std::max(1, std::min(kMaxSplits, (c->wg_target + c->U - 1) / c->U));
 #define A(field, count) if ((rc = dev_alloc(c, &P.field, (count))) != ARKV_OK) { arkv_cache_destroy(c); return rc; }
   A(ok, LU * P.capO * D) A(ov, LU * P.capO * D)
@@ -264,7 +266,7 @@ int arkv_prefill_stats(arkv_cache* c, int32_t layer, const void* q_win, const vo
   while (MP < G * W) MP *= 2;
   if ((rc = grow(&c->rowstat, &c->rowstat_cap, (size_t)U * n_chunks * MP)) != ARKV_OK) return rc;
   // row constants [U][MP] floats (MP even, so what follows is 8-byte aligned) + statistics partials
-  const size_t stat_doubles = 4 * (size_t)c->cfg.batch * ((size_t)(T - W + 2047) / 2048);
+  const size_t stat_doubles = 4 * (size_t)c->cfg.batch * ((size_t)(T - W + 511) / 512);
   if ((rc = grow(&c->rowc, &c->rowc_cap, (size_t)U * MP + 2 * stat_doubles)) != ARKV_OK) return rc;
   PrefillLaunch a;
   a.q_win = static_cast<const uint16_t*>(q_win);
@@ -359,6 +361,7 @@ int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const
   int splits = (c->wg_target + a.n_units / 2) / a.n_units;
   splits = std::min(splits, std::max(1, l0.live / 64));
   a.splits = std::max(1, std::min(splits, c->P.max_splits));
+  a.wq = c->wq;
   a.cnt_known = 0;
   if (a.n_units <= kMaxUnitsKnown) {
     bool known = true;

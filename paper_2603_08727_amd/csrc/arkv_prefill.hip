@@ -144,78 +144,95 @@ __global__ __launch_bounds__(256) void k_prefill_rows(PrefillLaunch L) {
   }
 }
 
-__global__ void k_prefill_rowfinal(PrefillLaunch L, int MP, float* rowc) {
-  const int u = blockIdx.x;
-  for (int r = threadIdx.x; r < MP; r += blockDim.x) {
-    float mn = kNegBigP;
-    for (int c = 0; c < L.n_chunks; ++c) mn = fmaxf(mn, L.rowstat[((size_t)u * L.n_chunks + c) * MP + r].x);
-    float s = 0.f;
-    for (int c = 0; c < L.n_chunks; ++c) {
-      const float2 t = L.rowstat[((size_t)u * L.n_chunks + c) * MP + r];
-      s += t.y * exp2f(t.x - mn);
-    }
-    rowc[(size_t)u * MP + r] = s > 0.f ? mn + log2f(s) : 0.f;
+__global__ __launch_bounds__(256) void k_prefill_rowfinal(PrefillLaunch L, int MP, float* rowc) {
+  // grid (MP/32, U): 32 rows per workgroup, 8 threads per row share the chunks
+  __shared__ float sm_m[32][8], sm_s[32][8];
+  const int u = blockIdx.y, r = blockIdx.x * 32 + (threadIdx.x >> 3), part = threadIdx.x & 7;
+  float mn = kNegBigP;
+  for (int c = part; c < L.n_chunks; c += 8) mn = fmaxf(mn, L.rowstat[((size_t)u * L.n_chunks + c) * MP + r].x);
+  sm_m[threadIdx.x >> 3][part] = mn;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 8; ++i) mn = fmaxf(mn, sm_m[threadIdx.x >> 3][i]);
+  float s = 0.f;
+  for (int c = part; c < L.n_chunks; c += 8) {
+    const float2 t = L.rowstat[((size_t)u * L.n_chunks + c) * MP + r];
+    s += t.y * pexp2(t.x - mn);
+  }
+  sm_s[threadIdx.x >> 3][part] = s;
+  __syncthreads();
+  if (part == 0) {
+    float tot = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) tot += sm_s[threadIdx.x >> 3][i];
+    rowc[(size_t)u * MP + r] = tot > 0.f ? mn + log2f(tot) : 0.f;
   }
 }
 
+// Second pass.  Here the MFMA is turned round (query rows on the M side, keys on the N side) so that a
+// lane owns ONE key and the sums over the M = G*W query rows are in-register additions: C[i] is row
+// rt*32 + 8(i/4) + 4(lane/32) + i%4 against key j0 + lane%32.  The row constants c_r come from LDS.
 template <int D, int RT>
 __global__ __launch_bounds__(256) void k_prefill_cols(PrefillLaunch L, const float* rowc) {
   extern __shared__ __align__(16) unsigned char sm[];
+  constexpr int RB = 2 * D + 16;
   const int chunk = blockIdx.x, u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int M = L.G * L.W, MP = RT * 32, T = L.T;
   stage_q<D>(sm, L.q_win + (size_t)u * M * D, M, MP);
+  float* crow = reinterpret_cast<float*>(sm + (size_t)MP * RB);   // [MP] -c_r (padded rows: +1e30 -> p = 0)
+  int* lastk = reinterpret_cast<int*>(crow + MP);                 // [MP] last visible key of the row
+  for (int r = tid; r < MP; r += 256) {
+    crow[r] = r < M ? -rowc[(size_t)u * MP + r] : kNegBigP;
+    lastk[r] = r < M ? T - L.W + (r % L.W) : -1;
+  }
   __syncthreads();
   const uint16_t* k = L.k + (size_t)u * T * D;
-  float cr[RT];
-  int last[RT];
-#pragma unroll
-  for (int rt = 0; rt < RT; ++rt) {
-    const int r = rt * 32 + (lane & 31);
-    cr[rt] = rowc[(size_t)u * MP + r];
-    last[rt] = r < M ? T - L.W + (r % L.W) : -1;
-  }
   const int jbeg = chunk * L.chunk, jend = min(jbeg + L.chunk, T);
   float2* pre = L.pre + (size_t)u * T;
-  float ncr[RT];
-#pragma unroll
-  for (int rt = 0; rt < RT; ++rt) ncr[rt] = -cr[rt];
+  const int hl = lane >> 5, kl = lane & 31;
   uint4 kf[D / 16], kn[D / 16];
   if (jbeg + w * 32 < jend) load_keys<D>(kf, k, jbeg + w * 32, T, lane);
   for (int j0 = jbeg + w * 32; j0 < jend; j0 += 128) {
     load_keys<D>(kn, k, j0 + 128, T, lane);
-    const bool full = (j0 + 32 <= T - L.W) && (RT * 32 == M);
-    float a1[16], a2[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) { a1[i] = 0.f; a2[i] = 0.f; }
+    const bool full = (j0 + 32 <= T - L.W) && (RT * 32 == M);   // no causal mask, no padded rows
+    const int j = j0 + kl;
+    float a1 = 0.f, a2 = 0.f;
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-      const f32x16 C = tile_logits<D>(kf, sm, rt, lane);
-      if (full) {
+      f32x16 C = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+      const unsigned char* qrow = sm + (size_t)(rt * 32 + kl) * RB + hl * 16;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float p = pexp2(fmaf(C[i], L.scale2, ncr[rt]));
-          a1[i] += p;
-          a2[i] = fmaf(p, p, a2[i]);
-        }
-      } else {
+      for (int kk = 0; kk < D / 16; ++kk) {
+        const uint4 qa = *reinterpret_cast<const uint4*>(qrow + kk * 32);
+        C = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, qa), __builtin_bit_cast(bf16x8, kf[kk]), C, 0, 0, 0);
+      }
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int j = j0 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-          const float p = j <= last[rt] ? pexp2(fmaf(C[i], L.scale2, ncr[rt])) : 0.f;
-          a1[i] += p;
-          a2[i] = fmaf(p, p, a2[i]);
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int r0 = rt * 32 + 8 * g4 + 4 * hl;
+        const float4 nc = *reinterpret_cast<const float4*>(crow + r0);
+        const float ncv[4] = {nc.x, nc.y, nc.z, nc.w};
+        if (full) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float p = pexp2(fmaf(C[4 * g4 + i], L.scale2, ncv[i]));
+            a1 += p;
+            a2 = fmaf(p, p, a2);
+          }
+        } else {
+          const int4 lk = *reinterpret_cast<const int4*>(lastk + r0);
+          const int lkv[4] = {lk.x, lk.y, lk.z, lk.w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float p = j <= lkv[i] ? pexp2(fmaf(C[4 * g4 + i], L.scale2, ncv[i])) : 0.f;
+            a1 += p;
+            a2 = fmaf(p, p, a2);
+          }
         }
       }
     }
-#pragma unroll
-    for (int i = 0; i < 16; ++i) { a1[i] = sum32(a1[i]); a2[i] = sum32(a2[i]); }
-    if ((lane & 31) == 0) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int j = j0 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-        if (j < T) pre[j] = make_float2(a1[i], a2[i]);
-      }
-    }
+    a1 += __shfl_xor(a1, 32);
+    a2 += __shfl_xor(a2, 32);
+    if (hl == 0 && j < T) pre[j] = make_float2(a1, a2);
 #pragma unroll
     for (int kk = 0; kk < D / 16; ++kk) kf[kk] = kn[kk];
   }
@@ -234,7 +251,7 @@ __device__ __forceinline__ double block_sum_d(double v, double* sm) {
 
 // Aggregated key distribution over ALL heads of a sequence and its three statistics, in three small
 // deterministic steps: per-chunk sums of c_j, per-chunk sums of -p ln p, (p - 1/n)^2, (p - 1/n)^4, final.
-constexpr int kStatChunk = 2048;   // keys per workgroup
+constexpr int kStatChunk = 512;    // keys per workgroup
 
 __global__ __launch_bounds__(256) void k_prefill_stats_z(PrefillLaunch L, double* zpart) {
   __shared__ double sm[16];
@@ -288,18 +305,18 @@ template <int D, int RT>
 static hipError_t launch_prefill_t(const PrefillLaunch& a, float* rowc, hipStream_t s) {
   const int U = a.B * a.Hkv, MP = RT * 32;
   const size_t shm = (size_t)MP * (2 * D + 16);
-  if (shm > 64 * 1024) {
+  if (shm + (size_t)MP * 8 > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_prefill_rows<D, RT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_prefill_cols<D, RT>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)(shm + (size_t)MP * 8));
     if (e != hipSuccess) return e;
   }
   dim3 grid(a.n_chunks, U);
   hipLaunchKernelGGL((k_prefill_rows<D, RT>), grid, dim3(256), shm, s, a);
-  hipLaunchKernelGGL(k_prefill_rowfinal, dim3(U), dim3(256), 0, s, a, MP, rowc);
-  hipLaunchKernelGGL((k_prefill_cols<D, RT>), grid, dim3(256), shm, s, a, (const float*)rowc);
+  hipLaunchKernelGGL(k_prefill_rowfinal, dim3(MP / 32, U), dim3(256), 0, s, a, MP, rowc);
+  hipLaunchKernelGGL((k_prefill_cols<D, RT>), grid, dim3(256), shm + (size_t)MP * 8, s, a, (const float*)rowc);
   const int nch = (a.T - a.W + kStatChunk - 1) / kStatChunk;
   double* zpart = reinterpret_cast<double*>(rowc + (size_t)U * MP);      // [B][nch], then [B][nch][3]
   double* mpart = zpart + (size_t)a.B * nch;
@@ -309,7 +326,7 @@ static hipError_t launch_prefill_t(const PrefillLaunch& a, float* rowc, hipStrea
   return hipGetLastError();
 }
 
-// rowc: scratch [U][MP] floats followed by 4*B*ceil((T-W)/2048) doubles for the statistics partials
+// rowc: scratch [U][MP] floats followed by 4*B*ceil((T-W)/512) doubles for the statistics partials
 hipError_t launch_prefill_stats(const PrefillLaunch& a, float* rowc, hipStream_t s) {
   const int M = a.G * a.W;
   int RT = 1;
