@@ -289,12 +289,13 @@ __global__ __launch_bounds__(256) void k_prefill_stats_m(PrefillLaunch L, const 
   }
 }
 
-__global__ void k_prefill_stats_final(PrefillLaunch L, const double* mpart, int nch) {
+__global__ __launch_bounds__(64) void k_prefill_stats_final(PrefillLaunch L, const double* mpart, int nch) {
   const int b = blockIdx.x;
-  if (threadIdx.x != 0) return;
   const int n = L.T - L.W;
   double h = 0, m2 = 0, m4 = 0;
-  for (int i = 0; i < nch; ++i) { const double* o = mpart + ((size_t)b * nch + i) * 3; h += o[0]; m2 += o[1]; m4 += o[2]; }
+  for (int i = threadIdx.x; i < nch; i += 64) { const double* o = mpart + ((size_t)b * nch + i) * 3; h += o[0]; m2 += o[1]; m4 += o[2]; }
+  for (int o = 32; o > 0; o >>= 1) { h += __shfl_xor(h, o); m2 += __shfl_xor(m2, o); m4 += __shfl_xor(m4, o); }
+  if (threadIdx.x != 0) return;
   m2 /= (double)n; m4 /= (double)n;
   L.stats[b * 3 + 0] = (float)h;
   L.stats[b * 3 + 1] = (float)m2;
