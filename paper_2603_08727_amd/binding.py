@@ -77,7 +77,7 @@ def load():
         "arkv_cache_progress": (C.c_int, [vp, i32, P(i32), P(i32), P(i32)]),
         "arkv_debug_time_attend": (C.c_int, [vp, i32]),
         "arkv_debug_attend_time": (C.c_int, [vp, P(C.c_double), P(C.c_int64)]),
-        "arkv_debug_stream_read": (C.c_int, [vp, C.c_uint64, C.c_uint64, i32, vp, P(C.c_float)]),
+        "arkv_debug_stream_read": (C.c_int, [vp, C.c_uint64, C.c_uint64, i32, i32, vp, P(C.c_float)]),
         "arkv_strerror": (C.c_char_p, [C.c_int]),
         "arkv_last_hip_error": (C.c_char_p, []),
     }
@@ -253,10 +253,12 @@ def arkv_debug_attend_time(cache):
     return ms.value, n.value
 
 
-def arkv_debug_stream_read(buf, bytes_per_launch: int, launches: int) -> float:
-    """Average microseconds per launch of a plain streaming read over the GPU tensor `buf`."""
+def arkv_debug_stream_read(buf, bytes_per_launch: int, launches: int, pattern: int = 0) -> float:
+    """Average microseconds per launch of a plain streaming read over the GPU tensor `buf`
+    (pattern 0: coalesced; 1: the attention kernel's key-operand layout)."""
     us = C.c_float()
     nbytes = buf.numel() * buf.element_size()
-    _check(load().arkv_debug_stream_read(_dev_ptr(buf), nbytes, bytes_per_launch, launches, _stream(), C.byref(us)),
+    _check(load().arkv_debug_stream_read(_dev_ptr(buf), nbytes, bytes_per_launch, launches, pattern, _stream(),
+                                         C.byref(us)),
            "arkv_debug_stream_read")
     return us.value

@@ -104,7 +104,7 @@ struct PrefillLaunch {
 
 hipError_t launch_decode(const Pools& P, const DecodeLaunch& a, hipStream_t s, hipEvent_t ev0 = nullptr,
                          hipEvent_t ev1 = nullptr);  // ev0/ev1: recorded around the attention kernel
-hipError_t launch_stream_read(const void* buf, size_t offset_bytes, size_t bytes, unsigned* sink /*[2048]*/, hipStream_t s);
+hipError_t launch_stream_read(const void* buf, size_t offset_bytes, size_t bytes, int pattern, unsigned* sink /*[2048]*/, hipStream_t s);
 hipError_t launch_flush_scores(const Pools& P, int unit_begin, int n_units, int parity, hipStream_t s);
 hipError_t launch_tailor(const Pools& P, const TailorLaunch& a, hipStream_t s);
 hipError_t launch_commit(const Pools& P, const CommitLaunch& a, uint64_t* commit_keys /*[U][T]*/, hipStream_t s);

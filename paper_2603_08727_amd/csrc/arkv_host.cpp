@@ -577,10 +577,10 @@ int arkv_debug_attend_time(arkv_cache* c, double* total_ms, int64_t* launches) {
   return ARKV_OK;
 }
 
-int arkv_debug_stream_read(const void* buf, uint64_t buf_bytes, uint64_t bytes_per_launch, int32_t launches,
-                           void* hip_stream, float* avg_us) {
-  if (!buf || !avg_us || launches < 1 || bytes_per_launch == 0 || bytes_per_launch % 32768 != 0 ||
-      bytes_per_launch > buf_bytes)
+int arkv_debug_stream_read(void* buf, uint64_t buf_bytes, uint64_t bytes_per_launch, int32_t launches,
+                           int32_t pattern, void* hip_stream, float* avg_us) {
+  if (!buf || !avg_us || launches < 1 || bytes_per_launch == 0 || bytes_per_launch % 524288 != 0 ||
+      bytes_per_launch > buf_bytes || pattern < 0 || pattern > 2)
     return ARKV_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   unsigned* sink = nullptr;
@@ -593,7 +593,7 @@ int arkv_debug_stream_read(const void* buf, uint64_t buf_bytes, uint64_t bytes_p
     if (pass == 1) HIP_TRY(hipEventRecord(e0, st));
     const int n = pass == 0 ? std::min(launches, 8) : launches;
     for (int i = 0; i < n; ++i)
-      HIP_TRY(launch_stream_read(buf, (size_t)((uint64_t)i % windows) * bytes_per_launch, (size_t)bytes_per_launch, sink, st));
+      HIP_TRY(launch_stream_read(buf, (size_t)((uint64_t)i % windows) * bytes_per_launch, (size_t)bytes_per_launch, pattern, sink, st));
     if (pass == 1) HIP_TRY(hipEventRecord(e1, st));
   }
   HIP_TRY(hipEventSynchronize(e1));

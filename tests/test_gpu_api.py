@@ -134,7 +134,8 @@ def test_measurement_hooks():
         assert n == wl.decode_steps and 0 < ms < 100
         A.arkv_debug_time_attend(c, False)
         buf = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
-        us = A.arkv_debug_stream_read(buf, 16 << 20, 20)
-        assert 0 < us < 1e4
+        for pattern in (0, 1, 2):
+            us = A.arkv_debug_stream_read(buf, 16 << 20, 20, pattern)
+            assert 0 < us < 1e4
     finally:
         A.arkv_cache_destroy(c)
