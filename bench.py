@@ -45,6 +45,21 @@ def algorithmic_bytes_attend(n_o, n_q, d, G, bits):
     return n_o * c_o + n_q * c_q + 16 * n_live + 2 * G * d * 2 + c_o
 
 
+def stored_traffic(workload):
+    """HBM bytes per launch of the attention kernel from the committed rocprofv3 counter runs
+    (profiles/decode_c3_hbm_counters.txt: FETCH_SIZE and WRITE_SIZE, each scaled by the factor the same
+    counter shows for a copy kernel of known size).  Not measured live: counters need rocprofv3."""
+    if workload != "c3_qwen3_8b_32k_b4":
+        return None
+    try:
+        for line in open(os.path.join(ROOT, "profiles", "decode_c3_hbm_counters.txt")):
+            if line.startswith("traffic_bytes_per_launch"):
+                return int(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(wl, k, v, qw, dq, scale, rho, seconds_budget=25.0):
     """The oracle as it stands on one sequence of one layer: commit + a few decode steps, timed on
     the host; scaled to layer-batch steps per second by the batch size."""
@@ -221,7 +236,7 @@ def main():
     att_us = att_ms * 1e3 / max(att_n, 1)
     achieved = bytes_per_launch / (att_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": "k_decode_attend", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": stored_traffic(wl.name),
                 "avg_kernel_us": round(att_us, 2), "launches_timed": int(att_n),
                 "algorithmic_bytes_per_launch": int(bytes_per_launch),
                 "tokens_per_unit": {"original": round(float(mean_no), 1), "quantized": round(float(mean_nq), 1)}}
