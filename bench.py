@@ -99,6 +99,84 @@ def cpu_baseline(wl, k, v, qw, dq, scale, rho, seconds_budget=25.0):
     }, stats
 
 
+def quick_measure(wl, rho_force=None, steps=24, warmup=4):
+    """Prefill + commit + a short timed decode run of one workload (all its layers); returns steps/s per
+    layer-batch, the attention kernel's average duration and its algorithmic bytes.  Used for the policy
+    and workload variants; the headline run in main() is more thorough."""
+    import numpy as np
+    import torch
+    from paper_2603_08727_amd import binding as A
+    from paper_2603_08727_amd import synth
+    dev = "cuda"
+    L, B, Hq, Hkv, d, T, W = wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.prefill, wl.window
+    G, U = wl.group, wl.batch * wl.n_kv_heads
+    cfg = A.arkv_config_default(n_layers=L, batch=B, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d,
+                                capacity_tokens=wl.capacity, window=W, alpha=wl.alpha, gamma=wl.gamma,
+                                tau=wl.tau, quant_bits=wl.bits)
+    cache = A.arkv_cache_create(cfg)
+    try:
+        scales = [synth.softmax_scale(wl, l) for l in range(L)]
+        stats = torch.zeros((L, B, 3), dtype=torch.float32, device=dev)
+        for l in range(L):
+            k, v, qw = synth.prefill_inputs(wl, l, device=dev)
+            A.arkv_prefill_stats(cache, l, qw, k, T, scales[l], stats[l])
+            del k, v, qw
+        rho = A.arkv_oq_ratio(stats.cpu().numpy(), wl.tau)
+        if rho_force is not None:
+            rho = np.full_like(rho, rho_force)
+        for l in range(L):
+            k, v, qw = synth.prefill_inputs(wl, l, device=dev)
+            A.arkv_prefill_commit(cache, l, k, v, T, rho[l])
+            del k, v, qw
+        total = warmup + 2 * steps
+        per_layer = [synth.decode_inputs(wl, l, total, device=dev) for l in range(L)]
+        q_all = torch.stack([p[0] for p in per_layer], dim=1).contiguous()
+        kn_all = torch.stack([p[1] for p in per_layer], dim=1).contiguous()
+        vn_all = torch.stack([p[2] for p in per_layer], dim=1).contiguous()
+        del per_layer
+        out = torch.empty((L, B, Hq, d), dtype=torch.bfloat16, device=dev)
+        lib = A.load()
+        stream = torch.cuda.current_stream().cuda_stream
+        qs_, ks_, os_ = B * Hq * d * 2, B * Hkv * d * 2, B * Hq * d * 2
+        qp, kp, vp, op = q_all.data_ptr(), kn_all.data_ptr(), vn_all.data_ptr(), out.data_ptr()
+        t_i = 0
+
+        def run(n):
+            nonlocal t_i
+            for _ in range(n):
+                for l in range(L):
+                    rc = lib.arkv_decode_step(cache, l, qp + (t_i * L + l) * qs_, kp + (t_i * L + l) * ks_,
+                                              vp + (t_i * L + l) * ks_, float(scales[l]), op + l * os_, stream)
+                    if rc != 0:
+                        raise A.ArkvError(rc, "arkv_decode_step")
+                t_i += 1
+
+        run(warmup)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(steps)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        no = nq = 0.0
+        for l in range(L):
+            a_, b_, _ = A.arkv_cache_counters(cache, l, U)
+            no += a_.sum(); nq += b_.sum()
+        no /= L * U; nq /= L * U
+        A.arkv_debug_time_attend(cache, True)
+        run(steps)
+        ms, n = A.arkv_debug_attend_time(cache)
+        A.arkv_debug_time_attend(cache, False)
+        bpl = U * algorithmic_bytes_attend(no + steps / 2.0, nq, d, G, wl.bits)
+        us = ms * 1e3 / max(n, 1)
+        return {"steps_per_s_per_layer_batch": round(L * steps / dt, 1), "attend_us": round(us, 2),
+                "algorithmic_MB_per_launch": round(bpl / 1e6, 2), "achieved_GBps": round(bpl / (us * 1e-6) / 1e9, 1),
+                "frac_of_hbm_peak": round(bpl / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                "tokens_per_unit": {"original": round(float(no), 1), "quantized": round(float(nq), 1)},
+                "capacity_tokens": wl.capacity, "context": T, "n_layers": L, "batch": B, "quant_bits": wl.bits}
+    finally:
+        A.arkv_cache_destroy(cache)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -112,6 +190,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=8)
     ap.add_argument("--no-tailor-run", action="store_true", help="skip stepping 4 layers up to their next tailor")
+    ap.add_argument("--no-variants", action="store_true", help="skip the policy / other-workload variant runs")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures ONE GPU (units of the cache never interact across GPUs; "
@@ -331,13 +410,38 @@ def main():
         "stream_read_ceiling": ceiling,
         "tailor": tailor,
     }
+    A.arkv_cache_destroy(cache)
+    cache = None
+    del q_all, kn_all, vn_all
+    torch.cuda.empty_cache()
+    if not args.no_variants:
+        # kernel-level counterpart of the paper's baselines (Sec. V-C) on the same 32K-context shape, 12 layers:
+        # full cache (no limit), evict-only (rho = 1), quantise-all-kept (rho = 0), and a mixed cache (rho = 0.5)
+        base12 = wl.scaled(n_layers=min(L, 12))
+        full = base12.scaled(budget_frac=(T + 128) / T)
+        pol = {
+            "base_full_cache": quick_measure(full),
+            "origin_evict_only_rho1": quick_measure(base12, rho_force=1.0),
+            "quant_all_kept_rho0": quick_measure(base12, rho_force=0.0),
+            "arkv_mixed_rho0.5": quick_measure(base12, rho_force=0.5),
+            "arkv_scored_rho": quick_measure(base12),
+        }
+        ref = pol["base_full_cache"]["steps_per_s_per_layer_batch"]
+        for v_ in pol.values():
+            v_["relative_to_full_cache"] = round(v_["steps_per_s_per_layer_batch"] / ref, 3)
+        result["policies"] = pol
+        # the other decode configurations (8 layers each), same measurement
+        result["other_workloads"] = {
+            "c2_llama3_8b_8k": quick_measure(synth.C2.scaled(n_layers=8)),
+            "c4_llama3_8b_128k_2bit": quick_measure(synth.C4.scaled(n_layers=8)),
+            "c4_shape_all_original_100pct": quick_measure(synth.C4.scaled(n_layers=4, budget_frac=(synth.C4.prefill + 128) / synth.C4.prefill)),
+        }
     if not args.no_cpu_baseline:
         cb, ref_stats = cpu_baseline(wl, *sample, dq_sample, scales[0], rho[0, 0])
         result["cpu_baseline"] = cb
         got = stats_h[0, 0]
         result["prefill"]["stats_rel_err_vs_oracle_layer0_seq0"] = [
             float(abs(got[i] - ref_stats[i]) / max(abs(ref_stats[i]), 1e-300)) for i in range(3)]
-    A.arkv_cache_destroy(cache)
     print(json.dumps(result))
 
 
