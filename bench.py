@@ -99,7 +99,7 @@ def cpu_baseline(wl, k, v, qw, dq, scale, rho, seconds_budget=25.0):
     }, stats
 
 
-def quick_measure(wl, rho_force=None, steps=24, warmup=4):
+def quick_measure(wl, rho_force=None, steps=24, warmup=4, every_step=False):
     """Prefill + commit + a short timed decode run of one workload (all its layers); returns steps/s per
     layer-batch, the attention kernel's average duration and its algorithmic bytes.  Used for the policy
     and workload variants; the headline run in main() is more thorough."""
@@ -112,7 +112,7 @@ def quick_measure(wl, rho_force=None, steps=24, warmup=4):
     G, U = wl.group, wl.batch * wl.n_kv_heads
     cfg = A.arkv_config_default(n_layers=L, batch=B, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d,
                                 capacity_tokens=wl.capacity, window=W, alpha=wl.alpha, gamma=wl.gamma,
-                                tau=wl.tau, quant_bits=wl.bits)
+                                tau=wl.tau, quant_bits=wl.bits, tailor_policy=1 if every_step else 0)
     cache = A.arkv_cache_create(cfg)
     try:
         scales = [synth.softmax_scale(wl, l) for l in range(L)]
@@ -159,7 +159,7 @@ def quick_measure(wl, rho_force=None, steps=24, warmup=4):
         dt = time.perf_counter() - t0
         no = nq = 0.0
         for l in range(L):
-            a_, b_, _ = A.arkv_cache_counters(cache, l, U)
+            a_, b_, _, _ = A.arkv_cache_counters(cache, l, U)
             no += a_.sum(); nq += b_.sum()
         no /= L * U; nq /= L * U
         A.arkv_debug_time_attend(cache, True)
@@ -172,7 +172,8 @@ def quick_measure(wl, rho_force=None, steps=24, warmup=4):
                 "algorithmic_MB_per_launch": round(bpl / 1e6, 2), "achieved_GBps": round(bpl / (us * 1e-6) / 1e9, 1),
                 "frac_of_hbm_peak": round(bpl / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
                 "tokens_per_unit": {"original": round(float(no), 1), "quantized": round(float(nq), 1)},
-                "capacity_tokens": wl.capacity, "context": T, "n_layers": L, "batch": B, "quant_bits": wl.bits}
+                "capacity_tokens": wl.capacity, "context": T, "n_layers": L, "batch": B, "quant_bits": wl.bits,
+                "us_per_call": round(dt / (L * steps) * 1e6, 2), "tailor_every_step": bool(every_step)}
     finally:
         A.arkv_cache_destroy(cache)
 
@@ -284,7 +285,7 @@ def main():
     torch.cuda.synchronize()
     no0 = np.zeros(L); nq0 = np.zeros(L)
     for l in range(L):
-        a_, b_, _ = A.arkv_cache_counters(cache, l, U)
+        a_, b_, _, _ = A.arkv_cache_counters(cache, l, U)
         no0[l], nq0[l] = a_.sum(), b_.sum()
     tailors0 = sum(A.arkv_cache_progress(cache, l)[0] for l in range(L))
     # ---- timed region -----------------------------------------------------------------------------
@@ -302,7 +303,7 @@ def main():
     A.arkv_debug_time_attend(cache, True)
     no_p = np.zeros(L); nq_p = np.zeros(L)
     for l in range(L):
-        a_, b_, _ = A.arkv_cache_counters(cache, l, U)
+        a_, b_, _, _ = A.arkv_cache_counters(cache, l, U)
         no_p[l], nq_p[l] = a_.sum(), b_.sum()
     for _ in range(args.profile_steps):
         one_step()
@@ -425,6 +426,7 @@ def main():
             "quant_all_kept_rho0": quick_measure(base12, rho_force=0.0),
             "arkv_mixed_rho0.5": quick_measure(base12, rho_force=0.5),
             "arkv_scored_rho": quick_measure(base12),
+            "arkv_scored_rho_tailor_every_step": quick_measure(base12.scaled(n_layers=4), every_step=True),
         }
         ref = pol["base_full_cache"]["steps_per_s_per_layer_batch"]
         for v_ in pol.values():

@@ -48,6 +48,9 @@ typedef struct {
   float   tau[3];           /* temperatures of the OQ score (eq. 6); default 7.774, 5.407, 5.528 */
   int32_t quant_bits;       /* bits per channel of a Quantized token: 4 or 2 */
   int32_t group_size;       /* channels per scale/zero pair: 32 */
+  int32_t tailor_policy;    /* 0: tailor when the cache is full, keeping b = floor(alpha (N-W)) tokens (Sec. IV-F,
+                               last paragraph: slack factor); 1: no slack, b = N-W-1, i.e. a tailor at every step once
+                               the cache is full (Sec. IV-F first sentence read literally; stress timing) */
 } arkv_config;
 
 /* Fills *cfg with the paper's tuned hyper-parameters, 4-bit groups of 32, and zero shapes. HOST. */
@@ -86,7 +89,7 @@ int arkv_prefill_stats(arkv_cache* cache, int32_t layer, const void* q_win, cons
 int arkv_oq_ratio(const float* stats, int32_t n_layers, int32_t batch, const float tau[3], float* rho);
 
 /* Token counts a tailor keeps (Alg. 1 "Assign origin budget", eq. 10).  HOST, pure.
- * b = min(floor(alpha (N-W)), N-W-1); n_o = min(floor(rho (N-W)), b); n_q = b - n_o. */
+ * b = min(floor(alpha (N-W)), N-W-1), or N-W-1 under tailor_policy 1; n_o = min(floor(rho (N-W)), b); n_q = b - n_o. */
 int arkv_budget_counts(const arkv_config* cfg, float rho, int32_t* n_o, int32_t* n_q, int32_t* b);
 
 /* Loads one layer's prompt into the cache and fixes the layer's budgets (Alg. 1, prefill phase).
@@ -122,9 +125,10 @@ int arkv_decode_step_layers(arkv_cache* cache, int32_t layer_begin, int32_t n, c
 /* ---- observability and parity hooks: HOST outputs, synchronise the cache's last stream ---- */
 
 /* Per unit of one layer, arrays [B][H_kv]: Original / Quantized token counts and live bytes
- * n_o*4d + n_q*2*(d*bits/8 + 4*d/32) (the left side of eq. 1 for that unit). */
+ * n_o*4d + n_q*2*(d*bits/8 + 4*d/32) (the left side of eq. 1 for that unit), and the number of tokens
+ * evicted so far (positions seen minus live tokens).  Any pointer may be NULL. */
 int arkv_cache_counters(arkv_cache* cache, int32_t layer, int32_t* n_original, int32_t* n_quantized,
-                        int64_t* live_bytes);
+                        int32_t* n_evicted, int64_t* live_bytes);
 
 /* Contents of one layer, per unit, tokens sorted by position.  max_tokens >= N.  Any output pointer
  * may be NULL.  n_live [U]; pos, state [U][max_tokens]; s1, s2 [U][max_tokens] running sums of

@@ -149,15 +149,18 @@ def oq_ratio(q):
     return q / mx
 
 
-def budget_counts(rho, N, W, alpha=PAPER_ALPHA):
+def budget_counts(rho, N, W, alpha=PAPER_ALPHA, every_step=False):
     """Token counts kept by a tailor (Alg. 1 'Assign origin budget', eq. 10).
 
     N = cache limit in tokens, same for every layer.  b = floor(alpha*(N-W))
     tokens survive outside the window (clamped to N-W-1 so that a tailor always
     frees a slot); of these n_o = min(floor(rho*(N-W)), b) are targeted
-    Original and n_q = b - n_o Quantized.  Returns (n_o, n_q, b).
+    Original and n_q = b - n_o Quantized.  every_step=True is the literal
+    'at each step' reading of Sec. IV-F with no slack: the cache is kept full,
+    b = N-W-1, so exactly one slot is freed and the tailor runs at every step.
+    Returns (n_o, n_q, b).
     """
-    b = int(np.floor(alpha * (N - W)))
+    b = N - W - 1 if every_step else int(np.floor(alpha * (N - W)))
     b = max(0, min(b, N - W - 1))
     n_o = min(int(np.floor(float(rho) * (N - W))), b)
     return n_o, b - n_o, b
@@ -334,7 +337,8 @@ class SequenceCacheOracle:
     """
 
     def __init__(self, n_q_heads, n_kv_heads, head_dim, N, W=PAPER_W, alpha=PAPER_ALPHA,
-                 gamma=PAPER_GAMMA, bits=4):
+                 gamma=PAPER_GAMMA, bits=4, every_step=False):
+        self.every_step = every_step
         self.Hq, self.Hkv, self.d = n_q_heads, n_kv_heads, head_dim
         self.G = n_q_heads // n_kv_heads
         self.N, self.W, self.alpha, self.gamma, self.bits = N, W, alpha, gamma, bits
@@ -353,7 +357,7 @@ class SequenceCacheOracle:
         k = np.asarray(k, dtype=np.float32); v = np.asarray(v, dtype=np.float32)
         T = k.shape[1]
         self.T, self.P = T, T - 1
-        self.n_o, self.n_q, self.b = budget_counts(rho, self.N, self.W, self.alpha)
+        self.n_o, self.n_q, self.b = budget_counts(rho, self.N, self.W, self.alpha, self.every_step)
         for g, u in enumerate(self.units):
             u.pos = np.arange(T, dtype=np.int64)
             u.state = np.zeros(T, dtype=np.int8)

@@ -32,7 +32,7 @@ class arkv_config(C.Structure):
         ("n_layers", C.c_int32), ("batch", C.c_int32), ("n_q_heads", C.c_int32),
         ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("capacity_tokens", C.c_int32),
         ("window", C.c_int32), ("alpha", C.c_float), ("gamma", C.c_float), ("tau", C.c_float * 3),
-        ("quant_bits", C.c_int32), ("group_size", C.c_int32),
+        ("quant_bits", C.c_int32), ("group_size", C.c_int32), ("tailor_policy", C.c_int32),
     ]
 
 
@@ -70,7 +70,7 @@ def load():
         "arkv_prefill_commit": (C.c_int, [vp, i32, vp, vp, i32, vp, vp]),
         "arkv_decode_step": (C.c_int, [vp, i32, vp, vp, vp, f32, vp, vp]),
         "arkv_decode_step_layers": (C.c_int, [vp, i32, i32, vp, vp, vp, vp, vp, vp]),
-        "arkv_cache_counters": (C.c_int, [vp, i32, vp, vp, vp]),
+        "arkv_cache_counters": (C.c_int, [vp, i32, vp, vp, vp, vp]),
         "arkv_cache_export": (C.c_int, [vp, i32, i32] + [vp] * 13),
         "arkv_debug_last_tailor_scores": (C.c_int, [vp, i32, i32, vp, vp, vp]),
         "arkv_debug_last_out_f32": (C.c_int, [vp, i32, vp]),
@@ -194,9 +194,10 @@ def arkv_decode_step_layers(cache, layer_begin, n, q, k_new, v_new, softmax_scal
 
 def arkv_cache_counters(cache, layer, n_units):
     no = np.empty(n_units, dtype=np.int32); nq = np.empty(n_units, dtype=np.int32)
-    lb = np.empty(n_units, dtype=np.int64)
-    _check(load().arkv_cache_counters(cache, layer, _np_ptr(no), _np_ptr(nq), _np_ptr(lb)), "arkv_cache_counters")
-    return no, nq, lb
+    ne = np.empty(n_units, dtype=np.int32); lb = np.empty(n_units, dtype=np.int64)
+    _check(load().arkv_cache_counters(cache, layer, _np_ptr(no), _np_ptr(nq), _np_ptr(ne), _np_ptr(lb)),
+           "arkv_cache_counters")
+    return no, nq, ne, lb
 
 
 def arkv_cache_progress(cache, layer):

@@ -72,6 +72,7 @@ static int validate(const arkv_config* c) {
   for (int i = 0; i < 3; ++i)
     if (!(c->tau[i] > 0.0f)) return ARKV_EINVAL;
   if (c->group_size != kGroup) return ARKV_EINVAL;
+  if (c->tailor_policy != 0 && c->tailor_policy != 1) return ARKV_EINVAL;
   const int G = c->n_q_heads / c->n_kv_heads;
   if (c->head_dim != 64 && c->head_dim != 128) return ARKV_EUNSUPPORTED;
   if (G != 1 && G != 2 && G != 4 && G != 8) return ARKV_EUNSUPPORTED;
@@ -82,7 +83,7 @@ static int validate(const arkv_config* c) {
 
 static int survivors_b(const arkv_config* c) {
   const int nw = c->capacity_tokens - c->window;
-  int b = (int)floor((double)c->alpha * (double)nw);
+  int b = c->tailor_policy == 1 ? nw - 1 : (int)floor((double)c->alpha * (double)nw);
   b = std::min(b, nw - 1);
   return std::max(b, 0);
 }
@@ -421,7 +422,7 @@ int arkv_decode_step(arkv_cache* c, int32_t layer, const void* q, const void* k_
 // ---- observability ---------------------------------------------------------------------------
 
 int arkv_cache_counters(arkv_cache* c, int32_t layer, int32_t* n_original, int32_t* n_quantized,
-                        int64_t* live_bytes) {
+                        int32_t* n_evicted, int64_t* live_bytes) {
   if (!c || layer < 0 || layer >= c->L) return ARKV_EINVAL;
   if (!c->layers[(size_t)layer].committed) return ARKV_ESTATE;
   HIP_TRY(hipStreamSynchronize(c->last_stream));
@@ -432,6 +433,7 @@ int arkv_cache_counters(arkv_cache* c, int32_t layer, int32_t* n_original, int32
   for (int u = 0; u < c->U; ++u) {
     if (n_original) n_original[u] = cnt[(size_t)u].x;
     if (n_quantized) n_quantized[u] = cnt[(size_t)u].y;
+    if (n_evicted) n_evicted[u] = c->layers[(size_t)layer].P + 1 - cnt[(size_t)u].x - cnt[(size_t)u].y;
     if (live_bytes) live_bytes[u] = cnt[(size_t)u].x * co + cnt[(size_t)u].y * cq;
   }
   return ARKV_OK;

@@ -27,11 +27,11 @@ def bf16_round(x32: np.ndarray) -> np.ndarray:
     return (u >> 16).astype(np.uint16)
 
 
-def make_cfg(wl: synth.Workload):
+def make_cfg(wl: synth.Workload, every_step=False):
     return A.arkv_config_default(
         n_layers=wl.n_layers, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
         head_dim=wl.head_dim, capacity_tokens=wl.capacity, window=wl.window, alpha=wl.alpha,
-        gamma=wl.gamma, tau=wl.tau, quant_bits=wl.bits)
+        gamma=wl.gamma, tau=wl.tau, quant_bits=wl.bits, tailor_policy=1 if every_step else 0)
 
 
 class SideBySide:
@@ -39,10 +39,12 @@ class SideBySide:
     GPU ran a tailor, the oracle's tailor of the same step ranks on the GPU's fp32 scores, so that
     states / codes / scales can be compared bit for bit; everything floating point is compared at TOL."""
 
-    def __init__(self, wl: synth.Workload, rho_override=None, device="cuda"):
+    def __init__(self, wl: synth.Workload, rho_override=None, device="cuda", every_step=False, lockstep=True):
         self.wl = wl
         self.dev = device
-        self.cfg = make_cfg(wl)
+        self.every_step = every_step
+        self.lockstep = lockstep       # False: the oracle ranks on its own fp64 scores (free-running protocol)
+        self.cfg = make_cfg(wl, every_step)
         self.cache = A.arkv_cache_create(self.cfg)
         self.U = wl.batch * wl.n_kv_heads
         self.rho_override = rho_override
@@ -94,12 +96,13 @@ class SideBySide:
             for b in range(wl.batch):
                 oc = O.SequenceCacheOracle(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.capacity, W=wl.window,
                                            alpha=float(np.float32(wl.alpha)), gamma=float(np.float32(wl.gamma)),
-                                           bits=wl.bits)
+                                           bits=wl.bits, every_step=self.every_step)
                 s1, s2 = self.ref_acc[(l, b)]
                 if over is not None:
                     self._check_scores(oc, l, b, over, commit=(s1, s2))
                 oc.commit(synth.to_numpy_f32(k[b]), synth.to_numpy_f32(v[b]), s1, s2, float(rho[b]),
-                          S_override=None if over is None else over[b * wl.n_kv_heads:(b + 1) * wl.n_kv_heads])
+                          S_override=None if (over is None or not self.lockstep)
+                          else over[b * wl.n_kv_heads:(b + 1) * wl.n_kv_heads])
                 self.oracles[(l, b)] = oc
             self.compare_state(l)
 
@@ -154,7 +157,7 @@ class SideBySide:
                         probe = _clone_for_scores(oc, qn, knn, vnn, self.scales[l])
                         self._check_scores(probe, l, b, over)
                     ref, ofired = oc.decode_step(qn, knn, vnn, self.scales[l],
-                                                 S_override=None if over is None else
+                                                 S_override=None if (over is None or not self.lockstep) else
                                                  over[b * wl.n_kv_heads:(b + 1) * wl.n_kv_heads])
                     assert ofired == fired
                     for h in range(wl.n_q_heads):
@@ -166,7 +169,7 @@ class SideBySide:
     def compare_state(self, layer):
         wl = self.wl
         ex = A.arkv_cache_export(self.cache, layer, self.cfg)
-        no, nq, lb = A.arkv_cache_counters(self.cache, layer, self.U)
+        no, nq, ne, lb = A.arkv_cache_counters(self.cache, layer, self.U)
         for b in range(wl.batch):
             oc = self.oracles[(layer, b)]
             for g in range(wl.n_kv_heads):
@@ -178,6 +181,7 @@ class SideBySide:
                 assert np.array_equal(ex["pos"][u, :n], ou.pos[order])              # bit-exact: who survived
                 assert np.array_equal(ex["state"][u, :n], ou.state[order].astype(np.uint8))   # and in which state
                 assert (no[u], nq[u]) == oc.counts(g) and lb[u] == oc.live_bytes(g)
+                assert ne[u] == oc.P + 1 - n                                       # evicted so far
                 assert lb[u] <= wl.capacity * 4 * wl.head_dim                      # eq. 1, per unit
                 self.max_err["s1"] = max(self.max_err["s1"], rel_err(ex["s1"][u, :n], ou.s1[order]))
                 self.max_err["s2"] = max(self.max_err["s2"], rel_err(ex["s2"][u, :n], ou.s2[order]))

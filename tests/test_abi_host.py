@@ -40,7 +40,7 @@ def _cfg(**kw):
     (dict(alpha=0.0), A.EINVAL), (dict(alpha=1.5), A.EINVAL), (dict(gamma=-1.0), A.EINVAL),
     (dict(group_size=64), A.EINVAL), (dict(head_dim=96), A.EUNSUPPORTED),
     (dict(quant_bits=3), A.EUNSUPPORTED), (dict(n_q_heads=6, n_kv_heads=2), A.EUNSUPPORTED),
-    (dict(tau=(1.0, 0.0, 1.0)), A.EINVAL),
+    (dict(tau=(1.0, 0.0, 1.0)), A.EINVAL), (dict(tailor_policy=2), A.EINVAL),
 ])
 def test_create_rejects_bad_config_without_gpu(kw, code):
     with pytest.raises(A.ArkvError) as e:
@@ -64,6 +64,10 @@ def test_budget_counts_match_oracle(N, W, alpha):
         got = A.arkv_budget_counts(cfg, float(rho))
         want = O.budget_counts(float(rho), N, W, float(np.float32(alpha)))
         assert got == want
+    cfg1 = _cfg(capacity_tokens=N, window=W, alpha=alpha, tailor_policy=1)
+    for rho in (0.0, 0.3, 1.0):
+        assert A.arkv_budget_counts(cfg1, rho) == O.budget_counts(rho, N, W, float(np.float32(alpha)), every_step=True)
+        assert A.arkv_budget_counts(cfg1, rho)[2] == N - W - 1
 
 
 def test_oq_ratio_matches_oracle():

@@ -10,8 +10,8 @@ from helpers import SideBySide
 pytestmark = pytest.mark.gpu
 
 
-def _run(wl, rho=None, steps=None, check_every=4, stats=True):
-    sb = SideBySide(wl, rho_override=rho)
+def _run(wl, rho=None, steps=None, check_every=4, stats=True, **kw):
+    sb = SideBySide(wl, rho_override=rho, **kw)
     try:
         sb.prefill()
         sb.commit()
@@ -70,3 +70,19 @@ def test_group_sizes(hq, hkv, d, bits):
     wl = synth.C1.scaled(name=f"g{hq // hkv}_d{d}_b{bits}", n_q_heads=hq, n_kv_heads=hkv, head_dim=d, bits=bits,
                          prefill=300, budget_frac=0.3, decode_steps=30)
     _run(wl)
+
+
+def test_every_step_policy():
+    """tailor_policy 1: no slack, the cache stays full and a tailor runs at every decode step."""
+    wl = synth.C1.scaled(name="every_step", decode_steps=24)
+    sb = _run(wl, rho=0.4, check_every=1, every_step=True)
+    oc = sb.oracles[(0, 0)]
+    assert oc.n_tailors == 1 + wl.decode_steps and oc.b == wl.capacity - wl.window - 1
+    assert all(len(u.pos) == wl.capacity - 1 for u in oc.units)
+
+
+def test_free_running_protocol():
+    """No score hand-over: the oracle ranks on its own fp64 scores.  With fp32 score errors around 1e-6
+    the two sides keep and quantise exactly the same tokens on this seed, through 3 tailors."""
+    wl = synth.C1.scaled(name="free_running", decode_steps=60)
+    _run(wl, check_every=6, lockstep=False)
