@@ -60,7 +60,7 @@ def stored_traffic(workload):
     return None
 
 
-def cpu_baseline(wl, k, v, qw, dq, scale, rho, seconds_budget=25.0):
+def cpu_baseline(wl, k, v, qw, dq, scale, rho, seconds_budget=12.0):
     """The oracle as it stands on one sequence of one layer: commit + a few decode steps, timed on
     the host; scaled to layer-batch steps per second by the batch size."""
     import numpy as np
@@ -439,6 +439,9 @@ def main():
             "c4_shape_all_original_100pct": quick_measure(synth.C4.scaled(n_layers=4, budget_frac=(synth.C4.prefill + 128) / synth.C4.prefill)),
         }
     if not args.no_cpu_baseline:
+        # the oracle needs ~10 ms per sequence-step at this shape: 1500 steps of sequence 0 bound the sample
+        # to the time budget below (same recipe as the GPU run's decode inputs, a longer draw)
+        dq_sample = tuple(p[:, 0].cpu() for p in synth.decode_inputs(wl, 0, 1500, device=dev))
         cb, ref_stats = cpu_baseline(wl, *sample, dq_sample, scales[0], rho[0, 0])
         result["cpu_baseline"] = cb
         got = stats_h[0, 0]

@@ -1,11 +1,14 @@
 // Decode step kernels (Alg. 1 "Decoding Phase" + "Reconstruction Before Attention", fused):
 //   k_decode_attend : append + split-K attention of one query per head over the bf16 pool and the
-//                     packed low-bit pool (dequantisation inside the QK and PV loops) + the score
-//                     update of the PREVIOUS step (its probabilities need that step's final
-//                     softmax denominator, which only exists after the split-K merge)
-//   k_decode_combine: merge of the split-K partials (a fused "last workgroup merges" variant was
-//                     measured 3-6x slower: it needs a device-scope fence in every workgroup)
-//   k_flush_scores  : adds the pending probabilities to (s1, s2) when something needs them now
+//                     packed low-bit pool (dequantisation inside the QK and PV loops)
+//                     + the score update of the PREVIOUS step: its probabilities need that step's
+//                     final softmax denominator, which only exists after the split-K merge, so they
+//                     are recomputed here from the previous query against the key tile that is in
+//                     registers anyway (same instructions, same bits as the step itself produced)
+//                     + the merge of the split-K partials by the unit's last workgroup (partials
+//                     move through device-scope atomics; a device-scope fence per workgroup instead
+//                     was measured 3-6x slower, a second kernel costs a launch gap per step)
+//   k_flush_scores  : the same score update on its own, when something needs the scores now
 //                     (tailor, export)
 #include <hip/hip_fp16.h>
 
@@ -122,44 +125,117 @@ __device__ __forceinline__ f32x4 mfma16(const uint4& a, const uint4& b, f32x4 c)
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
-// (s1, s2) += sum_h p_h, sum_h p_h^2 with p_h = 2^(lg_h - m_h) / Z_h, slots [a, b), one thread per slot.
-template <int G>
-__device__ __forceinline__ void apply_pending(float2* acc, const float* lg, int a, int b,
-                                              const float (&pm)[G], const float (&pinv)[G], int tid,
-                                              int nthreads) {
-  for (int i = a + tid; i < b; i += nthreads) {
-    float v[G];
-    if constexpr (G == 4) {
-      const float4 t = *reinterpret_cast<const float4*>(lg + (size_t)i * G);
-      v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
-    } else {
+// ---- pieces shared by the attention kernel and the stand-alone score update ----------------------
+
+// Query operand of a unit: lane holds head lane%16 (zero beyond G), channels 32kk + 8(lane/16) .. +7.
+template <int D, int G>
+__device__ __forceinline__ void load_query(const uint16_t* q_unit, int lane, uint4 (&qa)[D / 32]) {
+  const int tok = lane & 15, blk = lane >> 4;
+  const uint16_t* q = q_unit + (size_t)(tok < G ? tok : 0) * D + 8 * blk;
 #pragma unroll
-      for (int h = 0; h < G; ++h) v[h] = lg[(size_t)i * G + h];
-    }
-    float s1 = 0.f, s2 = 0.f;
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-      const float p = exp2f(v[h] - pm[h]) * pinv[h];
-      s1 += p;
-      s2 = fmaf(p, p, s2);
-    }
-    float2 t = acc[i];
-    t.x += s1; t.y += s2;
-    acc[i] = t;
+  for (int kk = 0; kk < D / 32; ++kk) {
+    const uint4 v = *reinterpret_cast<const uint4*>(q + 32 * kk);
+    qa[kk] = tok < G ? v : make_uint4(0, 0, 0, 0);
   }
 }
 
-// Merge of a unit's split-K partials: output row, the step's (max, 1/sum) per head, token count.
+// Dot products of the unit's heads with 16 bf16 key rows held in operand layout.
+template <int KK>
+__device__ __forceinline__ f32x4 dots_bf16(const uint4 (&qa)[KK], const uint4 (&kb)[KK]) {
+  f32x4 C = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) C = mfma16(qa[kk], kb[kk], C);
+  return C;
+}
+
+// What the packed-row path needs of a query: the code-order permutation of its operand and, per head
+// and quantisation group, the sum over the group's channels (an MFMA against an all-ones tile).
+template <int KK, int HPL>
+struct PackedQuery { uint4 qp[KK]; float qs[KK][HPL]; };
+template <int KK, int HPL>
+__device__ __forceinline__ void prep_packed_query(const uint4 (&qa)[KK], PackedQuery<KK, HPL>& pq) {
+  const uint4 ones = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) {
+    f32x4 C = {0.f, 0.f, 0.f, 0.f};
+    C = mfma16(qa[kk], ones, C);
+#pragma unroll
+    for (int i = 0; i < HPL; ++i) pq.qs[kk][i] = C[i];
+    pq.qp[kk] = permute_for_codes(qa[kk]);
+  }
+}
+
+// Dot products with 16 packed key rows: codes are OR-ed into bf16 "128 + code" operands, one MFMA per
+// quantisation group; scale, zero and the 128 offset are applied to the per-group results.
+template <int KK, int HPL, int BITS>
+__device__ __forceinline__ void dots_packed(const PackedQuery<KK, HPL>& pq, const uint32_t (&kcw)[KK],
+                                            const uint32_t (&kmeta)[KK], float (&x)[HPL]) {
+#pragma unroll
+  for (int i = 0; i < HPL; ++i) x[i] = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) {
+    f32x4 C = {0.f, 0.f, 0.f, 0.f};
+    C = mfma16(pq.qp[kk], codes_to_bf16_biased<BITS>(kcw[kk]), C);
+    const float sc = half_bits_to_float(kmeta[kk]), z = half_bits_to_float(kmeta[kk] >> 16);
+#pragma unroll
+    for (int i = 0; i < HPL; ++i) x[i] += fmaf(sc, C[i] - 128.0f * pq.qs[kk][i], z * pq.qs[kk][i]);
+  }
+}
+
+// Key codes and group metadata of row rk for lane (token lane%16, block lane/16).
+template <int D, int BITS>
+__device__ __forceinline__ void load_packed_keys(const uint8_t* kc, const uint32_t* km, int rk, int blk,
+                                                 uint32_t (&kcw)[D / 32], uint32_t (&kmeta)[D / 32]) {
+  constexpr int CB = D * BITS / 8, CW = BITS, NG = D / kGroup;
+#pragma unroll
+  for (int kk = 0; kk < D / 32; ++kk) {
+    const uint8_t* p = kc + (unsigned)rk * CB + kk * (4 * CW) + blk * CW;
+    kcw[kk] = BITS == 4 ? *reinterpret_cast<const uint32_t*>(p) : (uint32_t)*reinterpret_cast<const uint16_t*>(p);
+    kmeta[kk] = km[(unsigned)rk * NG + kk];
+  }
+}
+
+// Eq. 9 running moments: the lane's HPL logits of one token (base-2 units) -> probabilities with the
+// step's final (max, 1/sum) -> their sum and sum of squares over the unit's heads, valid in block 0.
+template <int HPL, int HB>
+__device__ __forceinline__ float2 prob_moments(const float (&x)[HPL], const float (&pm)[HPL], const float (&pinv)[HPL]) {
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int i = 0; i < HPL; ++i) {
+    const float p = fexp2(x[i] - pm[i]) * pinv[i];
+    s1 += p;
+    s2 = fmaf(p, p, s2);
+  }
+  if constexpr (HB == 2) { s1 += __shfl_xor(s1, 16); s2 += __shfl_xor(s2, 16); }
+  return make_float2(s1, s2);
+}
+
+// Split-K partials cross workgroups that may sit on different XCDs, whose L2 caches are not coherent
+// with each other for ordinary accesses.  They are therefore written and read with device-scope relaxed
+// atomics (write-through stores, loads that do not hit a stale L2 line); no cache-wide flush is needed.
+__device__ __forceinline__ void st_dev(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_dev(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Merge of a unit's split-K partials by the workgroup that finished last: output row, the step's
+// (max, 1/sum) per head, token count.  All 256 threads of that workgroup take part.
 template <int D, int G>
 __device__ __forceinline__ void combine_splits(const Pools& P, const DecodeLaunch& L, int lu, int gu, int tid) {
   __shared__ float cm[kMaxSplits][G], cl[kMaxSplits][G], cw[kMaxSplits][G];
   __shared__ float cInv[G];
-  const float* part = P.part + (size_t)gu * P.max_splits * G * (D + 2);
+  constexpr int RS = G * (D + 2);                  // floats per split
+  const float* part = P.part + (size_t)gu * P.max_splits * RS;
   const int S = L.splits;
   for (int i = tid; i < S * G; i += 256) {
     const int s = i / G, h = i % G;
-    const float2 ml = *reinterpret_cast<const float2*>(part + ((size_t)s * G + h) * (D + 2) + D);
-    cm[s][h] = ml.x; cl[s][h] = ml.y;
+    const unsigned long long ml = __hip_atomic_load(
+        reinterpret_cast<const unsigned long long*>(part + (size_t)s * RS + h * (D + 2) + D), __ATOMIC_RELAXED,
+        __HIP_MEMORY_SCOPE_AGENT);
+    cm[s][h] = __uint_as_float((unsigned)ml);
+    cl[s][h] = __uint_as_float((unsigned)(ml >> 32));
   }
   __syncthreads();
   if (tid < G) {
@@ -175,22 +251,35 @@ __device__ __forceinline__ void combine_splits(const Pools& P, const DecodeLaunc
     P.fin[(size_t)(L.parity ^ 1) * P.fin_stride + (size_t)gu * G + tid] = make_float2(M, 1.0f / l);
   }
   __syncthreads();
-  for (int idx = tid; idx < G * D; idx += 256) {
-    const int h = idx / D, c = idx % D;
-    const float* ph = part + (size_t)h * (D + 2) + c;
-    float a[4] = {0.f, 0.f, 0.f, 0.f};
-    int s = 0;
-    for (; s + 4 <= S; s += 4) {
-      float v[4];
+  constexpr int NI = (G * D + 255) / 256;          // output elements per thread
+  float o[NI];
+  int hh[NI], off[NI];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) v[j] = ph[(size_t)(s + j) * G * (D + 2)];
+  for (int i = 0; i < NI; ++i) {
+    const int idx = min(tid + 256 * i, G * D - 1);
+    hh[i] = idx / D;
+    off[i] = hh[i] * (D + 2) + idx % D;
+    o[i] = 0.f;
+  }
+  for (int s0 = 0; s0 < S; s0 += 8) {              // 8 * NI loads in flight
+    float v[NI][8];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) a[j] = fmaf(v[j], cw[s + j][h], a[j]);
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[i][j] = ld_dev(part + (size_t)min(s0 + j, S - 1) * RS + off[i]);
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int i = 0; i < NI; ++i) o[i] = fmaf(v[i][j], s0 + j < S ? cw[s0 + j][hh[i]] : 0.f, o[i]);
+  }
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int idx = tid + 256 * i;
+    if (idx < G * D) {
+      const float r = o[i] * cInv[hh[i]];
+      P.outf[(size_t)gu * G * D + idx] = r;
+      L.out[(size_t)lu * G * D + idx] = float_to_bf16_rne(r);
     }
-    for (; s < S; ++s) a[0] = fmaf(ph[(size_t)s * G * (D + 2)], cw[s][h], a[0]);
-    const float o = ((a[0] + a[1]) + (a[2] + a[3])) * cInv[h];
-    P.outf[((size_t)gu * G + h) * D + c] = o;
-    L.out[((size_t)lu * G + h) * D + c] = float_to_bf16_rne(o);
   }
   if (tid == 0) P.cnt[gu].x += 1;
 }
@@ -199,14 +288,14 @@ __device__ __forceinline__ void combine_splits(const Pools& P, const DecodeLaunc
 //
 // A wave works on tiles of 16 tokens.  QK^T of a tile is D/32 MFMAs (A = the unit's G query rows padded
 // to 16, B = 16 key rows loaded from HBM straight into operand layout); lane (token t = lane%16, block
-// b = lane/16) then owns the logits of token t for heads 4b..4b+3.  Probabilities go through a small
-// LDS buffer to the value layout (lane = 8 channels of one of 64/(D/8) rows), where PV runs on the
-// vector ALU.  The softmax reference maximum is only moved when a logit exceeds it by more than 8
-// (base-2 units), which is rare, so the accumulators are almost never rescaled.  Packed rows: codes are
-// OR-ed into bf16 "128 + code" operands, one MFMA per quantisation group, and scale / zero / the 128
-// offset are applied to the per-group dot products.
+// b = lane/16) then owns the logits of token t for heads 4b..4b+3.  The same key tile is multiplied with
+// the previous step's query as well: those logits, with that step's final (max, 1/sum), are the
+// probabilities Eq. 9 accumulates.  This step's probabilities go through a small LDS buffer to the value
+// layout (lane = 8 channels of one of 64/(D/8) rows), where PV runs on the vector ALU.  The softmax
+// reference maximum is only moved when a logit exceeds it by more than 8 (base-2 units), which is rare,
+// so the accumulators are almost never rescaled.
 template <int D, int G, int BITS>
-__global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) {
+__global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch L) {
   constexpr int KK = D / 32;           // MFMA k-steps = quantisation groups per row
   constexpr int LPR = D / 8;           // lanes per value row
   constexpr int R = 64 / LPR;          // value rows per wave load
@@ -228,31 +317,33 @@ __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) 
   __shared__ __align__(16) float pspare[4][16][4];
   __shared__ float sm_a[4][G][D];
   __shared__ float sm_m[4][G], sm_l[4][G];
+  __shared__ int sm_last;
 
   int cO, cQ;
   if (L.cnt_known) { cO = L.cnt_o[lu]; cQ = L.cnt_q[lu]; }
   else { const int2 cnt = P.cnt[gu]; cO = cnt.x; cQ = cnt.y; }
-
-  // logits of the previous step (read by the score workgroups) and of this step (written here)
-  const float* olg_prev = P.olg + ((size_t)L.parity * P.lg_stride_o + (size_t)gu * P.capO) * G;
-  const float* qlg_prev = P.qlg + ((size_t)L.parity * P.lg_stride_q + (size_t)gu * P.capQ) * G;
-  float* olg = P.olg + ((size_t)(L.parity ^ 1) * P.lg_stride_o + (size_t)gu * P.capO) * G;
-  float* qlg = P.qlg + ((size_t)(L.parity ^ 1) * P.lg_stride_q + (size_t)gu * P.capQ) * G;
 
   int ao, bo, aq, bq;
   split_range(cO, cQ, L.wq, L.splits, s, ao, bo, aq, bq);
 
   const uint16_t* ok_ = P.ok + (size_t)gu * P.capO * D;
   const uint16_t* ov_ = P.ov + (size_t)gu * P.capO * D;
+  float2* oacc_ = P.oacc + (size_t)gu * P.capO;
+  float2* qacc_ = P.qacc + (size_t)gu * P.capQ;
 
-  // query operand: lane holds head lane%16 (zero beyond G), channels 32kk + 8(lane/16) .. +7
-  uint4 qa[KK];
+  // this step's query and the previous step's (kept per unit, ping-pong by step parity), its scale and
+  // its final softmax constants for the lane's heads
+  uint4 qa[KK], qb[KK];
+  load_query<D, G>(L.q + (size_t)lu * G * D, lane, qa);
+  load_query<D, G>(P.qprev + ((size_t)L.parity * P.fin_stride + (size_t)gu * G) * D, lane, qb);
+  const float scale2_prev = P.qscale[(size_t)L.parity * (P.fin_stride / G) + gu];
+  float pm[HPL], pinv[HPL];
   {
-    const uint16_t* q = L.q + ((size_t)lu * G + (tok < G ? tok : 0)) * D + 8 * blk;
+    const float2* f = P.fin + (size_t)L.parity * P.fin_stride + (size_t)gu * G;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      const uint4 v = *reinterpret_cast<const uint4*>(q + 32 * kk);
-      qa[kk] = tok < G ? v : make_uint4(0, 0, 0, 0);
+    for (int i = 0; i < HPL; ++i) {
+      const float2 t = f[active ? 4 * blk + i : i];
+      pm[i] = t.x; pinv[i] = t.y;
     }
   }
 
@@ -265,7 +356,7 @@ __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) 
     for (int c = 0; c < 8; ++c) acc[h][c] = 0.f;
 
   // logits x[] of this lane's token -> reference-max check, probabilities, PV with the tile's value rows
-  auto softmax_pv = [&](bool live, const float (&x)[HPL], const float (&vf)[NV][8]) {
+  auto softmax_pv = [&](bool live, const float (&x)[HPL], auto&& value_row) {
     bool need = false;
 #pragma unroll
     for (int i = 0; i < HPL; ++i) need |= active && (x[i] > Mreg[i] + 8.0f);
@@ -303,44 +394,28 @@ __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) 
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       const float* pp = &pbuf[w][R * j + vrow][0];
+      float vf[8];
+      value_row(j, vf);                        // 8 channels of value row R*j + vrow as floats
 #pragma unroll
       for (int h = 0; h < G; ++h) {
         const float ph = pp[h];
 #pragma unroll
-        for (int c = 0; c < 8; ++c) acc[h][c] = fmaf(ph, vf[j][c], acc[h][c]);
+        for (int c = 0; c < 8; ++c) acc[h][c] = fmaf(ph, vf[c], acc[h][c]);
       }
     }
     __builtin_amdgcn_wave_barrier();
   };
 
-  // this step's logits of the lane's token (predicated store: a skipped store only makes a later
-  // wait count conservative by one)
-  auto store_logits = [&](bool own, float* dst, const float (&x)[HPL]) {
-    if (own) {
-      if constexpr (HPL == 4) {
-        *reinterpret_cast<float4*>(dst) = make_float4(x[0], x[1], x[2], x[3]);
-      } else {
-#pragma unroll
-        for (int i = 0; i < HPL; ++i) dst[i] = x[i];
-      }
-    }
-  };
-
-  // ---------------- deferred score update of the rows this split owns ----------------
-  // One thread per token, fully coalesced; reads the previous step's logits (the other buffer of the
-  // ping-pong) and its final (max, 1/sum).  Called once, right after the first tile's loads are issued.
-  auto score_phase = [&]() {
-    if (!L.has_pending) return;
-    float pm[G], pinv[G];
-    const float2* f = P.fin + (size_t)L.parity * P.fin_stride + (size_t)gu * G;
-#pragma unroll
-    for (int h = 0; h < G; ++h) { pm[h] = f[h].x; pinv[h] = f[h].y; }
-    apply_pending<G>(P.oacc + (size_t)gu * P.capO, olg_prev, ao, bo, pm, pinv, tid, 256);
-    apply_pending<G>(P.qacc + (size_t)gu * P.capQ, qlg_prev, aq, bq, pm, pinv, tid, 256);
+  // deferred score update of the lane's token: x[] are the previous step's logits (raw dot products
+  // times that step's scale).  The store is predicated: a skipped store only makes a later wait count
+  // conservative by one.
+  auto fold_prev = [&](const float (&xprev)[HPL], float2 ac, bool own, float2* acp, int row) {
+    const float2 m = prob_moments<HPL, HB>(xprev, pm, pinv);
+    if (own && blk == 0 && L.has_pending) acp[row] = make_float2(ac.x + m.x, ac.y + m.y);
   };
 
   // ---------------- Original rows ----------------
-  struct OTile { uint4 kb[KK]; uint4 vr[NV]; };
+  struct OTile { uint4 kb[KK]; uint4 vr[NV]; float2 ac; };
   auto load_o = [&](OTile& t, int row0) {
     const int rk = min(row0 + tok, bo - 1);
     {
@@ -354,22 +429,18 @@ __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) 
       const int rv = min(row0 + R * j + vrow, bo - 1);
       t.vr[j] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(ov_) + (unsigned)rv * (2 * D) + 16 * sub);
     }
+    t.ac = oacc_[rk];
   };
   auto compute_o = [&](const OTile& t, int row0) {
-    f32x4 C = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) C = mfma16(qa[kk], t.kb[kk], C);
+    const f32x4 C = dots_bf16<KK>(qa, t.kb);
+    const f32x4 Cp = dots_bf16<KK>(qb, t.kb);
     const bool own = (row0 + tok < bo) && active;
-    float x[HPL];
+    float x[HPL], xp[HPL];
 #pragma unroll
-    for (int i = 0; i < HPL; ++i) x[i] = own ? C[i] * scale2 : kNegBig;
-    store_logits(own, olg + (unsigned)min(row0 + tok, bo - 1) * G + 4 * blk, x);
-    float vf[NV][8];
-#pragma unroll
-    for (int j = 0; j < NV; ++j) unpack_bf16x8(t.vr[j], vf[j]);
-    softmax_pv(own, x, vf);
+    for (int i = 0; i < HPL; ++i) { x[i] = own ? C[i] * scale2 : kNegBig; xp[i] = Cp[i] * scale2_prev; }
+    fold_prev(xp, t.ac, own, oacc_, min(row0 + tok, bo - 1));
+    softmax_pv(own, x, [&](int j, float (&f)[8]) { unpack_bf16x8(t.vr[j], f); });
   };
-  if (ao >= bo) score_phase();
   if (ao < bo) {
     // two tiles in registers: while one is consumed the other is in flight.  Loads past the end of the
     // range are clamped to its last row; every load in the loop is unconditional so that the wait
@@ -377,7 +448,6 @@ __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) 
     OTile ta, tb;
     int row0 = ao + 16 * w;
     load_o(ta, row0);
-    score_phase();                              // overlaps with the first tile's round trip
     for (; row0 + 128 < bo; row0 += 128) {      // this wave still has two more tiles after this one
       load_o(tb, row0 + 64);
       compute_o(ta, row0);
@@ -391,35 +461,53 @@ __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) 
     }
   }
 
+  // ---------------- the token being generated (last split, wave 0) ----------------
+  if (s == L.splits - 1 && w == 0) {
+    const uint16_t* kn = L.k_new + (size_t)lu * D;
+    const uint16_t* vn = L.v_new + (size_t)lu * D;
+    uint4 kb[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) kb[kk] = *reinterpret_cast<const uint4*>(kn + 32 * kk + 8 * blk);
+    const uint4 vr = *reinterpret_cast<const uint4*>(vn + sub * 8);
+    const f32x4 C = dots_bf16<KK>(qa, kb);
+    const bool own = (tok == 0) && active;
+    float x[HPL];
+#pragma unroll
+    for (int i = 0; i < HPL; ++i) x[i] = own ? C[i] * scale2 : kNegBig;
+    softmax_pv(own, x, [&](int, float (&f)[8]) { unpack_bf16x8(vr, f); });
+    uint16_t* dk = P.ok + ((size_t)gu * P.capO + cO) * D;
+    uint16_t* dv = P.ov + ((size_t)gu * P.capO + cO) * D;
+    if (tok == 0) {
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) *reinterpret_cast<uint4*>(dk + 32 * kk + 8 * blk) = kb[kk];
+    }
+    if (vrow == 0) *reinterpret_cast<uint4*>(dv + sub * 8) = vr;
+    if (lane == 0) {
+      P.oacc[(size_t)gu * P.capO + cO] = make_float2(0.f, 0.f);
+      P.opos[(size_t)gu * P.capO + cO] = L.position;
+      P.qscale[(size_t)(L.parity ^ 1) * (P.fin_stride / G) + gu] = scale2;
+    }
+    // this step's query, for the next step's score update
+    if (tok < G) {
+      uint16_t* dq = P.qprev + ((size_t)(L.parity ^ 1) * P.fin_stride + (size_t)gu * G + tok) * D + 8 * blk;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) *reinterpret_cast<uint4*>(dq + 32 * kk) = qa[kk];
+    }
+  }
+
   // ---------------- Quantized rows ----------------
   if (aq < bq) {
     const uint8_t* kc = P.qkc + (size_t)gu * P.capQ * CB;
     const uint8_t* vc = P.qvc + (size_t)gu * P.capQ * CB;
     const uint32_t* km = P.qkm + (size_t)gu * P.capQ * NG;
     const uint32_t* vm = P.qvm + (size_t)gu * P.capQ * NG;
-    // per head and group: sum of the query over the group's channels (MFMA against an all-ones tile)
-    float qs[KK][HPL];
-    uint4 qp[KK];
-    {
-      const uint4 ones = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        f32x4 C = {0.f, 0.f, 0.f, 0.f};
-        C = mfma16(qa[kk], ones, C);
-#pragma unroll
-        for (int i = 0; i < HPL; ++i) qs[kk][i] = C[i];
-        qp[kk] = permute_for_codes(qa[kk]);
-      }
-    }
-    struct QTile { uint32_t kcw[KK]; uint32_t kmeta[KK]; uint32_t vcw[NV]; uint32_t vmeta[NV]; };
+    PackedQuery<KK, HPL> pqa, pqb;
+    prep_packed_query<KK, HPL>(qa, pqa);
+    prep_packed_query<KK, HPL>(qb, pqb);
+    struct QTile { uint32_t kcw[KK]; uint32_t kmeta[KK]; uint32_t vcw[NV]; uint32_t vmeta[NV]; float2 ac; };
     auto load_q = [&](QTile& t, int row0) {
       const int rk = min(row0 + tok, bq - 1);
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        const uint8_t* p = kc + (unsigned)rk * CB + kk * (4 * CW) + blk * CW;
-        t.kcw[kk] = BITS == 4 ? *reinterpret_cast<const uint32_t*>(p) : (uint32_t)*reinterpret_cast<const uint16_t*>(p);
-        t.kmeta[kk] = km[(unsigned)rk * NG + kk];
-      }
+      load_packed_keys<D, BITS>(kc, km, rk, blk, t.kcw, t.kmeta);
 #pragma unroll
       for (int j = 0; j < NV; ++j) {
         const int rv = min(row0 + R * j + vrow, bq - 1);
@@ -427,27 +515,17 @@ __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) 
         t.vcw[j] = BITS == 4 ? *reinterpret_cast<const uint32_t*>(p) : (uint32_t)*reinterpret_cast<const uint16_t*>(p);
         t.vmeta[j] = vm[(unsigned)rv * NG + sub / 4];
       }
+      t.ac = qacc_[rk];
     };
     auto compute_q = [&](const QTile& t, int row0) {
       const bool own = (row0 + tok < bq) && active;
-      float x[HPL];
+      float x[HPL], xp[HPL];
+      dots_packed<KK, HPL, BITS>(pqa, t.kcw, t.kmeta, x);
+      dots_packed<KK, HPL, BITS>(pqb, t.kcw, t.kmeta, xp);
 #pragma unroll
-      for (int i = 0; i < HPL; ++i) x[i] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        f32x4 C = {0.f, 0.f, 0.f, 0.f};
-        C = mfma16(qp[kk], codes_to_bf16_biased<BITS>(t.kcw[kk]), C);
-        const float sc = half_bits_to_float(t.kmeta[kk]), z = half_bits_to_float(t.kmeta[kk] >> 16);
-#pragma unroll
-        for (int i = 0; i < HPL; ++i) x[i] += fmaf(sc, C[i] - 128.0f * qs[kk][i], z * qs[kk][i]);
-      }
-#pragma unroll
-      for (int i = 0; i < HPL; ++i) x[i] = own ? x[i] * scale2 : kNegBig;
-      store_logits(own, qlg + (unsigned)min(row0 + tok, bq - 1) * G + 4 * blk, x);
-      float vf[NV][8];
-#pragma unroll
-      for (int j = 0; j < NV; ++j) dequant8<BITS>(t.vcw[j], t.vmeta[j], vf[j]);
-      softmax_pv(own, x, vf);
+      for (int i = 0; i < HPL; ++i) { x[i] = own ? x[i] * scale2 : kNegBig; xp[i] *= scale2_prev; }
+      fold_prev(xp, t.ac, own, qacc_, min(row0 + tok, bq - 1));
+      softmax_pv(own, x, [&](int j, float (&f)[8]) { dequant8<BITS>(t.vcw[j], t.vmeta[j], f); });
     };
     QTile ta, tb;
     int row0 = aq + 16 * w;
@@ -462,42 +540,6 @@ __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) 
       load_q(tb, row0 + 64);
       compute_q(ta, row0);
       if (row0 + 64 < bq) compute_q(tb, row0 + 64);
-    }
-  }
-
-  // ---------------- the token being generated (last split, wave 0) ----------------
-  if (s == L.splits - 1 && w == 0) {
-    const uint16_t* kn = L.k_new + (size_t)lu * D;
-    const uint16_t* vn = L.v_new + (size_t)lu * D;
-    uint4 kb[KK];
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) kb[kk] = *reinterpret_cast<const uint4*>(kn + 32 * kk + 8 * blk);
-    const uint4 vr = *reinterpret_cast<const uint4*>(vn + sub * 8);
-    f32x4 C = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) C = mfma16(qa[kk], kb[kk], C);
-    const bool own = (tok == 0) && active;
-    float x[HPL];
-#pragma unroll
-    for (int i = 0; i < HPL; ++i) x[i] = own ? C[i] * scale2 : kNegBig;
-    float vf[NV][8];
-#pragma unroll
-    for (int j = 0; j < NV; ++j) unpack_bf16x8(vr, vf[j]);
-    softmax_pv(own, x, vf);
-    uint16_t* dk = P.ok + ((size_t)gu * P.capO + cO) * D;
-    uint16_t* dv = P.ov + ((size_t)gu * P.capO + cO) * D;
-    if (tok == 0) {
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) *reinterpret_cast<uint4*>(dk + 32 * kk + 8 * blk) = kb[kk];
-      if (active) {
-#pragma unroll
-        for (int i = 0; i < HPL; ++i) olg[(size_t)cO * G + 4 * blk + i] = x[i];
-      }
-    }
-    if (vrow == 0) *reinterpret_cast<uint4*>(dv + sub * 8) = vr;
-    if (lane == 0) {
-      P.oacc[(size_t)gu * P.capO + cO] = make_float2(0.f, 0.f);
-      P.opos[(size_t)gu * P.capO + cO] = L.position;
     }
   }
 
@@ -536,27 +578,91 @@ __global__ __launch_bounds__(256) void k_decode_attend(Pools P, DecodeLaunch L) 
       a = fmaf(sm_a[i][h][c], cw_, a);
       l = fmaf(sm_l[i][h], cw_, l);
     }
-    part[h * (D + 2) + c] = a;
-    if (c == 0) { part[h * (D + 2) + D] = M; part[h * (D + 2) + D + 1] = l; }
+    st_dev(part + h * (D + 2) + c, a);
+    if (c == 0) { st_dev(part + h * (D + 2) + D, M); st_dev(part + h * (D + 2) + D + 1, l); }
   }
+
+  // ---------------- the unit's last workgroup merges ----------------
+  // Every lane waits until its own stores are acknowledged, the barrier collects the workgroup, then one
+  // lane takes a ticket.  The workgroup that draws the last ticket of the unit sees all partials.
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  if (tid == 0) {
+    const int old = __hip_atomic_fetch_add(P.ticket + gu, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int last = old == L.splits - 1;
+    if (last) __hip_atomic_store(P.ticket + gu, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
+    sm_last = last;
+  }
+  __syncthreads();
+  if (sm_last) combine_splits<D, G>(P, L, lu, gu, tid);
 }
 
-template <int D, int G>
-__global__ __launch_bounds__(256) void k_decode_combine(Pools P, DecodeLaunch L) {
-  combine_splits<D, G>(P, L, blockIdx.x, L.unit_begin + blockIdx.x, threadIdx.x);
-}
-
-template <int G>
+// The deferred score update on its own (before a tailor or an export): logits of the latest step are
+// recomputed from its stored query with the same tile code as in k_decode_attend.
+// grid (workgroups per unit, units); a wave takes every (4 * gridDim.x)-th tile of 16 rows.
+template <int D, int G, int BITS>
 __global__ __launch_bounds__(256) void k_flush_scores(Pools P, int unit_begin, int parity) {
+  constexpr int KK = D / 32;
+  constexpr int HB = (G + 3) / 4;
+  constexpr int HPL = G < 4 ? G : 4;
+  constexpr int CB = D * BITS / 8;
+  constexpr int NG = D / kGroup;
   const int gu = unit_begin + blockIdx.y;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int tok = lane & 15, blk = lane >> 4;
+  const bool active = blk < HB;
   const int2 cnt = P.cnt[gu];
-  float pm[G], pinv[G];
-  const float2* f = P.fin + (size_t)parity * P.fin_stride + (size_t)gu * G;
+  uint4 qb[KK];
+  load_query<D, G>(P.qprev + ((size_t)parity * P.fin_stride + (size_t)gu * G) * D, lane, qb);
+  const float scale2_prev = P.qscale[(size_t)parity * (P.fin_stride / G) + gu];
+  float pm[HPL], pinv[HPL];
+  {
+    const float2* f = P.fin + (size_t)parity * P.fin_stride + (size_t)gu * G;
 #pragma unroll
-  for (int h = 0; h < G; ++h) { pm[h] = f[h].x; pinv[h] = f[h].y; }
-  const int tid = blockIdx.x * 256 + threadIdx.x, nt = gridDim.x * 256;
-  apply_pending<G>(P.oacc + (size_t)gu * P.capO, P.olg + ((size_t)parity * P.lg_stride_o + (size_t)gu * P.capO) * G, 0, cnt.x, pm, pinv, tid, nt);
-  apply_pending<G>(P.qacc + (size_t)gu * P.capQ, P.qlg + ((size_t)parity * P.lg_stride_q + (size_t)gu * P.capQ) * G, 0, cnt.y, pm, pinv, tid, nt);
+    for (int i = 0; i < HPL; ++i) {
+      const float2 t = f[active ? 4 * blk + i : i];
+      pm[i] = t.x; pinv[i] = t.y;
+    }
+  }
+  const int wave = blockIdx.x * 4 + w, step = gridDim.x * 64;
+  {
+    const uint16_t* ok_ = P.ok + (size_t)gu * P.capO * D;
+    float2* acc = P.oacc + (size_t)gu * P.capO;
+    for (int row0 = 16 * wave; row0 < cnt.x; row0 += step) {
+      const int rk = min(row0 + tok, cnt.x - 1);
+      uint4 kb[KK];
+      const unsigned off = (unsigned)rk * (2 * D) + 16 * blk;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+        kb[kk] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(ok_) + off + 64 * kk);
+      const float2 ac = acc[rk];
+      const f32x4 Cp = dots_bf16<KK>(qb, kb);
+      float xp[HPL];
+#pragma unroll
+      for (int i = 0; i < HPL; ++i) xp[i] = Cp[i] * scale2_prev;
+      const float2 m = prob_moments<HPL, HB>(xp, pm, pinv);
+      if (row0 + tok < cnt.x && blk == 0) acc[rk] = make_float2(ac.x + m.x, ac.y + m.y);
+    }
+  }
+  if (cnt.y > 0) {
+    const uint8_t* kc = P.qkc + (size_t)gu * P.capQ * CB;
+    const uint32_t* km = P.qkm + (size_t)gu * P.capQ * NG;
+    float2* acc = P.qacc + (size_t)gu * P.capQ;
+    PackedQuery<KK, HPL> pqb;
+    prep_packed_query<KK, HPL>(qb, pqb);
+    for (int row0 = 16 * wave; row0 < cnt.y; row0 += step) {
+      const int rk = min(row0 + tok, cnt.y - 1);
+      uint32_t kcw[KK], kmeta[KK];
+      load_packed_keys<D, BITS>(kc, km, rk, blk, kcw, kmeta);
+      const float2 ac = acc[rk];
+      float xp[HPL];
+      dots_packed<KK, HPL, BITS>(pqb, kcw, kmeta, xp);
+#pragma unroll
+      for (int i = 0; i < HPL; ++i) xp[i] *= scale2_prev;
+      const float2 m = prob_moments<HPL, HB>(xp, pm, pinv);
+      if (row0 + tok < cnt.y && blk == 0) acc[rk] = make_float2(ac.x + m.x, ac.y + m.y);
+    }
+  }
 }
 
 template <int D, int G, int BITS>
@@ -566,7 +672,6 @@ static hipError_t launch_decode_t(const Pools& P, const DecodeLaunch& a, hipStre
   if (ev0) (void)hipEventRecord(ev0, s);
   hipLaunchKernelGGL((k_decode_attend<D, G, BITS>), grid, dim3(256), 0, s, P, a);
   if (ev1) (void)hipEventRecord(ev1, s);
-  hipLaunchKernelGGL((k_decode_combine<D, G>), dim3(a.n_units), dim3(256), 0, s, P, a);
   return hipGetLastError();
 }
 
@@ -656,19 +761,32 @@ hipError_t launch_stream_read(const void* buf, size_t offset_bytes, size_t bytes
   return hipGetLastError();
 }
 
+template <int D, int G>
+static hipError_t launch_flush_b(const Pools& P, dim3 grid, int unit_begin, int parity, hipStream_t s) {
+  if (P.bits == 4) hipLaunchKernelGGL((k_flush_scores<D, G, 4>), grid, dim3(256), 0, s, P, unit_begin, parity);
+  else hipLaunchKernelGGL((k_flush_scores<D, G, 2>), grid, dim3(256), 0, s, P, unit_begin, parity);
+  return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_flush_g(const Pools& P, dim3 grid, int unit_begin, int parity, hipStream_t s) {
+  switch (P.G) {
+    case 1: return launch_flush_b<D, 1>(P, grid, unit_begin, parity, s);
+    case 2: return launch_flush_b<D, 2>(P, grid, unit_begin, parity, s);
+    case 4: return launch_flush_b<D, 4>(P, grid, unit_begin, parity, s);
+    case 8: return launch_flush_b<D, 8>(P, grid, unit_begin, parity, s);
+  }
+  return hipErrorInvalidValue;
+}
+
 hipError_t launch_flush_scores(const Pools& P, int unit_begin, int n_units, int parity, hipStream_t s) {
   const int cap = P.capO > P.capQ ? P.capO : P.capQ;
-  int bx = (cap + 255) / 256;
+  int bx = (cap + 63) / 64;               // one tile per wave at most
   if (bx > 32) bx = 32;
-  dim3 grid(bx, n_units);
-  switch (P.G) {
-    case 1: hipLaunchKernelGGL((k_flush_scores<1>), grid, dim3(256), 0, s, P, unit_begin, parity); break;
-    case 2: hipLaunchKernelGGL((k_flush_scores<2>), grid, dim3(256), 0, s, P, unit_begin, parity); break;
-    case 4: hipLaunchKernelGGL((k_flush_scores<4>), grid, dim3(256), 0, s, P, unit_begin, parity); break;
-    case 8: hipLaunchKernelGGL((k_flush_scores<8>), grid, dim3(256), 0, s, P, unit_begin, parity); break;
-    default: return hipErrorInvalidValue;
-  }
-  return hipGetLastError();
+  const dim3 grid(bx, n_units);
+  if (P.D == 128) return launch_flush_g<128>(P, grid, unit_begin, parity, s);
+  if (P.D == 64) return launch_flush_g<64>(P, grid, unit_begin, parity, s);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace arkv

@@ -23,7 +23,6 @@ struct Pools {
   uint16_t* ov;         // [LU][capO][D] bf16 values
   int32_t*  opos;       // [LU][capO] position of the token in the sequence
   float2*   oacc;       // [LU][capO] (s1, s2): running sums of attention and attention^2 (eq. 9)
-  float*    olg;        // [2][LU][capO][G] logits of the latest two steps (base-2 units), ping-pong by step parity
   // Q pool
   uint8_t*  qkc;        // [LU][capQ][D*bits/8] key codes, canonical packing
   uint8_t*  qvc;        // [LU][capQ][D*bits/8]
@@ -31,14 +30,15 @@ struct Pools {
   uint32_t* qvm;        // [LU][capQ][D/32]
   int32_t*  qpos;       // [LU][capQ]
   float2*   qacc;       // [LU][capQ]
-  float*    qlg;        // [2][LU][capQ][G]
-  size_t    lg_stride_o, lg_stride_q;   // LU*capO, LU*capQ (slots between the two logits buffers)
   // per unit
   int2*     cnt;        // [LU] (tokens in O pool, tokens in Q pool)
   float2*   fin;        // [2][LU][G] (row max in base-2 units, 1/denominator) of the latest two steps
   size_t    fin_stride; // LU*G
+  uint16_t* qprev;      // [2][LU][G][D] bf16 queries of the latest two steps (the score update recomputes logits)
+  float*    qscale;     // [2][LU] softmax scale * log2(e) those queries were used with
   float*    part;       // [LU][max_splits][G][D+2] split-K partials: acc[D], max, sum
   int       max_splits;
+  int*      ticket;     // [LU] splits of the unit finished in the current launch (0 between launches)
   float*    outf;       // [LU][G][D] fp32 output of the latest step (parity hook)
   int32_t*  n_o;        // [LU] Original target of the unit's layer/sequence
   // tailor scratch
@@ -62,8 +62,8 @@ struct DecodeLaunch {
   int units_per_layer;
   int splits;
   int position;           // P of the token being appended
-  int has_pending;        // 1: olg/qlg[parity] hold logits of the previous step not yet added to (s1,s2)
-  int parity;             // fin/olg/qlg[parity] belong to the previous step; this step writes [parity^1]
+  int has_pending;        // 1: the previous step's probabilities are not yet added to (s1,s2)
+  int parity;             // fin/qprev/qscale[parity] belong to the previous step; this step writes [parity^1]
   int wq;                 // cost of a packed row in sixteenths of a bf16 row (split balancing)
   int cnt_known;          // 1: cnt_o / cnt_q below are the units' token counts (saves a dependent load)
   int cnt_o[kMaxUnitsKnown], cnt_q[kMaxUnitsKnown];

@@ -202,22 +202,25 @@ int arkv_cache_create(const arkv_config* cfg, arkv_cache** out) {
   const size_t LU = (size_t)c->L * c->U, D = (size_t)P.D, G = (size_t)P.G;
   const size_t CB = D * P.bits / 8, NG = D / kGroup;
   P.fin_stride = LU * G;
-  P.lg_stride_o = LU * (size_t)P.capO;
-  P.lg_stride_q = LU * (size_t)P.capQ;
   P.plan_stride = kPlanHdr + 3 * P.capO + 2 * P.capQ;
   if (const char* e = getenv("ARKV_WG_TARGET")) c->wg_target = std::max(1, atoi(e));
   if (const char* e = getenv("ARKV_WQ")) c->wq = std::max(1, std::min(16, atoi(e)));
   P.max_splits = std::max(1, std::min(kMaxSplits, (c->wg_target + c->U - 1) / c->U));
 #define A(field, count) if ((rc = dev_alloc(c, &P.field, (count))) != ARKV_OK) { arkv_cache_destroy(c); return rc; }
   A(ok, LU * P.capO * D) A(ov, LU * P.capO * D)
-  A(opos, LU * P.capO) A(oacc, LU * P.capO) A(olg, 2 * LU * P.capO * G)
+  A(opos, LU * P.capO) A(oacc, LU * P.capO)
   A(qkc, LU * P.capQ * CB) A(qvc, LU * P.capQ * CB)
   A(qkm, LU * P.capQ * NG) A(qvm, LU * P.capQ * NG)
-  A(qpos, LU * P.capQ) A(qacc, LU * P.capQ) A(qlg, 2 * LU * P.capQ * G)
-  A(cnt, LU) A(fin, 2 * LU * G) A(part, LU * (size_t)P.max_splits * G * (D + 2)) A(outf, LU * G * D) A(n_o, LU)
+  A(qpos, LU * P.capQ) A(qacc, LU * P.capQ)
+  A(cnt, LU) A(fin, 2 * LU * G) A(qprev, 2 * LU * G * D) A(qscale, 2 * LU) A(part, LU * (size_t)P.max_splits * G * (D + 2)) A(outf, LU * G * D) A(n_o, LU) A(ticket, LU)
   A(keys, LU * (size_t)(P.capO + P.capQ)) A(thr, LU * 2) A(plan, LU * (size_t)P.plan_stride)
 #undef A
   hipError_t e = hipMemset(P.cnt, 0, LU * sizeof(int2));
+  if (e == hipSuccess) e = hipMemset(P.ticket, 0, LU * sizeof(int));
+  // read (and ignored) by the first step after a commit: keep them finite
+  if (e == hipSuccess) e = hipMemset(P.fin, 0, 2 * LU * G * sizeof(float2));
+  if (e == hipSuccess) e = hipMemset(P.qprev, 0, 2 * LU * G * D * sizeof(uint16_t));
+  if (e == hipSuccess) e = hipMemset(P.qscale, 0, 2 * LU * sizeof(float));
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) { arkv_cache_destroy(c); return hip_fail(e, "hipMemset"); }
   *out = c;
