@@ -74,11 +74,13 @@ __device__ __forceinline__ uint16_t float_to_bf16_rne(float x) {
 }
 
 // Rows [ao,bo) of the O pool and [aq,bq) of the Q pool that split s of S owns.  Rows are weighted by
-// their measured cost (bf16 row = 16 units, packed row = wq units) so that splits take equal time.
+// their measured cost (bf16 row = 16 units, packed row = wq units) so that splits take equal time; the
+// last split also appends the new token, which is charged like kNewTokenRows bf16 rows.
+constexpr unsigned kNewTokenRows = 32;
 __host__ __device__ inline void split_range(int cO, int cQ, int wq, int S, int s, int& ao, int& bo,
                                             int& aq, int& bq) {
   // 16 cO + wq cQ < 2^19 and S <= 128: everything fits 32 bits
-  const unsigned tot = 16u * (unsigned)cO + (unsigned)wq * (unsigned)cQ;
+  const unsigned tot = 16u * (unsigned)cO + (unsigned)wq * (unsigned)cQ + 16u * kNewTokenRows;
   const unsigned v0 = tot * (unsigned)s / (unsigned)S, v1 = tot * (unsigned)(s + 1) / (unsigned)S;
   auto mapO = [&](unsigned v) { const int r = (int)((v + 15u) / 16u); return r < cO ? r : cO; };
   auto mapQ = [&](unsigned v) {
@@ -284,6 +286,16 @@ __device__ __forceinline__ void combine_splits(const Pools& P, const DecodeLaunc
   if (tid == 0) P.cnt[gu].x += 1;
 }
 
+// Profiling builds (-DARKV_PHASE_TRACE) record a 100 MHz timestamp per workgroup at the phase boundaries
+// marked TRACE(i); arkv_debug_trace_dump copies them out.  Product builds compile none of it.
+#ifdef ARKV_PHASE_TRACE
+__device__ unsigned long long g_trace[8192][8];
+#define TRACE(i) do { if (threadIdx.x == 0) g_trace[blockIdx.y * gridDim.x + blockIdx.x][i] = wall_clock64(); } while (0)
+__global__ void k_trace_mark(int slot) { if (threadIdx.x == 0) g_trace[8190][slot] = wall_clock64(); }
+#else
+#define TRACE(i)
+#endif
+
 // Attention of one query per head over this split's share of a unit's cache.
 //
 // A wave works on tiles of 16 tokens.  QK^T of a tile is D/32 MFMAs (A = the unit's G query rows padded
@@ -312,6 +324,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   const int vrow = lane / LPR, sub = lane % LPR;
   const bool active = blk < HB;
   const float scale2 = L.scale2[lu / L.units_per_layer];
+  TRACE(0);
 
   __shared__ __align__(16) float pbuf[4][16][G < 4 ? 4 : G];
   __shared__ __align__(16) float pspare[4][16][4];
@@ -319,9 +332,14 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   __shared__ float sm_m[4][G], sm_l[4][G];
   __shared__ int sm_last;
 
-  int cO, cQ;
-  if (L.cnt_known) { cO = L.cnt_o[lu]; cQ = L.cnt_q[lu]; }
-  else { const int2 cnt = P.cnt[gu]; cO = cnt.x; cQ = cnt.y; }
+  // token counts: from the launch arguments when the host knows them (a scalar load, no round trip to
+  // memory before the first tile can be requested), else from the unit's counters
+  const int lk = lu < kMaxUnitsKnown ? lu : 0;
+  int cO = L.cnt_o[lk], cQ = L.cnt_q[lk];
+  if (!L.cnt_known) {
+    const volatile int* cnt = reinterpret_cast<const volatile int*>(P.cnt + gu);
+    cO = cnt[0]; cQ = cnt[1];
+  }
 
   int ao, bo, aq, bq;
   split_range(cO, cQ, L.wq, L.splits, s, ao, bo, aq, bq);
@@ -448,6 +466,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
     OTile ta, tb;
     int row0 = ao + 16 * w;
     load_o(ta, row0);
+    TRACE(1);
     for (; row0 + 128 < bo; row0 += 128) {      // this wave still has two more tiles after this one
       load_o(tb, row0 + 64);
       compute_o(ta, row0);
@@ -461,8 +480,9 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
     }
   }
 
-  // ---------------- the token being generated (last split, wave 0) ----------------
-  if (s == L.splits - 1 && w == 0) {
+  TRACE(2);
+  // ---------------- the token being generated (last split; wave 3 has the fewest tiles) ----------------
+  if (s == L.splits - 1 && w == 3) {
     const uint16_t* kn = L.k_new + (size_t)lu * D;
     const uint16_t* vn = L.v_new + (size_t)lu * D;
     uint4 kb[KK];
@@ -495,6 +515,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
     }
   }
 
+  TRACE(3);
   // ---------------- Quantized rows ----------------
   if (aq < bq) {
     const uint8_t* kc = P.qkc + (size_t)gu * P.capQ * CB;
@@ -543,6 +564,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
     }
   }
 
+  TRACE(4);
   // ---------------- reduce within the wave, across the 4 waves ----------------
 #pragma unroll
   for (int i = 0; i < HPL; ++i) lsum[i] = row_sum16(lsum[i]);
@@ -582,6 +604,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
     if (c == 0) { st_dev(part + h * (D + 2) + D, M); st_dev(part + h * (D + 2) + D + 1, l); }
   }
 
+  TRACE(5);
   // ---------------- the unit's last workgroup merges ----------------
   // Every lane waits until its own stores are acknowledged, the barrier collects the workgroup, then one
   // lane takes a ticket.  The workgroup that draws the last ticket of the unit sees all partials.
@@ -595,6 +618,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   }
   __syncthreads();
   if (sm_last) combine_splits<D, G>(P, L, lu, gu, tid);
+  TRACE(6);
 }
 
 // The deferred score update on its own (before a tailor or an export): logits of the latest step are
@@ -670,7 +694,13 @@ static hipError_t launch_decode_t(const Pools& P, const DecodeLaunch& a, hipStre
                                   hipEvent_t ev1) {
   dim3 grid(a.splits, a.n_units);
   if (ev0) (void)hipEventRecord(ev0, s);
+#ifdef ARKV_PHASE_TRACE
+  hipLaunchKernelGGL(k_trace_mark, dim3(1), dim3(64), 0, s, 0);
+#endif
   hipLaunchKernelGGL((k_decode_attend<D, G, BITS>), grid, dim3(256), 0, s, P, a);
+#ifdef ARKV_PHASE_TRACE
+  hipLaunchKernelGGL(k_trace_mark, dim3(1), dim3(64), 0, s, 1);
+#endif
   if (ev1) (void)hipEventRecord(ev1, s);
   return hipGetLastError();
 }
@@ -743,6 +773,12 @@ __global__ __launch_bounds__(256) void k_stream_copy(uint4* __restrict__ buf, un
     for (int u = 0; u < 4; ++u) { const unsigned j = i + u * 256; if (j < n_per_wg) p[(size_t)half + j] = v[u]; }
   }
 }
+
+#ifdef ARKV_PHASE_TRACE
+extern "C" int arkv_debug_trace_dump(unsigned long long* host, int n_wg) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), (size_t)n_wg * 8 * sizeof(unsigned long long));
+}
+#endif
 
 hipError_t launch_stream_read(const void* buf, size_t offset_bytes, size_t bytes, int pattern, unsigned* sink, hipStream_t s) {
   if (pattern == 2) {
