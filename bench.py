@@ -178,6 +178,52 @@ def quick_measure(wl, rho_force=None, steps=24, warmup=4, every_step=False):
         A.arkv_cache_destroy(cache)
 
 
+def scorer_measure(wl, window, layers=4):
+    """Prefill scorer alone (window logits, causal softmax, column sums, the three statistics) on `layers`
+    layers of a workload with the observation window set to `window`: time per layer against both roofs."""
+    import torch
+    from paper_2603_08727_amd import binding as A
+    from paper_2603_08727_amd import synth
+    wl = wl.scaled(n_layers=layers, window=window)
+    dev = "cuda"
+    L, B, Hq, Hkv, d, T, W = wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.prefill, wl.window
+    cfg = A.arkv_config_default(n_layers=L, batch=B, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d,
+                                capacity_tokens=wl.capacity, window=W, alpha=wl.alpha, gamma=wl.gamma,
+                                tau=wl.tau, quant_bits=wl.bits)
+    cache = A.arkv_cache_create(cfg)
+    try:
+        stats = torch.zeros((L, B, 3), dtype=torch.float32, device=dev)
+        ms = []
+        for rep in range(2):                  # second round: warm code, same work
+            if rep:
+                A.arkv_cache_reset(cache, -1)
+            for l in range(L):
+                k, v, qw = synth.prefill_inputs(wl, l, device=dev)
+                del v
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                A.arkv_prefill_stats(cache, l, qw, k, T, synth.softmax_scale(wl, l), stats[l])
+                e1.record()
+                torch.cuda.synchronize()
+                if rep:
+                    ms.append(e0.elapsed_time(e1))
+                del k, qw
+        t = sum(ms) / len(ms) * 1e-3
+        flops = 2.0 * W * Hq * T * d * B      # one pass of the window logits; the kernels make two
+        kbytes = B * Hkv * T * d * 2
+        t_hbm, t_mfma = kbytes / (HBM_PEAK_GBPS * 1e9), flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+        return {"window": W, "query_rows_per_unit": W * (Hq // Hkv), "ms_per_layer": round(t * 1e3, 4),
+                "TFLOPs_one_pass": round(flops / t / 1e12, 1), "TFLOPs_executed_two_passes": round(2 * flops / t / 1e12, 1),
+                "frac_of_bf16_mfma_peak_executed": round(2 * flops / t / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                "GBps_keys_once": round(kbytes / t / 1e9, 1),
+                "roof_us_keys_once_at_hbm_peak": round(t_hbm * 1e6, 1), "roof_us_one_pass_at_mfma_peak": round(t_mfma * 1e6, 1),
+                "bound": "hbm" if t_hbm > t_mfma else "mfma",
+                "frac_of_min_roof": round(max(t_hbm, t_mfma) / t, 4),
+                "batch": B, "context": T, "layers_timed": L}
+    finally:
+        A.arkv_cache_destroy(cache)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -438,6 +484,10 @@ def main():
             "c4_llama3_8b_128k_2bit": quick_measure(synth.C4.scaled(n_layers=8)),
             "c4_shape_all_original_100pct": quick_measure(synth.C4.scaled(n_layers=4, budget_frac=(synth.C4.prefill + 128) / synth.C4.prefill)),
         }
+    if not args.no_variants:
+        # prefill-scorer stress shape (16K context, batch 8) at the paper's window and at a 4x window, where the
+        # contraction is compute-bound
+        result["scorer_stress"] = {"c5_w32": scorer_measure(synth.C5, 32), "c5_w128": scorer_measure(synth.C5, 128)}
     if not args.no_cpu_baseline:
         # the oracle needs ~10 ms per sequence-step at this shape: 1500 steps of sequence 0 bound the sample
         # to the time budget below (same recipe as the GPU run's decode inputs, a longer draw)

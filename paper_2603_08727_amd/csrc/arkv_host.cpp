@@ -77,7 +77,7 @@ static int validate(const arkv_config* c) {
   if (c->head_dim != 64 && c->head_dim != 128) return ARKV_EUNSUPPORTED;
   if (G != 1 && G != 2 && G != 4 && G != 8) return ARKV_EUNSUPPORTED;
   if (c->quant_bits != 2 && c->quant_bits != 4) return ARKV_EUNSUPPORTED;
-  if (G * c->window > 256) return ARKV_EUNSUPPORTED;
+  if (G * c->window > 512) return ARKV_EUNSUPPORTED;
   return ARKV_OK;
 }
 

@@ -119,6 +119,9 @@ __global__ __launch_bounds__(256) void k_prefill_rows(PrefillLaunch L) {
         for (int i = 0; i < 16; ++i) s += pexp2(x[i] - mn);   // masked entries: 2^(-1e30 - mn) = 0
       }
       m[rt] = mn; l[rt] = s;
+      // one row tile at a time: without this the compiler interleaves all RT tiles and the kernel drops
+      // to one wave per SIMD; other waves fill the MFMA -> VALU gaps instead
+      __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
     for (int kk = 0; kk < D / 16; ++kk) kf[kk] = kn[kk];
@@ -229,6 +232,7 @@ __global__ __launch_bounds__(256) void k_prefill_cols(PrefillLaunch L, const flo
           }
         }
       }
+      __builtin_amdgcn_sched_barrier(0);     // one row tile at a time (register pressure, see k_prefill_rows)
     }
     a1 += __shfl_xor(a1, 32);
     a2 += __shfl_xor(a2, 32);
@@ -332,10 +336,10 @@ hipError_t launch_prefill_stats(const PrefillLaunch& a, float* rowc, hipStream_t
   const int M = a.G * a.W;
   int RT = 1;
   while (RT * 32 < M) RT *= 2;
-  if (RT > 8) return hipErrorInvalidValue;
+  if (RT > 16) return hipErrorInvalidValue;
 #define ARKV_PF(D_, RT_) if (a.D == D_ && RT == RT_) return launch_prefill_t<D_, RT_>(a, rowc, s);
-  ARKV_PF(128, 1) ARKV_PF(128, 2) ARKV_PF(128, 4) ARKV_PF(128, 8)
-  ARKV_PF(64, 1) ARKV_PF(64, 2) ARKV_PF(64, 4) ARKV_PF(64, 8)
+  ARKV_PF(128, 1) ARKV_PF(128, 2) ARKV_PF(128, 4) ARKV_PF(128, 8) ARKV_PF(128, 16)
+  ARKV_PF(64, 1) ARKV_PF(64, 2) ARKV_PF(64, 4) ARKV_PF(64, 8) ARKV_PF(64, 16)
 #undef ARKV_PF
   return hipErrorInvalidValue;
 }

@@ -86,3 +86,9 @@ def test_free_running_protocol():
     the two sides keep and quantise exactly the same tokens on this seed, through 3 tailors."""
     wl = synth.C1.scaled(name="free_running", decode_steps=60)
     _run(wl, check_every=6, lockstep=False)
+
+
+def test_wide_window():
+    """Observation window of 128: G*W = 512 query rows per unit, 16 row tiles in the prefill scorer."""
+    wl = synth.C1.scaled(name="wide_window", window=128, prefill=1500, decode_steps=12)
+    _run(wl, check_every=4)
