@@ -264,6 +264,7 @@ int arkv_prefill_stats(arkv_cache* c, int32_t layer, const void* q_win, const vo
   int rc;
   if ((rc = grow(&ls.pre, &ls.pre_cap, (size_t)U * T)) != ARKV_OK) return rc;
   int chunk = 1024;
+  if (const char* e = getenv("ARKV_PREFILL_CHUNK")) chunk = std::max(128, atoi(e) / 128 * 128);
   while (chunk > 128 && (size_t)((T + chunk - 1) / chunk) * U < 1024) chunk >>= 1;
   const int n_chunks = (T + chunk - 1) / chunk;
   int MP = 32;
