@@ -57,9 +57,9 @@ typedef struct {
 int arkv_config_default(arkv_config* cfg);
 
 /* Allocates the pools of all layers on the current device (per unit: N bf16 K and V rows, b packed
- * rows, per-slot position / score accumulators / pending logits) and returns the cache in *out.
+ * rows, per-slot position / score accumulators, the latest queries per unit) and returns the cache in *out.
  * Synchronous.  ARKV_EINVAL: null pointers, non-positive shapes, W >= N - 1, alpha outside (0,1],
- * gamma < 0, group_size != 32.  ARKV_EUNSUPPORTED: head_dim not in {64,128}, G not in {1,2,4,8},
+ * gamma < 0, group_size != 32.  ARKV_EUNSUPPORTED: head_dim not in {64,128}, G not in {1,2,4,8}, G*W > 512,
  * quant_bits not in {2,4}. */
 int arkv_cache_create(const arkv_config* cfg, arkv_cache** out);
 

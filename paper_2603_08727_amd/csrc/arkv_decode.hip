@@ -229,8 +229,23 @@ __device__ __forceinline__ void combine_splits(const Pools& P, const DecodeLaunc
   __shared__ float cm[kMaxSplits][G], cl[kMaxSplits][G], cw[kMaxSplits][G];
   __shared__ float cInv[G];
   constexpr int RS = G * (D + 2);                  // floats per split
+  constexpr int NI = (G * D + 255) / 256;          // output elements per thread
+  constexpr int NB = 16;                           // splits per batch of loads
   const float* part = P.part + (size_t)gu * P.max_splits * RS;
   const int S = L.splits;
+  int hh[NI], off[NI];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int idx = min(tid + 256 * i, G * D - 1);
+    hh[i] = idx / D;
+    off[i] = hh[i] * (D + 2) + idx % D;
+  }
+  // the first batch of partial values is requested together with the (max, sum) pairs: one round trip
+  float v[NI][NB];
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j) v[i][j] = ld_dev(part + (size_t)min(j, S - 1) * RS + off[i]);
   for (int i = tid; i < S * G; i += 256) {
     const int s = i / G, h = i % G;
     const unsigned long long ml = __hip_atomic_load(
@@ -253,26 +268,20 @@ __device__ __forceinline__ void combine_splits(const Pools& P, const DecodeLaunc
     P.fin[(size_t)(L.parity ^ 1) * P.fin_stride + (size_t)gu * G + tid] = make_float2(M, 1.0f / l);
   }
   __syncthreads();
-  constexpr int NI = (G * D + 255) / 256;          // output elements per thread
   float o[NI];
-  int hh[NI], off[NI];
 #pragma unroll
-  for (int i = 0; i < NI; ++i) {
-    const int idx = min(tid + 256 * i, G * D - 1);
-    hh[i] = idx / D;
-    off[i] = hh[i] * (D + 2) + idx % D;
-    o[i] = 0.f;
-  }
-  for (int s0 = 0; s0 < S; s0 += 8) {              // 8 * NI loads in flight
-    float v[NI][8];
+  for (int i = 0; i < NI; ++i) o[i] = 0.f;
+  for (int s0 = 0;;) {
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int i = 0; i < NI; ++i) o[i] = fmaf(v[i][j], s0 + j < S ? cw[s0 + j][hh[i]] : 0.f, o[i]);
+    s0 += NB;
+    if (s0 >= S) break;
 #pragma unroll
     for (int i = 0; i < NI; ++i)
 #pragma unroll
-      for (int j = 0; j < 8; ++j) v[i][j] = ld_dev(part + (size_t)min(s0 + j, S - 1) * RS + off[i]);
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-#pragma unroll
-      for (int i = 0; i < NI; ++i) o[i] = fmaf(v[i][j], s0 + j < S ? cw[s0 + j][hh[i]] : 0.f, o[i]);
+      for (int j = 0; j < NB; ++j) v[i][j] = ld_dev(part + (size_t)min(s0 + j, S - 1) * RS + off[i]);
   }
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
