@@ -9,7 +9,7 @@ table or helper with the GPU path.
 Arithmetic is fp64 unless a function says otherwise.  Two places are fp32 by
 design, because an integer decision hangs on them and both sides must take it
 in the same precision:
-  * quantize_groups (codes / fp16 scale / fp16 zero),
+  * quantize_groups and quantize_fp8_rows (codes / fp16 scale / fp16 zero),
   * hh_score(..., exact32=True)  (selection keys).
 
 What follows the paper, by passage:
@@ -22,6 +22,9 @@ What follows the paper, by passage:
   tailor_assign           Sec. IV-F, eq. 10; Alg. 1 "Decoding Phase"
   quantize_* / dequantize Alg. 1 "Reconstruction Before Attention" (uniform
                           low-bit scheme of the benchmark configs, groups of 32)
+  quantize_fp8_rows / dequantize_fp8_row
+                          the same passage in the paper's own format: fp8 codes
+                          with one scale per token row, x~ = q^ * s
   SequenceCacheOracle     Alg. 1 end to end for one (layer, sequence)
 
 Readings taken where the paper is silent or garbled are listed in DESIGN.md;
@@ -300,6 +303,68 @@ def unpack_codes(packed, bits):
 
 
 # --------------------------------------------------------------------------
+# fp8 quantiser with one scale per token row (Alg. 1 "Reconstruction Before
+# Attention": x~ = q^ * s, "per-token scale"; Sec. V-C "fp8 form")
+# --------------------------------------------------------------------------
+# The paper does not say which 8-bit float it uses.  Reading taken: the OCP
+# "E4M3" format without infinities (sign, 4 exponent bits with bias 7, 3
+# mantissa bits; largest finite value 448; exponent field 0 holds subnormals
+# m/8 * 2^-6; the all-ones magnitude 0x7F is NaN and never produced here).
+E4M3_MAX = 448.0
+
+
+def e4m3_magnitudes():
+    """Value of every non-negative code 0..126, straight from the format's definition."""
+    v = np.empty(127, dtype=np.float64)
+    for code in range(127):
+        e, m = code >> 3, code & 7
+        v[code] = (m / 8.0) * 2.0 ** -6 if e == 0 else (1.0 + m / 8.0) * 2.0 ** (e - 7)
+    return v
+
+
+def quantize_fp8_rows(x):
+    """Quantise rows x [..., d] (one K or V row of one token each); all arithmetic
+    IEEE fp32, one rounding per operation.
+
+    scale = fp16(amax / 448), stepped one fp16 up where 448*scale would stop short
+            of amax = max|x| (so no element saturates); an all-zero row gets scale 0;
+    t     = x / scale (fp32 division);
+    code  = the E4M3 value nearest to |t| (a tie goes to the code with an even
+            mantissa, i.e. the even code), capped at 448, sign bit set where x < 0.
+    Returns (codes uint8[..., d], scale fp16[...]).
+    """
+    f = np.float32
+    x = np.asarray(x, dtype=f)
+    assert np.all(np.isfinite(x))
+    amax = np.abs(x).max(axis=-1)
+    s = (amax / f(E4M3_MAX)).astype(f)
+    scale_h = s.astype(np.float16)
+    short = (scale_h.astype(f) * f(E4M3_MAX)).astype(f) < amax
+    scale_h = np.where(short, _f16_step(scale_h, +1), scale_h).astype(np.float16)
+    scale_h = np.where(amax == 0, np.float16(0), scale_h).astype(np.float16)
+    assert np.all(np.isfinite(scale_h.astype(f)))
+    sc = scale_h.astype(f)
+    safe = np.where(sc > 0, sc, f(1))
+    t = np.abs((x / safe[..., None]).astype(f)).astype(np.float64)
+    v = e4m3_magnitudes()
+    mid = (v[:-1] + v[1:]) / 2.0                     # exact in fp64
+    lo = np.searchsorted(mid, t, side="left")        # |t| <= mid[lo]  (first such), so v[lo] or a tie with v[lo+1]
+    tie = (lo < len(mid)) & (t == mid[np.minimum(lo, len(mid) - 1)])
+    code = np.where(tie & (lo % 2 == 1), lo + 1, lo)
+    code = np.minimum(code, 126).astype(np.uint8)
+    code = np.where((amax == 0)[..., None], np.uint8(0), code)
+    code = np.where(x < 0, code | np.uint8(0x80), code).astype(np.uint8)
+    return code, scale_h
+
+
+def dequantize_fp8_row(codes, scale):
+    """x~ = value(code) * scale in fp64, not re-rounded to bf16."""
+    codes = np.asarray(codes, dtype=np.uint8)
+    v = e4m3_magnitudes()[codes & 0x7F]
+    return np.where(codes & 0x80, -v, v) * float(np.asarray(scale, dtype=np.float64).reshape(-1)[0])
+
+
+# --------------------------------------------------------------------------
 # Decode attention over a set of live tokens (plain definition)
 # --------------------------------------------------------------------------
 def attend(q, keys, values, scale):
@@ -420,7 +485,16 @@ class SequenceCacheOracle:
             self.last_tailor.append({"pos": u.pos[idx].copy(), "S": np.asarray(S).copy(),
                                      "new_state": new_state.copy()})
             dem = idx[(new_state == STATE_Q) & (u.state[idx] == STATE_O)]
-            if len(dem):
+            if len(dem) and self.bits == 8:
+                codes, sc = quantize_fp8_rows(u.raw[dem])          # [n, 2, d], [n, 2]
+                none = np.zeros(1, dtype=np.float16)               # the format has no zero point
+                for n_, j in enumerate(dem):
+                    u.q[int(u.pos[j])] = dict(k_codes=codes[n_, 0], k_scale=sc[n_, 0:1], k_zero=none,
+                                              v_codes=codes[n_, 1], v_scale=sc[n_, 1:2], v_zero=none)
+                    u.kv[j, 0] = dequantize_fp8_row(codes[n_, 0], sc[n_, 0])
+                    u.kv[j, 1] = dequantize_fp8_row(codes[n_, 1], sc[n_, 1])
+                u.state[dem] = STATE_Q
+            elif len(dem):
                 d = self.d
                 codes, sc, zr = quantize_groups(u.raw[dem].reshape(len(dem), 2, d // GROUP, GROUP),
                                                 self.bits)
@@ -445,6 +519,8 @@ class SequenceCacheOracle:
 
     def live_bytes(self, g):
         """eq. 1 cost of one kv-head: n_o*C_orig + n_q*C_quant with
-        C_orig = 4d bytes (bf16 K and V), C_quant = 2*(d*bits/8 + (d/32)*4)."""
+        C_orig = 4d bytes (bf16 K and V), C_quant = 2*(d*bits/8 + (d/32)*4) for the
+        grouped low-bit formats and 2*(d + 2) for fp8 rows with one fp16 scale."""
         no, nq = self.counts(g)
-        return no * 4 * self.d + nq * 2 * (self.d * self.bits // 8 + (self.d // GROUP) * 4)
+        cq = 2 * (self.d + 2) if self.bits == 8 else 2 * (self.d * self.bits // 8 + (self.d // GROUP) * 4)
+        return no * 4 * self.d + nq * cq

@@ -287,3 +287,99 @@ def test_attend_bruteforce_and_special_cases():
     perm = rng.permutation(n)
     out2, _ = O.attend(q, K[perm], V[perm], 0.5)
     assert np.allclose(out, out2)
+
+
+# ---- fp8 rows with one scale per token (Alg. 1 "Reconstruction Before Attention") ---------------------------
+def test_e4m3_table_matches_the_format_definition():
+    """Values the OCP 8-bit float specification fixes for E4M3 (no infinities): 448 largest, 2^-6 smallest
+    normal, 2^-9 smallest subnormal, 0x38 = 1.0; and torch's float8_e4m3fn decodes every code to the same value."""
+    v = O.e4m3_magnitudes()
+    assert v[0x7E] == 448.0 and v[0x08] == 2.0 ** -6 and v[0x01] == 2.0 ** -9 and v[0x38] == 1.0 and v[0] == 0.0
+    assert np.all(np.diff(v) > 0)
+    import torch
+    codes = torch.arange(0, 127, dtype=torch.uint8)
+    lib = codes.view(torch.float8_e4m3fn).to(torch.float32).numpy().astype(np.float64)
+    assert np.array_equal(lib, v)
+
+
+def test_fp8_codes_match_library_rounding():
+    """On rows whose scale comes out as a power of two the division is exact, so the codes must equal the
+    library's round-to-nearest-even cast of x / scale (an independent implementation of the rounding)."""
+    import torch
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((64, 128)).astype(np.float32) * 3.0
+    x = torch.tensor(x).to(torch.bfloat16).to(torch.float32).numpy()
+    x[:, 0] = 448.0 * 2.0 ** -4                     # amax fixed: scale = 2^-4 exactly
+    x = np.clip(x, -28.0, 28.0)
+    codes, scale = O.quantize_fp8_rows(x)
+    assert np.all(scale.astype(np.float32) == 2.0 ** -4)
+    want = torch.tensor(x / np.float32(2.0 ** -4)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    neg_zero = (want == 0x80) & (x == 0)            # the library keeps the sign of -0.0; the oracle stores +0
+    assert np.array_equal(np.where(neg_zero, 0, want), codes)
+
+
+def test_fp8_nearest_by_brute_force_and_ties():
+    v = O.e4m3_magnitudes()
+    # ties: exactly halfway between neighbours -> the even code; scale 1 via amax = 448
+    for i in (0, 1, 7, 8, 15, 16, 100, 125):
+        t = (v[i] + v[i + 1]) / 2.0
+        assert float(np.float32(t)) == t
+        x = np.array([448.0, t, -t], dtype=np.float32)
+        codes, scale = O.quantize_fp8_rows(x)
+        assert scale == np.float16(1.0)
+        even = i if i % 2 == 0 else i + 1
+        assert codes[1] == even and codes[2] == (even | 0x80)
+    rng = np.random.default_rng(11)
+    x = (rng.standard_normal(2000) * np.exp(rng.uniform(-12, 3, 2000))).astype(np.float32)
+    x[0] = 448.0
+    codes, scale = O.quantize_fp8_rows(x)
+    t = np.abs(x.astype(np.float64))
+    best = np.abs(t[:, None] - v[None, :]).argmin(axis=1)          # exhaustive nearest
+    dist = np.abs(t - v[codes & 0x7F])
+    assert np.all(dist <= np.abs(t - v[best]) + 0.0)               # never farther than the best code
+    assert np.all((codes >> 7) == (x < 0))
+
+
+def test_fp8_rows_error_bound_and_no_saturation():
+    """|x - x~| <= scale * (half the spacing of the codes around x/scale); 448*scale >= amax so nothing clips;
+    relative error of normal-range elements <= 2^-4; an all-zero row -> scale 0, codes 0."""
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((200, 64)).astype(np.float32) * np.exp(rng.uniform(-6, 6, (200, 1))).astype(np.float32)
+    x[7] = 0.0
+    codes, scale = O.quantize_fp8_rows(x)
+    sc = scale.astype(np.float64)
+    assert np.all(448.0 * sc >= np.abs(x).max(axis=-1))
+    assert sc[7] == 0 and not codes[7].any()
+    v = O.e4m3_magnitudes()
+    for r in range(x.shape[0]):
+        xt = O.dequantize_fp8_row(codes[r], scale[r])
+        err = np.abs(xt - x[r])
+        mag = codes[r] & 0x7F
+        spacing = np.where(mag >= 8, 2.0 ** ((mag >> 3).astype(np.float64) - 7 - 3), 2.0 ** -9)
+        # one fp32 rounding of the division can move x/scale by half an fp32 ulp before the code is chosen
+        assert np.all(err <= sc[r] * spacing / 2 * (1 + 1e-6) + 1e-30), r
+        normal = np.abs(x[r]) >= sc[r] * 2.0 ** -6
+        assert np.all(err[normal] <= np.abs(x[r][normal]) * 2.0 ** -4)
+
+
+def test_fp8_cache_trajectory_invariants():
+    """The cache oracle with the fp8 format: monotone states, budget, live bytes with C_quant = 2(d + 2)."""
+    rng = np.random.default_rng(2)
+    d, N, W = 64, 48, 8
+    oc = O.SequenceCacheOracle(4, 2, d, N, W=W, bits=8)
+    T = 80
+    k = rng.standard_normal((2, T, d)).astype(np.float32)
+    v = rng.standard_normal((2, T, d)).astype(np.float32)
+    s1 = rng.random((2, T)); s2 = s1 ** 2 / 8
+    oc.commit(k, v, s1, s2, rho=0.5)
+    for t in range(30):
+        oc.decode_step(rng.standard_normal((4, d)), rng.standard_normal((2, d)).astype(np.float32),
+                       rng.standard_normal((2, d)).astype(np.float32), 0.125)
+    for g in range(2):
+        no, nq = oc.counts(g)
+        assert nq > 0 and no + nq <= N
+        assert oc.live_bytes(g) == no * 4 * d + nq * 2 * (d + 2)
+        u = oc.units[g]
+        for j in np.nonzero(u.state == O.STATE_Q)[0]:
+            e = u.q[int(u.pos[j])]
+            assert np.array_equal(u.kv[j, 0], O.dequantize_fp8_row(e["k_codes"], e["k_scale"]))
