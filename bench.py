@@ -33,7 +33,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 def kv_bytes_per_token(d, bits):
     c_o = 4 * d
-    c_q = 2 * (d * bits // 8 + (d // 32) * 4)
+    c_q = 2 * (d + 2) if bits == 8 else 2 * (d * bits // 8 + (d // 32) * 4)
     return c_o, c_q
 
 
@@ -438,7 +438,7 @@ def main():
         "metric": "decode steps/sec per layer-batch at 32K ctx", "value": round(value, 1), "unit": "steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32 accumulate over bf16 / int%d rows" % wl.bits, "data": "synthetic",
+        "dtype": "f32 accumulate over bf16 / %s rows" % ("fp8" if wl.bits == 8 else "int%d" % wl.bits), "data": "synthetic",
         "config": {"workload": wl.name, "n_layers": L, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": d, "context": T, "capacity_tokens": wl.capacity, "quant_bits": wl.bits,
                    "window": W, "launch": "one arkv_decode_step per layer"},
@@ -472,6 +472,8 @@ def main():
             "quant_all_kept_rho0": quick_measure(base12, rho_force=0.0),
             "arkv_mixed_rho0.5": quick_measure(base12, rho_force=0.5),
             "arkv_scored_rho": quick_measure(base12),
+            "quant_all_kept_rho0_fp8_rows": quick_measure(base12.scaled(bits=8), rho_force=0.0),
+            "arkv_mixed_rho0.5_fp8_rows": quick_measure(base12.scaled(bits=8), rho_force=0.5),
             "arkv_scored_rho_tailor_every_step": quick_measure(base12.scaled(n_layers=4), every_step=True),
         }
         ref = pol["base_full_cache"]["steps_per_s_per_layer_batch"]

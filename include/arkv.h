@@ -46,7 +46,9 @@ typedef struct {
   float   alpha;            /* slack factor of Top-b, b = floor(alpha (N-W)) (eq. 10); default 0.75 */
   float   gamma;            /* weight of the variance in the heavy-hitter score (eq. 9); default 263.81 */
   float   tau[3];           /* temperatures of the OQ score (eq. 6); default 7.774, 5.407, 5.528 */
-  int32_t quant_bits;       /* bits per channel of a Quantized token: 4 or 2 */
+  int32_t quant_bits;       /* format of a Quantized token: 4 or 2 = uniform codes, groups of 32 channels, fp16
+                             * scale and zero per group; 8 = fp8 E4M3 codes with one fp16 scale per K (V) row
+                             * (Alg. 1 "Reconstruction Before Attention": x~ = q^ * s, per-token scale) */
   int32_t group_size;       /* channels per scale/zero pair: 32 */
   int32_t tailor_policy;    /* 0: tailor when the cache is full, keeping b = floor(alpha (N-W)) tokens (Sec. IV-F,
                                last paragraph: slack factor); 1: no slack, b = N-W-1, i.e. a tailor at every step once
@@ -60,7 +62,7 @@ int arkv_config_default(arkv_config* cfg);
  * rows, per-slot position / score accumulators, the latest queries per unit) and returns the cache in *out.
  * Synchronous.  ARKV_EINVAL: null pointers, non-positive shapes, W >= N - 1, alpha outside (0,1],
  * gamma < 0, group_size != 32.  ARKV_EUNSUPPORTED: head_dim not in {64,128}, G not in {1,2,4,8}, G*W > 512,
- * quant_bits not in {2,4}. */
+ * quant_bits not in {2,4,8}. */
 int arkv_cache_create(const arkv_config* cfg, arkv_cache** out);
 
 /* Frees everything.  Synchronises the device first.  NULL is accepted. */
@@ -125,7 +127,8 @@ int arkv_decode_step_layers(arkv_cache* cache, int32_t layer_begin, int32_t n, c
 /* ---- observability and parity hooks: HOST outputs, synchronise the cache's last stream ---- */
 
 /* Per unit of one layer, arrays [B][H_kv]: Original / Quantized token counts and live bytes
- * n_o*4d + n_q*2*(d*bits/8 + 4*d/32) (the left side of eq. 1 for that unit), and the number of tokens
+ * n_o*4d + n_q*C_q, C_q = 2*(d*bits/8 + 4*d/32) or 2*(d + 2) for fp8 rows (the left side of eq. 1 for that
+ * unit), and the number of tokens
  * evicted so far (positions seen minus live tokens).  Any pointer may be NULL. */
 int arkv_cache_counters(arkv_cache* cache, int32_t layer, int32_t* n_original, int32_t* n_quantized,
                         int32_t* n_evicted, int64_t* live_bytes);
@@ -134,8 +137,9 @@ int arkv_cache_counters(arkv_cache* cache, int32_t layer, int32_t* n_original, i
  * may be NULL.  n_live [U]; pos, state [U][max_tokens]; s1, s2 [U][max_tokens] running sums of
  * attention and squared attention; rows_k, rows_v bf16 [U][max_tokens][d] (Original tokens, else 0);
  * codes_k, codes_v uint8 [U][max_tokens][d*bits/8] in canonical packing (channel c of a 4-bit row in
- * byte c/2 bits 4(c%2)..; of a 2-bit row in byte c/4 bits 2(c%4)..); scale_*, zero_* fp16 bits
- * [U][max_tokens][d/32] (Quantized tokens, else 0).  U = B*H_kv. */
+ * byte c/2 bits 4(c%2)..; of a 2-bit row in byte c/4 bits 2(c%4)..; of an fp8 row in byte c); scale_*,
+ * zero_* fp16 bits [U][max_tokens][d/32], for fp8 rows [U][max_tokens][1] with zero_* = 0 (Quantized
+ * tokens, else 0).  U = B*H_kv. */
 int arkv_cache_export(arkv_cache* cache, int32_t layer, int32_t max_tokens, int32_t* n_live,
                       int32_t* pos, uint8_t* state, float* s1, float* s2,
                       uint16_t* rows_k, uint16_t* rows_v, uint8_t* codes_k, uint8_t* codes_v,

@@ -210,7 +210,7 @@ def arkv_cache_export(cache, layer, cfg: arkv_config, rows=True, codes=True):
     """Returns a dict of NumPy arrays, tokens of every unit sorted by position (see arkv.h)."""
     U = cfg.batch * cfg.n_kv_heads
     MT, d = cfg.capacity_tokens, cfg.head_dim
-    CB, NG = d * cfg.quant_bits // 8, d // 32
+    CB, NG = d * cfg.quant_bits // 8, (1 if cfg.quant_bits == 8 else d // 32)
     out = dict(
         n_live=np.zeros(U, np.int32), pos=np.full((U, MT), -1, np.int32), state=np.full((U, MT), 255, np.uint8),
         s1=np.zeros((U, MT), np.float32), s2=np.zeros((U, MT), np.float32),

@@ -150,52 +150,112 @@ __device__ __forceinline__ f32x4 dots_bf16(const uint4 (&qa)[KK], const uint4 (&
   return C;
 }
 
-// What the packed-row path needs of a query: the code-order permutation of its operand and, per head
-// and quantisation group, the sum over the group's channels (an MFMA against an all-ones tile).
-template <int KK, int HPL>
-struct PackedQuery { uint4 qp[KK]; float qs[KK][HPL]; };
-template <int KK, int HPL>
-__device__ __forceinline__ void prep_packed_query(const uint4 (&qa)[KK], PackedQuery<KK, HPL>& pq) {
-  const uint4 ones = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
+// ---- packed row formats -------------------------------------------------------------------------
+// PackedFmt<D, HPL, BITS> gives the attention loop what it needs of a Quantized row: what to keep of a
+// query, how lane (token lane%16, block lane/16) loads the key codes of row rk and turns them into the
+// token's HPL dot products, and how lane (row, 8-channel chunk `sub`) loads and decodes values.
+//
+// BITS = 2, 4: uniform codes, groups of 32 channels, fp16 scale and zero per group.  Codes are OR-ed into
+// bf16 "128 + code" operands, one MFMA per group; scale, zero and the 128 offset are applied to the
+// per-group results, which needs the query's per-group channel sums (an MFMA against an all-ones tile).
+template <int D, int HPL, int BITS>
+struct PackedFmt {
+  static constexpr int KK = D / 32, CB = D * BITS / 8, NG = D / kGroup, CW = BITS;
+  struct Query { uint4 qp[KK]; float qs[KK][HPL]; };
+  struct Keys { uint32_t cw[KK], meta[KK]; };
+  struct Vals { uint32_t cw, meta; };
+  static __device__ __forceinline__ void prep(const uint4 (&qa)[KK], Query& q) {
+    const uint4 ones = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk) {
-    f32x4 C = {0.f, 0.f, 0.f, 0.f};
-    C = mfma16(qa[kk], ones, C);
+    for (int kk = 0; kk < KK; ++kk) {
+      f32x4 C = {0.f, 0.f, 0.f, 0.f};
+      C = mfma16(qa[kk], ones, C);
 #pragma unroll
-    for (int i = 0; i < HPL; ++i) pq.qs[kk][i] = C[i];
-    pq.qp[kk] = permute_for_codes(qa[kk]);
+      for (int i = 0; i < HPL; ++i) q.qs[kk][i] = C[i];
+      q.qp[kk] = permute_for_codes(qa[kk]);
+    }
   }
-}
+  static __device__ __forceinline__ void load_keys(const uint8_t* kc, const uint32_t* km, int rk, int blk, Keys& k) {
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const uint8_t* p = kc + (unsigned)rk * CB + kk * (4 * CW) + blk * CW;
+      k.cw[kk] = BITS == 4 ? *reinterpret_cast<const uint32_t*>(p) : (uint32_t)*reinterpret_cast<const uint16_t*>(p);
+      k.meta[kk] = km[(unsigned)rk * NG + kk];
+    }
+  }
+  static __device__ __forceinline__ void dots(const Query& q, const Keys& k, float (&x)[HPL]) {
+#pragma unroll
+    for (int i = 0; i < HPL; ++i) x[i] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      f32x4 C = {0.f, 0.f, 0.f, 0.f};
+      C = mfma16(q.qp[kk], codes_to_bf16_biased<BITS>(k.cw[kk]), C);
+      const float sc = half_bits_to_float(k.meta[kk]), z = half_bits_to_float(k.meta[kk] >> 16);
+#pragma unroll
+      for (int i = 0; i < HPL; ++i) x[i] += fmaf(sc, C[i] - 128.0f * q.qs[kk][i], z * q.qs[kk][i]);
+    }
+  }
+  static __device__ __forceinline__ void load_vals(const uint8_t* vc, const uint32_t* vm, int rv, int sub, Vals& v) {
+    const uint8_t* p = vc + (unsigned)rv * CB + sub * CW;
+    v.cw = BITS == 4 ? *reinterpret_cast<const uint32_t*>(p) : (uint32_t)*reinterpret_cast<const uint16_t*>(p);
+    v.meta = vm[(unsigned)rv * NG + sub / 4];
+  }
+  static __device__ __forceinline__ void value_row(const Vals& v, float (&f)[8]) { dequant8<BITS>(v.cw, v.meta, f); }
+};
 
-// Dot products with 16 packed key rows: codes are OR-ed into bf16 "128 + code" operands, one MFMA per
-// quantisation group; scale, zero and the 128 offset are applied to the per-group results.
-template <int KK, int HPL, int BITS>
-__device__ __forceinline__ void dots_packed(const PackedQuery<KK, HPL>& pq, const uint32_t (&kcw)[KK],
-                                            const uint32_t (&kmeta)[KK], float (&x)[HPL]) {
+// BITS = 8: the paper's own format (Alg. 1 "Reconstruction Before Attention", x~ = q^ * s): one fp8 E4M3
+// byte per channel and one fp16 scale per row.  Every E4M3 value is a bf16 value, so the codes become MFMA
+// operands by conversion alone and the row scale multiplies the finished dot product.
+__device__ __forceinline__ void fp8x8_to_f32(const uint2& w, float (&f)[8]) {
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w.x, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w.x, true);
+  const f32x2 c = __builtin_amdgcn_cvt_pk_f32_fp8((int)w.y, false), d = __builtin_amdgcn_cvt_pk_f32_fp8((int)w.y, true);
+  f[0] = a[0]; f[1] = a[1]; f[2] = b[0]; f[3] = b[1]; f[4] = c[0]; f[5] = c[1]; f[6] = d[0]; f[7] = d[1];
+}
+__device__ __forceinline__ uint4 fp8x8_to_bf16x8(const uint2& w) {
+  float f[8];
+  fp8x8_to_f32(w, f);
+  uint4 r;   // exact: an E4M3 value has 4 significant bits
+  r.x = (__float_as_uint(f[0]) >> 16) | (__float_as_uint(f[1]) & 0xffff0000u);
+  r.y = (__float_as_uint(f[2]) >> 16) | (__float_as_uint(f[3]) & 0xffff0000u);
+  r.z = (__float_as_uint(f[4]) >> 16) | (__float_as_uint(f[5]) & 0xffff0000u);
+  r.w = (__float_as_uint(f[6]) >> 16) | (__float_as_uint(f[7]) & 0xffff0000u);
+  return r;
+}
+template <int D, int HPL>
+struct PackedFmt<D, HPL, 8> {
+  static constexpr int KK = D / 32, CB = D, NG = 1;
+  struct Query { uint4 q[KK]; };
+  struct Keys { uint2 cw[KK]; uint32_t meta; };
+  struct Vals { uint2 cw; uint32_t meta; };
+  static __device__ __forceinline__ void prep(const uint4 (&qa)[KK], Query& q) {
 #pragma unroll
-  for (int i = 0; i < HPL; ++i) x[i] = 0.f;
+    for (int kk = 0; kk < KK; ++kk) q.q[kk] = qa[kk];
+  }
+  static __device__ __forceinline__ void load_keys(const uint8_t* kc, const uint32_t* km, int rk, int blk, Keys& k) {
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk) {
+    for (int kk = 0; kk < KK; ++kk) k.cw[kk] = *reinterpret_cast<const uint2*>(kc + (unsigned)rk * CB + 32 * kk + 8 * blk);
+    k.meta = km[rk];
+  }
+  static __device__ __forceinline__ void dots(const Query& q, const Keys& k, float (&x)[HPL]) {
     f32x4 C = {0.f, 0.f, 0.f, 0.f};
-    C = mfma16(pq.qp[kk], codes_to_bf16_biased<BITS>(kcw[kk]), C);
-    const float sc = half_bits_to_float(kmeta[kk]), z = half_bits_to_float(kmeta[kk] >> 16);
 #pragma unroll
-    for (int i = 0; i < HPL; ++i) x[i] += fmaf(sc, C[i] - 128.0f * pq.qs[kk][i], z * pq.qs[kk][i]);
-  }
-}
-
-// Key codes and group metadata of row rk for lane (token lane%16, block lane/16).
-template <int D, int BITS>
-__device__ __forceinline__ void load_packed_keys(const uint8_t* kc, const uint32_t* km, int rk, int blk,
-                                                 uint32_t (&kcw)[D / 32], uint32_t (&kmeta)[D / 32]) {
-  constexpr int CB = D * BITS / 8, CW = BITS, NG = D / kGroup;
+    for (int kk = 0; kk < KK; ++kk) C = mfma16(q.q[kk], fp8x8_to_bf16x8(k.cw[kk]), C);
+    const float sc = half_bits_to_float(k.meta);
 #pragma unroll
-  for (int kk = 0; kk < D / 32; ++kk) {
-    const uint8_t* p = kc + (unsigned)rk * CB + kk * (4 * CW) + blk * CW;
-    kcw[kk] = BITS == 4 ? *reinterpret_cast<const uint32_t*>(p) : (uint32_t)*reinterpret_cast<const uint16_t*>(p);
-    kmeta[kk] = km[(unsigned)rk * NG + kk];
+    for (int i = 0; i < HPL; ++i) x[i] = C[i] * sc;
   }
-}
+  static __device__ __forceinline__ void load_vals(const uint8_t* vc, const uint32_t* vm, int rv, int sub, Vals& v) {
+    v.cw = *reinterpret_cast<const uint2*>(vc + (unsigned)rv * CB + 8 * sub);
+    v.meta = vm[rv];
+  }
+  static __device__ __forceinline__ void value_row(const Vals& v, float (&f)[8]) {
+    fp8x8_to_f32(v.cw, f);
+    const float sc = half_bits_to_float(v.meta);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) f[c] *= sc;
+  }
+};
 
 // Eq. 9 running moments: the lane's HPL logits of one token (base-2 units) -> probabilities with the
 // step's final (max, 1/sum) -> their sum and sum of squares over the unit's heads, valid in block 0.
@@ -323,9 +383,6 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   constexpr int NV = 16 / R;           // value loads per tile
   constexpr int HB = (G + 3) / 4;      // lane blocks holding real heads
   constexpr int HPL = G < 4 ? G : 4;   // heads per lane
-  constexpr int CB = D * BITS / 8;     // code bytes per row
-  constexpr int NG = D / kGroup;
-  constexpr int CW = BITS;             // code bytes per 8 channels
   const int s = blockIdx.x, lu = blockIdx.y;
   const int gu = L.unit_begin + lu;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -527,35 +584,31 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   TRACE(3);
   // ---------------- Quantized rows ----------------
   if (aq < bq) {
-    const uint8_t* kc = P.qkc + (size_t)gu * P.capQ * CB;
-    const uint8_t* vc = P.qvc + (size_t)gu * P.capQ * CB;
-    const uint32_t* km = P.qkm + (size_t)gu * P.capQ * NG;
-    const uint32_t* vm = P.qvm + (size_t)gu * P.capQ * NG;
-    PackedQuery<KK, HPL> pqa, pqb;
-    prep_packed_query<KK, HPL>(qa, pqa);
-    prep_packed_query<KK, HPL>(qb, pqb);
-    struct QTile { uint32_t kcw[KK]; uint32_t kmeta[KK]; uint32_t vcw[NV]; uint32_t vmeta[NV]; float2 ac; };
+    using Fmt = PackedFmt<D, HPL, BITS>;
+    const uint8_t* kc = P.qkc + (size_t)gu * P.capQ * Fmt::CB;
+    const uint8_t* vc = P.qvc + (size_t)gu * P.capQ * Fmt::CB;
+    const uint32_t* km = P.qkm + (size_t)gu * P.capQ * Fmt::NG;
+    const uint32_t* vm = P.qvm + (size_t)gu * P.capQ * Fmt::NG;
+    typename Fmt::Query pqa, pqb;
+    Fmt::prep(qa, pqa);
+    Fmt::prep(qb, pqb);
+    struct QTile { typename Fmt::Keys k; typename Fmt::Vals v[NV]; float2 ac; };
     auto load_q = [&](QTile& t, int row0) {
       const int rk = min(row0 + tok, bq - 1);
-      load_packed_keys<D, BITS>(kc, km, rk, blk, t.kcw, t.kmeta);
+      Fmt::load_keys(kc, km, rk, blk, t.k);
 #pragma unroll
-      for (int j = 0; j < NV; ++j) {
-        const int rv = min(row0 + R * j + vrow, bq - 1);
-        const uint8_t* p = vc + (unsigned)rv * CB + sub * CW;
-        t.vcw[j] = BITS == 4 ? *reinterpret_cast<const uint32_t*>(p) : (uint32_t)*reinterpret_cast<const uint16_t*>(p);
-        t.vmeta[j] = vm[(unsigned)rv * NG + sub / 4];
-      }
+      for (int j = 0; j < NV; ++j) Fmt::load_vals(vc, vm, min(row0 + R * j + vrow, bq - 1), sub, t.v[j]);
       t.ac = qacc_[rk];
     };
     auto compute_q = [&](const QTile& t, int row0) {
       const bool own = (row0 + tok < bq) && active;
       float x[HPL], xp[HPL];
-      dots_packed<KK, HPL, BITS>(pqa, t.kcw, t.kmeta, x);
-      dots_packed<KK, HPL, BITS>(pqb, t.kcw, t.kmeta, xp);
+      Fmt::dots(pqa, t.k, x);
+      Fmt::dots(pqb, t.k, xp);
 #pragma unroll
       for (int i = 0; i < HPL; ++i) { x[i] = own ? x[i] * scale2 : kNegBig; xp[i] *= scale2_prev; }
       fold_prev(xp, t.ac, own, qacc_, min(row0 + tok, bq - 1));
-      softmax_pv(own, x, [&](int j, float (&f)[8]) { dequant8<BITS>(t.vcw[j], t.vmeta[j], f); });
+      softmax_pv(own, x, [&](int j, float (&f)[8]) { Fmt::value_row(t.v[j], f); });
     };
     QTile ta, tb;
     int row0 = aq + 16 * w;
@@ -638,8 +691,6 @@ __global__ __launch_bounds__(256) void k_flush_scores(Pools P, int unit_begin, i
   constexpr int KK = D / 32;
   constexpr int HB = (G + 3) / 4;
   constexpr int HPL = G < 4 ? G : 4;
-  constexpr int CB = D * BITS / 8;
-  constexpr int NG = D / kGroup;
   const int gu = unit_begin + blockIdx.y;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int tok = lane & 15, blk = lane >> 4;
@@ -678,18 +729,19 @@ __global__ __launch_bounds__(256) void k_flush_scores(Pools P, int unit_begin, i
     }
   }
   if (cnt.y > 0) {
-    const uint8_t* kc = P.qkc + (size_t)gu * P.capQ * CB;
-    const uint32_t* km = P.qkm + (size_t)gu * P.capQ * NG;
+    using Fmt = PackedFmt<D, HPL, BITS>;
+    const uint8_t* kc = P.qkc + (size_t)gu * P.capQ * Fmt::CB;
+    const uint32_t* km = P.qkm + (size_t)gu * P.capQ * Fmt::NG;
     float2* acc = P.qacc + (size_t)gu * P.capQ;
-    PackedQuery<KK, HPL> pqb;
-    prep_packed_query<KK, HPL>(qb, pqb);
+    typename Fmt::Query pqb;
+    Fmt::prep(qb, pqb);
     for (int row0 = 16 * wave; row0 < cnt.y; row0 += step) {
       const int rk = min(row0 + tok, cnt.y - 1);
-      uint32_t kcw[KK], kmeta[KK];
-      load_packed_keys<D, BITS>(kc, km, rk, blk, kcw, kmeta);
+      typename Fmt::Keys k;
+      Fmt::load_keys(kc, km, rk, blk, k);
       const float2 ac = acc[rk];
       float xp[HPL];
-      dots_packed<KK, HPL, BITS>(pqb, kcw, kmeta, xp);
+      Fmt::dots(pqb, k, xp);
 #pragma unroll
       for (int i = 0; i < HPL; ++i) xp[i] *= scale2_prev;
       const float2 m = prob_moments<HPL, HB>(xp, pm, pinv);
@@ -716,6 +768,7 @@ static hipError_t launch_decode_t(const Pools& P, const DecodeLaunch& a, hipStre
 
 template <int D, int G>
 static hipError_t launch_decode_b(const Pools& P, const DecodeLaunch& a, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
+  if (P.bits == 8) return launch_decode_t<D, G, 8>(P, a, s, e0, e1);
   return P.bits == 4 ? launch_decode_t<D, G, 4>(P, a, s, e0, e1) : launch_decode_t<D, G, 2>(P, a, s, e0, e1);
 }
 
@@ -808,7 +861,8 @@ hipError_t launch_stream_read(const void* buf, size_t offset_bytes, size_t bytes
 
 template <int D, int G>
 static hipError_t launch_flush_b(const Pools& P, dim3 grid, int unit_begin, int parity, hipStream_t s) {
-  if (P.bits == 4) hipLaunchKernelGGL((k_flush_scores<D, G, 4>), grid, dim3(256), 0, s, P, unit_begin, parity);
+  if (P.bits == 8) hipLaunchKernelGGL((k_flush_scores<D, G, 8>), grid, dim3(256), 0, s, P, unit_begin, parity);
+  else if (P.bits == 4) hipLaunchKernelGGL((k_flush_scores<D, G, 4>), grid, dim3(256), 0, s, P, unit_begin, parity);
   else hipLaunchKernelGGL((k_flush_scores<D, G, 2>), grid, dim3(256), 0, s, P, unit_begin, parity);
   return hipGetLastError();
 }

@@ -14,6 +14,9 @@ constexpr int kMaxUnitsKnown = 64;     // launches with at most this many units 
 // launch over several layers is just a launch over more units.  "O pool": bf16 rows of Original
 // tokens, slots [0, cnt.x) dense.  "Q pool": packed rows of Quantized tokens, slots [0, cnt.y) dense.
 // A tailor compacts both pools in place; between tailors tokens are only appended to the O pool.
+// 32-bit metadata words of one packed K (or V) row
+__host__ __device__ constexpr int metas_per_row(int D, int bits) { return bits == 8 ? 1 : D / kGroup; }
+
 struct Pools {
   int U;                // units per layer
   int capO, capQ;       // slots per unit: N and b
@@ -24,10 +27,10 @@ struct Pools {
   int32_t*  opos;       // [LU][capO] position of the token in the sequence
   float2*   oacc;       // [LU][capO] (s1, s2): running sums of attention and attention^2 (eq. 9)
   // Q pool
-  uint8_t*  qkc;        // [LU][capQ][D*bits/8] key codes, canonical packing
+  uint8_t*  qkc;        // [LU][capQ][D*bits/8] key codes, canonical packing (bits = 8: one fp8 E4M3 byte per channel)
   uint8_t*  qvc;        // [LU][capQ][D*bits/8]
-  uint32_t* qkm;        // [LU][capQ][D/32] (fp16 scale | fp16 zero << 16)
-  uint32_t* qvm;        // [LU][capQ][D/32]
+  uint32_t* qkm;        // [LU][capQ][metas_per_row] (fp16 scale | fp16 zero << 16) per group; bits = 8: one fp16 scale per row
+  uint32_t* qvm;        // [LU][capQ][metas_per_row]
   int32_t*  qpos;       // [LU][capQ]
   float2*   qacc;       // [LU][capQ]
   // per unit

@@ -76,7 +76,7 @@ static int validate(const arkv_config* c) {
   const int G = c->n_q_heads / c->n_kv_heads;
   if (c->head_dim != 64 && c->head_dim != 128) return ARKV_EUNSUPPORTED;
   if (G != 1 && G != 2 && G != 4 && G != 8) return ARKV_EUNSUPPORTED;
-  if (c->quant_bits != 2 && c->quant_bits != 4) return ARKV_EUNSUPPORTED;
+  if (c->quant_bits != 2 && c->quant_bits != 4 && c->quant_bits != 8) return ARKV_EUNSUPPORTED;
   if (G * c->window > 512) return ARKV_EUNSUPPORTED;
   return ARKV_OK;
 }
@@ -200,7 +200,7 @@ int arkv_cache_create(const arkv_config* cfg, arkv_cache** out) {
   P.G = cfg->n_q_heads / cfg->n_kv_heads;
   P.bits = cfg->quant_bits;
   const size_t LU = (size_t)c->L * c->U, D = (size_t)P.D, G = (size_t)P.G;
-  const size_t CB = D * P.bits / 8, NG = D / kGroup;
+  const size_t CB = D * P.bits / 8, NG = (size_t)metas_per_row(P.D, P.bits);
   P.fin_stride = LU * G;
   P.plan_stride = kPlanHdr + 3 * P.capO + 2 * P.capQ;
   if (const char* e = getenv("ARKV_WG_TARGET")) c->wg_target = std::max(1, atoi(e));
@@ -433,7 +433,8 @@ int arkv_cache_counters(arkv_cache* c, int32_t layer, int32_t* n_original, int32
   std::vector<int2> cnt;
   int rc = fetch(cnt, c->P.cnt + (size_t)layer * c->U, (size_t)c->U);
   if (rc != ARKV_OK) return rc;
-  const int64_t d = c->P.D, co = 4 * d, cq = 2 * (d * c->P.bits / 8 + (d / kGroup) * 4);
+  const int64_t d = c->P.D, co = 4 * d;
+  const int64_t cq = c->P.bits == 8 ? 2 * (d + 2) : 2 * (d * c->P.bits / 8 + (d / kGroup) * 4);
   for (int u = 0; u < c->U; ++u) {
     if (n_original) n_original[u] = cnt[(size_t)u].x;
     if (n_quantized) n_quantized[u] = cnt[(size_t)u].y;
@@ -462,7 +463,7 @@ int arkv_cache_export(arkv_cache* c, int32_t layer, int32_t max_tokens, int32_t*
   if (rc != ARKV_OK) return rc;
   const Pools& P = c->P;
   const size_t U = (size_t)c->U, off = (size_t)layer * U, D = (size_t)P.D;
-  const size_t CB = D * P.bits / 8, NG = D / kGroup, cO = (size_t)P.capO, cQ = (size_t)P.capQ;
+  const size_t CB = D * P.bits / 8, NG = (size_t)metas_per_row(P.D, P.bits), cO = (size_t)P.capO, cQ = (size_t)P.capQ;
   std::vector<int2> cnt;
   std::vector<int32_t> opos, qpos;
   std::vector<float2> oacc, qacc;

@@ -299,32 +299,87 @@ __device__ __forceinline__ void unpack8(const uint4& r, float (&f)[8]) {
   f[6] = __uint_as_float(r.w << 16); f[7] = __uint_as_float(r.w & 0xffff0000u);
 }
 
+// fp8 rows with one scale per token (Alg. 1 "Reconstruction Before Attention": x~ = q^ * s).
+// |t| <= 448 -> nearest E4M3 code (sign, 4 exponent bits with bias 7, 3 mantissa bits, subnormals below
+// 2^-6, no infinities), ties to the even code, in integer arithmetic on the fp32 bits.
+__device__ __forceinline__ uint32_t e4m3_code(float t) {
+  const float a = fminf(fabsf(t), 448.0f);
+  uint32_t code;
+  if (a < 0.015625f) {
+    code = (uint32_t)rintf(a * 512.0f);             // subnormals are multiples of 2^-9; 8 = the smallest normal
+  } else {
+    uint32_t b = __float_as_uint(a);
+    b += 0x7FFFFu + ((b >> 20) & 1u);               // round to 3 mantissa bits, ties to even
+    code = (((b >> 23) - 120u) << 3) | ((b >> 20) & 7u);
+  }
+  return code;
+}
+
+// x: the 8 channels of this lane; the LPR lanes of a row share one scale.
+// Returns the lane's 8 codes (byte c = channel c) and the row's scale (fp16 bits).
+template <int LPR>
+__device__ __forceinline__ void quantize8_fp8(const float (&x)[8], uint2& codes, uint32_t& meta) {
+  float amax = fabsf(x[0]);
+#pragma unroll
+  for (int c = 1; c < 8; ++c) amax = fmaxf(amax, fabsf(x[c]));
+  amax = fmaxf(amax, dppf<0xB1>(amax));
+  amax = fmaxf(amax, dppf<0x4E>(amax));
+  amax = fmaxf(amax, dppf<0x141>(amax));             // 8 lanes
+  if (LPR == 16) amax = fmaxf(amax, dppf<0x140>(amax));
+  uint16_t sh = 0;
+  codes = make_uint2(0, 0);
+  if (amax != 0.0f) {
+    const float s = amax / 448.0f;
+    sh = f2h(s);
+    float sc = h2f(sh);
+    if (sc * 448.0f < amax) { sh = h_next_up(sh); sc = h2f(sh); }
+    uint32_t w[2] = {0, 0};
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const uint32_t code = e4m3_code(x[c] / sc) | (x[c] < 0.0f ? 0x80u : 0u);
+      w[c >> 2] |= code << (8 * (c & 3));
+    }
+    codes = make_uint2(w[0], w[1]);
+  }
+  meta = sh;
+}
+
 // One wave: lanes [0,LPR) quantise the K row, lanes [LPR,2LPR) the V row, into Q slot dst of unit gu.
 template <int D, int BITS>
 __device__ __forceinline__ void quantize_into(const Pools& P, int gu, int dst, const uint16_t* krow,
                                               const uint16_t* vrow, int lane) {
-  constexpr int LPR = D / 8, CB = D * BITS / 8, NG = D / kGroup;
+  constexpr int LPR = D / 8, CB = D * BITS / 8, NG = metas_per_row(D, BITS);
   const bool isv = lane >= LPR;
   const int sub = lane % LPR;
-  // all 64 lanes run the arithmetic (the quad exchanges need them active); lanes >= 2LPR redo V
+  // all 64 lanes run the arithmetic (the lane exchanges need them active); lanes >= 2LPR redo V
   const uint16_t* src = (isv ? vrow : krow) + sub * 8;
   const uint4 raw = *reinterpret_cast<const uint4*>(src);
   float x[8];
   unpack8(raw, x);
-  uint32_t codes, meta;
-  quantize8<BITS>(x, codes, meta);
-  if (lane < 2 * LPR) {
-    uint8_t* cdst = (isv ? P.qvc : P.qkc) + ((size_t)gu * P.capQ + dst) * CB;
-    uint32_t* mdst = (isv ? P.qvm : P.qkm) + ((size_t)gu * P.capQ + dst) * NG;
-    if (BITS == 4) *reinterpret_cast<uint32_t*>(cdst + sub * 4) = codes;
-    else *reinterpret_cast<uint16_t*>(cdst + sub * 2) = (uint16_t)codes;
-    if ((sub & 3) == 0) mdst[sub >> 2] = meta;
+  uint8_t* cdst = (isv ? P.qvc : P.qkc) + ((size_t)gu * P.capQ + dst) * CB;
+  uint32_t* mdst = (isv ? P.qvm : P.qkm) + ((size_t)gu * P.capQ + dst) * NG;
+  if constexpr (BITS == 8) {
+    uint2 codes;
+    uint32_t meta;
+    quantize8_fp8<LPR>(x, codes, meta);
+    if (lane < 2 * LPR) {
+      *reinterpret_cast<uint2*>(cdst + sub * 8) = codes;
+      if (sub == 0) mdst[0] = meta;
+    }
+  } else {
+    uint32_t codes, meta;
+    quantize8<BITS>(x, codes, meta);
+    if (lane < 2 * LPR) {
+      if (BITS == 4) *reinterpret_cast<uint32_t*>(cdst + sub * 4) = codes;
+      else *reinterpret_cast<uint16_t*>(cdst + sub * 2) = (uint16_t)codes;
+      if ((sub & 3) == 0) mdst[sub >> 2] = meta;
+    }
   }
 }
 
 template <int D, int BITS>
 __global__ __launch_bounds__(256) void k_tailor_move_q(Pools P, TailorLaunch L) {
-  constexpr int CB = D * BITS / 8, NG = D / kGroup;
+  constexpr int CB = D * BITS / 8, NG = metas_per_row(D, BITS);
   const int gu = L.unit_begin + blockIdx.y, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int32_t* plan = P.plan + (size_t)gu * P.plan_stride;
   const int nD = plan[PL_N_DEM], nM = plan[PL_N_QMOV];
@@ -470,6 +525,8 @@ hipError_t launch_tailor(const Pools& P, const TailorLaunch& a, hipStream_t s) {
   else if (P.D == 128 && P.bits == 2) launch_tailor_moves<128, 2>(P, a, s);
   else if (P.D == 64 && P.bits == 4) launch_tailor_moves<64, 4>(P, a, s);
   else if (P.D == 64 && P.bits == 2) launch_tailor_moves<64, 2>(P, a, s);
+  else if (P.D == 128 && P.bits == 8) launch_tailor_moves<128, 8>(P, a, s);
+  else if (P.D == 64 && P.bits == 8) launch_tailor_moves<64, 8>(P, a, s);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }
@@ -491,6 +548,8 @@ hipError_t launch_commit(const Pools& P, const CommitLaunch& a, uint64_t* ckeys,
   else if (P.D == 128 && P.bits == 2) launch_commit_scatter<128, 2>(P, a, s);
   else if (P.D == 64 && P.bits == 4) launch_commit_scatter<64, 4>(P, a, s);
   else if (P.D == 64 && P.bits == 2) launch_commit_scatter<64, 2>(P, a, s);
+  else if (P.D == 128 && P.bits == 8) launch_commit_scatter<128, 8>(P, a, s);
+  else if (P.D == 64 && P.bits == 8) launch_commit_scatter<64, 8>(P, a, s);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

@@ -65,7 +65,8 @@ def test_long_context_shape_scaled_2bit():
     _run(wl)
 
 
-@pytest.mark.parametrize("hq,hkv,d,bits", [(8, 1, 64, 4), (2, 2, 128, 2), (4, 2, 64, 2), (8, 8, 128, 4)])
+@pytest.mark.parametrize("hq,hkv,d,bits", [(8, 1, 64, 4), (2, 2, 128, 2), (4, 2, 64, 2), (8, 8, 128, 4),
+                                           (8, 2, 128, 8), (4, 2, 64, 8), (8, 1, 64, 8)])
 def test_group_sizes(hq, hkv, d, bits):
     wl = synth.C1.scaled(name=f"g{hq // hkv}_d{d}_b{bits}", n_q_heads=hq, n_kv_heads=hkv, head_dim=d, bits=bits,
                          prefill=300, budget_frac=0.3, decode_steps=30)
@@ -92,3 +93,10 @@ def test_wide_window():
     """Observation window of 128: G*W = 512 query rows per unit, 16 row tiles in the prefill scorer."""
     wl = synth.C1.scaled(name="wide_window", window=128, prefill=1500, decode_steps=12)
     _run(wl, check_every=4)
+
+
+@pytest.mark.parametrize("rho", [0.0, 0.5])
+def test_fp8_rows(rho):
+    """The paper's own Quantized format: fp8 codes with one scale per token row."""
+    wl = synth.C1.scaled(name="fp8", bits=8, head_dim=128, decode_steps=60)
+    _run(wl, rho=rho, check_every=6)
