@@ -398,32 +398,69 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   __shared__ float sm_m[4][G], sm_l[4][G];
   __shared__ int sm_last;
 
-  // token counts: from the launch arguments when the host knows them (a scalar load, no round trip to
-  // memory before the first tile can be requested), else from the unit's counters
+  // Everything the first tile request depends on is read from the launch arguments in ONE batch of scalar
+  // loads (the empty asm pins the values here); left to itself the compiler fetches each where it is first
+  // used, six dependent round trips before the first request to HBM.
   const int lk = lu < kMaxUnitsKnown ? lu : 0;
   int cO = L.cnt_o[lk], cQ = L.cnt_q[lk];
-  if (!L.cnt_known) {
+  const int known = L.cnt_known, wq = L.wq, splits = L.splits, parity = L.parity;
+  const int capO = P.capO, capQ = P.capQ;
+  const size_t fin_stride = P.fin_stride;
+  const uint16_t* const pok = P.ok;
+  const uint16_t* const pov = P.ov;
+  float2* const poacc = P.oacc;
+  float2* const pqacc = P.qacc;
+  const uint16_t* const pq = L.q;
+  const uint16_t* const pqprev = P.qprev;
+  const float* const pqscale = P.qscale;
+  const float2* const pfin = P.fin;
+  asm volatile("" ::"s"(cO), "s"(cQ), "s"(known), "s"(wq), "s"(splits), "s"(parity), "s"(capO), "s"(capQ),
+               "s"(fin_stride), "s"(pok), "s"(pov), "s"(poacc), "s"(pqacc), "s"(pq), "s"(pqprev), "s"(pqscale),
+               "s"(pfin));
+  // token counts: from the launch arguments when the host knows them, else from the unit's counters
+  if (!known) {
     const volatile int* cnt = reinterpret_cast<const volatile int*>(P.cnt + gu);
     cO = cnt[0]; cQ = cnt[1];
   }
 
   int ao, bo, aq, bq;
-  split_range(cO, cQ, L.wq, L.splits, s, ao, bo, aq, bq);
+  split_range(cO, cQ, wq, splits, s, ao, bo, aq, bq);
 
-  const uint16_t* ok_ = P.ok + (size_t)gu * P.capO * D;
-  const uint16_t* ov_ = P.ov + (size_t)gu * P.capO * D;
-  float2* oacc_ = P.oacc + (size_t)gu * P.capO;
-  float2* qacc_ = P.qacc + (size_t)gu * P.capQ;
+  const uint16_t* ok_ = pok + (size_t)gu * capO * D;
+  const uint16_t* ov_ = pov + (size_t)gu * capO * D;
+  float2* oacc_ = poacc + (size_t)gu * capO;
+  float2* qacc_ = pqacc + (size_t)gu * capQ;
+
+  struct OTile { uint4 kb[KK]; uint4 vr[NV]; float2 ac; };
+  auto load_o = [&](OTile& t, int row0) {
+    const int rk = min(row0 + tok, bo - 1);
+    {
+      const unsigned off = (unsigned)rk * (2 * D) + 16 * blk;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+        t.kb[kk] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(ok_) + off + 64 * kk);
+    }
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int rv = min(row0 + R * j + vrow, bo - 1);
+      t.vr[j] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(ov_) + (unsigned)rv * (2 * D) + 16 * sub);
+    }
+    t.ac = oacc_[rk];
+  };
+  // the first tile is requested before anything else touches memory
+  OTile ta, tb;
+  if (ao < bo) load_o(ta, ao + 16 * w);
+  TRACE(1);
 
   // this step's query and the previous step's (kept per unit, ping-pong by step parity), its scale and
   // its final softmax constants for the lane's heads
   uint4 qa[KK], qb[KK];
-  load_query<D, G>(L.q + (size_t)lu * G * D, lane, qa);
-  load_query<D, G>(P.qprev + ((size_t)L.parity * P.fin_stride + (size_t)gu * G) * D, lane, qb);
-  const float scale2_prev = P.qscale[(size_t)L.parity * (P.fin_stride / G) + gu];
+  load_query<D, G>(pq + (size_t)lu * G * D, lane, qa);
+  load_query<D, G>(pqprev + ((size_t)parity * fin_stride + (size_t)gu * G) * D, lane, qb);
+  const float scale2_prev = pqscale[(size_t)parity * (fin_stride / G) + gu];
   float pm[HPL], pinv[HPL];
   {
-    const float2* f = P.fin + (size_t)L.parity * P.fin_stride + (size_t)gu * G;
+    const float2* f = pfin + (size_t)parity * fin_stride + (size_t)gu * G;
 #pragma unroll
     for (int i = 0; i < HPL; ++i) {
       const float2 t = f[active ? 4 * blk + i : i];
@@ -499,22 +536,6 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   };
 
   // ---------------- Original rows ----------------
-  struct OTile { uint4 kb[KK]; uint4 vr[NV]; float2 ac; };
-  auto load_o = [&](OTile& t, int row0) {
-    const int rk = min(row0 + tok, bo - 1);
-    {
-      const unsigned off = (unsigned)rk * (2 * D) + 16 * blk;
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk)
-        t.kb[kk] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(ok_) + off + 64 * kk);
-    }
-#pragma unroll
-    for (int j = 0; j < NV; ++j) {
-      const int rv = min(row0 + R * j + vrow, bo - 1);
-      t.vr[j] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(ov_) + (unsigned)rv * (2 * D) + 16 * sub);
-    }
-    t.ac = oacc_[rk];
-  };
   auto compute_o = [&](const OTile& t, int row0) {
     const f32x4 C = dots_bf16<KK>(qa, t.kb);
     const f32x4 Cp = dots_bf16<KK>(qb, t.kb);
@@ -529,10 +550,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
     // two tiles in registers: while one is consumed the other is in flight.  Loads past the end of the
     // range are clamped to its last row; every load in the loop is unconditional so that the wait
     // counts the compiler derives are exact and a prefetch is never drained early.
-    OTile ta, tb;
     int row0 = ao + 16 * w;
-    load_o(ta, row0);
-    TRACE(1);
     for (; row0 + 128 < bo; row0 += 128) {      // this wave still has two more tiles after this one
       load_o(tb, row0 + 64);
       compute_o(ta, row0);
