@@ -272,6 +272,85 @@ __device__ __forceinline__ float2 prob_moments(const float (&x)[HPL], const floa
   return make_float2(s1, s2);
 }
 
+// ---- score update of the steps that wait for it -------------------------------------------------
+// Per unit the latest steps' queries, scales and final softmax constants sit in a ring (Pools::qprev,
+// qscale, fin).  A workgroup that is to add n waiting steps to (s1, s2) first copies their state to LDS;
+// then, per 16-token key tile, the logits of every waiting step are recomputed (same MFMA sequence on the
+// same bits as in the step itself), turned into probabilities and their moments added in step order.
+template <int D, int G>
+struct PendingLds {
+  uint16_t q[kRing - 1][G][D];       // query rows of waiting step j (0 = oldest)
+  float2 fin[kRing - 1][G];          // its final (max, 1/sum) per head
+  float scale[kRing - 1];            // its softmax scale * log2(e)
+};
+
+template <int D, int G>
+__device__ __forceinline__ void stage_pending(const Pools& P, int gu, int n, int slot, PendingLds<D, G>& sm, int tid,
+                                              int nthreads) {
+  const size_t LU = P.fin_stride / G;
+  for (int i = tid; i < n * (G * D / 8); i += nthreads) {
+    const int j = i / (G * D / 8), c = i % (G * D / 8);
+    const int sl = (slot - n + j + kRing) % kRing;
+    reinterpret_cast<uint4*>(&sm.q[j][0][0])[c] =
+        reinterpret_cast<const uint4*>(P.qprev + ((size_t)sl * P.fin_stride + (size_t)gu * G) * D)[c];
+  }
+  for (int i = tid; i < n * G; i += nthreads) {
+    const int j = i / G, h = i % G;
+    const int sl = (slot - n + j + kRing) % kRing;
+    sm.fin[j][h] = P.fin[(size_t)sl * P.fin_stride + (size_t)gu * G + h];
+    if (h == 0) sm.scale[j] = P.qscale[(size_t)sl * LU + gu];
+  }
+}
+
+// Adds the moments of the n waiting steps to (s1, s2) of the lane's token.  dots(qop, x) must fill x with
+// the token's raw dot products against query operand qop; a token takes part from waiting step `first` on
+// (it did not exist before).  The result is valid in lanes of block 0.
+//
+// The MFMA has 16 query rows and a step only needs G of them, so several waiting steps share one operand:
+// step j0 + b occupies rows [b*RPS, b*RPS + G).  Their logits land in different lane blocks, where the
+// probabilities and moments of up to four steps are computed by the same instructions; block 0 then
+// collects them and adds them in step order (the same fp32 additions as one step at a time).
+template <int D, int G, typename Dots>
+__device__ __forceinline__ float2 fold_pending(const PendingLds<D, G>& sm, int n, int first, float2 ac, int lane, Dots&& dots) {
+  constexpr int KK = D / 32, HB = (G + 3) / 4, HPL = G < 4 ? G : 4;
+  constexpr int RPS = G <= 4 ? 4 : 8;        // operand rows per step
+  constexpr int SPR = 16 / RPS;              // steps per round
+  const int tok = lane & 15, blk = lane >> 4;
+  for (int j0 = 0; j0 < n; j0 += SPR) {
+    uint4 qop[KK];
+    {
+      const int rstep = j0 + tok / RPS, rhead = tok % RPS;
+      const bool rvalid = rhead < G && rstep < n;
+      const uint16_t* src = &sm.q[rvalid ? rstep : 0][rvalid ? rhead : 0][8 * blk];
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const uint4 v = *reinterpret_cast<const uint4*>(src + 32 * kk);
+        qop[kk] = rvalid ? v : make_uint4(0, 0, 0, 0);
+      }
+    }
+    float x[HPL], pm[HPL], pinv[HPL];
+    dots(qop, x);
+    // this lane's results are rows 4*blk .. +3 of the operand: step js, heads h0 .. h0+3
+    const int js = min(j0 + (4 * blk) / RPS, n - 1), h0 = (4 * blk) % RPS;
+    const float sc = sm.scale[js];
+#pragma unroll
+    for (int i = 0; i < HPL; ++i) {
+      const float2 f = sm.fin[js][h0 + i];
+      pm[i] = f.x; pinv[i] = f.y;
+      x[i] *= sc;
+    }
+    const float2 m = prob_moments<HPL, HB>(x, pm, pinv);   // valid in the first block of every step
+#pragma unroll
+    for (int b = 0; b < SPR; ++b) {
+      const int srcl = tok + 16 * (b * RPS / 4);
+      const float mx = __shfl(m.x, srcl), my = __shfl(m.y, srcl);
+      const int j = j0 + b;
+      if (j < n && j >= first) { ac.x += mx; ac.y += my; }
+    }
+  }
+  return ac;
+}
+
 // Split-K partials cross workgroups that may sit on different XCDs, whose L2 caches are not coherent
 // with each other for ordinary accesses.  They are therefore written and read with device-scope relaxed
 // atomics (write-through stores, loads that do not hit a stale L2 line); no cache-wide flush is needed.
@@ -325,7 +404,7 @@ __device__ __forceinline__ void combine_splits(const Pools& P, const DecodeLaunc
       l = fmaf(cl[s][tid], w_, l);
     }
     cInv[tid] = 1.0f / l;
-    P.fin[(size_t)(L.parity ^ 1) * P.fin_stride + (size_t)gu * G + tid] = make_float2(M, 1.0f / l);
+    P.fin[(size_t)L.slot * P.fin_stride + (size_t)gu * G + tid] = make_float2(M, 1.0f / l);
   }
   __syncthreads();
   float o[NI];
@@ -375,7 +454,7 @@ __global__ void k_trace_mark(int slot) { if (threadIdx.x == 0) g_trace[8190][slo
 // layout (lane = 8 channels of one of 64/(D/8) rows), where PV runs on the vector ALU.  The softmax
 // reference maximum is only moved when a logit exceeds it by more than 8 (base-2 units), which is rare,
 // so the accumulators are almost never rescaled.
-template <int D, int G, int BITS>
+template <int D, int G, int BITS, bool FOLD>
 __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch L) {
   constexpr int KK = D / 32;           // MFMA k-steps = quantisation groups per row
   constexpr int LPR = D / 8;           // lanes per value row
@@ -397,13 +476,14 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   __shared__ float sm_a[4][G][D];
   __shared__ float sm_m[4][G], sm_l[4][G];
   __shared__ int sm_last;
+  __shared__ PendingLds<D, G> sm_pend;   // only touched when FOLD
 
   // Everything the first tile request depends on is read from the launch arguments in ONE batch of scalar
   // loads (the empty asm pins the values here); left to itself the compiler fetches each where it is first
   // used, six dependent round trips before the first request to HBM.
   const int lk = lu < kMaxUnitsKnown ? lu : 0;
   int cO = L.cnt_o[lk], cQ = L.cnt_q[lk];
-  const int known = L.cnt_known, wq = L.wq, splits = L.splits, parity = L.parity;
+  const int known = L.cnt_known, wq = L.wq, splits = L.splits, npend = L.n_pending;
   const int capO = P.capO, capQ = P.capQ;
   const size_t fin_stride = P.fin_stride;
   const uint16_t* const pok = P.ok;
@@ -411,12 +491,8 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   float2* const poacc = P.oacc;
   float2* const pqacc = P.qacc;
   const uint16_t* const pq = L.q;
-  const uint16_t* const pqprev = P.qprev;
-  const float* const pqscale = P.qscale;
-  const float2* const pfin = P.fin;
-  asm volatile("" ::"s"(cO), "s"(cQ), "s"(known), "s"(wq), "s"(splits), "s"(parity), "s"(capO), "s"(capQ),
-               "s"(fin_stride), "s"(pok), "s"(pov), "s"(poacc), "s"(pqacc), "s"(pq), "s"(pqprev), "s"(pqscale),
-               "s"(pfin));
+  asm volatile("" ::"s"(cO), "s"(cQ), "s"(known), "s"(wq), "s"(splits), "s"(npend), "s"(capO), "s"(capQ),
+               "s"(fin_stride), "s"(pok), "s"(pov), "s"(poacc), "s"(pqacc), "s"(pq));
   // token counts: from the launch arguments when the host knows them, else from the unit's counters
   if (!known) {
     const volatile int* cnt = reinterpret_cast<const volatile int*>(P.cnt + gu);
@@ -445,27 +521,19 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
       const int rv = min(row0 + R * j + vrow, bo - 1);
       t.vr[j] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(ov_) + (unsigned)rv * (2 * D) + 16 * sub);
     }
-    t.ac = oacc_[rk];
+    if constexpr (FOLD) t.ac = oacc_[rk];
   };
   // the first tile is requested before anything else touches memory
   OTile ta, tb;
   if (ao < bo) load_o(ta, ao + 16 * w);
   TRACE(1);
 
-  // this step's query and the previous step's (kept per unit, ping-pong by step parity), its scale and
-  // its final softmax constants for the lane's heads
-  uint4 qa[KK], qb[KK];
+  // this step's query; on a launch that also updates the scores, the waiting steps' state goes to LDS
+  uint4 qa[KK];
   load_query<D, G>(pq + (size_t)lu * G * D, lane, qa);
-  load_query<D, G>(pqprev + ((size_t)parity * fin_stride + (size_t)gu * G) * D, lane, qb);
-  const float scale2_prev = pqscale[(size_t)parity * (fin_stride / G) + gu];
-  float pm[HPL], pinv[HPL];
-  {
-    const float2* f = pfin + (size_t)parity * fin_stride + (size_t)gu * G;
-#pragma unroll
-    for (int i = 0; i < HPL; ++i) {
-      const float2 t = f[active ? 4 * blk + i : i];
-      pm[i] = t.x; pinv[i] = t.y;
-    }
+  if constexpr (FOLD) {
+    stage_pending<D, G>(P, gu, npend, L.slot, sm_pend, tid, 256);
+    __syncthreads();
   }
 
   float Mreg[HPL], lsum[HPL], acc[G][8];
@@ -527,23 +595,29 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
     __builtin_amdgcn_wave_barrier();
   };
 
-  // deferred score update of the lane's token: x[] are the previous step's logits (raw dot products
-  // times that step's scale).  The store is predicated: a skipped store only makes a later wait count
-  // conservative by one.
-  auto fold_prev = [&](const float (&xprev)[HPL], float2 ac, bool own, float2* acp, int row) {
-    const float2 m = prob_moments<HPL, HB>(xprev, pm, pinv);
-    if (own && blk == 0 && L.has_pending) acp[row] = make_float2(ac.x + m.x, ac.y + m.y);
+  // deferred score update of the lane's token (FOLD launches only).  The store is predicated: a skipped
+  // store only makes a later wait count conservative by one.
+  auto store_acc = [&](float2 ac, bool own, float2* acp, int row) {
+    if (own && blk == 0) acp[row] = ac;
   };
 
   // ---------------- Original rows ----------------
   auto compute_o = [&](const OTile& t, int row0) {
     const f32x4 C = dots_bf16<KK>(qa, t.kb);
-    const f32x4 Cp = dots_bf16<KK>(qb, t.kb);
     const bool own = (row0 + tok < bo) && active;
-    float x[HPL], xp[HPL];
+    float x[HPL];
 #pragma unroll
-    for (int i = 0; i < HPL; ++i) { x[i] = own ? C[i] * scale2 : kNegBig; xp[i] = Cp[i] * scale2_prev; }
-    fold_prev(xp, t.ac, own, oacc_, min(row0 + tok, bo - 1));
+    for (int i = 0; i < HPL; ++i) x[i] = own ? C[i] * scale2 : kNegBig;
+    if constexpr (FOLD) {
+      // the token appended by waiting step j sits at row cO - npend + j: older steps did not see it
+      const int row = min(row0 + tok, bo - 1);
+      const float2 ac = fold_pending<D, G>(sm_pend, npend, row - (cO - npend), t.ac, lane, [&](const uint4 (&qop)[KK], float (&xp)[HPL]) {
+        const f32x4 Cp = dots_bf16<KK>(qop, t.kb);
+#pragma unroll
+        for (int i = 0; i < HPL; ++i) xp[i] = Cp[i];
+      });
+      store_acc(ac, own, oacc_, row);
+    }
     softmax_pv(own, x, [&](int j, float (&f)[8]) { unpack_bf16x8(t.vr[j], f); });
   };
   if (ao < bo) {
@@ -589,11 +663,11 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
     if (lane == 0) {
       P.oacc[(size_t)gu * P.capO + cO] = make_float2(0.f, 0.f);
       P.opos[(size_t)gu * P.capO + cO] = L.position;
-      P.qscale[(size_t)(L.parity ^ 1) * (P.fin_stride / G) + gu] = scale2;
+      P.qscale[(size_t)L.slot * (P.fin_stride / G) + gu] = scale2;
     }
     // this step's query, for the next step's score update
     if (tok < G) {
-      uint16_t* dq = P.qprev + ((size_t)(L.parity ^ 1) * P.fin_stride + (size_t)gu * G + tok) * D + 8 * blk;
+      uint16_t* dq = P.qprev + ((size_t)L.slot * P.fin_stride + (size_t)gu * G + tok) * D + 8 * blk;
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) *reinterpret_cast<uint4*>(dq + 32 * kk) = qa[kk];
     }
@@ -607,25 +681,30 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
     const uint8_t* vc = P.qvc + (size_t)gu * P.capQ * Fmt::CB;
     const uint32_t* km = P.qkm + (size_t)gu * P.capQ * Fmt::NG;
     const uint32_t* vm = P.qvm + (size_t)gu * P.capQ * Fmt::NG;
-    typename Fmt::Query pqa, pqb;
+    typename Fmt::Query pqa;
     Fmt::prep(qa, pqa);
-    Fmt::prep(qb, pqb);
     struct QTile { typename Fmt::Keys k; typename Fmt::Vals v[NV]; float2 ac; };
     auto load_q = [&](QTile& t, int row0) {
       const int rk = min(row0 + tok, bq - 1);
       Fmt::load_keys(kc, km, rk, blk, t.k);
 #pragma unroll
       for (int j = 0; j < NV; ++j) Fmt::load_vals(vc, vm, min(row0 + R * j + vrow, bq - 1), sub, t.v[j]);
-      t.ac = qacc_[rk];
+      if constexpr (FOLD) t.ac = qacc_[rk];
     };
     auto compute_q = [&](const QTile& t, int row0) {
       const bool own = (row0 + tok < bq) && active;
-      float x[HPL], xp[HPL];
+      float x[HPL];
       Fmt::dots(pqa, t.k, x);
-      Fmt::dots(pqb, t.k, xp);
 #pragma unroll
-      for (int i = 0; i < HPL; ++i) { x[i] = own ? x[i] * scale2 : kNegBig; xp[i] *= scale2_prev; }
-      fold_prev(xp, t.ac, own, qacc_, min(row0 + tok, bq - 1));
+      for (int i = 0; i < HPL; ++i) x[i] = own ? x[i] * scale2 : kNegBig;
+      if constexpr (FOLD) {
+        const float2 ac = fold_pending<D, G>(sm_pend, npend, 0, t.ac, lane, [&](const uint4 (&qop)[KK], float (&xp)[HPL]) {
+          typename Fmt::Query pq_;
+          Fmt::prep(qop, pq_);
+          Fmt::dots(pq_, t.k, xp);
+        });
+        store_acc(ac, own, qacc_, min(row0 + tok, bq - 1));
+      }
       softmax_pv(own, x, [&](int j, float (&f)[8]) { Fmt::value_row(t.v[j], f); });
     };
     QTile ta, tb;
@@ -701,31 +780,20 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   TRACE(6);
 }
 
-// The deferred score update on its own (before a tailor or an export): logits of the latest step are
-// recomputed from its stored query with the same tile code as in k_decode_attend.
+// The deferred score update on its own (before a tailor or an export): the same fold as in
+// k_decode_attend, over all rows of the unit.
 // grid (workgroups per unit, units); a wave takes every (4 * gridDim.x)-th tile of 16 rows.
 template <int D, int G, int BITS>
-__global__ __launch_bounds__(256) void k_flush_scores(Pools P, int unit_begin, int parity) {
+__global__ __launch_bounds__(256) void k_flush_scores(Pools P, int unit_begin, int n_pending, int slot) {
   constexpr int KK = D / 32;
-  constexpr int HB = (G + 3) / 4;
   constexpr int HPL = G < 4 ? G : 4;
+  __shared__ PendingLds<D, G> sm_pend;
   const int gu = unit_begin + blockIdx.y;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int tok = lane & 15, blk = lane >> 4;
-  const bool active = blk < HB;
   const int2 cnt = P.cnt[gu];
-  uint4 qb[KK];
-  load_query<D, G>(P.qprev + ((size_t)parity * P.fin_stride + (size_t)gu * G) * D, lane, qb);
-  const float scale2_prev = P.qscale[(size_t)parity * (P.fin_stride / G) + gu];
-  float pm[HPL], pinv[HPL];
-  {
-    const float2* f = P.fin + (size_t)parity * P.fin_stride + (size_t)gu * G;
-#pragma unroll
-    for (int i = 0; i < HPL; ++i) {
-      const float2 t = f[active ? 4 * blk + i : i];
-      pm[i] = t.x; pinv[i] = t.y;
-    }
-  }
+  stage_pending<D, G>(P, gu, n_pending, slot, sm_pend, threadIdx.x, 256);
+  __syncthreads();
   const int wave = blockIdx.x * 4 + w, step = gridDim.x * 64;
   {
     const uint16_t* ok_ = P.ok + (size_t)gu * P.capO * D;
@@ -737,13 +805,14 @@ __global__ __launch_bounds__(256) void k_flush_scores(Pools P, int unit_begin, i
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk)
         kb[kk] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(ok_) + off + 64 * kk);
-      const float2 ac = acc[rk];
-      const f32x4 Cp = dots_bf16<KK>(qb, kb);
-      float xp[HPL];
+      // the token appended by waiting step j sits at row cnt.x - n_pending + j
+      const float2 ac = fold_pending<D, G>(sm_pend, n_pending, rk - (cnt.x - n_pending), acc[rk], lane,
+                                           [&](const uint4 (&qop)[KK], float (&xp)[HPL]) {
+        const f32x4 Cp = dots_bf16<KK>(qop, kb);
 #pragma unroll
-      for (int i = 0; i < HPL; ++i) xp[i] = Cp[i] * scale2_prev;
-      const float2 m = prob_moments<HPL, HB>(xp, pm, pinv);
-      if (row0 + tok < cnt.x && blk == 0) acc[rk] = make_float2(ac.x + m.x, ac.y + m.y);
+        for (int i = 0; i < HPL; ++i) xp[i] = Cp[i];
+      });
+      if (row0 + tok < cnt.x && blk == 0) acc[rk] = ac;
     }
   }
   if (cnt.y > 0) {
@@ -751,19 +820,16 @@ __global__ __launch_bounds__(256) void k_flush_scores(Pools P, int unit_begin, i
     const uint8_t* kc = P.qkc + (size_t)gu * P.capQ * Fmt::CB;
     const uint32_t* km = P.qkm + (size_t)gu * P.capQ * Fmt::NG;
     float2* acc = P.qacc + (size_t)gu * P.capQ;
-    typename Fmt::Query pqb;
-    Fmt::prep(qb, pqb);
     for (int row0 = 16 * wave; row0 < cnt.y; row0 += step) {
       const int rk = min(row0 + tok, cnt.y - 1);
       typename Fmt::Keys k;
       Fmt::load_keys(kc, km, rk, blk, k);
-      const float2 ac = acc[rk];
-      float xp[HPL];
-      Fmt::dots(pqb, k, xp);
-#pragma unroll
-      for (int i = 0; i < HPL; ++i) xp[i] *= scale2_prev;
-      const float2 m = prob_moments<HPL, HB>(xp, pm, pinv);
-      if (row0 + tok < cnt.y && blk == 0) acc[rk] = make_float2(ac.x + m.x, ac.y + m.y);
+      const float2 ac = fold_pending<D, G>(sm_pend, n_pending, 0, acc[rk], lane, [&](const uint4 (&qop)[KK], float (&xp)[HPL]) {
+        typename Fmt::Query pq_;
+        Fmt::prep(qop, pq_);
+        Fmt::dots(pq_, k, xp);
+      });
+      if (row0 + tok < cnt.y && blk == 0) acc[rk] = ac;
     }
   }
 }
@@ -776,7 +842,8 @@ static hipError_t launch_decode_t(const Pools& P, const DecodeLaunch& a, hipStre
 #ifdef ARKV_PHASE_TRACE
   hipLaunchKernelGGL(k_trace_mark, dim3(1), dim3(64), 0, s, 0);
 #endif
-  hipLaunchKernelGGL((k_decode_attend<D, G, BITS>), grid, dim3(256), 0, s, P, a);
+  if (a.fold) hipLaunchKernelGGL((k_decode_attend<D, G, BITS, true>), grid, dim3(256), 0, s, P, a);
+  else hipLaunchKernelGGL((k_decode_attend<D, G, BITS, false>), grid, dim3(256), 0, s, P, a);
 #ifdef ARKV_PHASE_TRACE
   hipLaunchKernelGGL(k_trace_mark, dim3(1), dim3(64), 0, s, 1);
 #endif
@@ -878,31 +945,31 @@ hipError_t launch_stream_read(const void* buf, size_t offset_bytes, size_t bytes
 }
 
 template <int D, int G>
-static hipError_t launch_flush_b(const Pools& P, dim3 grid, int unit_begin, int parity, hipStream_t s) {
-  if (P.bits == 8) hipLaunchKernelGGL((k_flush_scores<D, G, 8>), grid, dim3(256), 0, s, P, unit_begin, parity);
-  else if (P.bits == 4) hipLaunchKernelGGL((k_flush_scores<D, G, 4>), grid, dim3(256), 0, s, P, unit_begin, parity);
-  else hipLaunchKernelGGL((k_flush_scores<D, G, 2>), grid, dim3(256), 0, s, P, unit_begin, parity);
+static hipError_t launch_flush_b(const Pools& P, dim3 grid, int unit_begin, int n_pending, int slot, hipStream_t s) {
+  if (P.bits == 8) hipLaunchKernelGGL((k_flush_scores<D, G, 8>), grid, dim3(256), 0, s, P, unit_begin, n_pending, slot);
+  else if (P.bits == 4) hipLaunchKernelGGL((k_flush_scores<D, G, 4>), grid, dim3(256), 0, s, P, unit_begin, n_pending, slot);
+  else hipLaunchKernelGGL((k_flush_scores<D, G, 2>), grid, dim3(256), 0, s, P, unit_begin, n_pending, slot);
   return hipGetLastError();
 }
 
 template <int D>
-static hipError_t launch_flush_g(const Pools& P, dim3 grid, int unit_begin, int parity, hipStream_t s) {
+static hipError_t launch_flush_g(const Pools& P, dim3 grid, int unit_begin, int n_pending, int slot, hipStream_t s) {
   switch (P.G) {
-    case 1: return launch_flush_b<D, 1>(P, grid, unit_begin, parity, s);
-    case 2: return launch_flush_b<D, 2>(P, grid, unit_begin, parity, s);
-    case 4: return launch_flush_b<D, 4>(P, grid, unit_begin, parity, s);
-    case 8: return launch_flush_b<D, 8>(P, grid, unit_begin, parity, s);
+    case 1: return launch_flush_b<D, 1>(P, grid, unit_begin, n_pending, slot, s);
+    case 2: return launch_flush_b<D, 2>(P, grid, unit_begin, n_pending, slot, s);
+    case 4: return launch_flush_b<D, 4>(P, grid, unit_begin, n_pending, slot, s);
+    case 8: return launch_flush_b<D, 8>(P, grid, unit_begin, n_pending, slot, s);
   }
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_flush_scores(const Pools& P, int unit_begin, int n_units, int parity, hipStream_t s) {
+hipError_t launch_flush_scores(const Pools& P, int unit_begin, int n_units, int n_pending, int slot, hipStream_t s) {
   const int cap = P.capO > P.capQ ? P.capO : P.capQ;
   int bx = (cap + 63) / 64;               // one tile per wave at most
   if (bx > 32) bx = 32;
   const dim3 grid(bx, n_units);
-  if (P.D == 128) return launch_flush_g<128>(P, grid, unit_begin, parity, s);
-  if (P.D == 64) return launch_flush_g<64>(P, grid, unit_begin, parity, s);
+  if (P.D == 128) return launch_flush_g<128>(P, grid, unit_begin, n_pending, slot, s);
+  if (P.D == 64) return launch_flush_g<64>(P, grid, unit_begin, n_pending, slot, s);
   return hipErrorInvalidValue;
 }
 

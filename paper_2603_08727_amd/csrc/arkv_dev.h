@@ -14,6 +14,10 @@ constexpr int kMaxUnitsKnown = 64;     // launches with at most this many units 
 // launch over several layers is just a launch over more units.  "O pool": bf16 rows of Original
 // tokens, slots [0, cnt.x) dense.  "Q pool": packed rows of Quantized tokens, slots [0, cnt.y) dense.
 // A tailor compacts both pools in place; between tailors tokens are only appended to the O pool.
+// Slots of per-step state (query, scale, final softmax constants) kept per unit: up to kRing-1 finished steps
+// wait for their score update, one slot is written by the step in flight.
+constexpr int kRing = 9;
+
 // 32-bit metadata words of one packed K (or V) row
 __host__ __device__ constexpr int metas_per_row(int D, int bits) { return bits == 8 ? 1 : D / kGroup; }
 
@@ -35,10 +39,10 @@ struct Pools {
   float2*   qacc;       // [LU][capQ]
   // per unit
   int2*     cnt;        // [LU] (tokens in O pool, tokens in Q pool)
-  float2*   fin;        // [2][LU][G] (row max in base-2 units, 1/denominator) of the latest two steps
+  float2*   fin;        // [kRing][LU][G] (row max in base-2 units, 1/denominator) of the latest steps, ring by step
   size_t    fin_stride; // LU*G
-  uint16_t* qprev;      // [2][LU][G][D] bf16 queries of the latest two steps (the score update recomputes logits)
-  float*    qscale;     // [2][LU] softmax scale * log2(e) those queries were used with
+  uint16_t* qprev;      // [kRing][LU][G][D] bf16 queries of the latest steps (the score update recomputes logits)
+  float*    qscale;     // [kRing][LU] softmax scale * log2(e) those queries were used with
   float*    part;       // [LU][max_splits][G][D+2] split-K partials: acc[D], max, sum
   int       max_splits;
   int*      ticket;     // [LU] splits of the unit finished in the current launch (0 between launches)
@@ -65,8 +69,10 @@ struct DecodeLaunch {
   int units_per_layer;
   int splits;
   int position;           // P of the token being appended
-  int has_pending;        // 1: the previous step's probabilities are not yet added to (s1,s2)
-  int parity;             // fin/qprev/qscale[parity] belong to the previous step; this step writes [parity^1]
+  int n_pending;          // steps whose probabilities are not yet added to (s1,s2), 0..kRing-1; the j-th oldest
+                          // of them used ring slot (slot - n_pending + j) mod kRing
+  int slot;               // ring slot of fin/qprev/qscale this step writes
+  int fold;               // 1: this launch adds the pending steps to (s1,s2)
   int wq;                 // cost of a packed row in sixteenths of a bf16 row (split balancing)
   int cnt_known;          // 1: cnt_o / cnt_q below are the units' token counts (saves a dependent load)
   int cnt_o[kMaxUnitsKnown], cnt_q[kMaxUnitsKnown];
@@ -80,7 +86,7 @@ struct TailorLaunch {
   int window;
   int b;              // survivors outside the window
   float gamma;
-  int has_pending, parity;
+  int n_pending, slot;  // pending steps to add to (s1,s2) before ranking; slot the NEXT step would write
 };
 
 struct CommitLaunch {
@@ -108,7 +114,7 @@ struct PrefillLaunch {
 hipError_t launch_decode(const Pools& P, const DecodeLaunch& a, hipStream_t s, hipEvent_t ev0 = nullptr,
                          hipEvent_t ev1 = nullptr);  // ev0/ev1: recorded around the attention kernel
 hipError_t launch_stream_read(const void* buf, size_t offset_bytes, size_t bytes, int pattern, unsigned* sink /*[2048]*/, hipStream_t s);
-hipError_t launch_flush_scores(const Pools& P, int unit_begin, int n_units, int parity, hipStream_t s);
+hipError_t launch_flush_scores(const Pools& P, int unit_begin, int n_units, int n_pending, int slot, hipStream_t s);
 hipError_t launch_tailor(const Pools& P, const TailorLaunch& a, hipStream_t s);
 hipError_t launch_commit(const Pools& P, const CommitLaunch& a, uint64_t* commit_keys /*[U][T]*/, hipStream_t s);
 hipError_t launch_prefill_stats(const PrefillLaunch& a, float* rowc /*[U][MP] scratch*/, hipStream_t s);

@@ -30,8 +30,8 @@ static int hip_fail(hipError_t e, const char* what) {
   } while (0)
 
 struct LayerState {
-  bool scored = false, committed = false, pending = false;
-  int scored_T = 0, T = 0, P = -1, live = 0, parity = 0, n_tailors = 0;
+  bool scored = false, committed = false;
+  int scored_T = 0, T = 0, P = -1, live = 0, n_pending = 0, slot = 0, n_tailors = 0;
   int last_tailor = 0;          // 0 none, 1 at commit (keys in commit scratch), 2 during decode
   float2* pre = nullptr;        // [U][T] window sums from the prefill scorer
   size_t pre_cap = 0;
@@ -115,9 +115,9 @@ static int grow(T** p, size_t* cap, size_t count) {
 
 static int flush_and_sync(arkv_cache* c, int layer) {
   LayerState& ls = c->layers[(size_t)layer];
-  if (ls.pending) {
-    HIP_TRY(launch_flush_scores(c->P, layer * c->U, c->U, ls.parity, c->last_stream));
-    ls.pending = false;
+  if (ls.n_pending > 0) {
+    HIP_TRY(launch_flush_scores(c->P, layer * c->U, c->U, ls.n_pending, ls.slot, c->last_stream));
+    ls.n_pending = 0;
   }
   HIP_TRY(hipStreamSynchronize(c->last_stream));
   return ARKV_OK;
@@ -212,15 +212,14 @@ int arkv_cache_create(const arkv_config* cfg, arkv_cache** out) {
   A(qkc, LU * P.capQ * CB) A(qvc, LU * P.capQ * CB)
   A(qkm, LU * P.capQ * NG) A(qvm, LU * P.capQ * NG)
   A(qpos, LU * P.capQ) A(qacc, LU * P.capQ)
-  A(cnt, LU) A(fin, 2 * LU * G) A(qprev, 2 * LU * G * D) A(qscale, 2 * LU) A(part, LU * (size_t)P.max_splits * G * (D + 2)) A(outf, LU * G * D) A(n_o, LU) A(ticket, LU)
+  A(cnt, LU) A(fin, kRing * LU * G) A(qprev, kRing * LU * G * D) A(qscale, kRing * LU) A(part, LU * (size_t)P.max_splits * G * (D + 2)) A(outf, LU * G * D) A(n_o, LU) A(ticket, LU)
   A(keys, LU * (size_t)(P.capO + P.capQ)) A(thr, LU * 2) A(plan, LU * (size_t)P.plan_stride)
 #undef A
   hipError_t e = hipMemset(P.cnt, 0, LU * sizeof(int2));
   if (e == hipSuccess) e = hipMemset(P.ticket, 0, LU * sizeof(int));
-  // read (and ignored) by the first step after a commit: keep them finite
-  if (e == hipSuccess) e = hipMemset(P.fin, 0, 2 * LU * G * sizeof(float2));
-  if (e == hipSuccess) e = hipMemset(P.qprev, 0, 2 * LU * G * D * sizeof(uint16_t));
-  if (e == hipSuccess) e = hipMemset(P.qscale, 0, 2 * LU * sizeof(float));
+  if (e == hipSuccess) e = hipMemset(P.fin, 0, kRing * LU * G * sizeof(float2));
+  if (e == hipSuccess) e = hipMemset(P.qprev, 0, kRing * LU * G * D * sizeof(uint16_t));
+  if (e == hipSuccess) e = hipMemset(P.qscale, 0, kRing * LU * sizeof(float));
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) { arkv_cache_destroy(c); return hip_fail(e, "hipMemset"); }
   *out = c;
@@ -246,8 +245,8 @@ int arkv_cache_reset(arkv_cache* c, int32_t layer) {
   for (int l = 0; l < c->L; ++l) {
     if (layer >= 0 && l != layer) continue;
     LayerState& s = c->layers[(size_t)l];
-    s.scored = s.committed = s.pending = s.cnt_valid = false;
-    s.scored_T = s.T = s.live = s.parity = s.n_tailors = s.last_tailor = 0;
+    s.scored = s.committed = s.cnt_valid = false;
+    s.scored_T = s.T = s.live = s.n_pending = s.slot = s.n_tailors = s.last_tailor = 0;
     s.P = -1;
   }
   return ARKV_OK;
@@ -317,7 +316,7 @@ int arkv_prefill_commit(arkv_cache* c, int32_t layer, const void* k, const void*
     c->ckeys_layer = layer; c->ckeys_T = T;
   }
   HIP_TRY(launch_commit(c->P, a, c->ckeys, st));
-  ls.committed = true; ls.T = T; ls.P = T - 1; ls.pending = false; ls.parity = 0;
+  ls.committed = true; ls.T = T; ls.P = T - 1; ls.n_pending = 0; ls.slot = 0;
   if (a.select) {
     ls.live = std::min(c->b, T - W) + W;
     ls.n_tailors = 1; ls.last_tailor = 1;
@@ -348,7 +347,7 @@ int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const
   for (int i = 0; i < n; ++i) {
     const LayerState& li = c->layers[(size_t)(layer_begin + i)];
     if (!li.committed) return ARKV_ESTATE;
-    if (li.T != l0.T || li.P != l0.P || li.live != l0.live || li.pending != l0.pending || li.parity != l0.parity)
+    if (li.T != l0.T || li.P != l0.P || li.live != l0.live || li.n_pending != l0.n_pending || li.slot != l0.slot)
       return ARKV_ESTATE;
     if (!(softmax_scale[i] > 0.0f)) return ARKV_EINVAL;
   }
@@ -380,8 +379,9 @@ int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const
     }
   }
   a.position = l0.P + 1;
-  a.has_pending = l0.pending ? 1 : 0;
-  a.parity = l0.parity;
+  a.n_pending = l0.n_pending;
+  a.slot = l0.slot;
+  a.fold = l0.n_pending == kRing - 1 ? 1 : 0;   // the ring is full: add the waiting steps now
   for (int i = 0; i < n; ++i) a.scale2[i] = softmax_scale[i] * 1.4426950408889634f;
   hipEvent_t e0 = nullptr, e1 = nullptr;
   if (c->timing) {
@@ -396,21 +396,22 @@ int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const
     c->ev_used += 2;
   }
   HIP_TRY(launch_decode(c->P, a, st, e0, e1));
-  const int P = l0.P + 1, live = l0.live + 1, parity = l0.parity ^ 1;
+  const int P = l0.P + 1, live = l0.live + 1;
+  const int n_pending = (a.fold ? 0 : l0.n_pending) + 1, slot = (l0.slot + 1) % kRing;
   bool tailor = live >= N;
   int live_after = live;
   if (tailor) {
     TailorLaunch t;
     t.unit_begin = a.unit_begin; t.n_units = a.n_units;
     t.position = P; t.t_prefill = l0.T; t.window = W; t.b = c->b; t.gamma = cfg.gamma;
-    t.has_pending = 1; t.parity = parity;
+    t.n_pending = n_pending; t.slot = slot;
     HIP_TRY(launch_tailor(c->P, t, st));
     const int wcount = std::min(W, P + 1);
     live_after = std::min(c->b, live - wcount) + wcount;
   }
   for (int i = 0; i < n; ++i) {
     LayerState& li = c->layers[(size_t)(layer_begin + i)];
-    li.P = P; li.live = live_after; li.parity = parity; li.pending = !tailor;
+    li.P = P; li.live = live_after; li.slot = slot; li.n_pending = tailor ? 0 : n_pending;
     for (auto& v : li.cnt_o) v += 1;
     if (tailor) { li.n_tailors += 1; li.last_tailor = 2; li.cnt_valid = false; }
   }

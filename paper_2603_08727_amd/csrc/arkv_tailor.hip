@@ -505,8 +505,8 @@ static void launch_tailor_moves(const Pools& P, const TailorLaunch& a, hipStream
 }
 
 hipError_t launch_tailor(const Pools& P, const TailorLaunch& a, hipStream_t s) {
-  if (a.has_pending) {
-    hipError_t e = launch_flush_scores(P, a.unit_begin, a.n_units, a.parity, s);
+  if (a.n_pending > 0) {
+    hipError_t e = launch_flush_scores(P, a.unit_begin, a.n_units, a.n_pending, a.slot, s);
     if (e != hipSuccess) return e;
   }
   const int ntot = P.capO + P.capQ;
