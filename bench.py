@@ -37,12 +37,16 @@ def kv_bytes_per_token(d, bits):
     return c_o, c_q
 
 
+SCORE_UPDATE_EVERY = 8   # steps whose score update is done in one pass (kRing - 1 in csrc/arkv_dev.h)
+
+
 def algorithmic_bytes_attend(n_o, n_q, d, G, bits):
-    """Bytes the method itself must move for one unit in one decode step: every live K and V row
-    once, each token's (s1, s2) read and written, the unit's queries and outputs, the appended row."""
+    """Bytes the path must move for one unit in one decode step: every live K and V row once, each
+    token's (s1, s2) read and written once per SCORE_UPDATE_EVERY steps, the unit's queries and outputs,
+    the appended row."""
     c_o, c_q = kv_bytes_per_token(d, bits)
     n_live = n_o + n_q
-    return n_o * c_o + n_q * c_q + 16 * n_live + 2 * G * d * 2 + c_o
+    return n_o * c_o + n_q * c_q + 16.0 * n_live / SCORE_UPDATE_EVERY + 2 * G * d * 2 + c_o
 
 
 def stored_traffic(workload):
