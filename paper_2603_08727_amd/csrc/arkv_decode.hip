@@ -1,13 +1,15 @@
 // Decode step kernels (Alg. 1 "Decoding Phase" + "Reconstruction Before Attention", fused):
 //   k_decode_attend : append + split-K attention of one query per head over the bf16 pool and the
-//                     packed low-bit pool (dequantisation inside the QK and PV loops)
-//                     + the score update of the PREVIOUS step: its probabilities need that step's
-//                     final softmax denominator, which only exists after the split-K merge, so they
-//                     are recomputed here from the previous query against the key tile that is in
-//                     registers anyway (same instructions, same bits as the step itself produced)
+//                     packed pool (dequantisation inside the QK and PV loops)
 //                     + the merge of the split-K partials by the unit's last workgroup (partials
 //                     move through device-scope atomics; a device-scope fence per workgroup instead
 //                     was measured 3-6x slower, a second kernel costs a launch gap per step)
+//                     + on every (kRing-1)-th launch the score update (Eq. 9) of the steps since the
+//                     last one: a step's probabilities need its final softmax denominator, which
+//                     only exists after the merge, so they are formed later, from the step's stored
+//                     query against the key tile that is in registers anyway (same instructions on
+//                     the same bits as the step itself), several waiting steps per MFMA operand.
+//                     The other launches only read the cache.
 //   k_flush_scores  : the same score update on its own, when something needs the scores now
 //                     (tailor, export)
 #include <hip/hip_fp16.h>
@@ -448,12 +450,12 @@ __global__ void k_trace_mark(int slot) { if (threadIdx.x == 0) g_trace[8190][slo
 //
 // A wave works on tiles of 16 tokens.  QK^T of a tile is D/32 MFMAs (A = the unit's G query rows padded
 // to 16, B = 16 key rows loaded from HBM straight into operand layout); lane (token t = lane%16, block
-// b = lane/16) then owns the logits of token t for heads 4b..4b+3.  The same key tile is multiplied with
-// the previous step's query as well: those logits, with that step's final (max, 1/sum), are the
-// probabilities Eq. 9 accumulates.  This step's probabilities go through a small LDS buffer to the value
-// layout (lane = 8 channels of one of 64/(D/8) rows), where PV runs on the vector ALU.  The softmax
-// reference maximum is only moved when a logit exceeds it by more than 8 (base-2 units), which is rare,
-// so the accumulators are almost never rescaled.
+// b = lane/16) then owns the logits of token t for heads 4b..4b+3.  FOLD launches multiply the same key
+// tile with the waiting steps' queries as well (fold_pending) and update the tokens' (s1, s2).  This
+// step's probabilities go through a small LDS buffer to the value layout (lane = 8 channels of one of
+// 64/(D/8) rows), where PV runs on the vector ALU.  The softmax reference maximum is only moved when a
+// logit exceeds it by more than 8 (base-2 units), which is rare, so the accumulators are almost never
+// rescaled.
 template <int D, int G, int BITS, bool FOLD>
 __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch L) {
   constexpr int KK = D / 32;           // MFMA k-steps = quantisation groups per row
