@@ -70,55 +70,87 @@ __global__ __launch_bounds__(256) void k_commit_keys(uint64_t* keys, CommitLaunc
 // thr[unit][x] = that key, or ~0 when k = 0 (nothing qualifies).  k is clamped to the number of
 // eligible keys, so "fewer candidates than b" keeps everything.
 // ------------------------------------------------------------------------------------------
+// Radix select, most significant byte first.  The candidates of a pass often share their byte (scores of
+// one unit have the same exponent), which would serialise plain LDS atomics; lanes of a wave that hit the
+// same bin as the wave's first candidate are therefore counted with a ballot and added once.  The keys a thread owns stay in registers
+// for all eight passes when they fit (n <= 32 per thread), else they are re-read.
+constexpr int kSelKeys = 32;   // keys per thread held in registers
 __global__ __launch_bounds__(1024) void k_select(const uint64_t* keys_all, size_t stride, int n,
                                                  const int32_t* n_o, int unit_begin, int b,
                                                  uint64_t* thr) {
   __shared__ int hist[256];
-  __shared__ int sfx[256];
-  __shared__ int s_sel, s_k, s_cnt;
-  const int lu = blockIdx.y, gu = unit_begin + lu, which = blockIdx.x, tid = threadIdx.x;
+  __shared__ int s_sel, s_k, s_tot;
+  const int lu = blockIdx.y, gu = unit_begin + lu, which = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
   const uint64_t* keys = keys_all + (size_t)lu * stride;
-  if (tid == 0) s_cnt = 0;
-  __syncthreads();
-  int c = 0;
-  for (int i = tid; i < n; i += 1024) c += keys[i] != 0;
-  for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o);
-  if ((tid & 63) == 0 && c) atomicAdd(&s_cnt, c);
-  __syncthreads();
-  const int n_elig = s_cnt;
-  int k = which == 0 ? n_o[gu] : b;
-  if (k > n_elig) k = n_elig;
-  if (k <= 0) {
-    if (tid == 0) thr[(size_t)gu * 2 + which] = ~0ull;
-    return;
+  const bool in_regs = n <= 1024 * kSelKeys;
+  uint64_t mine[kSelKeys];
+  if (in_regs) {
+#pragma unroll
+    for (int j = 0; j < kSelKeys; ++j) {
+      const int i = tid + 1024 * j;
+      mine[j] = i < n ? keys[i] : 0;
+    }
   }
+  int k = which == 0 ? n_o[gu] : b;
   uint64_t prefix = 0;
   for (int pass = 0; pass < 8; ++pass) {
     const int shift = 56 - 8 * pass;
     if (tid < 256) hist[tid] = 0;
     __syncthreads();
-    for (int i = tid; i < n; i += 1024) {
-      const uint64_t key = keys[i];
-      if (key == 0) continue;
-      if (pass > 0 && (key >> (shift + 8)) != prefix) continue;
-      atomicAdd(&hist[(int)((key >> shift) & 255)], 1);
+    auto count = [&](uint64_t key) {
+      bool cand = key != 0 && (pass == 0 || (key >> (shift + 8)) == prefix);
+      const int bin = (int)((key >> shift) & 255);
+      const unsigned long long todo = __ballot(cand);
+      if (todo) {
+        // the bin of the wave's first candidate is counted once for all lanes that share it (the common
+        // case in the leading bytes); whoever differs adds for itself, to bins with little contention
+        const int leader = __ffsll((long long)todo) - 1;
+        const int lb = __shfl(bin, leader);
+        const unsigned long long same = __ballot(cand && bin == lb);
+        if (lane == leader) atomicAdd(&hist[lb], __popcll(same));
+        else if (cand && bin != lb) atomicAdd(&hist[bin], 1);
+      }
+    };
+    if (in_regs) {
+#pragma unroll
+      for (int j = 0; j < kSelKeys; ++j)
+        if (1024 * j < n) count(mine[j]);               // uniform: whole rounds past the end are skipped
+    } else {
+      for (int i0 = 0; i0 < n; i0 += 1024) count(i0 + tid < n ? keys[i0 + tid] : 0);
     }
     __syncthreads();
-    // sfx[t] = number of candidates in bins > t
-    if (tid < 256) sfx[tid] = hist[tid];
-    __syncthreads();
-    for (int o = 1; o < 256; o <<= 1) {
-      int v = 0;
-      if (tid < 256 && tid + o < 256) v = sfx[tid + o];
-      __syncthreads();
-      if (tid < 256) sfx[tid] += v;
-      __syncthreads();
+    // wave 0: lane l owns bins 4l..4l+3; ge(bin) = candidates in bins >= bin
+    if (tid < 64) {
+      int h[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) h[i] = hist[4 * tid + i];
+      const int own = h[0] + h[1] + h[2] + h[3];
+      int above = own;                                   // inclusive suffix sum over lanes
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_down(above, o);
+        if (tid + o < 64) above += t;
+      }
+      if (pass == 0 && tid == 0) s_tot = above;
+      const int total = __shfl(above, 0);
+      int kk = k;
+      if (pass == 0 && kk > total) kk = total;           // fewer candidates than k: keep them all
+      int ge = above - own;                              // candidates in bins of higher lanes
+#pragma unroll
+      for (int i = 3; i >= 0; --i) {
+        const int gt = ge;
+        ge += h[i];
+        if (kk > 0 && gt < kk && kk <= ge) { s_sel = 4 * tid + i; s_k = kk - gt; }
+      }
     }
-    if (tid < 256) {
-      const int ge = sfx[tid], gt = ge - hist[tid];
-      if (gt < k && k <= ge) { s_sel = tid; s_k = k - gt; }
-    }
     __syncthreads();
+    if (pass == 0) {
+      if (k > s_tot) k = s_tot;
+      if (k <= 0) {
+        if (tid == 0) thr[(size_t)gu * 2 + which] = ~0ull;
+        return;
+      }
+    }
     prefix = (prefix << 8) | (uint64_t)s_sel;
     k = s_k;
     __syncthreads();
