@@ -152,7 +152,14 @@ def oq_ratio(q):
     return q / mx
 
 
-def budget_counts(rho, N, W, alpha=PAPER_ALPHA, every_step=False):
+def row_bytes(d, bits):
+    """(C_orig, C_quant) of eq. 1 for one token of one kv-head: bf16 K and V rows; packed K and V rows with
+    their scales (grouped low-bit formats: fp16 scale and zero per 32 channels; fp8: one fp16 scale per row)."""
+    c_q = 2 * (d + 2) if bits == 8 else 2 * (d * bits // 8 + (d // GROUP) * 4)
+    return 4 * d, c_q
+
+
+def budget_counts(rho, N, W, alpha=PAPER_ALPHA, every_step=False, byte_costs=None):
     """Token counts kept by a tailor (Alg. 1 'Assign origin budget', eq. 10).
 
     N = cache limit in tokens, same for every layer.  b = floor(alpha*(N-W))
@@ -161,11 +168,20 @@ def budget_counts(rho, N, W, alpha=PAPER_ALPHA, every_step=False):
     Original and n_q = b - n_o Quantized.  every_step=True is the literal
     'at each step' reading of Sec. IV-F with no slack: the cache is kept full,
     b = N-W-1, so exactly one slot is freed and the tailor runs at every step.
-    Returns (n_o, n_q, b).
+
+    byte_costs=(C_orig, C_quant) reads eq. 1 and eq. 8 in bytes: the limit is
+    N*C_orig bytes; the Original budget is n_o rows as above, and what the token
+    rule would spend on Quantized rows at full cost, (b - n_o)*C_orig bytes, buys
+    n_q = floor((b - n_o)*C_orig / C_quant) Quantized tokens instead.
+    Returns (n_o, n_q, n_o + n_q).
     """
     b = N - W - 1 if every_step else int(np.floor(alpha * (N - W)))
     b = max(0, min(b, N - W - 1))
     n_o = min(int(np.floor(float(rho) * (N - W))), b)
+    if byte_costs is not None:
+        c_o, c_q = byte_costs
+        n_q = ((b - n_o) * c_o) // c_q
+        return n_o, n_q, n_o + n_q
     return n_o, b - n_o, b
 
 
@@ -402,8 +418,13 @@ class SequenceCacheOracle:
     """
 
     def __init__(self, n_q_heads, n_kv_heads, head_dim, N, W=PAPER_W, alpha=PAPER_ALPHA,
-                 gamma=PAPER_GAMMA, bits=4, every_step=False):
+                 gamma=PAPER_GAMMA, bits=4, every_step=False, byte_budget=False):
         self.every_step = every_step
+        # byte_budget: the limit is N*C_orig bytes (eq. 1) and Quantized tokens are charged C_quant.  The
+        # tailor still fires on a fixed schedule: occupancy is booked in rows as if every survivor of the
+        # token rule's b were Original, which bounds the live bytes from above whatever the tokens' states.
+        self.byte_budget = byte_budget
+        self.occ = None        # booked occupancy in rows (== live tokens in token mode)
         self.Hq, self.Hkv, self.d = n_q_heads, n_kv_heads, head_dim
         self.G = n_q_heads // n_kv_heads
         self.N, self.W, self.alpha, self.gamma, self.bits = N, W, alpha, gamma, bits
@@ -422,7 +443,10 @@ class SequenceCacheOracle:
         k = np.asarray(k, dtype=np.float32); v = np.asarray(v, dtype=np.float32)
         T = k.shape[1]
         self.T, self.P = T, T - 1
-        self.n_o, self.n_q, self.b = budget_counts(rho, self.N, self.W, self.alpha, self.every_step)
+        self.n_o, self.n_q, self.b = budget_counts(rho, self.N, self.W, self.alpha, self.every_step,
+                                                   row_bytes(self.d, self.bits) if self.byte_budget else None)
+        self.b_rows = budget_counts(rho, self.N, self.W, self.alpha, self.every_step)[2]
+        self.occ = T
         for g, u in enumerate(self.units):
             u.pos = np.arange(T, dtype=np.int64)
             u.state = np.zeros(T, dtype=np.int8)
@@ -444,7 +468,7 @@ class SequenceCacheOracle:
         self.P += 1
         out = np.empty((self.Hq, self.d), dtype=np.float64)
         for g, u in enumerate(self.units):
-            assert len(u.pos) < self.N
+            assert self.occ < self.N
             row = np.stack([k_new[g], v_new[g]])[None]
             u.pos = np.append(u.pos, self.P)
             u.state = np.append(u.state, np.int8(STATE_O))
@@ -456,8 +480,9 @@ class SequenceCacheOracle:
                 out[h], p = attend(q[h], u.kv[:, 0], u.kv[:, 1], scale)
                 u.s1 += p
                 u.s2 += p * p
+        self.occ += 1
         fired = False
-        if len(self.units[0].pos) >= self.N:
+        if self.occ >= self.N:
             self.tailor(S_override)
             fired = True
         return out, fired
@@ -474,6 +499,8 @@ class SequenceCacheOracle:
         lock-step parity tests so that both sides select on identical scores."""
         self.n_tailors += 1
         self.last_tailor = []
+        window = min(self.W, self.P + 1)
+        self.occ = window + min(self.b_rows, len(self.units[0].pos) - window)
         for g, u in enumerate(self.units):
             elig = u.pos < self.P + 1 - self.W
             idx = np.nonzero(elig)[0]
@@ -522,5 +549,5 @@ class SequenceCacheOracle:
         C_orig = 4d bytes (bf16 K and V), C_quant = 2*(d*bits/8 + (d/32)*4) for the
         grouped low-bit formats and 2*(d + 2) for fp8 rows with one fp16 scale."""
         no, nq = self.counts(g)
-        cq = 2 * (self.d + 2) if self.bits == 8 else 2 * (self.d * self.bits // 8 + (self.d // GROUP) * 4)
-        return no * 4 * self.d + nq * cq
+        co, cq = row_bytes(self.d, self.bits)
+        return no * co + nq * cq

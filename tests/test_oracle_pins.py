@@ -383,3 +383,48 @@ def test_fp8_cache_trajectory_invariants():
         for j in np.nonzero(u.state == O.STATE_Q)[0]:
             e = u.q[int(u.pos[j])]
             assert np.array_equal(u.kv[j, 0], O.dequantize_fp8_row(e["k_codes"], e["k_scale"]))
+
+
+# ---- eq. 1 / eq. 8 read in bytes ---------------------------------------------------------------------------
+def test_byte_budget_counts_closed_form():
+    """Worked numbers: N = 8192, W = 32, alpha = 0.75, rho = 0.5, d = 128, 4-bit rows (C_orig = 512,
+    C_quant = 160): b = 6120 rows, n_o = 4080, and the 2040 rows' worth of bytes left buy
+    floor(2040 * 512 / 160) = 6528 Quantized tokens.  With C_quant = C_orig the byte rule is the token rule."""
+    co, cq = O.row_bytes(128, 4)
+    assert (co, cq) == (512, 160) and O.row_bytes(128, 2) == (512, 96) and O.row_bytes(128, 8) == (512, 260)
+    assert O.budget_counts(0.5, 8192, 32, 0.75, byte_costs=(co, cq)) == (4080, 6528, 10608)
+    assert O.budget_counts(1.0, 8192, 32, 0.75, byte_costs=(co, cq)) == (6120, 0, 6120)
+    assert O.budget_counts(0.0, 8192, 32, 0.75, byte_costs=(co, cq)) == (0, 19584, 19584)
+    for rho in (0.0, 0.3, 0.77, 1.0):
+        assert O.budget_counts(rho, 500, 16, 0.6, byte_costs=(64, 64)) == O.budget_counts(rho, 500, 16, 0.6)
+        n_o, n_q, b = O.budget_counts(rho, 500, 16, 0.6, byte_costs=(co, cq))
+        b_rows = O.budget_counts(rho, 500, 16, 0.6)[2]
+        assert n_o * co + n_q * cq <= b_rows * co < n_o * co + (n_q + 1) * cq     # the budget is used up to one token
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_byte_budget_trajectory_respects_eq1(bits):
+    """Byte mode keeps more tokens than token mode, never exceeds N * C_orig live bytes per kv-head (eq. 1),
+    and tailors on the same schedule."""
+    rng = np.random.default_rng(8)
+    d, N, W, T, steps = 64, 64, 8, 100, 70
+    k = rng.standard_normal((2, T, d)).astype(np.float32)
+    v = rng.standard_normal((2, T, d)).astype(np.float32)
+    s1 = rng.random((2, T)); s2 = s1 ** 2 / 8
+    caches = [O.SequenceCacheOracle(4, 2, d, N, W=W, bits=bits, byte_budget=bb) for bb in (False, True)]
+    for c in caches:
+        c.commit(k, v, s1, s2, rho=0.3)
+    co, cq = O.row_bytes(d, bits)
+    more = False
+    for t in range(steps):
+        q = rng.standard_normal((4, d)); kn = rng.standard_normal((2, d)).astype(np.float32)
+        vn = rng.standard_normal((2, d)).astype(np.float32)
+        fired = [c.decode_step(q, kn, vn, 0.125)[1] for c in caches]
+        assert fired[0] == fired[1]
+        for g in range(2):
+            assert caches[1].live_bytes(g) <= N * co
+            assert caches[1].live_bytes(g) <= caches[1].occ * co            # the booked rows bound the bytes
+            n_tok, n_byte = sum(caches[0].counts(g)), sum(caches[1].counts(g))
+            assert n_byte >= n_tok
+            more |= n_byte > n_tok
+    assert more and caches[0].n_tailors == caches[1].n_tailors >= 3
