@@ -103,7 +103,7 @@ def cpu_baseline(wl, k, v, qw, dq, scale, rho, seconds_budget=12.0):
     }, stats
 
 
-def quick_measure(wl, rho_force=None, steps=24, warmup=4, every_step=False):
+def quick_measure(wl, rho_force=None, steps=24, warmup=4, every_step=False, byte_budget=False):
     """Prefill + commit + a short timed decode run of one workload (all its layers); returns steps/s per
     layer-batch, the attention kernel's average duration and its algorithmic bytes.  Used for the policy
     and workload variants; the headline run in main() is more thorough."""
@@ -116,7 +116,8 @@ def quick_measure(wl, rho_force=None, steps=24, warmup=4, every_step=False):
     G, U = wl.group, wl.batch * wl.n_kv_heads
     cfg = A.arkv_config_default(n_layers=L, batch=B, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d,
                                 capacity_tokens=wl.capacity, window=W, alpha=wl.alpha, gamma=wl.gamma,
-                                tau=wl.tau, quant_bits=wl.bits, tailor_policy=1 if every_step else 0)
+                                tau=wl.tau, quant_bits=wl.bits, tailor_policy=1 if every_step else 0,
+                                budget_mode=1 if byte_budget else 0)
     cache = A.arkv_cache_create(cfg)
     try:
         scales = [synth.softmax_scale(wl, l) for l in range(L)]
@@ -478,6 +479,7 @@ def main():
             "arkv_scored_rho": quick_measure(base12),
             "quant_all_kept_rho0_fp8_rows": quick_measure(base12.scaled(bits=8), rho_force=0.0),
             "arkv_mixed_rho0.5_fp8_rows": quick_measure(base12.scaled(bits=8), rho_force=0.5),
+            "arkv_mixed_rho0.5_byte_budget": quick_measure(base12, rho_force=0.5, byte_budget=True),
             "arkv_scored_rho_tailor_every_step": quick_measure(base12.scaled(n_layers=4), every_step=True),
         }
         ref = pol["base_full_cache"]["steps_per_s_per_layer_batch"]

@@ -53,6 +53,11 @@ typedef struct {
   int32_t tailor_policy;    /* 0: tailor when the cache is full, keeping b = floor(alpha (N-W)) tokens (Sec. IV-F,
                                last paragraph: slack factor); 1: no slack, b = N-W-1, i.e. a tailor at every step once
                                the cache is full (Sec. IV-F first sentence read literally; stress timing) */
+  int32_t budget_mode;      /* 0: the limit and the budgets are token counts (Sec. V: "512, 1024, 2048 tokens");
+                               1: eq. 1 and eq. 8 in bytes: the limit is N*C_orig bytes per (sequence, kv-head),
+                               a Quantized token is charged C_quant, so n_q = floor((b - n_o) C_orig / C_quant)
+                               tokens fit where the token rule keeps b - n_o.  Tailors keep the token rule's
+                               schedule (occupancy is booked as if every survivor were Original). */
 } arkv_config;
 
 /* Fills *cfg with the paper's tuned hyper-parameters, 4-bit groups of 32, and zero shapes. HOST. */
@@ -91,7 +96,8 @@ int arkv_prefill_stats(arkv_cache* cache, int32_t layer, const void* q_win, cons
 int arkv_oq_ratio(const float* stats, int32_t n_layers, int32_t batch, const float tau[3], float* rho);
 
 /* Token counts a tailor keeps (Alg. 1 "Assign origin budget", eq. 10).  HOST, pure.
- * b = min(floor(alpha (N-W)), N-W-1), or N-W-1 under tailor_policy 1; n_o = min(floor(rho (N-W)), b); n_q = b - n_o. */
+ * b = min(floor(alpha (N-W)), N-W-1), or N-W-1 under tailor_policy 1; n_o = min(floor(rho (N-W)), b); n_q = b - n_o.
+ * Under budget_mode 1 (needs head_dim and quant_bits): n_q = floor((b - n_o) C_orig / C_quant) and *b = n_o + n_q. */
 int arkv_budget_counts(const arkv_config* cfg, float rho, int32_t* n_o, int32_t* n_q, int32_t* b);
 
 /* Loads one layer's prompt into the cache and fixes the layer's budgets (Alg. 1, prefill phase).

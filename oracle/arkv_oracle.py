@@ -414,7 +414,8 @@ class SequenceCacheOracle:
     'scores are averaged within each group to preserve KV sharing': the heads of
     a group are samples of one token's mean and variance).  Budgets are token
     counts; the tailor fires after the attention of the step at which the number
-    of live tokens reaches N, so that the next append has room.
+    of live tokens reaches N, so that the next append has room (byte_budget:
+    see __init__).
     """
 
     def __init__(self, n_q_heads, n_kv_heads, head_dim, N, W=PAPER_W, alpha=PAPER_ALPHA,

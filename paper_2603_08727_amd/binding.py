@@ -33,6 +33,7 @@ class arkv_config(C.Structure):
         ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("capacity_tokens", C.c_int32),
         ("window", C.c_int32), ("alpha", C.c_float), ("gamma", C.c_float), ("tau", C.c_float * 3),
         ("quant_bits", C.c_int32), ("group_size", C.c_int32), ("tailor_policy", C.c_int32),
+        ("budget_mode", C.c_int32),
     ]
 
 
@@ -209,7 +210,9 @@ def arkv_cache_progress(cache, layer):
 def arkv_cache_export(cache, layer, cfg: arkv_config, rows=True, codes=True):
     """Returns a dict of NumPy arrays, tokens of every unit sorted by position (see arkv.h)."""
     U = cfg.batch * cfg.n_kv_heads
-    MT, d = cfg.capacity_tokens, cfg.head_dim
+    d = cfg.head_dim
+    # token mode: at most N live tokens; byte mode: N bf16 rows' worth of bytes can hold more packed tokens
+    MT = cfg.capacity_tokens + (arkv_budget_counts(cfg, 0.0)[2] if cfg.budget_mode == 1 else 0)
     CB, NG = d * cfg.quant_bits // 8, (1 if cfg.quant_bits == 8 else d // 32)
     out = dict(
         n_live=np.zeros(U, np.int32), pos=np.full((U, MT), -1, np.int32), state=np.full((U, MT), 255, np.uint8),

@@ -48,6 +48,7 @@ struct Pools {
   int*      ticket;     // [LU] splits of the unit finished in the current launch (0 between launches)
   float*    outf;       // [LU][G][D] fp32 output of the latest step (parity hook)
   int32_t*  n_o;        // [LU] Original target of the unit's layer/sequence
+  int32_t*  nb;         // [LU] survivors outside the window (n_o + n_q) of the unit's layer/sequence
   // tailor scratch
   uint64_t* keys;       // [LU][capO+capQ] selection keys of the latest tailor (0 = not eligible)
   uint64_t* thr;        // [LU][2] keys of rank n_o and rank b
@@ -84,7 +85,6 @@ struct TailorLaunch {
   int position;       // P of the latest token
   int t_prefill;      // T
   int window;
-  int b;              // survivors outside the window
   float gamma;
   int n_pending, slot;  // pending steps to add to (s1,s2) before ranking; slot the NEXT step would write
 };
@@ -94,7 +94,7 @@ struct CommitLaunch {
   const uint16_t* v;
   const float2* pre;  // [U][T] window sums (s1, s2) from the prefill scorer
   int unit_begin, n_units;
-  int T, window, b;
+  int T, window;
   float gamma;
   int select;         // 1: T >= N, run the first tailor; 0: copy everything as Original
 };

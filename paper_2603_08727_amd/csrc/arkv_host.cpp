@@ -73,6 +73,7 @@ static int validate(const arkv_config* c) {
     if (!(c->tau[i] > 0.0f)) return ARKV_EINVAL;
   if (c->group_size != kGroup) return ARKV_EINVAL;
   if (c->tailor_policy != 0 && c->tailor_policy != 1) return ARKV_EINVAL;
+  if (c->budget_mode != 0 && c->budget_mode != 1) return ARKV_EINVAL;
   const int G = c->n_q_heads / c->n_kv_heads;
   if (c->head_dim != 64 && c->head_dim != 128) return ARKV_EUNSUPPORTED;
   if (G != 1 && G != 2 && G != 4 && G != 8) return ARKV_EUNSUPPORTED;
@@ -144,12 +145,26 @@ int arkv_config_default(arkv_config* cfg) {
   return ARKV_OK;
 }
 
+// (C_orig, C_quant) of eq. 1 for one token of one kv-head
+static void row_bytes(int d, int bits, int64_t* c_o, int64_t* c_q) {
+  *c_o = 4 * (int64_t)d;
+  *c_q = bits == 8 ? 2 * ((int64_t)d + 2) : 2 * ((int64_t)d * bits / 8 + ((int64_t)d / kGroup) * 4);
+}
+
 int arkv_budget_counts(const arkv_config* cfg, float rho, int32_t* n_o, int32_t* n_q, int32_t* b) {
   if (!cfg || !n_o || !n_q || !b) return ARKV_EINVAL;
   if (cfg->window < 1 || cfg->window >= cfg->capacity_tokens - 1) return ARKV_EINVAL;
   if (!(cfg->alpha > 0.0f && cfg->alpha <= 1.0f) || !(rho >= 0.0f && rho <= 1.0f)) return ARKV_EINVAL;
   const int bb = survivors_b(cfg);
   const int no = std::min((int)floor((double)rho * (double)(cfg->capacity_tokens - cfg->window)), bb);
+  if (cfg->budget_mode == 1) {
+    if (cfg->head_dim <= 0 || (cfg->quant_bits != 2 && cfg->quant_bits != 4 && cfg->quant_bits != 8)) return ARKV_EINVAL;
+    int64_t co, cq;
+    row_bytes(cfg->head_dim, cfg->quant_bits, &co, &cq);
+    const int64_t nq = (int64_t)(bb - no) * co / cq;
+    *n_o = no; *n_q = (int32_t)nq; *b = (int32_t)(no + nq);
+    return ARKV_OK;
+  }
   *n_o = no; *n_q = bb - no; *b = bb;
   return ARKV_OK;
 }
@@ -195,7 +210,11 @@ int arkv_cache_create(const arkv_config* cfg, arkv_cache** out) {
   P.U = c->U;
   // 17 spare rows per unit: keeps the units' 2^k-byte regions from landing on the same HBM channels
   P.capO = cfg->capacity_tokens + 17;
-  P.capQ = std::max(c->b, 1);
+  {
+    int32_t no0, nq0, b0;
+    if (arkv_budget_counts(cfg, 0.0f, &no0, &nq0, &b0) != ARKV_OK) { delete c; return ARKV_EINVAL; }
+    P.capQ = std::max(b0, 1);             // every survivor may be Quantized
+  }
   P.D = cfg->head_dim;
   P.G = cfg->n_q_heads / cfg->n_kv_heads;
   P.bits = cfg->quant_bits;
@@ -212,7 +231,7 @@ int arkv_cache_create(const arkv_config* cfg, arkv_cache** out) {
   A(qkc, LU * P.capQ * CB) A(qvc, LU * P.capQ * CB)
   A(qkm, LU * P.capQ * NG) A(qvm, LU * P.capQ * NG)
   A(qpos, LU * P.capQ) A(qacc, LU * P.capQ)
-  A(cnt, LU) A(fin, kRing * LU * G) A(qprev, kRing * LU * G * D) A(qscale, kRing * LU) A(part, LU * (size_t)P.max_splits * G * (D + 2)) A(outf, LU * G * D) A(n_o, LU) A(ticket, LU)
+  A(cnt, LU) A(fin, kRing * LU * G) A(qprev, kRing * LU * G * D) A(qscale, kRing * LU) A(part, LU * (size_t)P.max_splits * G * (D + 2)) A(outf, LU * G * D) A(n_o, LU) A(nb, LU) A(ticket, LU)
   A(keys, LU * (size_t)(P.capO + P.capQ)) A(thr, LU * 2) A(plan, LU * (size_t)P.plan_stride)
 #undef A
   hipError_t e = hipMemset(P.cnt, 0, LU * sizeof(int2));
@@ -292,23 +311,27 @@ int arkv_prefill_commit(arkv_cache* c, int32_t layer, const void* k, const void*
   if (ls.committed || !ls.scored || ls.scored_T != T) return ARKV_ESTATE;
   const arkv_config& cfg = c->cfg;
   const int N = cfg.capacity_tokens, W = cfg.window, U = c->U;
-  std::vector<int32_t> no_units((size_t)U);
+  std::vector<int32_t> no_units((size_t)U), nb_units((size_t)U);
   for (int s = 0; s < cfg.batch; ++s) {
     int32_t no, nq, bb;
     int rc = arkv_budget_counts(&cfg, rho[s], &no, &nq, &bb);
     if (rc != ARKV_OK) return rc;
     ls.n_o[(size_t)s] = no;
-    for (int g = 0; g < cfg.n_kv_heads; ++g) no_units[(size_t)s * cfg.n_kv_heads + g] = no;
+    for (int g = 0; g < cfg.n_kv_heads; ++g) {
+      no_units[(size_t)s * cfg.n_kv_heads + g] = no;
+      nb_units[(size_t)s * cfg.n_kv_heads + g] = bb;
+    }
   }
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   HIP_TRY(hipStreamSynchronize(st));
   HIP_TRY(hipMemcpy(c->P.n_o + (size_t)layer * U, no_units.data(), (size_t)U * sizeof(int32_t), hipMemcpyHostToDevice));
+  HIP_TRY(hipMemcpy(c->P.nb + (size_t)layer * U, nb_units.data(), (size_t)U * sizeof(int32_t), hipMemcpyHostToDevice));
   CommitLaunch a;
   a.k = static_cast<const uint16_t*>(k);
   a.v = static_cast<const uint16_t*>(v);
   a.pre = ls.pre;
   a.unit_begin = layer * U; a.n_units = U;
-  a.T = T; a.window = W; a.b = c->b; a.gamma = cfg.gamma;
+  a.T = T; a.window = W; a.gamma = cfg.gamma;
   a.select = T >= N ? 1 : 0;
   if (a.select) {
     int rc = grow(&c->ckeys, &c->ckeys_cap, (size_t)U * T);
@@ -326,7 +349,7 @@ int arkv_prefill_commit(arkv_cache* c, int32_t layer, const void* k, const void*
   // every prompt token starts Original, so the first tailor's split is known without looking at the data
   for (int u = 0; u < U; ++u) {
     if (a.select) {
-      const int nel = T - W, keep = std::min(c->b, nel), no = std::min(no_units[(size_t)u], nel);
+      const int nel = T - W, keep = std::min(nb_units[(size_t)u], nel), no = std::min(no_units[(size_t)u], nel);
       ls.cnt_o[(size_t)u] = W + no;
       ls.cnt_q[(size_t)u] = keep - no;
     } else {
@@ -403,7 +426,7 @@ int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const
   if (tailor) {
     TailorLaunch t;
     t.unit_begin = a.unit_begin; t.n_units = a.n_units;
-    t.position = P; t.t_prefill = l0.T; t.window = W; t.b = c->b; t.gamma = cfg.gamma;
+    t.position = P; t.t_prefill = l0.T; t.window = W; t.gamma = cfg.gamma;
     t.n_pending = n_pending; t.slot = slot;
     HIP_TRY(launch_tailor(c->P, t, st));
     const int wcount = std::min(W, P + 1);
@@ -434,8 +457,8 @@ int arkv_cache_counters(arkv_cache* c, int32_t layer, int32_t* n_original, int32
   std::vector<int2> cnt;
   int rc = fetch(cnt, c->P.cnt + (size_t)layer * c->U, (size_t)c->U);
   if (rc != ARKV_OK) return rc;
-  const int64_t d = c->P.D, co = 4 * d;
-  const int64_t cq = c->P.bits == 8 ? 2 * (d + 2) : 2 * (d * c->P.bits / 8 + (d / kGroup) * 4);
+  int64_t co, cq;
+  row_bytes(c->P.D, c->P.bits, &co, &cq);
   for (int u = 0; u < c->U; ++u) {
     if (n_original) n_original[u] = cnt[(size_t)u].x;
     if (n_quantized) n_quantized[u] = cnt[(size_t)u].y;

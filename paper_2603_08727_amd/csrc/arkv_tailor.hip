@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256) void k_commit_keys(uint64_t* keys, CommitLaunc
 }
 
 // ------------------------------------------------------------------------------------------
-// exact k-th largest key.  grid (2, units): x = 0 -> k = n_o[unit], x = 1 -> k = b.
+// exact k-th largest key.  grid (2, units): x = 0 -> k = n_o[unit], x = 1 -> k = nb[unit].
 // thr[unit][x] = that key, or ~0 when k = 0 (nothing qualifies).  k is clamped to the number of
 // eligible keys, so "fewer candidates than b" keeps everything.
 // ------------------------------------------------------------------------------------------
@@ -76,7 +76,7 @@ __global__ __launch_bounds__(256) void k_commit_keys(uint64_t* keys, CommitLaunc
 // for all eight passes when they fit (n <= 32 per thread), else they are re-read.
 constexpr int kSelKeys = 32;   // keys per thread held in registers
 __global__ __launch_bounds__(1024) void k_select(const uint64_t* keys_all, size_t stride, int n,
-                                                 const int32_t* n_o, int unit_begin, int b,
+                                                 const int32_t* n_o, const int32_t* nb, int unit_begin,
                                                  uint64_t* thr) {
   __shared__ int hist[256];
   __shared__ int s_sel, s_k, s_tot;
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(1024) void k_select(const uint64_t* keys_all, size_
       mine[j] = i < n ? keys[i] : 0;
     }
   }
-  int k = which == 0 ? n_o[gu] : b;
+  int k = which == 0 ? n_o[gu] : nb[gu];
   uint64_t prefix = 0;
   for (int pass = 0; pass < 8; ++pass) {
     const int shift = 56 - 8 * pass;
@@ -551,7 +551,7 @@ hipError_t launch_tailor(const Pools& P, const TailorLaunch& a, hipStream_t s) {
     default: return hipErrorInvalidValue;
   }
   hipLaunchKernelGGL(k_select, dim3(2, a.n_units), dim3(1024), 0, s,
-                     P.keys + (size_t)a.unit_begin * ntot, (size_t)ntot, ntot, P.n_o, a.unit_begin, a.b, P.thr);
+                     P.keys + (size_t)a.unit_begin * ntot, (size_t)ntot, ntot, P.n_o, P.nb, a.unit_begin, P.thr);
   hipLaunchKernelGGL(k_tailor_plan, dim3(a.n_units), dim3(1024), 0, s, P, a);
   if (P.D == 128 && P.bits == 4) launch_tailor_moves<128, 4>(P, a, s);
   else if (P.D == 128 && P.bits == 2) launch_tailor_moves<128, 2>(P, a, s);
@@ -573,7 +573,7 @@ hipError_t launch_commit(const Pools& P, const CommitLaunch& a, uint64_t* ckeys,
   if (a.select) {
     hipLaunchKernelGGL(k_commit_keys, dim3((a.T + 255) / 256, a.n_units), dim3(256), 0, s, ckeys, a, P.G);
     hipLaunchKernelGGL(k_select, dim3(2, a.n_units), dim3(1024), 0, s, (const uint64_t*)ckeys, (size_t)a.T,
-                       a.T, P.n_o, a.unit_begin, a.b, P.thr);
+                       a.T, P.n_o, P.nb, a.unit_begin, P.thr);
     hipLaunchKernelGGL(k_commit_plan, dim3(a.n_units), dim3(1024), 0, s, P, a, (const uint64_t*)ckeys);
   }
   if (P.D == 128 && P.bits == 4) launch_commit_scatter<128, 4>(P, a, s);

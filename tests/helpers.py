@@ -27,11 +27,12 @@ def bf16_round(x32: np.ndarray) -> np.ndarray:
     return (u >> 16).astype(np.uint16)
 
 
-def make_cfg(wl: synth.Workload, every_step=False):
+def make_cfg(wl: synth.Workload, every_step=False, byte_budget=False):
     return A.arkv_config_default(
         n_layers=wl.n_layers, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
         head_dim=wl.head_dim, capacity_tokens=wl.capacity, window=wl.window, alpha=wl.alpha,
-        gamma=wl.gamma, tau=wl.tau, quant_bits=wl.bits, tailor_policy=1 if every_step else 0)
+        gamma=wl.gamma, tau=wl.tau, quant_bits=wl.bits, tailor_policy=1 if every_step else 0,
+        budget_mode=1 if byte_budget else 0)
 
 
 class SideBySide:
@@ -39,12 +40,14 @@ class SideBySide:
     GPU ran a tailor, the oracle's tailor of the same step ranks on the GPU's fp32 scores, so that
     states / codes / scales can be compared bit for bit; everything floating point is compared at TOL."""
 
-    def __init__(self, wl: synth.Workload, rho_override=None, device="cuda", every_step=False, lockstep=True):
+    def __init__(self, wl: synth.Workload, rho_override=None, device="cuda", every_step=False, lockstep=True,
+                 byte_budget=False):
         self.wl = wl
         self.dev = device
         self.every_step = every_step
         self.lockstep = lockstep       # False: the oracle ranks on its own fp64 scores (free-running protocol)
-        self.cfg = make_cfg(wl, every_step)
+        self.byte_budget = byte_budget
+        self.cfg = make_cfg(wl, every_step, byte_budget)
         self.cache = A.arkv_cache_create(self.cfg)
         self.U = wl.batch * wl.n_kv_heads
         self.rho_override = rho_override
@@ -96,7 +99,7 @@ class SideBySide:
             for b in range(wl.batch):
                 oc = O.SequenceCacheOracle(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.capacity, W=wl.window,
                                            alpha=float(np.float32(wl.alpha)), gamma=float(np.float32(wl.gamma)),
-                                           bits=wl.bits, every_step=self.every_step)
+                                           bits=wl.bits, every_step=self.every_step, byte_budget=self.byte_budget)
                 s1, s2 = self.ref_acc[(l, b)]
                 if over is not None:
                     self._check_scores(oc, l, b, over, commit=(s1, s2))
@@ -108,7 +111,7 @@ class SideBySide:
 
     def _gpu_scores(self, layer):
         """Per unit: dict position -> fp32 score of the tailor the GPU just ran."""
-        mt = max(self.wl.prefill, self.wl.capacity)
+        mt = max(self.wl.prefill, 4 * self.wl.capacity + 64)
         cnt, pos, sc = A.arkv_debug_last_tailor_scores(self.cache, layer, self.U, mt)
         assert (cnt >= 0).all()
         return [dict(zip(pos[u, :cnt[u]].tolist(), sc[u, :cnt[u]])) for u in range(self.U)]

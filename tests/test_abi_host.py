@@ -40,7 +40,7 @@ def _cfg(**kw):
     (dict(alpha=0.0), A.EINVAL), (dict(alpha=1.5), A.EINVAL), (dict(gamma=-1.0), A.EINVAL),
     (dict(group_size=64), A.EINVAL), (dict(head_dim=96), A.EUNSUPPORTED),
     (dict(quant_bits=3), A.EUNSUPPORTED), (dict(n_q_heads=6, n_kv_heads=2), A.EUNSUPPORTED),
-    (dict(tau=(1.0, 0.0, 1.0)), A.EINVAL), (dict(tailor_policy=2), A.EINVAL),
+    (dict(tau=(1.0, 0.0, 1.0)), A.EINVAL), (dict(tailor_policy=2), A.EINVAL), (dict(budget_mode=3), A.EINVAL),
 ])
 def test_create_rejects_bad_config_without_gpu(kw, code):
     with pytest.raises(A.ArkvError) as e:
@@ -64,6 +64,10 @@ def test_budget_counts_match_oracle(N, W, alpha):
         got = A.arkv_budget_counts(cfg, float(rho))
         want = O.budget_counts(float(rho), N, W, float(np.float32(alpha)))
         assert got == want
+    cfgb = _cfg(capacity_tokens=N, window=W, alpha=alpha, budget_mode=1, head_dim=128, quant_bits=4)
+    for rho in (0.0, 0.25, 0.9, 1.0):
+        assert A.arkv_budget_counts(cfgb, rho) == O.budget_counts(rho, N, W, float(np.float32(alpha)),
+                                                                  byte_costs=O.row_bytes(128, 4))
     cfg1 = _cfg(capacity_tokens=N, window=W, alpha=alpha, tailor_policy=1)
     for rho in (0.0, 0.3, 1.0):
         assert A.arkv_budget_counts(cfg1, rho) == O.budget_counts(rho, N, W, float(np.float32(alpha)), every_step=True)

@@ -100,3 +100,14 @@ def test_fp8_rows(rho):
     """The paper's own Quantized format: fp8 codes with one scale per token row."""
     wl = synth.C1.scaled(name="fp8", bits=8, head_dim=128, decode_steps=60)
     _run(wl, rho=rho, check_every=6)
+
+
+@pytest.mark.parametrize("bits,rho", [(4, 0.3), (8, 0.0), (2, 0.6)])
+def test_byte_budget_mode(bits, rho):
+    """eq. 1 in bytes: Quantized tokens are charged C_quant, more of them are kept; live bytes stay within
+    N * C_orig (checked in compare_state) and everything else matches the oracle as in token mode."""
+    wl = synth.C1.scaled(name=f"bytes_b{bits}", bits=bits, head_dim=128, decode_steps=70)
+    sb = _run(wl, rho=rho, check_every=5, byte_budget=True)
+    oc = sb.oracles[(0, 0)]
+    assert oc.b > oc.b_rows and oc.n_tailors >= 3
+    assert max(sum(oc.counts(g)) for g in range(wl.n_kv_heads)) > wl.capacity * 3 // 4   # more tokens than the token rule keeps
