@@ -41,7 +41,10 @@ class SideBySide:
     states / codes / scales can be compared bit for bit; everything floating point is compared at TOL."""
 
     def __init__(self, wl: synth.Workload, rho_override=None, device="cuda", every_step=False, lockstep=True,
-                 byte_budget=False):
+                 byte_budget=False, mutate_prefill=None, mutate_decode=None):
+        # mutate_prefill(layer, k, v, qw) / mutate_decode(layer, q, k_new, v_new): in-place edits of the drawn
+        # CPU tensors before either side sees them (degenerate rows, zero queries, ...)
+        self.mutate_prefill, self.mutate_decode = mutate_prefill, mutate_decode
         self.wl = wl
         self.dev = device
         self.every_step = every_step
@@ -70,6 +73,8 @@ class SideBySide:
         ref_acc = {}
         for l in range(L):
             k, v, qw = synth.prefill_inputs(wl, l)          # CPU draw, copied to the GPU
+            if self.mutate_prefill is not None:
+                self.mutate_prefill(l, k, v, qw)
             self.inputs.append((k, v, qw))
             kd, qd = k.to(self.dev), qw.to(self.dev)
             A.arkv_prefill_stats(self.cache, l, qd, kd, wl.prefill, self.scales[l], stats[l])
@@ -141,6 +146,9 @@ class SideBySide:
         wl = self.wl
         S = wl.decode_steps if steps is None else steps
         ins = [synth.decode_inputs(wl, l, S) for l in range(wl.n_layers)]
+        if self.mutate_decode is not None:
+            for l in range(wl.n_layers):
+                self.mutate_decode(l, *ins[l])
         dins = [tuple(t.to(self.dev) for t in x) for x in ins]
         out = torch.empty((wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.bfloat16, device=self.dev)
         for t in range(S):

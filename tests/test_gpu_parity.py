@@ -111,3 +111,23 @@ def test_byte_budget_mode(bits, rho):
     oc = sb.oracles[(0, 0)]
     assert oc.b > oc.b_rows and oc.n_tailors >= 3
     assert max(sum(oc.counts(g)) for g in range(wl.n_kv_heads)) > wl.capacity * 3 // 4   # more tokens than the token rule keeps
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_degenerate_rows_and_queries(bits):
+    """All-zero and constant K / V rows (scale 0, constant groups), a decode step with an all-zero query
+    (uniform attention), a new token whose key and value are zero; everything is demoted (rho = 0) so the
+    degenerate rows go through the quantiser."""
+    def mp(layer, k, v, qw):
+        k[:, :, 10:14, :] = 0.0                      # zero key rows
+        v[:, :, 10:12, :] = 0.0                      # zero value rows
+        v[:, :, 20:24, :] = 1.5                      # constant value rows: every group is constant
+        k[:, :, 30, 32:64] = -2.0                    # one constant group inside a row
+        qw[:, :, 5, :] = 0.0                         # a zero query row inside the window
+
+    def md(layer, q, kn, vn):
+        q[3] = 0.0                                   # zero query at step 3
+        kn[5] = 0.0; vn[5] = 0.0                     # zero new token at step 5
+
+    wl = synth.C1.scaled(name=f"degenerate_b{bits}", bits=bits, head_dim=64, decode_steps=40)
+    _run(wl, rho=0.0, check_every=2, mutate_prefill=mp, mutate_decode=md)
