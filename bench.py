@@ -434,9 +434,24 @@ def main():
             torch.cuda.synchronize()
             tailor_ms += e0.elapsed_time(e1)
         fired = all(A.arkv_cache_progress(cache, l)[0] == 2 for l in range(nl))
+        # the same layers right after their tailor (cache back at W + b tokens, counts re-read from the device)
+        def run_after(nsteps):
+            nonlocal t_idx
+            for _ in range(nsteps):
+                t_idx += 1
+                t_ = t_idx % total_steps
+                for l in range(nl):
+                    lib.arkv_decode_step(cache, l, qp + (t_ * L + l) * qs_, kp + (t_ * L + l) * ks_,
+                                         vp + (t_ * L + l) * ks_, sc_f[l], op + l * os_, stream)
+        run_after(8)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_after(32)
+        torch.cuda.synchronize()
+        after_us = (time.perf_counter() - t0) / (32 * nl) * 1e6
         cadence = N - (min(int(np.floor(np.float32(wl.alpha) * (N - W))), N - W - 1) + W)
         tailor = {"layers_stepped": nl, "fired": bool(fired), "step_with_tailor_us": round(tailor_ms * 1e3 / nl, 1),
-                  "cadence_steps": int(cadence),
+                  "cadence_steps": int(cadence), "us_per_call_after_tailor": round(after_us, 2),
                   "amortised_us_per_step": round((tailor_ms * 1e3 / nl - call_us) / max(cadence, 1), 3)}
 
     result = {

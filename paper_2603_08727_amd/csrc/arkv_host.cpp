@@ -40,6 +40,12 @@ struct LayerState {
   // appends happen; a decode-time tailor makes the split data dependent and invalidates it
   bool cnt_valid = false;
   std::vector<int32_t> cnt_o, cnt_q;   // [U]
+  // after a decode-time tailor the counts are copied back asynchronously; the mirror is valid again once
+  // the copy has landed (checked without waiting at the following steps)
+  int2* cnt_host = nullptr;     // pinned, [U]
+  hipEvent_t cnt_ev = nullptr;
+  bool cnt_refresh = false;
+  int cnt_refresh_P = 0;        // position of the step whose tailor the snapshot follows
 };
 
 struct arkv_cache {
@@ -234,13 +240,18 @@ int arkv_cache_create(const arkv_config* cfg, arkv_cache** out) {
   A(cnt, LU) A(fin, kRing * LU * G) A(qprev, kRing * LU * G * D) A(qscale, kRing * LU) A(part, LU * (size_t)P.max_splits * G * (D + 2)) A(outf, LU * G * D) A(n_o, LU) A(nb, LU) A(ticket, LU)
   A(keys, LU * (size_t)(P.capO + P.capQ)) A(thr, LU * 2) A(plan, LU * (size_t)P.plan_stride)
 #undef A
-  hipError_t e = hipMemset(P.cnt, 0, LU * sizeof(int2));
+  hipError_t e = hipSuccess;
+  for (auto& ls : c->layers) {
+    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&ls.cnt_host), (size_t)c->U * sizeof(int2), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ls.cnt_ev, hipEventDisableTiming);
+  }
+  if (e == hipSuccess) e = hipMemset(P.cnt, 0, LU * sizeof(int2));
   if (e == hipSuccess) e = hipMemset(P.ticket, 0, LU * sizeof(int));
   if (e == hipSuccess) e = hipMemset(P.fin, 0, kRing * LU * G * sizeof(float2));
   if (e == hipSuccess) e = hipMemset(P.qprev, 0, kRing * LU * G * D * sizeof(uint16_t));
   if (e == hipSuccess) e = hipMemset(P.qscale, 0, kRing * LU * sizeof(float));
   if (e == hipSuccess) e = hipDeviceSynchronize();
-  if (e != hipSuccess) { arkv_cache_destroy(c); return hip_fail(e, "hipMemset"); }
+  if (e != hipSuccess) { arkv_cache_destroy(c); return hip_fail(e, "cache set-up"); }
   *out = c;
   return ARKV_OK;
 }
@@ -249,8 +260,11 @@ int arkv_cache_destroy(arkv_cache* c) {
   if (!c) return ARKV_OK;
   (void)hipDeviceSynchronize();
   for (void* p : c->allocs) (void)hipFree(p);
-  for (auto& ls : c->layers)
+  for (auto& ls : c->layers) {
     if (ls.pre) (void)hipFree(ls.pre);
+    if (ls.cnt_host) (void)hipHostFree(ls.cnt_host);
+    if (ls.cnt_ev) (void)hipEventDestroy(ls.cnt_ev);
+  }
   if (c->rowstat) (void)hipFree(c->rowstat);
   if (c->rowc) (void)hipFree(c->rowc);
   if (c->ckeys) (void)hipFree(c->ckeys);
@@ -264,7 +278,7 @@ int arkv_cache_reset(arkv_cache* c, int32_t layer) {
   for (int l = 0; l < c->L; ++l) {
     if (layer >= 0 && l != layer) continue;
     LayerState& s = c->layers[(size_t)l];
-    s.scored = s.committed = s.cnt_valid = false;
+    s.scored = s.committed = s.cnt_valid = s.cnt_refresh = false;
     s.scored_T = s.T = s.live = s.n_pending = s.slot = s.n_tailors = s.last_tailor = 0;
     s.P = -1;
   }
@@ -389,6 +403,14 @@ int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const
   splits = std::min(splits, std::max(1, l0.live / 64));
   a.splits = std::max(1, std::min(splits, c->P.max_splits));
   a.wq = c->wq;
+  for (int i = 0; i < n; ++i) {
+    LayerState& li = c->layers[(size_t)(layer_begin + i)];
+    if (li.cnt_valid || !li.cnt_refresh) continue;
+    if (hipEventQuery(li.cnt_ev) != hipSuccess) { (void)hipGetLastError(); continue; }   // not landed yet
+    const int steps = li.P - li.cnt_refresh_P;
+    for (int u = 0; u < U; ++u) { li.cnt_o[(size_t)u] = li.cnt_host[u].x + steps; li.cnt_q[(size_t)u] = li.cnt_host[u].y; }
+    li.cnt_valid = true; li.cnt_refresh = false;
+  }
   a.cnt_known = 0;
   if (a.n_units <= kMaxUnitsKnown) {
     bool known = true;
@@ -436,7 +458,15 @@ int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const
     LayerState& li = c->layers[(size_t)(layer_begin + i)];
     li.P = P; li.live = live_after; li.slot = slot; li.n_pending = tailor ? 0 : n_pending;
     for (auto& v : li.cnt_o) v += 1;
-    if (tailor) { li.n_tailors += 1; li.last_tailor = 2; li.cnt_valid = false; }
+    if (tailor) {
+      li.n_tailors += 1; li.last_tailor = 2; li.cnt_valid = false; li.cnt_refresh = false;
+      if (cfg.tailor_policy == 0) {       // with a tailor at every step the snapshot would never be used
+        HIP_TRY(hipMemcpyAsync(li.cnt_host, c->P.cnt + (size_t)(layer_begin + i) * U, (size_t)U * sizeof(int2),
+                               hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipEventRecord(li.cnt_ev, st));
+        li.cnt_refresh = true; li.cnt_refresh_P = P;
+      }
+    }
   }
   c->last_stream = st;
   return ARKV_OK;
