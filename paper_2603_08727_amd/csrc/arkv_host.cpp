@@ -398,9 +398,10 @@ int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const
   a.v_new = static_cast<const uint16_t*>(v_new);
   a.out = static_cast<uint16_t*>(out);
   a.unit_begin = layer_begin * U; a.n_units = n * U; a.units_per_layer = U;
-  // split-K factor: enough workgroups to fill the chip, at least 64 rows each
+  // split-K factor: enough workgroups to fill the chip, at least 128 rows (two tiles per wave) each: below
+  // that the merge of more partials costs more than the shorter loops save (measured on the 8K-context shape)
   int splits = (c->wg_target + a.n_units / 2) / a.n_units;
-  splits = std::min(splits, std::max(1, l0.live / 64));
+  splits = std::min(splits, std::max(1, l0.live / 128));
   a.splits = std::max(1, std::min(splits, c->P.max_splits));
   a.wq = c->wq;
   for (int i = 0; i < n; ++i) {
