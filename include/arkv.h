@@ -170,6 +170,14 @@ int arkv_cache_progress(arkv_cache* cache, int32_t layer, int32_t* n_tailors, in
 int arkv_debug_time_attend(arkv_cache* cache, int32_t enable);
 int arkv_debug_attend_time(arkv_cache* cache, double* total_ms, int64_t* launches);
 
+/* Parity hook, HOST, pure: the rows split `split` of `n_splits` owns in a decode launch over a unit with
+ * n_original bf16 rows and n_quantized packed rows (a packed row weighs packed_weight sixteenths of a bf16
+ * row; the last split is charged for appending the new token).  range[0..3] = first and one-past-last row of
+ * the Original pool, then of the Quantized pool.  ARKV_EINVAL: null pointer, negative counts, n_splits not in
+ * [1, 128], split outside [0, n_splits), packed_weight outside [1, 16]. */
+int arkv_debug_split_range(int32_t n_original, int32_t n_quantized, int32_t packed_weight, int32_t n_splits,
+                           int32_t split, int32_t* range);
+
 /* Measurement hook: a plain streaming read (16 bytes per lane, nothing else) of bytes_per_launch bytes
  * per kernel launch, `launches` launches back to back on the stream, walking through the DEVICE buffer
  * buf of buf_bytes bytes and wrapping around.  pattern 0: fully coalesced (a wave reads 1 KB contiguous

@@ -22,7 +22,8 @@ EXPORTED = [
     "arkv_prefill_stats", "arkv_oq_ratio", "arkv_budget_counts", "arkv_prefill_commit",
     "arkv_decode_step", "arkv_decode_step_layers", "arkv_cache_counters", "arkv_cache_export",
     "arkv_debug_last_tailor_scores", "arkv_debug_last_out_f32", "arkv_cache_progress",
-    "arkv_debug_time_attend", "arkv_debug_attend_time", "arkv_debug_stream_read", "arkv_strerror",
+    "arkv_debug_time_attend", "arkv_debug_attend_time", "arkv_debug_stream_read", "arkv_debug_split_range",
+    "arkv_strerror",
     "arkv_last_hip_error",
 ]
 
@@ -266,3 +267,12 @@ def arkv_debug_stream_read(buf, bytes_per_launch: int, launches: int, pattern: i
                                          C.byref(us)),
            "arkv_debug_stream_read")
     return us.value
+
+
+def arkv_debug_split_range(n_original, n_quantized, packed_weight, n_splits, split):
+    r = (C.c_int32 * 4)()
+    lib = load()
+    lib.arkv_debug_split_range.argtypes = [C.c_int32] * 5 + [C.POINTER(C.c_int32)]
+    lib.arkv_debug_split_range.restype = C.c_int
+    _check(lib.arkv_debug_split_range(n_original, n_quantized, packed_weight, n_splits, split, r), "arkv_debug_split_range")
+    return tuple(r)

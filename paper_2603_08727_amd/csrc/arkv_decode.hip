@@ -14,6 +14,7 @@
 //                     (tailor, export)
 #include <hip/hip_fp16.h>
 
+#include "arkv.h"
 #include "arkv_dev.h"
 
 namespace arkv {
@@ -976,3 +977,15 @@ hipError_t launch_flush_scores(const Pools& P, int unit_begin, int n_units, int 
 }
 
 }  // namespace arkv
+
+extern "C" int arkv_debug_split_range(int32_t n_original, int32_t n_quantized, int32_t packed_weight, int32_t n_splits,
+                                      int32_t split, int32_t* range) {
+  if (!range || n_original < 0 || n_quantized < 0 || n_splits < 1 || n_splits > arkv::kMaxSplits || split < 0 ||
+      split >= n_splits || packed_weight < 1 || packed_weight > 16)
+    return ARKV_EINVAL;
+  int ao, bo, aq, bq;
+  arkv::split_range(n_original, n_quantized, packed_weight, n_splits, split, ao, bo, aq, bq);
+  range[0] = ao; range[1] = bo; range[2] = aq; range[3] = bq;
+  return ARKV_OK;
+}
+

@@ -90,3 +90,26 @@ def test_oq_ratio_matches_oracle():
     bad = stats.copy(); bad[0, 0, 1] = np.nan
     with pytest.raises(A.ArkvError):
         A.arkv_oq_ratio(bad, tau)
+
+
+def test_split_ranges_partition_the_pools():
+    """Host logic of the split-K decomposition: for any counts the splits' row ranges are contiguous, ordered,
+    cover both pools exactly once, and carry about equal weight (a packed row weighs w/16 of a bf16 row; the
+    last split is charged 32 rows for the appended token)."""
+    rng = np.random.default_rng(1)
+    cases = [(0, 0, 14, 1), (1, 0, 14, 1), (0, 5, 14, 4), (6180, 0, 14, 16), (60, 6120, 14, 16), (4140, 2040, 14, 16),
+             (8209, 19584, 16, 128), (33, 1, 1, 7)]
+    cases += [(int(rng.integers(0, 9000)), int(rng.integers(0, 20000)), int(rng.integers(1, 17)), int(rng.integers(1, 129)))
+              for _ in range(40)]
+    for cO, cQ, w, S in cases:
+        ends_o, ends_q, weights = 0, 0, []
+        for s in range(S):
+            ao, bo, aq, bq = A.arkv_debug_split_range(cO, cQ, w, S, s)
+            assert ao == ends_o and aq == ends_q and ao <= bo <= cO and aq <= bq <= cQ, (cO, cQ, w, S, s)
+            ends_o, ends_q = bo, bq
+            weights.append(16 * (bo - ao) + w * (bq - aq) + (16 * 32 if s == S - 1 else 0))
+        assert ends_o == cO and ends_q == cQ
+        assert max(weights) - min(weights) <= 2 * 16 + 16 * 32, (cO, cQ, w, S, weights)
+    for bad in [(-1, 0, 14, 4, 0), (0, 0, 0, 4, 0), (0, 0, 14, 0, 0), (0, 0, 14, 129, 0), (0, 0, 14, 4, 4)]:
+        with pytest.raises(A.ArkvError):
+            A.arkv_debug_split_range(*bad)
