@@ -37,3 +37,24 @@ def test_c3_qwen3_32k_batch4_one_layer():
 
 def test_c4_128k_2bit_one_layer():
     _run(synth.C4.scaled(n_layers=1), steps=3)
+
+
+def _run_scorer(wl):
+    sb = SideBySide(wl)
+    try:
+        sb.prefill()
+        sb.commit()          # compares the survivors' window sums (s1, s2), states and rows as well
+        print(wl.name, {k: f"{v:.2e}" for k, v in sb.max_err.items()}, flush=True)
+        sb.assert_within_tol()
+    finally:
+        sb.close()
+
+
+def test_c5_prefill_scorer_16k_batch8_one_layer():
+    """The prefill-scorer stress shape (16K context, batch 8, sharp and flat heads), one layer, paper window."""
+    _run_scorer(synth.C5.scaled(n_layers=1))
+
+
+def test_c5_prefill_scorer_window_128():
+    """Same shape with a 4x observation window (512 query rows per unit), two sequences."""
+    _run_scorer(synth.C5.scaled(n_layers=1, batch=2, window=128))
