@@ -14,6 +14,7 @@ in the same precision:
 
 What follows the paper, by passage:
   window_attention        Sec. IV-C, eq. 2   (observation window, causal softmax)
+  causal_attention_rows   the causal prefill attention eq. 2 is a slice of (Sec. IV-C, first paragraph)
   layer_statistics        Sec. IV-C, eqs. 3-5 (entropy, variance, kurtosis)
   prefill_accumulators    Sec. IV-E, eq. 9   (first samples of the per-token moments)
   oq_score / oq_ratio     Sec. IV-D, eqs. 6-7
@@ -132,6 +133,27 @@ def sample_count(pos, P, T_prefill, W, group):
     pos = np.asarray(pos, dtype=np.int64)
     first = np.maximum(pos, T_prefill - W)
     return group * (P - first + 1)
+
+
+def causal_attention_rows(q_rows, positions, k, v, scale, group):
+    """Causal self-attention of selected prompt positions (the prefill pass the scorer can be fused into:
+    the last W rows of this computation are exactly the rows of window_attention).
+
+    q_rows [Hq, R, d] are the queries of absolute positions `positions` [R]; k, v [Hkv, T, d]; the query at
+    position p sees keys j <= p.  Returns out [Hq, R, d] = softmax(scale * q k^T) v, fp64.
+    """
+    q_rows = np.asarray(q_rows, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64); v = np.asarray(v, dtype=np.float64)
+    Hq, R, d = q_rows.shape
+    out = np.zeros((Hq, R, d), dtype=np.float64)
+    for h in range(Hq):
+        g = h // group
+        for r in range(R):
+            nvis = int(positions[r]) + 1
+            logits = scale * (k[g, :nvis] @ q_rows[h, r])
+            e = np.exp(logits - logits.max())
+            out[h, r] = (e / e.sum()) @ v[g, :nvis]
+    return out
 
 
 # --------------------------------------------------------------------------

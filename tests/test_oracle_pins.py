@@ -428,3 +428,26 @@ def test_byte_budget_trajectory_respects_eq1(bits):
             assert n_byte >= n_tok
             more |= n_byte > n_tok
     assert more and caches[0].n_tailors == caches[1].n_tailors >= 3
+
+
+# ---- causal prefill attention (the pass the scorer can be fused into) -----------------------------------------
+def test_causal_attention_rows_match_library_and_window():
+    """Against torch's scaled_dot_product_attention (causal, GQA by repeating kv-heads) on a small prompt, and
+    against window_attention: the last W rows of the causal pass ARE eq. 2's rows."""
+    import torch
+    rng = np.random.default_rng(4)
+    Hq, Hkv, T, d, W = 4, 2, 37, 16, 5
+    q = rng.standard_normal((Hq, T, d)); k = rng.standard_normal((Hkv, T, d)); v = rng.standard_normal((Hkv, T, d))
+    scale = 0.31
+    out = O.causal_attention_rows(q, np.arange(T), k, v, scale, Hq // Hkv)
+    tq, tk, tv = (torch.tensor(x) for x in (q, np.repeat(k, 2, axis=0), np.repeat(v, 2, axis=0)))
+    ref = torch.nn.functional.scaled_dot_product_attention(tq[None], tk[None], tv[None], is_causal=True, scale=scale)[0]
+    assert np.allclose(out, ref.numpy(), rtol=1e-12, atol=1e-13)
+    a = O.window_attention(q[:, T - W:], k, scale, Hq // Hkv)                 # [Hq, W, T]
+    via_a = np.einsum("hwt,htd->hwd", a, np.repeat(v, 2, axis=0))
+    assert np.allclose(out[:, T - W:], via_a, rtol=1e-12, atol=1e-13)
+    # a subset of positions gives the same rows
+    sub = np.array([0, 7, 36])
+    assert np.allclose(O.causal_attention_rows(q[:, sub], sub, k, v, scale, 2), out[:, sub], rtol=1e-13, atol=1e-14)
+    # position 0 attends to itself only
+    assert np.allclose(out[:, 0], np.repeat(v, 2, axis=0)[:, 0])
