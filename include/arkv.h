@@ -90,6 +90,20 @@ int arkv_cache_reset(arkv_cache* cache, int32_t layer);
 int arkv_prefill_stats(arkv_cache* cache, int32_t layer, const void* q_win, const void* k, int32_t T,
                        float softmax_scale, float* stats, void* hip_stream);
 
+/* Causal self-attention of prompt queries with the scorer fused (Sec. IV-C: eq. 2's rows are the last W
+ * rows of the prompt's causal attention).  ASYNC on hip_stream.
+ * q [B][H_q][T_q][d] DEVICE bf16: the queries of positions [T - T_q, T); k, v [B][H_kv][T][d] DEVICE bf16: keys
+ * and values of positions [0, T), already position-encoded; out [B][H_q][T_q][d] DEVICE bf16:
+ * softmax(scale q k^T, causal) v.  A prompt may be fed in chunks: every call passes the keys so far and the new
+ * chunk's queries.
+ * stats == NULL: attention only.  stats != NULL ([B][3] DEVICE fp32, needs T_q >= W, T > W, layer not
+ * committed): the call also does what arkv_prefill_stats does for the last W queries; the softmax maxima and
+ * sums of those rows come out of the attention pass, so the scorer reads the keys once instead of twice.
+ * ARKV_EINVAL / ARKV_ESTATE as for arkv_prefill_stats. */
+int arkv_prefill_attention(arkv_cache* cache, int32_t layer, const void* q, const void* k, const void* v,
+                           int32_t T_q, int32_t T, float softmax_scale, void* out, float* stats,
+                           void* hip_stream);
+
 /* OQ score and ratio (eqs. 6-7).  HOST, pure.  stats [L][B][3] -> rho [L][B]:
  * q = H^(1/tau1) V^(1/tau2) Kurt^(1/tau3), rho = q / max over the layers of the same sequence;
  * if every q of a sequence is 0, every rho of it is 1. */

@@ -19,7 +19,7 @@ STATE_ORIGINAL, STATE_QUANTIZED, STATE_EVICTED = 0, 1, 2
 
 EXPORTED = [
     "arkv_config_default", "arkv_cache_create", "arkv_cache_destroy", "arkv_cache_reset",
-    "arkv_prefill_stats", "arkv_oq_ratio", "arkv_budget_counts", "arkv_prefill_commit",
+    "arkv_prefill_stats", "arkv_prefill_attention", "arkv_oq_ratio", "arkv_budget_counts", "arkv_prefill_commit",
     "arkv_decode_step", "arkv_decode_step_layers", "arkv_cache_counters", "arkv_cache_export",
     "arkv_debug_last_tailor_scores", "arkv_debug_last_out_f32", "arkv_cache_progress",
     "arkv_debug_time_attend", "arkv_debug_attend_time", "arkv_debug_stream_read", "arkv_debug_split_range",
@@ -152,6 +152,19 @@ def arkv_prefill_stats(cache, layer, q_win, k, T, softmax_scale, stats):
     _check(load().arkv_prefill_stats(cache, layer, _dev_ptr(q_win, torch.bfloat16), _dev_ptr(k, torch.bfloat16),
                                      T, softmax_scale, _dev_ptr(stats, torch.float32), _stream()),
            "arkv_prefill_stats")
+
+
+def arkv_prefill_attention(cache, layer, q, k, v, T_q, T, softmax_scale, out, stats=None):
+    import torch
+    lib = load()
+    lib.arkv_prefill_attention.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                           C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.arkv_prefill_attention.restype = C.c_int
+    _check(lib.arkv_prefill_attention(cache, layer, _dev_ptr(q, torch.bfloat16), _dev_ptr(k, torch.bfloat16),
+                                      _dev_ptr(v, torch.bfloat16), T_q, T, softmax_scale,
+                                      _dev_ptr(out, torch.bfloat16),
+                                      None if stats is None else _dev_ptr(stats, torch.float32), _stream()),
+           "arkv_prefill_attention")
 
 
 def arkv_oq_ratio(stats: np.ndarray, tau) -> np.ndarray:

@@ -100,12 +100,14 @@ struct CommitLaunch {
 };
 
 struct PrefillLaunch {
-  const uint16_t* q_win;  // [B][Hq][W][D]
+  const uint16_t* q_win;  // window query rows: row i of head h at q_win + h * q_head_stride + i * D
   const uint16_t* k;      // [B][Hkv][T][D]
   float2* pre;            // [U][T]  out: (s1, s2)
   float2* rowstat;        // [U][chunks][G*W] (row max base-2, row sum) partials
   float* stats;           // [B][3]
   int B, Hkv, G, W, D, T;
+  size_t q_head_stride;   // elements between heads (W*D for a packed [B][Hq][W][D] tensor)
+  int have_rowc;          // 1: the row constants are already in the scratch (attention pass), skip the first pass
   int chunk;              // keys per workgroup
   int n_chunks;
   float scale2;
@@ -117,6 +119,17 @@ hipError_t launch_stream_read(const void* buf, size_t offset_bytes, size_t bytes
 hipError_t launch_flush_scores(const Pools& P, int unit_begin, int n_units, int n_pending, int slot, hipStream_t s);
 hipError_t launch_tailor(const Pools& P, const TailorLaunch& a, hipStream_t s);
 hipError_t launch_commit(const Pools& P, const CommitLaunch& a, uint64_t* commit_keys /*[U][T]*/, hipStream_t s);
+// Causal prefill attention of T_q queries (positions [T - T_q, T)) over T keys.
+struct AttnLaunch {
+  const uint16_t* q;      // [B][Hq][Tq][D]
+  const uint16_t* k;      // [B][Hkv][T][D]
+  const uint16_t* v;
+  uint16_t* out;          // [B][Hq][Tq][D]
+  float* rowc;            // [U][MP] max + log2(sum) of the last W rows per head, or null
+  int B, Hq, Hkv, D, T, Tq, W, MP;
+  float scale2;
+};
+hipError_t launch_prefill_attn(const AttnLaunch& a, hipStream_t s);
 hipError_t launch_prefill_stats(const PrefillLaunch& a, float* rowc /*[U][MP] scratch*/, hipStream_t s);
 
 }  // namespace arkv

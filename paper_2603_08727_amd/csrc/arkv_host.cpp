@@ -285,13 +285,12 @@ int arkv_cache_reset(arkv_cache* c, int32_t layer) {
   return ARKV_OK;
 }
 
-int arkv_prefill_stats(arkv_cache* c, int32_t layer, const void* q_win, const void* k, int32_t T,
-                       float softmax_scale, float* stats, void* hip_stream) {
-  if (!c || !q_win || !k || !stats || layer < 0 || layer >= c->L) return ARKV_EINVAL;
-  if (T <= c->cfg.window || !(softmax_scale > 0.0f)) return ARKV_EINVAL;
+// Scorer of one layer (eqs. 2-5 + the window sums kept for the commit).  q_win: window query rows, heads
+// q_head_stride elements apart.  attn != nullptr: run the causal attention pass first; it leaves the window
+// rows' softmax constants in the scratch, so the scorer's own first pass over the keys is skipped.
+static int run_scorer(arkv_cache* c, int32_t layer, const uint16_t* q_win, size_t q_head_stride, const uint16_t* k,
+                      int32_t T, float softmax_scale, float* stats, hipStream_t s, AttnLaunch* attn) {
   LayerState& ls = c->layers[(size_t)layer];
-  if (ls.committed) return ARKV_ESTATE;
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int U = c->U, G = c->P.G, W = c->cfg.window;
   int rc;
   if ((rc = grow(&ls.pre, &ls.pre_cap, (size_t)U * T)) != ARKV_OK) return rc;
@@ -305,9 +304,15 @@ int arkv_prefill_stats(arkv_cache* c, int32_t layer, const void* q_win, const vo
   // row constants [U][MP] floats (MP even, so what follows is 8-byte aligned) + statistics partials
   const size_t stat_doubles = 4 * (size_t)c->cfg.batch * ((size_t)(T - W + 511) / 512);
   if ((rc = grow(&c->rowc, &c->rowc_cap, (size_t)U * MP + 2 * stat_doubles)) != ARKV_OK) return rc;
+  if (attn) {
+    attn->rowc = c->rowc; attn->MP = MP; attn->W = W;
+    HIP_TRY(launch_prefill_attn(*attn, s));
+  }
   PrefillLaunch a;
-  a.q_win = static_cast<const uint16_t*>(q_win);
-  a.k = static_cast<const uint16_t*>(k);
+  a.q_win = q_win;
+  a.q_head_stride = q_head_stride;
+  a.have_rowc = attn ? 1 : 0;
+  a.k = k;
   a.pre = ls.pre; a.rowstat = c->rowstat; a.stats = stats;
   a.B = c->cfg.batch; a.Hkv = c->cfg.n_kv_heads; a.G = G; a.W = W; a.D = c->P.D; a.T = T;
   a.chunk = chunk; a.n_chunks = n_chunks;
@@ -316,6 +321,41 @@ int arkv_prefill_stats(arkv_cache* c, int32_t layer, const void* q_win, const vo
   ls.scored = true; ls.scored_T = T;
   c->last_stream = s;
   return ARKV_OK;
+}
+
+int arkv_prefill_stats(arkv_cache* c, int32_t layer, const void* q_win, const void* k, int32_t T,
+                       float softmax_scale, float* stats, void* hip_stream) {
+  if (!c || !q_win || !k || !stats || layer < 0 || layer >= c->L) return ARKV_EINVAL;
+  if (T <= c->cfg.window || !(softmax_scale > 0.0f)) return ARKV_EINVAL;
+  if (c->layers[(size_t)layer].committed) return ARKV_ESTATE;
+  return run_scorer(c, layer, static_cast<const uint16_t*>(q_win), (size_t)c->cfg.window * c->P.D,
+                    static_cast<const uint16_t*>(k), T, softmax_scale, stats, static_cast<hipStream_t>(hip_stream),
+                    nullptr);
+}
+
+int arkv_prefill_attention(arkv_cache* c, int32_t layer, const void* q, const void* k, const void* v, int32_t T_q,
+                           int32_t T, float softmax_scale, void* out, float* stats, void* hip_stream) {
+  if (!c || !q || !k || !v || !out || layer < 0 || layer >= c->L) return ARKV_EINVAL;
+  if (T_q < 1 || T_q > T || !(softmax_scale > 0.0f)) return ARKV_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  AttnLaunch a;
+  a.q = static_cast<const uint16_t*>(q);
+  a.k = static_cast<const uint16_t*>(k);
+  a.v = static_cast<const uint16_t*>(v);
+  a.out = static_cast<uint16_t*>(out);
+  a.rowc = nullptr;
+  a.B = c->cfg.batch; a.Hq = c->cfg.n_q_heads; a.Hkv = c->cfg.n_kv_heads; a.D = c->P.D;
+  a.T = T; a.Tq = T_q; a.W = c->cfg.window; a.MP = 0;
+  a.scale2 = softmax_scale * 1.4426950408889634f;
+  if (!stats) {
+    HIP_TRY(launch_prefill_attn(a, s));
+    c->last_stream = s;
+    return ARKV_OK;
+  }
+  if (T_q < c->cfg.window || T <= c->cfg.window) return ARKV_EINVAL;
+  if (c->layers[(size_t)layer].committed) return ARKV_ESTATE;
+  const size_t D = (size_t)c->P.D;
+  return run_scorer(c, layer, a.q + (size_t)(T_q - c->cfg.window) * D, (size_t)T_q * D, a.k, T, softmax_scale, stats, s, &a);
 }
 
 int arkv_prefill_commit(arkv_cache* c, int32_t layer, const void* k, const void* v, int32_t T,

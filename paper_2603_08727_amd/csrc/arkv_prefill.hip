@@ -37,15 +37,16 @@ __device__ __forceinline__ float sum32(float x) {
   return x;
 }
 
-// Stage the unit's query rows in LDS: row r at byte r*(2D+16), rows >= M zero.
+// Stage the unit's query rows in LDS: row r = (head r / W, window query r % W) at byte r*(2D+16), rows >= M
+// zero.  q points at the unit's first head; heads are head_stride elements apart.
 template <int D>
-__device__ __forceinline__ void stage_q(unsigned char* sm, const uint16_t* q, int M, int MP) {
+__device__ __forceinline__ void stage_q(unsigned char* sm, const uint16_t* q, size_t head_stride, int W, int M, int MP) {
   constexpr int RB = 2 * D + 16;
   constexpr int VPR = D / 8;  // uint4 per row
   for (int i = threadIdx.x; i < MP * VPR; i += 256) {
     const int r = i / VPR, c = i % VPR;
     uint4 v = make_uint4(0, 0, 0, 0);
-    if (r < M) v = *reinterpret_cast<const uint4*>(q + (size_t)r * D + c * 8);
+    if (r < M) v = *reinterpret_cast<const uint4*>(q + (size_t)(r / W) * head_stride + (size_t)(r % W) * D + c * 8);
     *reinterpret_cast<uint4*>(sm + (size_t)r * RB + c * 16) = v;
   }
 }
@@ -78,7 +79,7 @@ __global__ __launch_bounds__(256) void k_prefill_rows(PrefillLaunch L) {
   extern __shared__ __align__(16) unsigned char sm[];
   const int chunk = blockIdx.x, u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int M = L.G * L.W, MP = RT * 32, T = L.T;
-  stage_q<D>(sm, L.q_win + (size_t)u * M * D, M, MP);
+  stage_q<D>(sm, L.q_win + (size_t)u * L.G * L.q_head_stride, L.q_head_stride, L.W, M, MP);
   __syncthreads();
   const uint16_t* k = L.k + (size_t)u * T * D;
   float m[RT], l[RT];
@@ -181,7 +182,7 @@ __global__ __launch_bounds__(256) void k_prefill_cols(PrefillLaunch L, const flo
   constexpr int RB = 2 * D + 16;
   const int chunk = blockIdx.x, u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int M = L.G * L.W, MP = RT * 32, T = L.T;
-  stage_q<D>(sm, L.q_win + (size_t)u * M * D, M, MP);
+  stage_q<D>(sm, L.q_win + (size_t)u * L.G * L.q_head_stride, L.q_head_stride, L.W, M, MP);
   float* crow = reinterpret_cast<float*>(sm + (size_t)MP * RB);   // [MP] -c_r (padded rows: +1e30 -> p = 0)
   int* lastk = reinterpret_cast<int*>(crow + MP);                 // [MP] last visible key of the row
   for (int r = tid; r < MP; r += 256) {
@@ -319,8 +320,10 @@ static hipError_t launch_prefill_t(const PrefillLaunch& a, float* rowc, hipStrea
     if (e != hipSuccess) return e;
   }
   dim3 grid(a.n_chunks, U);
-  hipLaunchKernelGGL((k_prefill_rows<D, RT>), grid, dim3(256), shm, s, a);
-  hipLaunchKernelGGL(k_prefill_rowfinal, dim3(MP / 32, U), dim3(256), 0, s, a, MP, rowc);
+  if (!a.have_rowc) {
+    hipLaunchKernelGGL((k_prefill_rows<D, RT>), grid, dim3(256), shm, s, a);
+    hipLaunchKernelGGL(k_prefill_rowfinal, dim3(MP / 32, U), dim3(256), 0, s, a, MP, rowc);
+  }
   hipLaunchKernelGGL((k_prefill_cols<D, RT>), grid, dim3(256), shm + (size_t)MP * 8, s, a, (const float*)rowc);
   const int nch = (a.T - a.W + kStatChunk - 1) / kStatChunk;
   double* zpart = reinterpret_cast<double*>(rowc + (size_t)U * MP);      // [B][nch], then [B][nch][3]

@@ -1,0 +1,128 @@
+"""Causal prefill attention with the scorer fused (arkv_prefill_attention) against the oracle: every output
+row on small prompts (whole prompt at once, in chunks, all group sizes, ragged lengths), sampled rows at the
+32K-context size, and the fused scorer against the stand-alone one and the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import arkv_oracle as O
+from paper_2603_08727_amd import binding as A
+from paper_2603_08727_amd import synth
+from helpers import TOL, SideBySide, make_cfg, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def _full_queries(wl, layer, qw):
+    """Queries of the whole prompt [B][Hq][T][d]: seeded draws for positions < T - W, the workload's window
+    queries for the last W positions."""
+    g = torch.Generator().manual_seed(wl.seed + 1000 * layer + 77)
+    q = torch.randn((wl.batch, wl.n_q_heads, wl.prefill, wl.head_dim), generator=g).to(torch.bfloat16)
+    q[:, :, wl.prefill - wl.window:, :] = qw
+    return q
+
+
+def _check_rows(out, q, k, v, scale, group, positions, q0):
+    """out [B][Hq][Tq][d] (GPU, bf16) rows at absolute `positions` against the oracle."""
+    worst = 0.0
+    for b in range(q.shape[0]):
+        ref = O.causal_attention_rows(synth.to_numpy_f32(q[b][:, positions - q0]), positions, synth.to_numpy_f32(k[b]),
+                                      synth.to_numpy_f32(v[b]), scale, group)
+        got = out[b][:, positions - q0].float().cpu().numpy()
+        for h in range(ref.shape[0]):
+            for r in range(ref.shape[1]):
+                worst = max(worst, rel_err(got[h, r], ref[h, r]))
+    return worst
+
+
+@pytest.mark.parametrize("hq,hkv,d,T", [(8, 2, 64, 200), (4, 4, 128, 97), (2, 1, 128, 160), (8, 1, 64, 131), (8, 2, 128, 33)])
+def test_attention_small_all_rows(hq, hkv, d, T):
+    wl = synth.C1.scaled(name="attn", n_q_heads=hq, n_kv_heads=hkv, head_dim=d, prefill=T, batch=2, budget_frac=2.0)
+    cfg = make_cfg(wl)
+    cache = A.arkv_cache_create(cfg)
+    try:
+        k, v, qw = synth.prefill_inputs(wl, 0)
+        q = _full_queries(wl, 0, qw)
+        scale = synth.softmax_scale(wl, 0)
+        out = torch.zeros_like(q, device="cuda")
+        A.arkv_prefill_attention(cache, 0, q.cuda(), k.cuda(), v.cuda(), T, T, scale, out)
+        torch.cuda.synchronize()
+        # bf16 output rounding adds up to 2^-9 relative per element
+        assert _check_rows(out, q, k, v, scale, hq // hkv, np.arange(T), 0) <= TOL + 2.0 ** -8
+        # the same prompt in three ragged chunks: keys so far, queries of the chunk
+        out2 = torch.zeros_like(out)
+        edges = sorted({0, min(40, T), min(41 + T // 3, T), T})
+        for a, e in zip(edges[:-1], edges[1:]):
+            if e <= a:
+                continue
+            oc = torch.zeros((wl.batch, hq, e - a, d), dtype=torch.bfloat16, device="cuda")
+            A.arkv_prefill_attention(cache, 0, q[:, :, a:e].contiguous().cuda(), k[:, :, :e].contiguous().cuda(),
+                                     v[:, :, :e].contiguous().cuda(), e - a, e, scale, oc)
+            out2[:, :, a:e] = oc
+        torch.cuda.synchronize()
+        assert torch.equal(out, out2)          # a row's result does not depend on how the prompt was cut
+    finally:
+        A.arkv_cache_destroy(cache)
+
+
+def test_fused_scorer_equals_standalone_and_oracle():
+    """arkv_prefill_attention(stats=...) then commit and decode: same statistics as arkv_prefill_stats (2e-3; the
+    row constants come from a different pass) and the usual state parity with the oracle afterwards."""
+    wl = synth.C1.scaled(name="fused", prefill=700, decode_steps=20, batch=2, n_layers=2)
+
+    class Fused(SideBySide):
+        def prefill(self):
+            super().prefill()                     # stand-alone scorer + oracle reference
+            stats_alone = self.stats_gpu.copy()
+            A.arkv_cache_reset(self.cache, -1)
+            wl_ = self.wl
+            stats = torch.zeros((wl_.n_layers, wl_.batch, 3), dtype=torch.float32, device=self.dev)
+            for l in range(wl_.n_layers):
+                k, v, qw = self.inputs[l]
+                q = _full_queries(wl_, l, qw)
+                out = torch.zeros_like(q, device=self.dev)
+                A.arkv_prefill_attention(self.cache, l, q.to(self.dev), k.to(self.dev), v.to(self.dev), wl_.prefill,
+                                         wl_.prefill, self.scales[l], out, stats[l])
+                pos = np.array([0, 1, 31, 32, 333, wl_.prefill - wl_.window - 1, wl_.prefill - 2, wl_.prefill - 1])
+                assert _check_rows(out, q, k, v, self.scales[l], wl_.group, pos, 0) <= TOL + 2.0 ** -8
+            torch.cuda.synchronize()
+            self.stats_gpu = stats.cpu().numpy()
+            assert np.all(np.abs(self.stats_gpu - stats_alone) <= TOL * np.abs(stats_alone))
+            err = np.abs(self.stats_gpu - self.stats_ref) / np.maximum(np.abs(self.stats_ref), 1e-300)
+            self.max_err["stats"] = float(err.max())
+            self.rho_gpu = A.arkv_oq_ratio(self.stats_gpu, wl_.tau)
+
+    sb = Fused(wl)
+    try:
+        sb.prefill()
+        sb.commit()
+        sb.decode(check_every=5)
+        sb.assert_within_tol()
+    finally:
+        sb.close()
+
+
+def test_attention_32k_sampled_rows():
+    """Config 3's prompt (32K tokens, batch 4, 32/8 heads, d = 128), one layer, whole prompt in one call; rows
+    the oracle can compute one by one: first, tile borders, middle, the window, last."""
+    wl = synth.C3.scaled(n_layers=1)
+    cfg = make_cfg(wl)
+    cache = A.arkv_cache_create(cfg)
+    try:
+        T = wl.prefill
+        k, v, qw = synth.prefill_inputs(wl, 0)
+        q = _full_queries(wl, 0, qw)
+        scale = synth.softmax_scale(wl, 0)
+        out = torch.zeros_like(q, device="cuda")
+        stats = torch.zeros((wl.batch, 3), dtype=torch.float32, device="cuda")
+        A.arkv_prefill_attention(cache, 0, q.cuda(), k.cuda(), v.cuda(), T, T, scale, out, stats)
+        torch.cuda.synchronize()
+        pos = np.array([0, 31, 32, 4097, 20000, T - wl.window, T - 1])
+        assert _check_rows(out, q, k, v, scale, wl.group, pos, 0) <= TOL + 2.0 ** -8
+        ref = []
+        for b in range(wl.batch):
+            a = O.window_attention(synth.to_numpy_f32(qw[b]), synth.to_numpy_f32(k[b]), scale, wl.group)
+            ref.append(O.layer_statistics(a, wl.window)[:3])
+        assert np.all(np.abs(stats.cpu().numpy() - np.array(ref)) <= TOL * np.abs(np.array(ref)))
+    finally:
+        A.arkv_cache_destroy(cache)
