@@ -229,6 +229,52 @@ def scorer_measure(wl, window, layers=4):
         A.arkv_cache_destroy(cache)
 
 
+def attention_measure(wl, layers=2):
+    """Causal prefill attention of the whole prompt (one call per layer) with the scorer fused, against the
+    bf16 matrix-core peak, and the scorer's cost with and without the fusion."""
+    import torch
+    from paper_2603_08727_amd import binding as A
+    from paper_2603_08727_amd import synth
+    wl = wl.scaled(n_layers=layers)
+    dev = "cuda"
+    L, B, Hq, Hkv, d, T, W = wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.prefill, wl.window
+    cfg = A.arkv_config_default(n_layers=L, batch=B, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d,
+                                capacity_tokens=wl.capacity, window=W, alpha=wl.alpha, gamma=wl.gamma,
+                                tau=wl.tau, quant_bits=wl.bits)
+    cache = A.arkv_cache_create(cfg)
+    try:
+        res = {}
+        for name, with_stats in (("attention_only", False), ("attention_with_scorer", True)):
+            ms = []
+            for rep in range(2):
+                A.arkv_cache_reset(cache, -1)
+                for l in range(L):
+                    k, v, qw = synth.prefill_inputs(wl, l, device=dev)
+                    g = torch.Generator(device=dev).manual_seed(wl.seed + 1000 * l + 77)
+                    q = torch.randn((B, Hq, T, d), generator=g, device=dev).to(torch.bfloat16)
+                    q[:, :, T - W:, :] = qw
+                    out = torch.empty_like(q)
+                    stats = torch.zeros((B, 3), dtype=torch.float32, device=dev) if with_stats else None
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    A.arkv_prefill_attention(cache, l, q, k, v, T, T, synth.softmax_scale(wl, l), out, stats)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    if rep:
+                        ms.append(e0.elapsed_time(e1))
+                    del q, k, v, out
+            res[name] = sum(ms) / len(ms)
+        flops = 4.0 * B * Hq * d * (T * (T + 1) / 2.0)          # QK^T and PV over the causal half
+        t = res["attention_only"] * 1e-3
+        return {"ms_per_layer_attention": round(res["attention_only"], 3),
+                "ms_per_layer_attention_with_scorer": round(res["attention_with_scorer"], 3),
+                "scorer_extra_ms_when_fused": round(res["attention_with_scorer"] - res["attention_only"], 3),
+                "TFLOPs": round(flops / t / 1e12, 1), "frac_of_bf16_mfma_peak": round(flops / t / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                "context": T, "batch": B, "layers_timed": L}
+    finally:
+        A.arkv_cache_destroy(cache)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -511,6 +557,8 @@ def main():
         # prefill-scorer stress shape (16K context, batch 8) at the paper's window and at a 4x window, where the
         # contraction is compute-bound
         result["scorer_stress"] = {"c5_w32": scorer_measure(synth.C5, 32), "c5_w128": scorer_measure(synth.C5, 128)}
+        # causal prefill attention of the 32K prompt with the scorer fused (the headline workload's prompt)
+        result["prefill_attention"] = attention_measure(wl)
     if not args.no_cpu_baseline:
         # the oracle needs ~10 ms per sequence-step at this shape: 1500 steps of sequence 0 bound the sample
         # to the time budget below (same recipe as the GPU run's decode inputs, a longer draw)

@@ -3,14 +3,18 @@
 // maxima and sums).
 //
 // One workgroup = 32 query positions of one (sequence, kv-head); wave w = q-head w of the group, so the G
-// heads of a group share every key and value tile.  Keys are on the M side of the logits MFMA
+// heads of a group share every key and value tile, which is fetched from HBM once per workgroup and staged
+// in LDS (double buffered, one barrier per 32-key tile).  Keys are on the M side of the logits MFMA
 // (v_mfma_f32_32x32x16_bf16, S^T = K Q^T), which leaves ONE query row per lane: the online softmax is
 // per-lane arithmetic plus one exchange between the two lane halves.  The probabilities a lane then holds
 // (keys 8(i/4) + 4(lane/32) + i%4 of the tile) are, eight at a time, exactly a B operand of the PV MFMA
-// (O^T = V^T P^T) if the contraction index is read in that key order; the value tile is staged in LDS
-// transposed ([channel][key], fp16) so that the matching A operand is two 8-byte reads.  Probabilities
-// are rounded to fp16 (values to fp16 exactly or nearly: bf16 has fewer mantissa bits), accumulation fp32.
+// (O^T = V^T P^T) if the contraction index is read in that key order; the value tile is staged transposed
+// ([channel][key], fp16) with its key columns permuted so that the matching A operand is one 16-byte read.
+// Probabilities are rounded to fp16 (values to fp16 exactly: bf16 has fewer mantissa bits; magnitudes
+// beyond fp16's range are not supported), accumulation fp32.
 #include <hip/hip_fp16.h>
+
+#include <type_traits>
 
 #include "arkv_dev.h"
 
@@ -21,23 +25,38 @@ typedef _Float16 f16x8a __attribute__((ext_vector_type(8)));
 typedef float f32x16a __attribute__((ext_vector_type(16)));
 
 constexpr float kNegBigA = -1.0e30f;
-constexpr int kVtPitch = 36;   // halves per channel row of the transposed value tile (32 keys + pad, 8-byte aligned)
+constexpr int kVtPitch = 40;   // halves per channel row of the transposed value tile: 32 keys + 8 (16-byte reads, 20-dword stride)
 
 __device__ __forceinline__ float aexp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// bf16 pair (low, high halves of a dword) -> fp16 pair
-__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t v) {
-  const float lo = __uint_as_float(v << 16), hi = __uint_as_float(v & 0xffff0000u);
-  const __half2 h = __floats2half2_rn(lo, hi);
+// two bf16 values (each in the LOW half of its dword) -> packed fp16 pair (a low, b high)
+__device__ __forceinline__ uint32_t bf16_pair_to_f16x2(uint32_t a, uint32_t b) {
+  const __half2 h = __floats2half2_rn(__uint_as_float(a << 16), __uint_as_float(b << 16));
   return *reinterpret_cast<const uint32_t*>(&h);
 }
 
+// column of key j (0..31) in the transposed value tile: the eight keys 16 jj + 8 a + 4 hh + r (a = 0, 1;
+// r = 0..3) that lane half hh contracts in PV step jj sit side by side at 16 jj + 8 hh + 4 a + r
+__device__ __forceinline__ int vt_col(int j) { return (j & 16) | ((j & 4) << 1) | ((j & 8) >> 1) | (j & 3); }
+
+template <int D>
+struct AttnLds {
+  static constexpr int KP = D + 8;              // halves per key row: 16-byte reads of 16 keys hit 64 banks
+  uint16_t k[2][32][KP];
+  _Float16 vt[2][D][kVtPitch];
+};
+
 template <int D, int G>
-__global__ __launch_bounds__(64 * G) void k_prefill_attn(AttnLaunch L) {
+__global__ __launch_bounds__(64 * G, G >= 4 ? 2 : 1) void k_prefill_attn(AttnLaunch L) {
   constexpr int KK = D / 16;          // k-steps of the logits MFMA
   constexpr int CBN = D / 32;         // 32-channel blocks of the output
   constexpr int NT = 64 * G;
-  __shared__ __align__(16) _Float16 vt[2][D][kVtPitch];
+  constexpr int CPR = D / 8;          // 16-byte chunks per row
+  constexpr int KCH = 32 * CPR;       // key chunks per tile
+  constexpr int VCH = 16 * CPR;       // value chunk pairs (two adjacent keys, eight channels) per tile
+  constexpr int KPT = (KCH + NT - 1) / NT;
+  constexpr int VPT = (VCH + NT - 1) / NT;
+  __shared__ __align__(16) AttnLds<D> sm;
   const int qb = gridDim.x - 1 - blockIdx.x;      // long rows first
   const int u = blockIdx.y, b = u / L.Hkv, g = u % L.Hkv;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -50,6 +69,7 @@ __global__ __launch_bounds__(64 * G) void k_prefill_attn(AttnLaunch L) {
   const int ntiles = (jmax + 31) / 32;
   const uint16_t* kbase = L.k + (size_t)u * T * D;
   const uint16_t* vbase = L.v + (size_t)u * T * D;
+  const float scale2 = L.scale2;
 
   // query operand (B of S^T = K Q^T): row n, channels 16 kk + 8 hh .. +7
   uint4 qreg[KK];
@@ -58,35 +78,40 @@ __global__ __launch_bounds__(64 * G) void k_prefill_attn(AttnLaunch L) {
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) qreg[kk] = *reinterpret_cast<const uint4*>(qp + 16 * kk);
   }
-  auto load_k = [&](uint4 (&kf)[KK], int j0) {
-    const int key = min(j0 + n, T - 1);
-    const uint16_t* p = kbase + (size_t)key * D + 8 * hh;
+  // global -> registers -> LDS staging of one tile (rows past the end are clamped: they are masked)
+  uint4 ks[KPT], vs[VPT][2];
+  auto fetch = [&](int j0) {
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) kf[kk] = *reinterpret_cast<const uint4*>(p + 16 * kk);
-  };
-  // value tile: 32 keys x D channels = 4 D uint4 chunks, spread over the workgroup
-  constexpr int VCH = 4 * D;                       // chunks of 8 channels
-  constexpr int VPT = (VCH + NT - 1) / NT;         // chunks per thread
-  auto load_v = [&](uint4 (&vr)[VPT], int j0) {
+    for (int c = 0; c < KPT; ++c) {
+      const int ch = min(tid + NT * c, KCH - 1);
+      const int key = min(j0 + ch / CPR, T - 1);
+      ks[c] = *reinterpret_cast<const uint4*>(kbase + (size_t)key * D + 8 * (ch % CPR));
+    }
 #pragma unroll
     for (int c = 0; c < VPT; ++c) {
       const int ch = min(tid + NT * c, VCH - 1);
-      const int key = min(j0 + ch / (D / 8), T - 1);
-      vr[c] = *reinterpret_cast<const uint4*>(vbase + (size_t)key * D + 8 * (ch % (D / 8)));
+      const int k0 = min(j0 + 2 * (ch % 16), T - 1), k1 = min(j0 + 2 * (ch % 16) + 1, T - 1);
+      vs[c][0] = *reinterpret_cast<const uint4*>(vbase + (size_t)k0 * D + 8 * (ch / 16));
+      vs[c][1] = *reinterpret_cast<const uint4*>(vbase + (size_t)k1 * D + 8 * (ch / 16));
     }
   };
-  auto stage_v = [&](const uint4 (&vr)[VPT], int buf) {
+  auto stage = [&](int buf) {
+#pragma unroll
+    for (int c = 0; c < KPT; ++c) {
+      const int ch = tid + NT * c;
+      if (KCH % NT == 0 || ch < KCH) *reinterpret_cast<uint4*>(&sm.k[buf][ch / CPR][8 * (ch % CPR)]) = ks[c];
+    }
 #pragma unroll
     for (int c = 0; c < VPT; ++c) {
       const int ch = tid + NT * c;
-      if (ch < VCH) {
-        const int key = ch / (D / 8), c0 = 8 * (ch % (D / 8));
-        const uint32_t h[4] = {bf16x2_to_f16x2(vr[c].x), bf16x2_to_f16x2(vr[c].y), bf16x2_to_f16x2(vr[c].z),
-                               bf16x2_to_f16x2(vr[c].w)};
+      if (VCH % NT == 0 || ch < VCH) {
+        const int col = vt_col(2 * (ch % 16)), c0 = 8 * (ch / 16);
+        const uint32_t a[4] = {vs[c][0].x, vs[c][0].y, vs[c][0].z, vs[c][0].w};
+        const uint32_t bq[4] = {vs[c][1].x, vs[c][1].y, vs[c][1].z, vs[c][1].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          reinterpret_cast<uint16_t&>(vt[buf][c0 + 2 * e][key]) = (uint16_t)(h[e] & 0xffffu);
-          reinterpret_cast<uint16_t&>(vt[buf][c0 + 2 * e + 1][key]) = (uint16_t)(h[e] >> 16);
+          *reinterpret_cast<uint32_t*>(&sm.vt[buf][c0 + 2 * e][col]) = bf16_pair_to_f16x2(a[e], bq[e]);
+          *reinterpret_cast<uint32_t*>(&sm.vt[buf][c0 + 2 * e + 1][col]) = bf16_pair_to_f16x2(a[e] >> 16, bq[e] >> 16);
         }
       }
     }
@@ -99,33 +124,28 @@ __global__ __launch_bounds__(64 * G) void k_prefill_attn(AttnLaunch L) {
     for (int i = 0; i < 16; ++i) acc[cb][i] = 0.f;
   float m_run = kNegBigA, l_run = 0.f;
 
-  uint4 kf[KK], kn[KK], vr[VPT];
-  load_k(kf, 0);
-  load_v(vr, 0);
-  stage_v(vr, 0);
-  __syncthreads();
-  for (int t = 0; t < ntiles; ++t) {
-    const int j0 = 32 * t, buf = t & 1;
-    load_k(kn, j0 + 32);                            // clamped past the end
-    load_v(vr, j0 + 32);
+  // one 32-key tile from LDS buffer `buf`; MASK: some key of the tile lies beyond some row of the block
+  auto tile = [&](auto mask_tag, int j0, int buf) {
+    constexpr bool MASK = decltype(mask_tag)::value;
     f32x16a C;
 #pragma unroll
     for (int i = 0; i < 16; ++i) C[i] = 0.f;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk)
-      C = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8a, kf[kk]), __builtin_bit_cast(bf16x8a, qreg[kk]), C, 0, 0, 0);
-    // logits of row n against keys j0 + 8(i/4) + 4hh + i%4
-    float x[16];
-    float mt = kNegBigA;
-    const bool need_mask = j0 + 31 > q0 + 32 * qb;   // some key of the tile is beyond some row of the block
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int j = j0 + 8 * (i >> 2) + 4 * hh + (i & 3);
-      x[i] = (!need_mask || j <= pos) ? C[i] * L.scale2 : kNegBigA;
-      mt = fmaxf(mt, x[i]);
+    for (int kk = 0; kk < KK; ++kk) {
+      const uint4 ka = *reinterpret_cast<const uint4*>(&sm.k[buf][n][16 * kk + 8 * hh]);
+      C = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8a, ka), __builtin_bit_cast(bf16x8a, qreg[kk]), C, 0, 0, 0);
     }
-    mt = fmaxf(mt, __shfl_xor(mt, 32));
-    if (__any(mt > m_run + 8.0f)) {                 // move the reference maximum (rare after the first tiles)
+    // C[i]: unscaled logit of row n against key j0 + 8(i/4) + 4hh + i%4
+    if (MASK) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        if (j0 + 8 * (i >> 2) + 4 * hh + (i & 3) > pos) C[i] = kNegBigA;
+    }
+    float mt = C[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) mt = fmaxf(mt, C[i]);
+    mt = fmaxf(mt, __shfl_xor(mt, 32)) * scale2;      // scale2 > 0: the maximum commutes with the scaling
+    if (__any(mt > m_run + 8.0f)) {                   // move the reference maximum (rare after the first tiles)
       const float mn = fmaxf(m_run, mt);
       const float f = aexp2(m_run - mn);
       m_run = mn;
@@ -137,7 +157,7 @@ __global__ __launch_bounds__(64 * G) void k_prefill_attn(AttnLaunch L) {
     }
     float p[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { p[i] = aexp2(x[i] - m_run); l_run += p[i]; }   // masked: 2^(-1e30 - m) = 0
+    for (int i = 0; i < 16; ++i) { p[i] = aexp2(fmaf(C[i], scale2, -m_run)); l_run += p[i]; }   // masked: 2^(-huge) = 0
     // probabilities as fp16, eight per PV k-step: jj = 0 -> i = 0..7, jj = 1 -> i = 8..15
     uint32_t ph[8];
 #pragma unroll
@@ -150,17 +170,22 @@ __global__ __launch_bounds__(64 * G) void k_prefill_attn(AttnLaunch L) {
       const uint4 pb = make_uint4(ph[4 * jj], ph[4 * jj + 1], ph[4 * jj + 2], ph[4 * jj + 3]);
 #pragma unroll
       for (int cb = 0; cb < CBN; ++cb) {
-        // A = V^T: channel 32 cb + n, keys 16 jj + 4 hh + (0..3) and 16 jj + 8 + 4 hh + (0..3)
-        const _Float16* vrow = &vt[buf][32 * cb + n][16 * jj + 4 * hh];
-        const uint2 a0 = *reinterpret_cast<const uint2*>(vrow);
-        const uint2 a1 = *reinterpret_cast<const uint2*>(vrow + 8);
-        const uint4 va = make_uint4(a0.x, a0.y, a1.x, a1.y);
+        // A = V^T: channel 32 cb + n, keys 16 jj + 4 hh + (0..3) and 16 jj + 8 + 4 hh + (0..3), adjacent in LDS
+        const uint4 va = *reinterpret_cast<const uint4*>(&sm.vt[buf][32 * cb + n][16 * jj + 8 * hh]);
         acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8a, va), __builtin_bit_cast(f16x8a, pb), acc[cb], 0, 0, 0);
       }
     }
-    stage_v(vr, buf ^ 1);                           // the other buffer was last read one iteration ago
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) kf[kk] = kn[kk];
+  };
+
+  fetch(0);
+  stage(0);
+  __syncthreads();
+  for (int t = 0; t < ntiles; ++t) {
+    const int j0 = 32 * t, buf = t & 1;
+    if (t + 1 < ntiles) fetch(j0 + 32);
+    if (j0 + 31 > q0 + 32 * qb) tile(std::true_type{}, j0, buf);
+    else tile(std::false_type{}, j0, buf);
+    if (t + 1 < ntiles) stage(buf ^ 1);               // the other buffer was last read one iteration ago
     __syncthreads();
   }
 
