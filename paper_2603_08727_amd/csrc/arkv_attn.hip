@@ -14,8 +14,6 @@
 // beyond fp16's range are not supported), accumulation fp32.
 #include <hip/hip_fp16.h>
 
-#include <type_traits>
-
 #include "arkv_dev.h"
 
 namespace arkv {
@@ -23,6 +21,7 @@ namespace arkv {
 typedef __bf16 bf16x8a __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8a __attribute__((ext_vector_type(8)));
 typedef float f32x16a __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4a __attribute__((ext_vector_type(4)));   // a 16-byte chunk the compiler keeps in registers
 
 constexpr float kNegBigA = -1.0e30f;
 constexpr int kVtPitch = 40;   // halves per channel row of the transposed value tile: 32 keys + 8 (16-byte reads, 20-dword stride)
@@ -79,27 +78,27 @@ __global__ __launch_bounds__(64 * G, G >= 4 ? 2 : 1) void k_prefill_attn(AttnLau
     for (int kk = 0; kk < KK; ++kk) qreg[kk] = *reinterpret_cast<const uint4*>(qp + 16 * kk);
   }
   // global -> registers -> LDS staging of one tile (rows past the end are clamped: they are masked)
-  uint4 ks[KPT], vs[VPT][2];
+  u32x4a ks[KPT], vs[VPT][2];
   auto fetch = [&](int j0) {
 #pragma unroll
     for (int c = 0; c < KPT; ++c) {
       const int ch = min(tid + NT * c, KCH - 1);
       const int key = min(j0 + ch / CPR, T - 1);
-      ks[c] = *reinterpret_cast<const uint4*>(kbase + (size_t)key * D + 8 * (ch % CPR));
+      ks[c] = *reinterpret_cast<const u32x4a*>(kbase + (size_t)key * D + 8 * (ch % CPR));
     }
 #pragma unroll
     for (int c = 0; c < VPT; ++c) {
       const int ch = min(tid + NT * c, VCH - 1);
       const int k0 = min(j0 + 2 * (ch % 16), T - 1), k1 = min(j0 + 2 * (ch % 16) + 1, T - 1);
-      vs[c][0] = *reinterpret_cast<const uint4*>(vbase + (size_t)k0 * D + 8 * (ch / 16));
-      vs[c][1] = *reinterpret_cast<const uint4*>(vbase + (size_t)k1 * D + 8 * (ch / 16));
+      vs[c][0] = *reinterpret_cast<const u32x4a*>(vbase + (size_t)k0 * D + 8 * (ch / 16));
+      vs[c][1] = *reinterpret_cast<const u32x4a*>(vbase + (size_t)k1 * D + 8 * (ch / 16));
     }
   };
   auto stage = [&](int buf) {
 #pragma unroll
     for (int c = 0; c < KPT; ++c) {
       const int ch = tid + NT * c;
-      if (KCH % NT == 0 || ch < KCH) *reinterpret_cast<uint4*>(&sm.k[buf][ch / CPR][8 * (ch % CPR)]) = ks[c];
+      if (KCH % NT == 0 || ch < KCH) *reinterpret_cast<u32x4a*>(&sm.k[buf][ch / CPR][8 * (ch % CPR)]) = ks[c];
     }
 #pragma unroll
     for (int c = 0; c < VPT; ++c) {
@@ -124,9 +123,8 @@ __global__ __launch_bounds__(64 * G, G >= 4 ? 2 : 1) void k_prefill_attn(AttnLau
     for (int i = 0; i < 16; ++i) acc[cb][i] = 0.f;
   float m_run = kNegBigA, l_run = 0.f;
 
-  // one 32-key tile from LDS buffer `buf`; MASK: some key of the tile lies beyond some row of the block
-  auto tile = [&](auto mask_tag, int j0, int buf) {
-    constexpr bool MASK = decltype(mask_tag)::value;
+  // one 32-key tile from LDS buffer `buf`; masked: some key of the tile lies beyond some row of the block
+  auto tile = [&](bool masked, int j0, int buf) {
     f32x16a C;
 #pragma unroll
     for (int i = 0; i < 16; ++i) C[i] = 0.f;
@@ -136,7 +134,7 @@ __global__ __launch_bounds__(64 * G, G >= 4 ? 2 : 1) void k_prefill_attn(AttnLau
       C = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8a, ka), __builtin_bit_cast(bf16x8a, qreg[kk]), C, 0, 0, 0);
     }
     // C[i]: unscaled logit of row n against key j0 + 8(i/4) + 4hh + i%4
-    if (MASK) {
+    if (masked) {
 #pragma unroll
       for (int i = 0; i < 16; ++i)
         if (j0 + 8 * (i >> 2) + 4 * hh + (i & 3) > pos) C[i] = kNegBigA;
@@ -144,9 +142,9 @@ __global__ __launch_bounds__(64 * G, G >= 4 ? 2 : 1) void k_prefill_attn(AttnLau
     float mt = C[0];
 #pragma unroll
     for (int i = 1; i < 16; ++i) mt = fmaxf(mt, C[i]);
-    mt = fmaxf(mt, __shfl_xor(mt, 32)) * scale2;      // scale2 > 0: the maximum commutes with the scaling
+    mt *= scale2;                                     // scale2 > 0: the maximum commutes with the scaling
     if (__any(mt > m_run + 8.0f)) {                   // move the reference maximum (rare after the first tiles)
-      const float mn = fmaxf(m_run, mt);
+      const float mn = fmaxf(m_run, fmaxf(mt, __shfl_xor(mt, 32)));   // both lane halves of a row agree on it
       const float f = aexp2(m_run - mn);
       m_run = mn;
       l_run *= f;
@@ -182,10 +180,9 @@ __global__ __launch_bounds__(64 * G, G >= 4 ? 2 : 1) void k_prefill_attn(AttnLau
   __syncthreads();
   for (int t = 0; t < ntiles; ++t) {
     const int j0 = 32 * t, buf = t & 1;
-    if (t + 1 < ntiles) fetch(j0 + 32);
-    if (j0 + 31 > q0 + 32 * qb) tile(std::true_type{}, j0, buf);
-    else tile(std::false_type{}, j0, buf);
-    if (t + 1 < ntiles) stage(buf ^ 1);               // the other buffer was last read one iteration ago
+    fetch(j0 + 32);                                   // past the last tile: clamped rows, staged but never read
+    tile(j0 + 31 > q0 + 32 * qb, j0, buf);
+    stage(buf ^ 1);                                   // the other buffer was last read one iteration ago
     __syncthreads();
   }
 
