@@ -41,20 +41,28 @@ __device__ __forceinline__ int vt_col(int j) { return (j & 16) | ((j & 4) << 1) 
 template <int D>
 struct AttnLds {
   static constexpr int KP = D + 8;              // halves per key row: 16-byte reads of 16 keys hit 64 banks
-  uint16_t k[2][32][KP];
+  uint16_t k[3][32][KP];                        // key tiles t + 1 (logits now), t + 2 (operands prefetched), t + 3 (being staged)
   _Float16 vt[2][D][kVtPitch];
 };
+
+// sched_group_barrier classes
+constexpr int kSgValu = 0x2, kSgMfma = 0x8, kSgDsRead = 0x100;
+typedef _Float16 f16x2a __attribute__((ext_vector_type(2)));
+constexpr float kSumLimit = 16384.0f;   // a lane's 16 probabilities may sum to this before the reference maximum moves
 
 template <int D, int G>
 __global__ __launch_bounds__(64 * G, G >= 4 ? 2 : 1) void k_prefill_attn(AttnLaunch L) {
   constexpr int KK = D / 16;          // k-steps of the logits MFMA
+  constexpr int KH = KK / 2;          // operands carried from the previous phase
   constexpr int CBN = D / 32;         // 32-channel blocks of the output
+  constexpr int NPV = 2 * CBN;        // PV MFMAs per tile
   constexpr int NT = 64 * G;
   constexpr int CPR = D / 8;          // 16-byte chunks per row
   constexpr int KCH = 32 * CPR;       // key chunks per tile
   constexpr int VCH = 16 * CPR;       // value chunk pairs (two adjacent keys, eight channels) per tile
   constexpr int KPT = (KCH + NT - 1) / NT;
   constexpr int VPT = (VCH + NT - 1) / NT;
+  static_assert(NPV >= KH, "operand prefetch pattern");
   __shared__ __align__(16) AttnLds<D> sm;
   const int qb = gridDim.x - 1 - blockIdx.x;      // long rows first
   const int u = blockIdx.y, b = u / L.Hkv, g = u % L.Hkv;
@@ -66,54 +74,85 @@ __global__ __launch_bounds__(64 * G, G >= 4 ? 2 : 1) void k_prefill_attn(AttnLau
   const int pos = q0 + rowc_;                      // its position: sees keys j <= pos
   const int jmax = min(T, q0 + 32 * qb + 32);      // keys any row of this workgroup can see
   const int ntiles = (jmax + 31) / 32;
+  const int jfull = q0 + 32 * qb - 31;             // tiles starting at or before this need no mask
   const uint16_t* kbase = L.k + (size_t)u * T * D;
   const uint16_t* vbase = L.v + (size_t)u * T * D;
   const float scale2 = L.scale2;
 
   // query operand (B of S^T = K Q^T): row n, channels 16 kk + 8 hh .. +7
-  uint4 qreg[KK];
+  u32x4a qreg[KK];
   {
     const uint16_t* qp = L.q + ((size_t)(b * L.Hq + g * G + w) * Tq + rowc_) * D + 8 * hh;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) qreg[kk] = *reinterpret_cast<const uint4*>(qp + 16 * kk);
+    for (int kk = 0; kk < KK; ++kk) qreg[kk] = *reinterpret_cast<const u32x4a*>(qp + 16 * kk);
   }
-  // global -> registers -> LDS staging of one tile (rows past the end are clamped: they are masked)
+  // global -> registers -> LDS staging of one tile.  A tile that ends inside the prompt is addressed as a
+  // uniform base plus a per-thread constant; the last, partial one (and the prefetch past it) clamps its rows
+  // to the prompt: the surplus keys are masked or never read.
   u32x4a ks[KPT], vs[VPT][2];
-  auto fetch = [&](int j0) {
+  auto fetch_k = [&](int j0) {
+    if (j0 + 32 <= T) {
+      const uint16_t* base = kbase + (size_t)j0 * D;
 #pragma unroll
-    for (int c = 0; c < KPT; ++c) {
-      const int ch = min(tid + NT * c, KCH - 1);
-      const int key = min(j0 + ch / CPR, T - 1);
-      ks[c] = *reinterpret_cast<const u32x4a*>(kbase + (size_t)key * D + 8 * (ch % CPR));
-    }
+      for (int c = 0; c < KPT; ++c) {
+        const int ch = min(tid + NT * c, KCH - 1);
+        ks[c] = *reinterpret_cast<const u32x4a*>(base + (ch / CPR) * D + 8 * (ch % CPR));
+      }
+    } else {
 #pragma unroll
-    for (int c = 0; c < VPT; ++c) {
-      const int ch = min(tid + NT * c, VCH - 1);
-      const int k0 = min(j0 + 2 * (ch % 16), T - 1), k1 = min(j0 + 2 * (ch % 16) + 1, T - 1);
-      vs[c][0] = *reinterpret_cast<const u32x4a*>(vbase + (size_t)k0 * D + 8 * (ch / 16));
-      vs[c][1] = *reinterpret_cast<const u32x4a*>(vbase + (size_t)k1 * D + 8 * (ch / 16));
+      for (int c = 0; c < KPT; ++c) {
+        const int ch = min(tid + NT * c, KCH - 1);
+        const int key = min(j0 + ch / CPR, T - 1);
+        ks[c] = *reinterpret_cast<const u32x4a*>(kbase + (size_t)key * D + 8 * (ch % CPR));
+      }
     }
   };
-  auto stage = [&](int buf) {
+  auto fetch_v = [&](int j0) {
+    if (j0 + 32 <= T) {
+      const uint16_t* base = vbase + (size_t)j0 * D;
+#pragma unroll
+      for (int c = 0; c < VPT; ++c) {
+        const int ch = min(tid + NT * c, VCH - 1);
+        const uint16_t* p = base + 2 * (ch % 16) * D + 8 * (ch / 16);
+        vs[c][0] = *reinterpret_cast<const u32x4a*>(p);
+        vs[c][1] = *reinterpret_cast<const u32x4a*>(p + D);
+      }
+    } else {
+#pragma unroll
+      for (int c = 0; c < VPT; ++c) {
+        const int ch = min(tid + NT * c, VCH - 1);
+        const int k0 = min(j0 + 2 * (ch % 16), T - 1), k1 = min(j0 + 2 * (ch % 16) + 1, T - 1);
+        vs[c][0] = *reinterpret_cast<const u32x4a*>(vbase + (size_t)k0 * D + 8 * (ch / 16));
+        vs[c][1] = *reinterpret_cast<const u32x4a*>(vbase + (size_t)k1 * D + 8 * (ch / 16));
+      }
+    }
+  };
+  auto stage_k = [&](int buf) {
 #pragma unroll
     for (int c = 0; c < KPT; ++c) {
       const int ch = tid + NT * c;
       if (KCH % NT == 0 || ch < KCH) *reinterpret_cast<u32x4a*>(&sm.k[buf][ch / CPR][8 * (ch % CPR)]) = ks[c];
     }
+  };
+  auto stage_v = [&](int buf) {
 #pragma unroll
     for (int c = 0; c < VPT; ++c) {
       const int ch = tid + NT * c;
       if (VCH % NT == 0 || ch < VCH) {
         const int col = vt_col(2 * (ch % 16)), c0 = 8 * (ch / 16);
-        const uint32_t a[4] = {vs[c][0].x, vs[c][0].y, vs[c][0].z, vs[c][0].w};
-        const uint32_t bq[4] = {vs[c][1].x, vs[c][1].y, vs[c][1].z, vs[c][1].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          *reinterpret_cast<uint32_t*>(&sm.vt[buf][c0 + 2 * e][col]) = bf16_pair_to_f16x2(a[e], bq[e]);
-          *reinterpret_cast<uint32_t*>(&sm.vt[buf][c0 + 2 * e + 1][col]) = bf16_pair_to_f16x2(a[e] >> 16, bq[e] >> 16);
+          *reinterpret_cast<uint32_t*>(&sm.vt[buf][c0 + 2 * e][col]) = bf16_pair_to_f16x2(vs[c][0][e], vs[c][1][e]);
+          *reinterpret_cast<uint32_t*>(&sm.vt[buf][c0 + 2 * e + 1][col]) = bf16_pair_to_f16x2(vs[c][0][e] >> 16, vs[c][1][e] >> 16);
         }
       }
     }
+  };
+  auto k_operand = [&](int buf, int kk) { return *reinterpret_cast<const u32x4a*>(&sm.k[buf][n][16 * kk + 8 * hh]); };
+  // A of O^T = V^T P^T, PV MFMA r = jj * CBN + cb: channel 32 cb + n, keys 16 jj + 4 hh + (0..3) and
+  // 16 jj + 8 + 4 hh + (0..3), adjacent in LDS
+  auto v_operand = [&](int buf, int r) {
+    return *reinterpret_cast<const u32x4a*>(&sm.vt[buf][32 * (r % CBN) + n][16 * (r / CBN) + 8 * hh]);
   };
 
   f32x16a acc[CBN];
@@ -122,29 +161,68 @@ __global__ __launch_bounds__(64 * G, G >= 4 ? 2 : 1) void k_prefill_attn(AttnLau
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[cb][i] = 0.f;
   float m_run = kNegBigA, l_run = 0.f;
+  u32x4a kop[KK], vop[NPV];
+  int kA = 1, kB = 2, kW = 0;       // LDS buffers of key tiles t + 1, t + 2 and t + 3 (= the one tile t leaves)
 
-  // one 32-key tile from LDS buffer `buf`; masked: some key of the tile lies beyond some row of the block
-  auto tile = [&](bool masked, int j0, int buf) {
-    f32x16a C;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) C[i] = 0.f;
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      const uint4 ka = *reinterpret_cast<const uint4*>(&sm.k[buf][n][16 * kk + 8 * hh]);
-      C = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8a, ka), __builtin_bit_cast(bf16x8a, qreg[kk]), C, 0, 0, 0);
-    }
-    // C[i]: unscaled logit of row n against key j0 + 8(i/4) + 4hh + i%4
-    if (masked) {
+  // fresh logits of the tile starting at j0 (C[i]: row n against key j0 + 8(i/4) + 4hh + i%4, unscaled):
+  // what lies beyond the row gets a logit whose probability is zero
+  auto mask = [&](f32x16a& C, int j0) {
+    if (j0 > jfull) {
 #pragma unroll
       for (int i = 0; i < 16; ++i)
         if (j0 + 8 * (i >> 2) + 4 * hh + (i & 3) > pos) C[i] = kNegBigA;
     }
-    float mt = C[0];
+  };
+  // probabilities of logits C against the running reference m_run, as fp16 pairs (ph[e]: elements 2e, 2e + 1),
+  // and their sum as rounded (the same numbers the PV MFMA multiplies)
+  auto probs = [&](const f32x16a& C, int i, uint32_t (&ph)[8], float& lt) {
+    const float p0 = aexp2(fmaf(C[i], scale2, -m_run)), p1 = aexp2(fmaf(C[i + 1], scale2, -m_run));
+    const __half2 h2 = __floats2half2_rn(p0, p1);
+    ph[i / 2] = *reinterpret_cast<const uint32_t*>(&h2);
+    lt = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2a, ph[i / 2]), f16x2a{(_Float16)1.0f, (_Float16)1.0f}, lt, false);
+  };
+
+  // One step of the two-stage pipeline over tiles.  Phase A: the logits MFMAs of tile t + 1 (into Cn), each
+  // followed in issue order by one LDS operand read for a later MFMA and by its share of tile t's softmax
+  // arithmetic (from C): the matrix pipe works in the background of the same wave's vector instructions only
+  // if the two alternate.  Phase B: the PV MFMAs of tile t between operand reads for the next step and the
+  // conversion of the tiles fetched at the top, which are staged into LDS at the end.
+  // The reference maximum is lazy: probabilities are taken against the row's current m_run, and only when a
+  // lane's sum shows that they grew large (or the reference is still unset) does the row move its reference
+  // to the tile's maximum and redo the tile.  A row decides from its own numbers only.
+  auto step = [&](f32x16a& C, f32x16a& Cn, int t) {
+    const int j0 = 32 * t, vb = t & 1;
+    fetch_k(j0 + 96);
+    fetch_v(j0 + 32);
+    uint32_t ph[8];
+    float lt0 = 0.f, lt1 = 0.f;
 #pragma unroll
-    for (int i = 1; i < 16; ++i) mt = fmaxf(mt, C[i]);
-    mt *= scale2;                                     // scale2 > 0: the maximum commutes with the scaling
-    if (__any(mt > m_run + 8.0f)) {                   // move the reference maximum (rare after the first tiles)
-      const float mn = fmaxf(m_run, fmaxf(mt, __shfl_xor(mt, 32)));   // both lane halves of a row agree on it
+    for (int i = 0; i < 16; ++i) Cn[i] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      if (kk + KH < KK) kop[kk + KH] = k_operand(kA, kk + KH);
+      else vop[kk + KH - KK] = v_operand(vb, kk + KH - KK);
+      Cn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8a, kop[kk]), __builtin_bit_cast(bf16x8a, qreg[kk]), Cn, 0, 0, 0);
+      constexpr int EPK = 16 / KK;                    // softmax elements per MFMA (2 at D = 128, 4 at D = 64)
+#pragma unroll
+      for (int e = 0; e < EPK; e += 2) probs(C, EPK * kk + e, ph, ((kk + e / 2) & 1) ? lt1 : lt0);
+    }
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      __builtin_amdgcn_sched_group_barrier(kSgMfma, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(kSgDsRead, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(kSgValu, 6 * 16 / (2 * KK), 0);
+    }
+    float lt = lt0 + lt1;
+    if (__any(!(lt <= kSumLimit))) {                  // rare after the first tile
+      const float lo = __shfl_xor(lt, 32);
+      const bool move = !(fmaxf(lt, lo) <= kSumLimit);   // both lane halves of a row agree
+      float mt = C[0];
+#pragma unroll
+      for (int i = 1; i < 16; ++i) mt = fmaxf(mt, C[i]);
+      mt *= scale2;                                   // scale2 > 0: the maximum commutes with the scaling
+      mt = fmaxf(mt, __shfl_xor(mt, 32));
+      const float mn = move ? fmaxf(m_run, mt) : m_run;
       const float f = aexp2(m_run - mn);
       m_run = mn;
       l_run *= f;
@@ -152,38 +230,57 @@ __global__ __launch_bounds__(64 * G, G >= 4 ? 2 : 1) void k_prefill_attn(AttnLau
       for (int cb = 0; cb < CBN; ++cb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[cb][i] *= f;
+      lt0 = 0.f; lt1 = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; i += 2) probs(C, i, ph, lt0);
+      lt = lt0;
     }
-    float p[16];
+    l_run += lt;
+    // PV: probabilities eight per k-step: jj = 0 -> elements 0..7, jj = 1 -> 8..15
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { p[i] = aexp2(fmaf(C[i], scale2, -m_run)); l_run += p[i]; }   // masked: 2^(-huge) = 0
-    // probabilities as fp16, eight per PV k-step: jj = 0 -> i = 0..7, jj = 1 -> i = 8..15
-    uint32_t ph[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const __half2 h2 = __floats2half2_rn(p[2 * e], p[2 * e + 1]);
-      ph[e] = *reinterpret_cast<const uint32_t*>(&h2);
+    for (int r = 0; r < NPV; ++r) {
+      if (r + KH < NPV) vop[r + KH] = v_operand(vb, r + KH);
+      else kop[r + KH - NPV] = k_operand(kB, r + KH - NPV);
+      const int jj = r / CBN, cb = r % CBN;
+      const u32x4a pb = {ph[4 * jj], ph[4 * jj + 1], ph[4 * jj + 2], ph[4 * jj + 3]};
+      acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8a, vop[r]), __builtin_bit_cast(f16x8a, pb), acc[cb], 0, 0, 0);
     }
 #pragma unroll
-    for (int jj = 0; jj < 2; ++jj) {
-      const uint4 pb = make_uint4(ph[4 * jj], ph[4 * jj + 1], ph[4 * jj + 2], ph[4 * jj + 3]);
-#pragma unroll
-      for (int cb = 0; cb < CBN; ++cb) {
-        // A = V^T: channel 32 cb + n, keys 16 jj + 4 hh + (0..3) and 16 jj + 8 + 4 hh + (0..3), adjacent in LDS
-        const uint4 va = *reinterpret_cast<const uint4*>(&sm.vt[buf][32 * cb + n][16 * jj + 8 * hh]);
-        acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8a, va), __builtin_bit_cast(f16x8a, pb), acc[cb], 0, 0, 0);
-      }
+    for (int r = 0; r < NPV; ++r) {
+      __builtin_amdgcn_sched_group_barrier(kSgMfma, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(kSgDsRead, 1, 0);
     }
+    __builtin_amdgcn_sched_barrier(0);                // the staging waits for this step's loads: keep it behind the MFMAs
+    stage_k(kW);                                      // tile t + 3 into the buffer tile t's logits came from
+    stage_v(vb ^ 1);                                  // tile t + 1; that buffer was last read one step ago
+    mask(Cn, j0 + 32);
+    const int k0 = kA; kA = kB; kB = kW; kW = k0;
+    __syncthreads();
   };
 
-  fetch(0);
-  stage(0);
+  fetch_k(0);
+  fetch_v(0);
+  stage_k(0);
+  stage_v(0);
+  fetch_k(32);
+  stage_k(1);
+  fetch_k(64);
+  stage_k(2);
   __syncthreads();
-  for (int t = 0; t < ntiles; ++t) {
-    const int j0 = 32 * t, buf = t & 1;
-    fetch(j0 + 32);                                   // past the last tile: clamped rows, staged but never read
-    tile(j0 + 31 > q0 + 32 * qb, j0, buf);
-    stage(buf ^ 1);                                   // the other buffer was last read one iteration ago
-    __syncthreads();
+  f32x16a C0, C1;
+  {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) C0[i] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk)
+      C0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8a, k_operand(0, kk)), __builtin_bit_cast(bf16x8a, qreg[kk]), C0, 0, 0, 0);
+    mask(C0, 0);
+#pragma unroll
+    for (int kk = 0; kk < KH; ++kk) kop[kk] = k_operand(1, kk);
+  }
+  for (int t = 0; t < ntiles; t += 2) {
+    step(C0, C1, t);
+    if (t + 1 < ntiles) step(C1, C0, t + 1);
   }
 
   const float l_tot = l_run + __shfl_xor(l_run, 32);
