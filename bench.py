@@ -289,6 +289,8 @@ def main():
     ap.add_argument("--profile-steps", type=int, default=8)
     ap.add_argument("--no-tailor-run", action="store_true", help="skip stepping 4 layers up to their next tailor")
     ap.add_argument("--no-variants", action="store_true", help="skip the policy / other-workload variant runs")
+    ap.add_argument("--attention-only", action="store_true",
+                    help="time only the causal prefill attention of the workload's prompt and print that entry")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures ONE GPU (units of the cache never interact across GPUs; "
@@ -309,6 +311,9 @@ def main():
         wl = wl.scaled(prefill=args.prefill)
     if args.budget:
         wl = wl.scaled(budget_frac=args.budget)
+    if args.attention_only:
+        print(json.dumps({"prefill_attention": attention_measure(wl), "workload": wl.name}))
+        return
     L, B, Hq, Hkv, d, T, W = wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.prefill, wl.window
     G, U = wl.group, wl.batch * wl.n_kv_heads
     total_steps = args.warmup + args.steps + args.profile_steps + 8

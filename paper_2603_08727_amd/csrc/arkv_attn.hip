@@ -50,8 +50,17 @@ constexpr int kSgValu = 0x2, kSgMfma = 0x8, kSgDsRead = 0x100;
 typedef _Float16 f16x2a __attribute__((ext_vector_type(2)));
 constexpr float kSumLimit = 16384.0f;   // a lane's 16 probabilities may sum to this before the reference maximum moves
 
+// Profiling builds (-DARKV_PHASE_TRACE): shader-clock and 100 MHz timestamps around the longest workgroup,
+// from which the shader clock the kernel ran at follows.  Product builds compile none of it.
+#ifdef ARKV_PHASE_TRACE
+__device__ unsigned long long g_attn_clock[4];
+#endif
+
 template <int D, int G>
 __global__ __launch_bounds__(64 * G, G >= 4 ? 2 : 1) void k_prefill_attn(AttnLaunch L) {
+#ifdef ARKV_PHASE_TRACE
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) { g_attn_clock[0] = clock64(); g_attn_clock[1] = wall_clock64(); }
+#endif
   constexpr int KK = D / 16;          // k-steps of the logits MFMA
   constexpr int KH = KK / 2;          // operands carried from the previous phase
   constexpr int CBN = D / 32;         // 32-channel blocks of the output
@@ -283,6 +292,9 @@ __global__ __launch_bounds__(64 * G, G >= 4 ? 2 : 1) void k_prefill_attn(AttnLau
     if (t + 1 < ntiles) step(C1, C0, t + 1);
   }
 
+#ifdef ARKV_PHASE_TRACE
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) { g_attn_clock[2] = clock64(); g_attn_clock[3] = wall_clock64(); }
+#endif
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   const float inv = 1.0f / l_tot;
   if (row < Tq) {
@@ -319,3 +331,9 @@ hipError_t launch_prefill_attn(const AttnLaunch& a, hipStream_t s) {
 }
 
 }  // namespace arkv
+
+#ifdef ARKV_PHASE_TRACE
+extern "C" int arkv_debug_attn_clock(unsigned long long* host) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(arkv::g_attn_clock), 4 * sizeof(unsigned long long));
+}
+#endif
