@@ -126,3 +126,52 @@ def test_attention_32k_sampled_rows():
         assert np.all(np.abs(stats.cpu().numpy() - np.array(ref)) <= TOL * np.abs(np.array(ref)))
     finally:
         A.arkv_cache_destroy(cache)
+
+
+def _run_attention(wl, q, k, v, scale, Tq, T):
+    """Queries q [B][Hq][Tq][d] at positions T - Tq .. T - 1 against the first T keys; returns the output."""
+    cfg = make_cfg(wl)
+    cache = A.arkv_cache_create(cfg)
+    try:
+        out = torch.zeros((wl.batch, wl.n_q_heads, Tq, wl.head_dim), dtype=torch.bfloat16, device="cuda")
+        A.arkv_prefill_attention(cache, 0, q.contiguous().cuda(), k[:, :, :T].contiguous().cuda(),
+                                 v[:, :, :T].contiguous().cuda(), Tq, T, scale, out)
+        torch.cuda.synchronize()
+        return out
+    finally:
+        A.arkv_cache_destroy(cache)
+
+
+@pytest.mark.parametrize("direction", [+1.0, -1.0])
+def test_attention_drifting_logits(direction):
+    """Logits that rise (or fall) by about 60 binary orders over the prompt: a row's lazy reference maximum has
+    to move many times, long after the first tile (or never again, with all later probabilities tiny).  Checked
+    against the oracle on every row, and bit for bit against the same prompt cut into ragged chunks."""
+    T, d = 300, 64
+    wl = synth.C1.scaled(name="drift", n_q_heads=8, n_kv_heads=2, head_dim=d, prefill=T, batch=1, budget_frac=2.0)
+    k, v, qw = synth.prefill_inputs(wl, 0)
+    q = _full_queries(wl, 0, qw)
+    scale = synth.softmax_scale(wl, 0)
+    u = torch.zeros(d); u[3] = 1.0
+    ramp = torch.arange(T, dtype=torch.float32) / T                       # 0 .. 1 along the keys
+    k = (k.float() + direction * 6.0 * ramp[None, None, :, None] * u).to(torch.bfloat16)
+    q = (q.float() + (60.0 / (6.0 * scale * 1.4427)) * u).to(torch.bfloat16)   # q.u * scale * log2(e) * 6 = 60
+    out = _run_attention(wl, q, k, v, scale, T, T)
+    assert _check_rows(out, q, k, v, scale, 4, np.arange(T), 0) <= TOL + 2.0 ** -8
+    out2 = torch.zeros_like(out)
+    for a, e in [(0, 7), (7, 100), (100, 101), (101, 263), (263, T)]:
+        out2[:, :, a:e] = _run_attention(wl, q[:, :, a:e], k, v, scale, e - a, e)
+    assert torch.equal(out, out2)
+
+
+@pytest.mark.parametrize("Tq,T", [(20, 20), (1, 300), (5, 77), (1, 1), (33, 64), (31, 95)])
+def test_attention_short_and_single_rows(Tq, T):
+    """Prompts shorter than one key tile, single query rows against a long context, chunks that start off a
+    tile border."""
+    wl = synth.C1.scaled(name="short", n_q_heads=8, n_kv_heads=2, head_dim=128, prefill=max(T, 40), batch=2, budget_frac=2.0)
+    k, v, qw = synth.prefill_inputs(wl, 0)
+    q = _full_queries(wl, 0, qw)
+    scale = synth.softmax_scale(wl, 0)
+    out = _run_attention(wl, q[:, :, T - Tq:T], k, v, scale, Tq, T)
+    kk, vv = k[:, :, :T], v[:, :, :T]
+    assert _check_rows(out, q[:, :, T - Tq:T], kk, vv, scale, 4, np.arange(T - Tq, T), T - Tq) <= TOL + 2.0 ** -8
