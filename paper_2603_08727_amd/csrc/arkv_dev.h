@@ -105,6 +105,7 @@ struct PrefillLaunch {
   float2* pre;            // [U][T]  out: (s1, s2)
   float2* rowstat;        // [U][chunks][G*W] (row max base-2, row sum) partials
   float* stats;           // [B][3]
+  int* stat_ticket;       // [B] workgroups of the sequence's statistics kernel that finished (0 between calls)
   int B, Hkv, G, W, D, T;
   size_t q_head_stride;   // elements between heads (W*D for a packed [B][Hq][W][D] tensor)
   int have_rowc;          // 1: the row constants are already in the scratch (attention pass), skip the first pass

@@ -57,6 +57,7 @@ struct arkv_cache {
   // grow-only scratch shared by all layers (calls on one cache are stream-ordered)
   float2* rowstat = nullptr; size_t rowstat_cap = 0;
   float* rowc = nullptr; size_t rowc_cap = 0;
+  int* stat_ticket = nullptr;     // [batch], zero between scorer calls
   uint64_t* ckeys = nullptr; size_t ckeys_cap = 0;
   int ckeys_layer = -1, ckeys_T = 0;
   hipStream_t last_stream = nullptr;
@@ -247,6 +248,8 @@ int arkv_cache_create(const arkv_config* cfg, arkv_cache** out) {
   }
   if (e == hipSuccess) e = hipMemset(P.cnt, 0, LU * sizeof(int2));
   if (e == hipSuccess) e = hipMemset(P.ticket, 0, LU * sizeof(int));
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->stat_ticket), (size_t)c->cfg.batch * sizeof(int));
+  if (e == hipSuccess) e = hipMemset(c->stat_ticket, 0, (size_t)c->cfg.batch * sizeof(int));
   if (e == hipSuccess) e = hipMemset(P.fin, 0, kRing * LU * G * sizeof(float2));
   if (e == hipSuccess) e = hipMemset(P.qprev, 0, kRing * LU * G * D * sizeof(uint16_t));
   if (e == hipSuccess) e = hipMemset(P.qscale, 0, kRing * LU * sizeof(float));
@@ -267,6 +270,7 @@ int arkv_cache_destroy(arkv_cache* c) {
   }
   if (c->rowstat) (void)hipFree(c->rowstat);
   if (c->rowc) (void)hipFree(c->rowc);
+  if (c->stat_ticket) (void)hipFree(c->stat_ticket);
   if (c->ckeys) (void)hipFree(c->ckeys);
   for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
   delete c;
@@ -302,7 +306,7 @@ static int run_scorer(arkv_cache* c, int32_t layer, const uint16_t* q_win, size_
   while (MP < G * W) MP *= 2;
   if ((rc = grow(&c->rowstat, &c->rowstat_cap, (size_t)U * n_chunks * MP)) != ARKV_OK) return rc;
   // row constants [U][MP] floats (MP even, so what follows is 8-byte aligned) + statistics partials
-  const size_t stat_doubles = 4 * (size_t)c->cfg.batch * ((size_t)(T - W + 511) / 512);
+  const size_t stat_doubles = (size_t)U * n_chunks + 3 * (size_t)c->cfg.batch * ((size_t)(T - W + 511) / 512);
   if ((rc = grow(&c->rowc, &c->rowc_cap, (size_t)U * MP + 2 * stat_doubles)) != ARKV_OK) return rc;
   if (attn) {
     attn->rowc = c->rowc; attn->MP = MP; attn->W = W;
@@ -313,7 +317,7 @@ static int run_scorer(arkv_cache* c, int32_t layer, const uint16_t* q_win, size_
   a.q_head_stride = q_head_stride;
   a.have_rowc = attn ? 1 : 0;
   a.k = k;
-  a.pre = ls.pre; a.rowstat = c->rowstat; a.stats = stats;
+  a.pre = ls.pre; a.rowstat = c->rowstat; a.stats = stats; a.stat_ticket = c->stat_ticket;
   a.B = c->cfg.batch; a.Hkv = c->cfg.n_kv_heads; a.G = G; a.W = W; a.D = c->P.D; a.T = T;
   a.chunk = chunk; a.n_chunks = n_chunks;
   a.scale2 = softmax_scale * 1.4426950408889634f;

@@ -9,7 +9,8 @@
 //   k_prefill_rowfinal per unit: c_r = max_r + log2(sum_r)
 //   k_prefill_cols     per (key chunk, unit): p = 2^(x - c_r); per key sum_r p and sum_r p^2 -> pre
 //   k_prefill_stats    per sequence: p_k over keys < T-W aggregated over all heads, entropy,
-//                      variance, kurtosis (fp64 reductions)
+//                      variance, kurtosis (fp64 reductions; the normaliser's partial sums come from
+//                      k_prefill_cols, the last workgroup of a sequence finishes)
 #include "arkv_dev.h"
 
 namespace arkv {
@@ -173,11 +174,22 @@ __global__ __launch_bounds__(256) void k_prefill_rowfinal(PrefillLaunch L, int M
   }
 }
 
+__device__ __forceinline__ double block_sum_d(double v, double* sm) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  const int w = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sm[w] = v;
+  __syncthreads();
+  double t = 0;
+  for (int i = 0; i < (int)(blockDim.x >> 6); ++i) t += sm[i];
+  return t;
+}
+
 // Second pass.  Here the MFMA is turned round (query rows on the M side, keys on the N side) so that a
 // lane owns ONE key and the sums over the M = G*W query rows are in-register additions: C[i] is row
 // rt*32 + 8(i/4) + 4(lane/32) + i%4 against key j0 + lane%32.  The row constants c_r come from LDS.
 template <int D, int RT>
-__global__ __launch_bounds__(256) void k_prefill_cols(PrefillLaunch L, const float* rowc) {
+__global__ __launch_bounds__(256) void k_prefill_cols(PrefillLaunch L, const float* rowc, double* zpart) {
   extern __shared__ __align__(16) unsigned char sm[];
   constexpr int RB = 2 * D + 16;
   const int chunk = blockIdx.x, u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -194,6 +206,7 @@ __global__ __launch_bounds__(256) void k_prefill_cols(PrefillLaunch L, const flo
   const int jbeg = chunk * L.chunk, jend = min(jbeg + L.chunk, T);
   float2* pre = L.pre + (size_t)u * T;
   const int hl = lane >> 5, kl = lane & 31;
+  double zacc = 0.0;                                              // this workgroup's share of eq. 3's normaliser
   uint4 kf[D / 16], kn[D / 16];
   if (jbeg + w * 32 < jend) load_keys<D>(kf, k, jbeg + w * 32, T, lane);
   for (int j0 = jbeg + w * 32; j0 < jend; j0 += 128) {
@@ -238,44 +251,34 @@ __global__ __launch_bounds__(256) void k_prefill_cols(PrefillLaunch L, const flo
     a1 += __shfl_xor(a1, 32);
     a2 += __shfl_xor(a2, 32);
     if (hl == 0 && j < T) pre[j] = make_float2(a1, a2);
+    if (hl == 0 && j < T - L.W) zacc += (double)a1;
 #pragma unroll
     for (int kk = 0; kk < D / 16; ++kk) kf[kk] = kn[kk];
   }
+  // sum over the chunk's keys before the window of the attention they received, in a fixed order
+  zacc = block_sum_d(zacc, reinterpret_cast<double*>(sm));       // (its first barrier ends the use of the queries)
+  if (tid == 0) zpart[(size_t)u * L.n_chunks + chunk] = zacc;
 }
 
-__device__ __forceinline__ double block_sum_d(double v, double* sm) {
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-  const int w = threadIdx.x >> 6;
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) sm[w] = v;
-  __syncthreads();
-  double t = 0;
-  for (int i = 0; i < (int)(blockDim.x >> 6); ++i) t += sm[i];
-  return t;
-}
+// Results that one workgroup writes and another reads inside the same launch go through device-scope relaxed
+// atomics (write-through stores, loads that do not hit a stale L2 line of another XCD); no cache-wide flush.
+__device__ __forceinline__ void st_dev_d(double* p, double v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ double ld_dev_d(const double* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
-// Aggregated key distribution over ALL heads of a sequence and its three statistics, in three small
-// deterministic steps: per-chunk sums of c_j, per-chunk sums of -p ln p, (p - 1/n)^2, (p - 1/n)^4, final.
+// Aggregated key distribution over ALL heads of a sequence and its three statistics (eqs. 3-5), fp64, every
+// sum in a fixed order: the normaliser Z from the column pass's per-workgroup sums; per chunk of keys the sums
+// of -p ln p, (p - 1/n)^2, (p - 1/n)^4; the workgroup of a sequence that finishes last (a ticket) adds the
+// chunks up and writes the statistics.
 constexpr int kStatChunk = 512;    // keys per workgroup
 
-__global__ __launch_bounds__(256) void k_prefill_stats_z(PrefillLaunch L, double* zpart) {
+__global__ __launch_bounds__(256) void k_prefill_stats(PrefillLaunch L, const double* zpart, double* mpart) {
   __shared__ double sm[16];
-  const int b = blockIdx.y, ch = blockIdx.x, n = L.T - L.W;
-  const float2* pre = L.pre + (size_t)b * L.Hkv * L.T;
-  const int j1 = min(n, (ch + 1) * kStatChunk);
-  double z = 0;
-  for (int j = ch * kStatChunk + threadIdx.x; j < j1; j += 256)
-    for (int g = 0; g < L.Hkv; ++g) z += (double)pre[(size_t)g * L.T + j].x;
-  z = block_sum_d(z, sm);
-  if (threadIdx.x == 0) zpart[b * gridDim.x + ch] = z;
-}
-
-__global__ __launch_bounds__(256) void k_prefill_stats_m(PrefillLaunch L, const double* zpart, double* mpart) {
-  __shared__ double sm[16];
+  __shared__ int last;
   const int b = blockIdx.y, ch = blockIdx.x, n = L.T - L.W, nch = gridDim.x;
   const float2* pre = L.pre + (size_t)b * L.Hkv * L.T;
   double Z = 0;
-  for (int i = 0; i < nch; ++i) Z += zpart[b * nch + i];
+  for (int i = threadIdx.x; i < L.Hkv * L.n_chunks; i += 256) Z += zpart[(size_t)b * L.Hkv * L.n_chunks + i];
+  Z = block_sum_d(Z, sm);
   const double pbar = 1.0 / (double)n;
   const int j1 = min(n, (ch + 1) * kStatChunk);
   double h = 0, m2 = 0, m4 = 0;
@@ -290,17 +293,20 @@ __global__ __launch_bounds__(256) void k_prefill_stats_m(PrefillLaunch L, const 
   h = block_sum_d(h, sm); m2 = block_sum_d(m2, sm); m4 = block_sum_d(m4, sm);
   if (threadIdx.x == 0) {
     double* o = mpart + ((size_t)b * nch + ch) * 3;
-    o[0] = h; o[1] = m2; o[2] = m4;
+    st_dev_d(o, h); st_dev_d(o + 1, m2); st_dev_d(o + 2, m4);
+    __builtin_amdgcn_s_waitcnt(0);                    // the partials are at the device's coherence point
+    last = __hip_atomic_fetch_add(L.stat_ticket + b, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == nch - 1;
   }
-}
-
-__global__ __launch_bounds__(64) void k_prefill_stats_final(PrefillLaunch L, const double* mpart, int nch) {
-  const int b = blockIdx.x;
-  const int n = L.T - L.W;
-  double h = 0, m2 = 0, m4 = 0;
-  for (int i = threadIdx.x; i < nch; i += 64) { const double* o = mpart + ((size_t)b * nch + i) * 3; h += o[0]; m2 += o[1]; m4 += o[2]; }
-  for (int o = 32; o > 0; o >>= 1) { h += __shfl_xor(h, o); m2 += __shfl_xor(m2, o); m4 += __shfl_xor(m4, o); }
+  __syncthreads();
+  if (!last) return;
+  h = 0; m2 = 0; m4 = 0;
+  for (int i = threadIdx.x; i < nch; i += 256) {
+    const double* o = mpart + ((size_t)b * nch + i) * 3;
+    h += ld_dev_d(o); m2 += ld_dev_d(o + 1); m4 += ld_dev_d(o + 2);
+  }
+  h = block_sum_d(h, sm); m2 = block_sum_d(m2, sm); m4 = block_sum_d(m4, sm);
   if (threadIdx.x != 0) return;
+  __hip_atomic_store(L.stat_ticket + b, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
   m2 /= (double)n; m4 /= (double)n;
   L.stats[b * 3 + 0] = (float)h;
   L.stats[b * 3 + 1] = (float)m2;
@@ -324,17 +330,15 @@ static hipError_t launch_prefill_t(const PrefillLaunch& a, float* rowc, hipStrea
     hipLaunchKernelGGL((k_prefill_rows<D, RT>), grid, dim3(256), shm, s, a);
     hipLaunchKernelGGL(k_prefill_rowfinal, dim3(MP / 32, U), dim3(256), 0, s, a, MP, rowc);
   }
-  hipLaunchKernelGGL((k_prefill_cols<D, RT>), grid, dim3(256), shm + (size_t)MP * 8, s, a, (const float*)rowc);
   const int nch = (a.T - a.W + kStatChunk - 1) / kStatChunk;
-  double* zpart = reinterpret_cast<double*>(rowc + (size_t)U * MP);      // [B][nch], then [B][nch][3]
-  double* mpart = zpart + (size_t)a.B * nch;
-  hipLaunchKernelGGL(k_prefill_stats_z, dim3(nch, a.B), dim3(256), 0, s, a, zpart);
-  hipLaunchKernelGGL(k_prefill_stats_m, dim3(nch, a.B), dim3(256), 0, s, a, (const double*)zpart, mpart);
-  hipLaunchKernelGGL(k_prefill_stats_final, dim3(a.B), dim3(64), 0, s, a, (const double*)mpart, nch);
+  double* zpart = reinterpret_cast<double*>(rowc + (size_t)U * MP);      // [U][n_chunks], then [B][nch][3]
+  double* mpart = zpart + (size_t)U * a.n_chunks;
+  hipLaunchKernelGGL((k_prefill_cols<D, RT>), grid, dim3(256), shm + (size_t)MP * 8, s, a, (const float*)rowc, zpart);
+  hipLaunchKernelGGL(k_prefill_stats, dim3(nch, a.B), dim3(256), 0, s, a, (const double*)zpart, mpart);
   return hipGetLastError();
 }
 
-// rowc: scratch [U][MP] floats followed by 4*B*ceil((T-W)/512) doubles for the statistics partials
+// rowc: scratch [U][MP] floats followed by U*n_chunks + 3*B*ceil((T-W)/512) doubles for the statistics partials
 hipError_t launch_prefill_stats(const PrefillLaunch& a, float* rowc, hipStream_t s) {
   const int M = a.G * a.W;
   int RT = 1;
