@@ -99,6 +99,8 @@ int arkv_prefill_stats(arkv_cache* cache, int32_t layer, const void* q_win, cons
  * stats == NULL: attention only.  stats != NULL ([B][3] DEVICE fp32, needs T_q >= W, T > W, layer not
  * committed): the call also does what arkv_prefill_stats does for the last W queries; the softmax maxima and
  * sums of those rows come out of the attention pass, so the scorer reads the keys once instead of twice.
+ * Arithmetic: bf16 logits MFMA, probabilities and values as fp16 in the PV MFMA, fp32 accumulation; values
+ * whose magnitude exceeds fp16's range (65504) are not supported.  All pointers 16-byte aligned.
  * ARKV_EINVAL / ARKV_ESTATE as for arkv_prefill_stats. */
 int arkv_prefill_attention(arkv_cache* cache, int32_t layer, const void* q, const void* k, const void* v,
                            int32_t T_q, int32_t T, float softmax_scale, void* out, float* stats,

@@ -121,6 +121,37 @@ def test_call_order_errors_and_reset():
         A.arkv_cache_destroy(c)
 
 
+def test_prefill_attention_argument_errors():
+    wl = synth.C1.scaled(name="attn_err", prefill=200, decode_steps=2)
+    cfg = make_cfg(wl)
+    c = A.arkv_cache_create(cfg)
+    try:
+        k, v, qw = (t.cuda() for t in synth.prefill_inputs(wl, 0))
+        T, W = wl.prefill, wl.window
+        q = torch.zeros((wl.batch, wl.n_q_heads, T, wl.head_dim), dtype=torch.bfloat16, device="cuda")
+        out = torch.empty_like(q)
+        stats = torch.zeros((wl.batch, 3), dtype=torch.float32, device="cuda")
+        for args in [(0, T + 1, T, 0.1, None),        # more queries than keys
+                     (0, 0, T, 0.1, None),            # no query
+                     (0, T, T, 0.0, None),            # scale must be positive
+                     (3, T, T, 0.1, None),            # layer out of range
+                     (0, W - 1, T, 0.1, stats),       # the scorer needs the whole window among the queries
+                     (0, W, W, 0.1, stats)]:          # ... and a prompt longer than the window
+            layer, Tq, Tk, scale, st = args
+            with pytest.raises(A.ArkvError) as e:
+                A.arkv_prefill_attention(c, layer, q[:, :, :max(Tq, 1)].contiguous(), k, v, Tq, Tk, scale, out, st)
+            assert e.value.code == A.EINVAL, args
+        A.arkv_prefill_attention(c, 0, q, k, v, T, T, 0.1, out, stats)      # scores the layer
+        A.arkv_prefill_commit(c, 0, k, v, T, np.full(wl.batch, 0.5, np.float32))
+        with pytest.raises(A.ArkvError) as e:                               # scoring a committed layer again
+            A.arkv_prefill_attention(c, 0, q, k, v, T, T, 0.1, out, stats)
+        assert e.value.code == A.ESTATE
+        A.arkv_prefill_attention(c, 0, q, k, v, T, T, 0.1, out, None)       # attention alone is still allowed
+        torch.cuda.synchronize()
+    finally:
+        A.arkv_cache_destroy(c)
+
+
 def test_measurement_hooks():
     wl = synth.C1.scaled(name="hooks", decode_steps=6)
     cfg, c = _prepare(wl)
