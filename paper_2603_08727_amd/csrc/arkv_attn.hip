@@ -4,9 +4,10 @@
 //
 // One workgroup = 32 query positions of one (sequence, kv-head); wave w = q-head w of the group, so the G
 // heads of a group share every key and value tile, which is fetched from HBM once per workgroup and staged
-// in LDS (double buffered, one barrier per 32-key tile).  Keys are on the M side of the logits MFMA
-// (v_mfma_f32_32x32x16_bf16, S^T = K Q^T), which leaves ONE query row per lane: the online softmax is
-// per-lane arithmetic plus one exchange between the two lane halves.  The probabilities a lane then holds
+// in LDS (keys in three buffers, values in two, one barrier per 32-key tile).  Keys are on the M side of the
+// logits MFMA (v_mfma_f32_32x32x16_bf16, S^T = K Q^T), which leaves ONE query row per lane: the online softmax
+// is per-lane arithmetic (the two lane halves of a row talk only when the row's reference maximum moves, which
+// is rare: see the step below).  The probabilities a lane then holds
 // (keys 8(i/4) + 4(lane/32) + i%4 of the tile) are, eight at a time, exactly a B operand of the PV MFMA
 // (O^T = V^T P^T) if the contraction index is read in that key order; the value tile is staged transposed
 // ([channel][key], fp16) with its key columns permuted so that the matching A operand is one 16-byte read.

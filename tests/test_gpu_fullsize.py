@@ -39,6 +39,29 @@ def test_c4_128k_2bit_one_layer():
     _run(synth.C4.scaled(n_layers=1), steps=3)
 
 
+@pytest.mark.parametrize("rho", [None, 0.5])
+def test_c3_full_size_decode_time_tailor(rho):
+    """Config 3's shape with almost no slack (alpha = 0.99: b = 8078 of N = 8192, a tailor every 82 decode steps) so
+    that a decode-time tailor over the full-size cache (eq. 10 on 8.2K tokens per unit, 32 units: select,
+    demotion with in-place quantisation, compaction) is compared with the oracle, then a few steps more.  rho = 0.5 forces a mixed cache, so that
+    rows are demoted and quantised in place; None takes the scored ratio of this layer."""
+    wl = synth.C3.scaled(name="c3_tight", n_layers=1, alpha=0.99)
+    sb = SideBySide(wl, rho_override=rho)
+    try:
+        sb.prefill()
+        sb.commit()
+        steps = wl.capacity - int(wl.alpha * (wl.capacity - wl.window)) - wl.window + 6
+        sb.decode(steps, check_every=steps)
+        print(wl.name, steps, {k: f"{v:.2e}" for k, v in sb.max_err.items()}, flush=True)
+        sb.assert_within_tol()
+        for oc in sb.oracles.values():
+            assert oc.n_tailors == 2
+            if rho is not None:
+                assert all(oc.counts(g)[1] > 1000 for g in range(wl.n_kv_heads))     # Quantized tokens per unit
+    finally:
+        sb.close()
+
+
 def _run_scorer(wl):
     sb = SideBySide(wl)
     try:
