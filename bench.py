@@ -385,10 +385,15 @@ def main():
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
-    no0 = np.zeros(L); nq0 = np.zeros(L)
+    no0 = np.zeros(L); nq0 = np.zeros(L); ne0 = np.zeros(L)
     for l in range(L):
-        a_, b_, _, _ = A.arkv_cache_counters(cache, l, U)
-        no0[l], nq0[l] = a_.sum(), b_.sum()
+        a_, b_, e_, _ = A.arkv_cache_counters(cache, l, U)
+        no0[l], nq0[l], ne0[l] = a_.sum(), b_.sum(), e_.sum()
+    # composition of the caches after the first tailor (the quantities of Table VII, here for the synthetic
+    # statistics of this workload): Quantized tokens over the capacity, evicted tokens over all tokens seen
+    composition = {"quant_ratio_of_capacity": round(float(nq0.sum() / (L * U * wl.capacity)), 4),
+                   "evict_ratio_of_tokens_seen": round(float(ne0.sum() / max(no0.sum() + nq0.sum() + ne0.sum(), 1.0)), 4),
+                   "layers_all_original": int((nq0 == 0).sum()), "n_layers": L}
     tailors0 = sum(A.arkv_cache_progress(cache, l)[0] for l in range(L))
     # ---- timed region -----------------------------------------------------------------------------
     torch.cuda.synchronize()
@@ -518,6 +523,7 @@ def main():
                  "achieved_GBps_whole_call": round(step_bytes / (call_us * 1e-6) / 1e9, 1),
                  "frac_of_hbm_peak_whole_call": round(step_bytes / (call_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
                  "tailors_in_timed_region": int(tailors1 - tailors0)},
+        "cache_composition": composition,
         "prefill": {"scorer_ms_per_layer": round(t_stats / L, 3),
                     "scorer_TFLOPs": round(2.0 * W * Hq * T * d * B / (t_stats / L * 1e-3) / 1e12, 1),
                     "scorer_frac_of_bf16_mfma_peak": round(2.0 * W * Hq * T * d * B / (t_stats / L * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
