@@ -528,6 +528,8 @@ def main():
                     "scorer_TFLOPs": round(2.0 * W * Hq * T * d * B / (t_stats / L * 1e-3) / 1e12, 1),
                     "scorer_frac_of_bf16_mfma_peak": round(2.0 * W * Hq * T * d * B / (t_stats / L * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                     "scorer_GBps_keys_once": round((B * Hkv * T * d * 2) / (t_stats / L * 1e-3) / 1e9, 1),
+                    # the keys are streamed twice by necessity (a probability needs its row's maximum and sum first)
+                    "scorer_frac_of_hbm_peak_two_passes": round(2 * (B * Hkv * T * d * 2) / (t_stats / L * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                     "commit_ms_per_layer": round(t_commit / L, 3),
                     "rho_min_mean_max": [round(float(rho.min()), 3), round(float(rho.mean()), 3), round(float(rho.max()), 3)]},
         "variants": variants,
