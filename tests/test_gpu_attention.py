@@ -175,3 +175,20 @@ def test_attention_short_and_single_rows(Tq, T):
     out = _run_attention(wl, q[:, :, T - Tq:T], k, v, scale, Tq, T)
     kk, vv = k[:, :, :T], v[:, :, :T]
     assert _check_rows(out, q[:, :, T - Tq:T], kk, vv, scale, 4, np.arange(T - Tq, T), T - Tq) <= TOL + 2.0 ** -8
+
+
+def test_attention_whole_prompt_and_chunks_agree_bitwise_600():
+    """A 601-token prompt at d = 128 (19 key tiles, the last one ragged) in one call and in four chunks of
+    very different lengths: same bits, and within tolerance of the oracle on sampled rows."""
+    T, d = 601, 128
+    wl = synth.C1.scaled(name="paths", n_q_heads=8, n_kv_heads=2, head_dim=d, prefill=T, batch=2, budget_frac=2.0)
+    k, v, qw = synth.prefill_inputs(wl, 0)
+    q = _full_queries(wl, 0, qw)
+    scale = synth.softmax_scale(wl, 0)
+    out = _run_attention(wl, q, k, v, scale, T, T)
+    pos = np.array([0, 31, 32, 255, 256, 300, 599, 600])
+    assert _check_rows(out, q, k, v, scale, 4, pos, 0) <= TOL + 2.0 ** -8
+    out2 = torch.zeros_like(out)
+    for a, e in [(0, 50), (50, 290), (290, 330), (330, T)]:
+        out2[:, :, a:e] = _run_attention(wl, q[:, :, a:e], k, v, scale, e - a, e)
+    assert torch.equal(out, out2)
