@@ -555,6 +555,8 @@ def main():
             "arkv_mixed_rho0.5_fp8_rows": quick_measure(base12.scaled(bits=8), rho_force=0.5),
             "arkv_mixed_rho0.5_byte_budget": quick_measure(base12, rho_force=0.5, byte_budget=True),
             "arkv_scored_rho_tailor_every_step": quick_measure(base12.scaled(n_layers=4), every_step=True),
+            # ceiling run of the packed-row stream: almost the whole 32K prompt kept, all of it Quantized
+            "ceiling_all_quantized_32k": quick_measure(base12.scaled(n_layers=6, budget_frac=0.99, alpha=0.99), rho_force=0.0),
         }
         ref = pol["base_full_cache"]["steps_per_s_per_layer_batch"]
         for v_ in pol.values():
