@@ -131,3 +131,32 @@ def test_degenerate_rows_and_queries(bits):
 
     wl = synth.C1.scaled(name=f"degenerate_b{bits}", bits=bits, head_dim=64, decode_steps=40)
     _run(wl, rho=0.0, check_every=2, mutate_prefill=mp, mutate_decode=md)
+
+
+def _combo(seed):
+    """One drawn combination of shape, format, policy and hyper-parameters (the draw is seeded: fixed cases)."""
+    r = np.random.default_rng(1000 + seed)
+    hkv = int(r.choice([1, 2, 4]))
+    g = int(r.choice([1, 2, 4, 8]))
+    d = int(r.choice([64, 128]))
+    bits = int(r.choice([2, 4, 8]))
+    window = int(r.choice([8, 16, 32]))
+    prefill = int(r.integers(window + 40, 700))
+    frac = float(r.choice([0.2, 0.35, 0.6, 1.5]))
+    alpha = float(r.choice([0.5, 0.75, 0.9, 1.0]))
+    rho = r.choice([None, 0.0, 0.3, 0.7, 1.0])
+    wl = synth.C1.scaled(name=f"combo{seed}", n_layers=int(r.choice([1, 2])), batch=int(r.choice([1, 2, 3])),
+                         n_q_heads=hkv * g, n_kv_heads=hkv, head_dim=d, bits=bits, window=window, prefill=prefill,
+                         budget_frac=frac, alpha=alpha, decode_steps=int(r.integers(20, 60)), seed=77 + seed)
+    kw = dict(every_step=bool(r.random() < 0.25), byte_budget=bool(r.random() < 0.3))
+    return wl, (None if rho is None else float(rho)), kw
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_drawn_combinations(seed):
+    """Shapes, formats, windows, slack factors, ratios and policies in combinations no other test names."""
+    wl, rho, kw = _combo(seed)
+    if wl.capacity <= wl.window + 2:
+        wl = wl.scaled(budget_frac=0.6)
+    print(wl, rho, kw, flush=True)
+    _run(wl, rho=rho, check_every=3, **kw)
