@@ -192,3 +192,27 @@ def test_attention_whole_prompt_and_chunks_agree_bitwise_600():
     for a, e in [(0, 50), (50, 290), (290, 330), (330, T)]:
         out2[:, :, a:e] = _run_attention(wl, q[:, :, a:e], k, v, scale, e - a, e)
     assert torch.equal(out, out2)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_attention_drawn_shapes_and_chunks(seed):
+    """Drawn group size, head dimension, prompt length, batch and chunking: sampled rows against the oracle and
+    the chunked run bit for bit against the single call."""
+    r = np.random.default_rng(500 + seed)
+    hkv = int(r.choice([1, 2, 3]))
+    g = int(r.choice([1, 2, 4, 8]))
+    d = int(r.choice([64, 128]))
+    T = int(r.integers(40, 420))
+    wl = synth.C1.scaled(name=f"attn_combo{seed}", n_q_heads=hkv * g, n_kv_heads=hkv, head_dim=d, prefill=T,
+                         batch=int(r.choice([1, 2])), budget_frac=2.0, seed=300 + seed)
+    k, v, qw = synth.prefill_inputs(wl, 0)
+    q = _full_queries(wl, 0, qw)
+    scale = synth.softmax_scale(wl, 0) * float(r.choice([0.5, 1.0, 3.0]))
+    out = _run_attention(wl, q, k, v, scale, T, T)
+    pos = np.unique(np.concatenate([[0, T - 1, T // 2], r.integers(0, T, 6)]))
+    assert _check_rows(out, q, k, v, scale, g, pos, 0) <= TOL + 2.0 ** -8
+    cuts = np.unique(np.concatenate([[0, T], r.integers(1, T, 3)]))
+    out2 = torch.zeros_like(out)
+    for a, e in zip(cuts[:-1], cuts[1:]):
+        out2[:, :, a:e] = _run_attention(wl, q[:, :, a:e], k, v, scale, int(e - a), int(e))
+    assert torch.equal(out, out2)
