@@ -79,16 +79,29 @@ __device__ __forceinline__ uint16_t float_to_bf16_rne(float x) {
 // Rows [ao,bo) of the O pool and [aq,bq) of the Q pool that split s of S owns.  Rows are weighted by
 // their measured cost (bf16 row = 16 units, packed row = wq units) so that splits take equal time; the
 // last split also appends the new token, which is charged like kNewTokenRows bf16 rows.
+// The two divisions (by S and by wq) are multiplications by reciprocals that the host puts in the launch
+// arguments: the cut points come first in every workgroup's life, in front of its first request to HBM.  They
+// need not be exact quotients, only the same monotone function of s everywhere, 0 at s = 0 and everything at S.
 constexpr unsigned kNewTokenRows = 32;
-__host__ __device__ inline void split_range(int cO, int cQ, int wq, int S, int s, int& ao, int& bo,
+__host__ __device__ inline unsigned mulhi_u32(unsigned a, unsigned b) {
+  return (unsigned)(((unsigned long long)a * (unsigned long long)b) >> 32);
+}
+__host__ __device__ inline void split_range(int cO, int cQ, int wq, int S, int s, SplitRecip rc, int& ao, int& bo,
                                             int& aq, int& bq) {
-  // 16 cO + wq cQ < 2^19 and S <= 128: everything fits 32 bits
+  // 16 cO + wq cQ < 2^19 and S <= 128: tot * S < 2^26, every product below fits 64 bits, every result 32
   const unsigned tot = 16u * (unsigned)cO + (unsigned)wq * (unsigned)cQ + 16u * kNewTokenRows;
-  const unsigned v0 = tot * (unsigned)s / (unsigned)S, v1 = tot * (unsigned)(s + 1) / (unsigned)S;
+  auto cut = [&](int i) {
+    if (i <= 0) return 0u;
+    if (i >= S) return tot;
+    const unsigned v = mulhi_u32(tot * (unsigned)i, rc.inv_s);
+    return v < tot ? v : tot;
+  };
+  const unsigned v0 = cut(s), v1 = cut(s + 1);
   auto mapO = [&](unsigned v) { const int r = (int)((v + 15u) / 16u); return r < cO ? r : cO; };
   auto mapQ = [&](unsigned v) {
     if (v <= 16u * (unsigned)cO) return 0;
-    const int r = (int)((v - 16u * (unsigned)cO + (unsigned)wq - 1u) / (unsigned)wq);
+    const unsigned x = v - 16u * (unsigned)cO + (unsigned)wq - 1u;
+    const int r = (int)(wq > 1 ? mulhi_u32(x, rc.inv_wq) : x);
     return r < cQ ? r : cQ;
   };
   ao = mapO(v0); bo = mapO(v1); aq = mapQ(v0); bq = mapQ(v1);
@@ -465,13 +478,13 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   constexpr int NV = 16 / R;           // value loads per tile
   constexpr int HB = (G + 3) / 4;      // lane blocks holding real heads
   constexpr int HPL = G < 4 ? G : 4;   // heads per lane
-  const int s = blockIdx.x, lu = blockIdx.y;
+  const int s = blockIdx.x, lu = blockIdx.z * L.units_per_layer + blockIdx.y;   // grid (splits, units of a layer, layers)
   const int gu = L.unit_begin + lu;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int tok = lane & 15, blk = lane >> 4;
   const int vrow = lane / LPR, sub = lane % LPR;
   const bool active = blk < HB;
-  const float scale2 = L.scale2[lu / L.units_per_layer];
+  const float scale2 = L.scale2[blockIdx.z];
   TRACE(0);
 
   __shared__ __align__(16) float pbuf[4][16][G < 4 ? 4 : G];
@@ -503,7 +516,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   }
 
   int ao, bo, aq, bq;
-  split_range(cO, cQ, wq, splits, s, ao, bo, aq, bq);
+  split_range(cO, cQ, wq, splits, s, SplitRecip{L.inv_splits, L.inv_wq}, ao, bo, aq, bq);
 
   const uint16_t* ok_ = pok + (size_t)gu * capO * D;
   const uint16_t* ov_ = pov + (size_t)gu * capO * D;
@@ -840,7 +853,7 @@ __global__ __launch_bounds__(256) void k_flush_scores(Pools P, int unit_begin, i
 template <int D, int G, int BITS>
 static hipError_t launch_decode_t(const Pools& P, const DecodeLaunch& a, hipStream_t s, hipEvent_t ev0,
                                   hipEvent_t ev1) {
-  dim3 grid(a.splits, a.n_units);
+  dim3 grid(a.splits, a.units_per_layer, a.n_units / a.units_per_layer);
   if (ev0) (void)hipEventRecord(ev0, s);
 #ifdef ARKV_PHASE_TRACE
   hipLaunchKernelGGL(k_trace_mark, dim3(1), dim3(64), 0, s, 0);
@@ -984,7 +997,8 @@ extern "C" int arkv_debug_split_range(int32_t n_original, int32_t n_quantized, i
       split >= n_splits || packed_weight < 1 || packed_weight > 16)
     return ARKV_EINVAL;
   int ao, bo, aq, bq;
-  arkv::split_range(n_original, n_quantized, packed_weight, n_splits, split, ao, bo, aq, bq);
+  arkv::split_range(n_original, n_quantized, packed_weight, n_splits, split, arkv::split_recip(n_splits, packed_weight), ao, bo,
+                    aq, bq);
   range[0] = ao; range[1] = bo; range[2] = aq; range[3] = bq;
   return ARKV_OK;
 }

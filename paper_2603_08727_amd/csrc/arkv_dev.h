@@ -60,6 +60,15 @@ constexpr int kPlanHdr = 16;
 // plan header fields (int32 each)
 enum { PL_CO_NEW = 0, PL_CQ_NEW, PL_N_DEM, PL_N_QMOV, PL_N_OMOV, PL_N_ELIG, PL_CO_OLD, PL_CQ_OLD };
 
+// Reciprocals for the decode kernel's split cut points (see split_range)
+struct SplitRecip { unsigned inv_s, inv_wq; };          // ceil(2^32 / S), ceil(2^32 / wq) (unused when S or wq is 1)
+__host__ __device__ inline SplitRecip split_recip(int S, int wq) {
+  SplitRecip r;
+  r.inv_s = S > 1 ? (unsigned)(0xFFFFFFFFull / (unsigned)S) + 1u : 0u;
+  r.inv_wq = wq > 1 ? (unsigned)(0xFFFFFFFFull / (unsigned)wq) + 1u : 0u;
+  return r;
+}
+
 struct DecodeLaunch {
   const uint16_t* q;      // [n][B][Hq][D]
   const uint16_t* k_new;  // [n][B][Hkv][D]
@@ -75,6 +84,7 @@ struct DecodeLaunch {
   int slot;               // ring slot of fin/qprev/qscale this step writes
   int fold;               // 1: this launch adds the pending steps to (s1,s2)
   int wq;                 // cost of a packed row in sixteenths of a bf16 row (split balancing)
+  unsigned inv_splits, inv_wq;   // ceil(2^32 / splits), ceil(2^32 / wq): the split cut points without divisions
   int cnt_known;          // 1: cnt_o / cnt_q below are the units' token counts (saves a dependent load)
   int cnt_o[kMaxUnitsKnown], cnt_q[kMaxUnitsKnown];
   float scale2[kMaxLayersPerLaunch];  // softmax scale * log2(e), per launched layer

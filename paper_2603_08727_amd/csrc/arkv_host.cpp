@@ -448,6 +448,7 @@ int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const
   splits = std::min(splits, std::max(1, l0.live / 128));
   a.splits = std::max(1, std::min(splits, c->P.max_splits));
   a.wq = c->wq;
+  { const SplitRecip rc = split_recip(a.splits, a.wq); a.inv_splits = rc.inv_s; a.inv_wq = rc.inv_wq; }
   for (int i = 0; i < n; ++i) {
     LayerState& li = c->layers[(size_t)(layer_begin + i)];
     if (li.cnt_valid || !li.cnt_refresh) continue;
