@@ -478,13 +478,11 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   constexpr int NV = 16 / R;           // value loads per tile
   constexpr int HB = (G + 3) / 4;      // lane blocks holding real heads
   constexpr int HPL = G < 4 ? G : 4;   // heads per lane
-  const int s = blockIdx.x, lu = blockIdx.z * L.units_per_layer + blockIdx.y;   // grid (splits, units of a layer, layers)
-  const int gu = L.unit_begin + lu;
+  const int s = blockIdx.x;                       // grid (splits, units of a layer, layers)
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int tok = lane & 15, blk = lane >> 4;
   const int vrow = lane / LPR, sub = lane % LPR;
   const bool active = blk < HB;
-  const float scale2 = L.scale2[blockIdx.z];
   TRACE(0);
 
   __shared__ __align__(16) float pbuf[4][16][G < 4 ? 4 : G];
@@ -497,7 +495,9 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   // Everything the first tile request depends on is read from the launch arguments in ONE batch of scalar
   // loads (the empty asm pins the values here); left to itself the compiler fetches each where it is first
   // used, six dependent round trips before the first request to HBM.
-  const int lk = lu < kMaxUnitsKnown ? lu : 0;
+  // (known counts come with single-layer launches only, so their index is the block index: its address does not
+  // wait for units_per_layer, and every launch argument is requested in the same batch)
+  const int lk = blockIdx.y < (unsigned)kMaxUnitsKnown ? (int)blockIdx.y : 0;
   int cO = L.cnt_o[lk], cQ = L.cnt_q[lk];
   const int known = L.cnt_known, wq = L.wq, splits = L.splits, npend = L.n_pending;
   const int capO = P.capO, capQ = P.capQ;
@@ -507,8 +507,14 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   float2* const poacc = P.oacc;
   float2* const pqacc = P.qacc;
   const uint16_t* const pq = L.q;
+  const int upl = L.units_per_layer, ubeg = L.unit_begin;
+  const unsigned inv_s = L.inv_splits, inv_wq = L.inv_wq;
+  const float scale2 = L.scale2[blockIdx.z];
   asm volatile("" ::"s"(cO), "s"(cQ), "s"(known), "s"(wq), "s"(splits), "s"(npend), "s"(capO), "s"(capQ),
-               "s"(fin_stride), "s"(pok), "s"(pov), "s"(poacc), "s"(pqacc), "s"(pq));
+               "s"(fin_stride), "s"(pok), "s"(pov), "s"(poacc), "s"(pqacc), "s"(pq), "s"(upl), "s"(ubeg), "s"(inv_s),
+               "s"(inv_wq), "s"(scale2));
+  const int lu = (int)blockIdx.z * upl + (int)blockIdx.y;
+  const int gu = ubeg + lu;
   // token counts: from the launch arguments when the host knows them, else from the unit's counters
   if (!known) {
     const volatile int* cnt = reinterpret_cast<const volatile int*>(P.cnt + gu);
@@ -516,7 +522,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   }
 
   int ao, bo, aq, bq;
-  split_range(cO, cQ, wq, splits, s, SplitRecip{L.inv_splits, L.inv_wq}, ao, bo, aq, bq);
+  split_range(cO, cQ, wq, splits, s, SplitRecip{inv_s, inv_wq}, ao, bo, aq, bq);
 
   const uint16_t* ok_ = pok + (size_t)gu * capO * D;
   const uint16_t* ov_ = pov + (size_t)gu * capO * D;

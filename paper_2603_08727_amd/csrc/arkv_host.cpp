@@ -458,7 +458,7 @@ int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const
     li.cnt_valid = true; li.cnt_refresh = false;
   }
   a.cnt_known = 0;
-  if (a.n_units <= kMaxUnitsKnown) {
+  if (n == 1 && a.n_units <= kMaxUnitsKnown) {   // one layer: the kernel indexes the counts by its block index
     bool known = true;
     for (int i = 0; i < n; ++i) known = known && c->layers[(size_t)(layer_begin + i)].cnt_valid;
     if (known) {
