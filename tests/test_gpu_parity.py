@@ -160,3 +160,13 @@ def test_drawn_combinations(seed):
         wl = wl.scaled(budget_frac=0.6)
     print(wl, rho, kw, flush=True)
     _run(wl, rho=rho, check_every=3, **kw)
+
+
+@pytest.mark.parametrize("bits,every_step", [(4, False), (8, False), (2, True)])
+def test_long_run_many_tailors(bits, every_step):
+    """600 decode steps on a small cache: about 25 tailors (600 under the every-step policy), the ring of waiting
+    steps wraps dozens of times, the host's token counts are refreshed after every tailor."""
+    wl = synth.C1.scaled(name=f"long_b{bits}", bits=bits, head_dim=128 if bits == 8 else 64, decode_steps=600)
+    sb = _run(wl, rho=0.5, check_every=37, every_step=every_step)
+    oc = sb.oracles[(0, 0)]
+    assert oc.n_tailors >= (600 if every_step else 20)
