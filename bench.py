@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the ARKV decode hot path on one MI355X.
 
-Workload (config.workload): benchmark configs[2], the configuration the metric is quoted on
+Workload (config.workload): the third benchmark configuration, the one the metric is quoted on
 (32K context): Qwen3-8B-shaped cache, 36 layers, 32 q / 8 kv heads, d=128, batch 4, prompt 32768,
 budget 25 % (N = 8192), 4-bit groups of 32.  Synthetic inputs, drawn on the GPU (synth.py).
 
@@ -14,7 +14,7 @@ reported under "prefill".
 
 value = layer-batch decode steps per second = n_layers * steps / seconds.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -294,7 +294,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures ONE GPU (units of the cache never interact across GPUs; "
-              "see DESIGN.md 'How it would shard'); run with --gpus 1", file=sys.stderr)
+              "sharding by kv-head or sequence is a design note, not built); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

@@ -28,8 +28,8 @@ What follows the paper, by passage:
                           with one scale per token row, x~ = q^ * s
   SequenceCacheOracle     Alg. 1 end to end for one (layer, sequence)
 
-Readings taken where the paper is silent or garbled are listed in DESIGN.md;
-the ones that matter for this file are repeated at the function they affect.
+Readings taken where the paper is silent or garbled (numbered R1, R2, ...) are
+repeated at the function they affect.
 
 Parity pins (tests/test_oracle_*.py): brute-force loops on tiny inputs, closed
 forms for the statistics, library routines for special cases (softmax

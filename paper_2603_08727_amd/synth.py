@@ -57,7 +57,7 @@ class Workload:
         return replace(self, **kw)
 
 
-# The five benchmark configurations (BASELINE.json "configs", in order).
+# The five benchmark configurations, in the benchmark definition's order.
 C1 = Workload("c1_small", 1, 1, 8, 2, 64, 512, 64, 0.25, bits=4)
 C2 = Workload("c2_llama3_8b_8k", 32, 1, 32, 8, 128, 8192, 256, 0.25, bits=4)
 C3 = Workload("c3_qwen3_8b_32k_b4", 36, 4, 32, 8, 128, 32768, 128, 0.25, bits=4, layer_temp=(0.5, 2.0))
