@@ -475,20 +475,31 @@ __global__ __launch_bounds__(1024) void k_commit_plan(Pools P, CommitLaunch L, c
   int32_t* osrc = plan + kPlanHdr;
   int32_t* qsrc = osrc + P.capO;
   int bo = 0, bq = 0;
-  for (int c0 = 0; c0 < L.T; c0 += 1024) {
-    const int j = c0 + tid;
-    bool o = false, q = false;
-    if (j < L.T) {
-      const uint64_t k = keys[j];
-      o = k == 0 || k >= thr_o;          // key 0 = window position
-      q = !o && k >= thr_b;
+  // eight consecutive positions per thread and round: one block scan per 8192 positions (the two counts are
+  // carried in the halves of one 64-bit word), positions stay in ascending order
+  constexpr int E = 8;
+  for (int c0 = 0; c0 < L.T; c0 += 1024 * E) {
+    const int j0 = c0 + E * tid;
+    unsigned om = 0, qm = 0;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      if (j0 + e < L.T) {
+        const uint64_t k = keys[j0 + e];
+        const bool o = k == 0 || k >= thr_o;          // key 0 = window position
+        om |= (unsigned)o << e;
+        qm |= (unsigned)(!o && k >= thr_b) << e;
+      }
     }
-    const uint64_t v = ((uint64_t)o << F0) | ((uint64_t)q << F1);
+    const uint64_t v = (uint64_t)__popc(om) | ((uint64_t)__popc(qm) << 32);
     uint64_t total;
     const uint64_t ex = block_excl_scan(v, sm, total);
-    if (o) osrc[bo + fld(ex, F0)] = j;
-    if (q) qsrc[bq + fld(ex, F1)] = j;
-    bo += fld(total, F0); bq += fld(total, F1);
+    int io = bo + (int)(ex & 0xFFFFFFFFu), iq = bq + (int)(ex >> 32);
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      if ((om >> e) & 1u) osrc[io++] = j0 + e;
+      if ((qm >> e) & 1u) qsrc[iq++] = j0 + e;
+    }
+    bo += (int)(total & 0xFFFFFFFFu); bq += (int)(total >> 32);
   }
   if (tid == 0) { plan[PL_CO_NEW] = bo; plan[PL_CQ_NEW] = bq; P.cnt[gu] = make_int2(bo, bq); }
 }
