@@ -451,3 +451,53 @@ def test_causal_attention_rows_match_library_and_window():
     assert np.allclose(O.causal_attention_rows(q[:, sub], sub, k, v, scale, 2), out[:, sub], rtol=1e-13, atol=1e-14)
     # position 0 attends to itself only
     assert np.allclose(out[:, 0], np.repeat(v, 2, axis=0)[:, 0])
+
+
+def _paper_constants():
+    import os
+    vals, table7, budgets = {}, [], []
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_constants.txt")) as f:
+        for line in f:
+            t = line.split("#")[0].split()
+            if not t:
+                continue
+            if t[0] == "table7":
+                table7.append((int(t[1]), float(t[2]), float(t[3])))
+            elif t[0] == "budget":
+                budgets.append(int(t[1]))
+            else:
+                vals[t[0]] = float(t[1])
+    return vals, table7, budgets
+
+
+def test_defaults_are_the_papers_tuned_values():
+    """The library's default configuration and the synthetic workloads carry the hyper-parameters the paper prints
+    (Sec. V "Main Results": tau, gamma, window; Sec. IV-F: alpha)."""
+    from paper_2603_08727_amd import binding as A
+    from paper_2603_08727_amd import synth
+    vals, _, _ = _paper_constants()
+    cfg = A.arkv_config_default()
+    assert [round(float(x), 3) for x in cfg.tau] == [vals["tau1"], vals["tau2"], vals["tau3"]]
+    assert round(float(cfg.gamma), 2) == vals["gamma"] and cfg.window == int(vals["window"])
+    assert float(cfg.alpha) == vals["alpha"]
+    for wl in synth.CONFIGS.values():
+        assert [round(float(x), 3) for x in wl.tau] == [vals["tau1"], vals["tau2"], vals["tau3"]]
+        assert round(float(wl.gamma), 2) == vals["gamma"] and float(wl.alpha) == vals["alpha"]
+
+
+def test_budget_rule_against_table7_aggregates():
+    """Plausibility only (aggregates over the paper's models, not a worked example): with the budget rule of
+    Alg. 1 (n_o = floor(rho (N - W)) capped at b = floor(alpha (N - W)), the rest of b Quantized) a mean ratio of
+    about 0.6 reproduces Table VII's Quantized share of the budget, about 14.4 % at all three cache limits, and
+    the share moves the right way with rho."""
+    vals, table7, budgets = _paper_constants()
+    W, alpha = int(vals["window"]), vals["alpha"]
+    assert [b for b, _, _ in table7] == budgets
+    for N, quant_pct, evict_pct in table7:
+        n_o, n_q, b = O.budget_counts(0.6, N, W, alpha)
+        assert n_o + n_q == b == int(np.floor(alpha * (N - W)))
+        assert abs(100.0 * n_q / N - quant_pct) < 1.5
+        lo = O.budget_counts(0.7, N, W, alpha)[1]
+        hi = O.budget_counts(0.5, N, W, alpha)[1]
+        assert lo < n_q < hi
+        assert 0.0 < evict_pct < 100.0
