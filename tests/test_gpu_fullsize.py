@@ -81,3 +81,61 @@ def test_c5_prefill_scorer_16k_batch8_one_layer():
 def test_c5_prefill_scorer_window_128():
     """Same shape with a 4x observation window (512 query rows per unit), two sequences."""
     _run_scorer(synth.C5.scaled(n_layers=1, batch=2, window=128))
+
+
+def test_c3_natural_tailor_cadence_invariants():
+    """Config 3 at full size, two layers, stepped past the first decode-time tailor at its natural cadence
+    (N - b - W = 2040 steps) without the oracle: what must hold at any size.  Every unit holds b + W + (steps since
+    the tailor) tokens; positions are distinct, the window and every token generated since the tailor are there and
+    Original; Original counts respect the budget; scores are finite and non-negative; live bytes within eq. 1."""
+    import torch
+    from paper_2603_08727_amd import binding as A
+    from helpers import make_cfg
+    wl = synth.C3.scaled(name="c3_cadence", n_layers=2)
+    cfg = make_cfg(wl)
+    L, B, Hq, Hkv, d, T, W, N = wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.prefill, wl.window, wl.capacity
+    U = B * Hkv
+    cache = A.arkv_cache_create(cfg)
+    try:
+        scales = [synth.softmax_scale(wl, l) for l in range(L)]
+        stats = torch.zeros((L, B, 3), dtype=torch.float32, device="cuda")
+        for l in range(L):
+            k, v, qw = synth.prefill_inputs(wl, l, device="cuda")
+            A.arkv_prefill_stats(cache, l, qw, k, T, scales[l], stats[l])
+        rho = A.arkv_oq_ratio(stats.cpu().numpy(), wl.tau)
+        rho[1, :] = 0.5                                    # layer 1: a mixed cache whatever the scorer says
+        for l in range(L):
+            k, v, qw = synth.prefill_inputs(wl, l, device="cuda")
+            A.arkv_prefill_commit(cache, l, k, v, T, rho[l])
+        b = int(np.floor(np.float32(wl.alpha) * (N - W)))
+        steps = (N - b - W) + 25
+        dq = [synth.decode_inputs(wl, l, steps, device="cuda") for l in range(L)]
+        out = torch.empty((B, Hq, d), dtype=torch.bfloat16, device="cuda")
+        for t in range(steps):
+            for l in range(L):
+                A.arkv_decode_step(cache, l, dq[l][0][t], dq[l][1][t], dq[l][2][t], scales[l], out)
+        torch.cuda.synchronize()
+        assert torch.isfinite(out.float()).all()
+        since = steps - (N - b - W)                         # steps after the tailor fired
+        for l in range(L):
+            n_tailors = A.arkv_cache_progress(cache, l)[0]
+            assert n_tailors == 2                           # the one at commit and the one at the cadence
+            ex = A.arkv_cache_export(cache, l, cfg, rows=False, codes=False)
+            no, nq, ne, lb = A.arkv_cache_counters(cache, l, U)
+            n_o_target = [A.arkv_budget_counts(cfg, float(rho[l, s]))[0] for s in range(B)]
+            for u in range(U):
+                n = int(ex["n_live"][u])
+                assert n == b + W + since == no[u] + nq[u]
+                pos = ex["pos"][u, :n]; st = ex["state"][u, :n]
+                assert len(np.unique(pos)) == n and pos.min() >= 0 and pos.max() == T + steps - 1
+                recent = pos >= T + steps - (W + since)      # the window at the tailor plus everything since
+                assert recent.sum() == W + since and (st[recent] == 0).all()
+                assert no[u] - (W + since) <= n_o_target[u // Hkv]
+                assert ne[u] == T + steps - n
+                s1 = ex["s1"][u, :n]; s2 = ex["s2"][u, :n]
+                assert np.isfinite(s1).all() and np.isfinite(s2).all() and (s1 >= 0).all() and (s2 >= 0).all()
+                assert lb[u] <= N * 4 * d
+            if l == 1:
+                assert (nq > 1000).all()
+    finally:
+        A.arkv_cache_destroy(cache)
