@@ -216,3 +216,36 @@ def test_attention_drawn_shapes_and_chunks(seed):
     for a, e in zip(cuts[:-1], cuts[1:]):
         out2[:, :, a:e] = _run_attention(wl, q[:, :, a:e], k, v, scale, int(e - a), int(e))
     assert torch.equal(out, out2)
+
+
+def test_fused_scorer_on_the_last_chunk_of_a_chunked_prompt():
+    """The prompt in three chunks, the statistics asked for with the last one (which holds the window): same
+    statistics as the stand-alone scorer, and the commit that follows accepts them."""
+    wl = synth.C1.scaled(name="chunk_stats", prefill=500, batch=2, n_layers=1, decode_steps=4)
+    cfg = make_cfg(wl)
+    T, W = wl.prefill, wl.window
+    k, v, qw = synth.prefill_inputs(wl, 0)
+    q = _full_queries(wl, 0, qw)
+    scale = synth.softmax_scale(wl, 0)
+    kd, vd, qd = k.cuda(), v.cuda(), q.cuda()
+    cache = A.arkv_cache_create(cfg)
+    try:
+        alone = torch.zeros((wl.batch, 3), dtype=torch.float32, device="cuda")
+        A.arkv_prefill_stats(cache, 0, qw.cuda(), kd, T, scale, alone)
+        A.arkv_cache_reset(cache, 0)
+        fused = torch.zeros_like(alone)
+        out = torch.zeros_like(qd)
+        for a, e in [(0, 190), (190, 431), (431, T)]:
+            oc = torch.zeros((wl.batch, wl.n_q_heads, e - a, wl.head_dim), dtype=torch.bfloat16, device="cuda")
+            A.arkv_prefill_attention(cache, 0, qd[:, :, a:e].contiguous(), kd[:, :, :e].contiguous(), vd[:, :, :e].contiguous(),
+                                     e - a, e, scale, oc, fused if e == T else None)
+            out[:, :, a:e] = oc
+        torch.cuda.synchronize()
+        sa, sf = alone.cpu().numpy(), fused.cpu().numpy()
+        assert np.all(np.abs(sf - sa) <= TOL * np.abs(sa))
+        pos = np.array([0, 189, 190, 430, 431, T - 1])
+        assert _check_rows(out, q, k, v, scale, wl.group, pos, 0) <= TOL + 2.0 ** -8
+        A.arkv_prefill_commit(cache, 0, kd, vd, T, A.arkv_oq_ratio(sf[None], wl.tau)[0])
+        assert A.arkv_cache_progress(cache, 0)[0] == 1
+    finally:
+        A.arkv_cache_destroy(cache)
