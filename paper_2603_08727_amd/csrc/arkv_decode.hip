@@ -50,6 +50,19 @@ __device__ __forceinline__ float row_max16(float x) {
   return x;
 }
 
+// over the whole wave, same result in every lane, fixed order
+__device__ __forceinline__ float lane_value(float x, int l) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), l));
+}
+__device__ __forceinline__ float wave_max(float x) {
+  x = row_max16(x);
+  return fmaxf(fmaxf(lane_value(x, 0), lane_value(x, 16)), fmaxf(lane_value(x, 32), lane_value(x, 48)));
+}
+__device__ __forceinline__ float wave_sum(float x) {
+  x = row_sum16(x);
+  return (lane_value(x, 0) + lane_value(x, 16)) + (lane_value(x, 32) + lane_value(x, 48));
+}
+
 __device__ __forceinline__ void unpack_bf16x8(const uint4& r, float (&f)[8]) {
   f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
   f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
@@ -367,89 +380,6 @@ __device__ __forceinline__ float2 fold_pending(const PendingLds<D, G>& sm, int n
   return ac;
 }
 
-// Split-K partials cross workgroups that may sit on different XCDs, whose L2 caches are not coherent
-// with each other for ordinary accesses.  They are therefore written and read with device-scope relaxed
-// atomics (write-through stores, loads that do not hit a stale L2 line); no cache-wide flush is needed.
-__device__ __forceinline__ void st_dev(float* p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float ld_dev(const float* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// Merge of a unit's split-K partials by the workgroup that finished last: output row, the step's
-// (max, 1/sum) per head, token count.  All 256 threads of that workgroup take part.
-template <int D, int G>
-__device__ __forceinline__ void combine_splits(const Pools& P, const DecodeLaunch& L, int lu, int gu, int tid) {
-  __shared__ float cm[kMaxSplits][G], cl[kMaxSplits][G], cw[kMaxSplits][G];
-  __shared__ float cInv[G];
-  constexpr int RS = G * (D + 2);                  // floats per split
-  constexpr int NI = (G * D + 255) / 256;          // output elements per thread
-  constexpr int NB = 16;                           // splits per batch of loads
-  const float* part = P.part + (size_t)gu * P.max_splits * RS;
-  const int S = L.splits;
-  int hh[NI], off[NI];
-#pragma unroll
-  for (int i = 0; i < NI; ++i) {
-    const int idx = min(tid + 256 * i, G * D - 1);
-    hh[i] = idx / D;
-    off[i] = hh[i] * (D + 2) + idx % D;
-  }
-  // the first batch of partial values is requested together with the (max, sum) pairs: one round trip
-  float v[NI][NB];
-#pragma unroll
-  for (int i = 0; i < NI; ++i)
-#pragma unroll
-    for (int j = 0; j < NB; ++j) v[i][j] = ld_dev(part + (size_t)min(j, S - 1) * RS + off[i]);
-  for (int i = tid; i < S * G; i += 256) {
-    const int s = i / G, h = i % G;
-    const unsigned long long ml = __hip_atomic_load(
-        reinterpret_cast<const unsigned long long*>(part + (size_t)s * RS + h * (D + 2) + D), __ATOMIC_RELAXED,
-        __HIP_MEMORY_SCOPE_AGENT);
-    cm[s][h] = __uint_as_float((unsigned)ml);
-    cl[s][h] = __uint_as_float((unsigned)(ml >> 32));
-  }
-  __syncthreads();
-  if (tid < G) {
-    float M = kNegBig;
-    for (int s = 0; s < S; ++s) M = fmaxf(M, cm[s][tid]);
-    float l = 0.f;
-    for (int s = 0; s < S; ++s) {
-      const float w_ = exp2f(cm[s][tid] - M);
-      cw[s][tid] = w_;
-      l = fmaf(cl[s][tid], w_, l);
-    }
-    cInv[tid] = 1.0f / l;
-    P.fin[(size_t)L.slot * P.fin_stride + (size_t)gu * G + tid] = make_float2(M, 1.0f / l);
-  }
-  __syncthreads();
-  float o[NI];
-#pragma unroll
-  for (int i = 0; i < NI; ++i) o[i] = 0.f;
-  for (int s0 = 0;;) {
-#pragma unroll
-    for (int j = 0; j < NB; ++j)
-#pragma unroll
-      for (int i = 0; i < NI; ++i) o[i] = fmaf(v[i][j], s0 + j < S ? cw[s0 + j][hh[i]] : 0.f, o[i]);
-    s0 += NB;
-    if (s0 >= S) break;
-#pragma unroll
-    for (int i = 0; i < NI; ++i)
-#pragma unroll
-      for (int j = 0; j < NB; ++j) v[i][j] = ld_dev(part + (size_t)min(s0 + j, S - 1) * RS + off[i]);
-  }
-#pragma unroll
-  for (int i = 0; i < NI; ++i) {
-    const int idx = tid + 256 * i;
-    if (idx < G * D) {
-      const float r = o[i] * cInv[hh[i]];
-      P.outf[(size_t)gu * G * D + idx] = r;
-      L.out[(size_t)lu * G * D + idx] = float_to_bf16_rne(r);
-    }
-  }
-  if (tid == 0) P.cnt[gu].x += 1;
-}
-
 // Profiling builds (-DARKV_PHASE_TRACE) record a 100 MHz timestamp per workgroup at the phase boundaries
 // marked TRACE(i); arkv_debug_trace_dump copies them out.  Product builds compile none of it.
 #ifdef ARKV_PHASE_TRACE
@@ -459,6 +389,146 @@ __global__ void k_trace_mark(int slot) { if (threadIdx.x == 0) g_trace[8190][slo
 #else
 #define TRACE(i)
 #endif
+#ifdef ARKV_PHASE_TRACE_MERGE
+__device__ unsigned long long g_trace_m[8192][8];
+#define TRACE_M(i) do { if (threadIdx.x == 0) g_trace_m[blockIdx.y * gridDim.x + blockIdx.x][i] = wall_clock64(); } while (0)
+extern "C" int arkv_debug_trace_dump_m(unsigned long long* host, int n_wg) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace_m), (size_t)n_wg * 8 * sizeof(unsigned long long));
+}
+#else
+#define TRACE_M(i)
+#endif
+
+// Split-K partials cross workgroups that may sit on different XCDs, whose L2 caches are not coherent
+// with each other for ordinary accesses.  They are therefore written and read with device-scope relaxed
+// atomics (write-through stores, loads that do not hit a stale L2 line); no cache-wide flush is needed.
+// (two adjacent floats, 8-byte aligned, per access)
+__device__ __forceinline__ void st_dev2(float* p, float a, float b) {
+  __hip_atomic_store(reinterpret_cast<unsigned long long*>(p),
+                     (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32),
+                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long ld_dev2(const float* p) {
+  return __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Merge of a unit's split-K partials by the workgroup that finished last: output row, the step's
+// (max, 1/sum) per head, token count.  All 256 threads of that workgroup take part; a thread owns pairs of
+// adjacent channels (8-byte loads), and the partials of up to 64 splits are requested before the first is
+// used, so the merge costs one round trip to memory where a launch has many splits per unit.
+template <int D, int G>
+__device__ __forceinline__ void combine_splits(const Pools& P, const DecodeLaunch& L, int lu, int gu, int tid) {
+  __shared__ __align__(16) float cw[G][kMaxSplits];   // weight of split s for head h; 0 beyond the launch's splits
+  __shared__ float cInv[G];
+  constexpr int RS = G * (D + 2);                  // floats per split
+  constexpr int NP = G * D / 2;                    // channel pairs per split
+  constexpr int NI = (NP + 255) / 256;             // pairs per thread
+  constexpr int NB = 64 / NI;                      // splits per batch of loads
+  TRACE_M(0);
+  const float* part = P.part + (size_t)gu * P.max_splits * RS;
+  const int S = L.splits;
+  int hh[NI], off[NI];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int idx = min(tid + 256 * i, NP - 1);
+    hh[i] = idx / (D / 2);
+    off[i] = hh[i] * (D + 2) + 2 * (idx % (D / 2));
+  }
+  unsigned long long v[NI][NB];
+  auto load_batch = [&](int s0) {
+#pragma unroll
+    for (int g = 0; g < NB / 16; ++g) {
+      if (s0 + 16 * g < S) {                       // uniform: whole groups of 16 splits are skipped
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj)
+#pragma unroll
+          for (int i = 0; i < NI; ++i)
+            v[i][16 * g + jj] = ld_dev2(part + (size_t)min(s0 + 16 * g + jj, S - 1) * RS + off[i]);
+      }
+    }
+  };
+  // (max, sum) of the splits: wave w takes heads w and w + 4; a lane takes splits lane and lane + 64 and the
+  // wave reduces in a fixed order.  The pairs are requested first and the first batch of partial values right
+  // behind them, so that the weights are worked out while the values are on their way: one round trip.
+  {
+    constexpr int NH = (G + 3) / 4;
+    const int lane = tid & 63, w = tid >> 6;
+    float m0[NH], l0[NH], m1[NH], l1[NH];
+#pragma unroll
+    for (int k = 0; k < NH; ++k) {
+      const int h = min(w + 4 * k, G - 1);
+      m0[k] = m1[k] = kNegBig; l0[k] = l1[k] = 0.f;
+      if (lane < S) {
+        const unsigned long long ml = ld_dev2(part + (size_t)lane * RS + h * (D + 2) + D);
+        m0[k] = __uint_as_float((unsigned)ml); l0[k] = __uint_as_float((unsigned)(ml >> 32));
+      }
+      if (lane + 64 < S) {
+        const unsigned long long ml = ld_dev2(part + (size_t)(lane + 64) * RS + h * (D + 2) + D);
+        m1[k] = __uint_as_float((unsigned)ml); l1[k] = __uint_as_float((unsigned)(ml >> 32));
+      }
+    }
+    load_batch(0);
+    TRACE_M(1);
+#pragma unroll
+    for (int k = 0; k < NH; ++k) {
+      const int h = w + 4 * k;
+      if (h < G) {                                 // uniform per wave
+        const float M = wave_max(fmaxf(m0[k], m1[k]));
+        const float w0 = lane < S ? exp2f(m0[k] - M) : 0.f, w1 = lane + 64 < S ? exp2f(m1[k] - M) : 0.f;
+        cw[h][lane] = w0;
+        cw[h][lane + 64] = w1;
+        const float l = wave_sum(fmaf(l0[k], w0, l1[k] * w1));
+        if (lane == 0) {
+          cInv[h] = 1.0f / l;
+          P.fin[(size_t)L.slot * P.fin_stride + (size_t)gu * G + h] = make_float2(M, 1.0f / l);
+        }
+      }
+    }
+  }
+  TRACE_M(2);
+  __syncthreads();
+  TRACE_M(3);
+  float o[NI][2];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) o[i][0] = o[i][1] = 0.f;
+  for (int s0 = 0;;) {
+#pragma unroll
+    for (int g = 0; g < NB / 16; ++g) {
+      if (s0 + 16 * g < S) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+#pragma unroll
+          for (int i = 0; i < NI; ++i) {
+            const float4 w4 = *reinterpret_cast<const float4*>(&cw[hh[i]][s0 + 16 * g + 4 * q]);
+            const float wgt[4] = {w4.x, w4.y, w4.z, w4.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const unsigned long long x = v[i][16 * g + 4 * q + e];
+              o[i][0] = fmaf(__uint_as_float((unsigned)x), wgt[e], o[i][0]);
+              o[i][1] = fmaf(__uint_as_float((unsigned)(x >> 32)), wgt[e], o[i][1]);
+            }
+          }
+        }
+      }
+    }
+    s0 += NB;
+    if (s0 >= S) break;
+    load_batch(s0);
+  }
+  TRACE_M(4);
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int idx = tid + 256 * i;
+    if (idx < NP) {
+      const float r0 = o[i][0] * cInv[hh[i]], r1 = o[i][1] * cInv[hh[i]];
+      *reinterpret_cast<float2*>(P.outf + (size_t)gu * G * D + 2 * idx) = make_float2(r0, r1);
+      *reinterpret_cast<uint32_t*>(L.out + (size_t)lu * G * D + 2 * idx) =
+          (uint32_t)float_to_bf16_rne(r0) | ((uint32_t)float_to_bf16_rne(r1) << 16);
+    }
+  }
+  if (tid == 0) P.cnt[gu].x += 1;
+  TRACE_M(5);
+}
 
 // Attention of one query per head over this split's share of a unit's cache.
 //
@@ -769,20 +839,21 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
 
   // ---------------- this split's partial ----------------
   float* part = P.part + ((size_t)gu * P.max_splits + s) * G * (D + 2);
-  for (int idx = tid; idx < G * D; idx += 256) {
-    const int h = idx / D, c = idx % D;
+  for (int idx = tid; idx < G * D / 2; idx += 256) {
+    const int h = idx / (D / 2), c = 2 * (idx % (D / 2));
     float M = sm_m[0][h];
 #pragma unroll
     for (int i = 1; i < 4; ++i) M = fmaxf(M, sm_m[i][h]);
-    float a = 0.f, l = 0.f;
+    float a0 = 0.f, a1 = 0.f, l = 0.f;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const float cw_ = fexp2(sm_m[i][h] - M);
-      a = fmaf(sm_a[i][h][c], cw_, a);
+      a0 = fmaf(sm_a[i][h][c], cw_, a0);
+      a1 = fmaf(sm_a[i][h][c + 1], cw_, a1);
       l = fmaf(sm_l[i][h], cw_, l);
     }
-    st_dev(part + h * (D + 2) + c, a);
-    if (c == 0) { st_dev(part + h * (D + 2) + D, M); st_dev(part + h * (D + 2) + D + 1, l); }
+    st_dev2(part + h * (D + 2) + c, a0, a1);
+    if (c == 0) st_dev2(part + h * (D + 2) + D, M, l);
   }
 
   TRACE(5);
