@@ -423,7 +423,7 @@ __device__ __forceinline__ void combine_splits(const Pools& P, const DecodeLaunc
   constexpr int RS = G * (D + 2);                  // floats per split
   constexpr int NP = G * D / 2;                    // channel pairs per split
   constexpr int NI = (NP + 255) / 256;             // pairs per thread
-  constexpr int NB = 64 / NI;                      // splits per batch of loads
+  constexpr int NB = (G <= 2 ? 32 : 64) / NI;      // splits per batch of loads (NI * NB * 2 registers)
   TRACE_M(0);
   const float* part = P.part + (size_t)gu * P.max_splits * RS;
   const int S = L.splits;
