@@ -445,6 +445,9 @@ int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const
   // split-K factor: enough workgroups to fill the chip, at least 128 rows (two tiles per wave) each: below
   // that the merge of more partials costs more than the shorter loops save (measured on the 8K-context shape)
   int splits = (c->wg_target + a.n_units / 2) / a.n_units;
+  // few units: beyond 32 splits the merge (one workgroup pulls every partial of its unit) costs more than the
+  // second workgroup per CU gains, so such launches use one workgroup per CU
+  if (splits > 32) splits = (splits + 1) / 2;
   splits = std::min(splits, std::max(1, l0.live / 128));
   a.splits = std::max(1, std::min(splits, c->P.max_splits));
   a.wq = c->wq;
