@@ -73,13 +73,14 @@ __global__ __launch_bounds__(256) void k_commit_keys(uint64_t* keys, CommitLaunc
 // Radix select, most significant byte first.  The candidates of a pass often share their byte (scores of
 // one unit have the same exponent), which would serialise plain LDS atomics; lanes of a wave that hit the
 // same bin as the wave's first candidate are therefore counted with a ballot and added once.  The keys a thread owns stay in registers
-// for all eight passes when they fit (n <= 32 per thread), else they are re-read.
+// for all passes when they fit (n <= 32 per thread), else they are re-read.  Keys are distinct (the position is part
+// of them), so once the chosen bin holds a single candidate the remaining passes are skipped: its owner writes it.
 constexpr int kSelKeys = 32;   // keys per thread held in registers
 __global__ __launch_bounds__(1024) void k_select(const uint64_t* keys_all, size_t stride, int n,
                                                  const int32_t* n_o, const int32_t* nb, int unit_begin,
                                                  uint64_t* thr) {
   __shared__ int hist[256];
-  __shared__ int s_sel, s_k, s_tot;
+  __shared__ int s_sel, s_k, s_tot, s_cnt;
   const int lu = blockIdx.y, gu = unit_begin + lu, which = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
   const uint64_t* keys = keys_all + (size_t)lu * stride;
   const bool in_regs = n <= 1024 * kSelKeys;
@@ -140,7 +141,7 @@ __global__ __launch_bounds__(1024) void k_select(const uint64_t* keys_all, size_
       for (int i = 3; i >= 0; --i) {
         const int gt = ge;
         ge += h[i];
-        if (kk > 0 && gt < kk && kk <= ge) { s_sel = 4 * tid + i; s_k = kk - gt; }
+        if (kk > 0 && gt < kk && kk <= ge) { s_sel = 4 * tid + i; s_k = kk - gt; s_cnt = h[i]; }
       }
     }
     __syncthreads();
@@ -153,7 +154,21 @@ __global__ __launch_bounds__(1024) void k_select(const uint64_t* keys_all, size_
     }
     prefix = (prefix << 8) | (uint64_t)s_sel;
     k = s_k;
+    const bool single = s_cnt == 1;                      // one candidate left: it is the answer
     __syncthreads();
+    if (single && pass < 7) {
+      auto claim = [&](uint64_t key) {
+        if (key != 0 && (key >> shift) == prefix) thr[(size_t)gu * 2 + which] = key;
+      };
+      if (in_regs) {
+#pragma unroll
+        for (int j = 0; j < kSelKeys; ++j)
+          if (1024 * j < n) claim(mine[j]);
+      } else {
+        for (int i0 = 0; i0 < n; i0 += 1024) claim(i0 + tid < n ? keys[i0 + tid] : 0);
+      }
+      return;
+    }
   }
   if (tid == 0) thr[(size_t)gu * 2 + which] = prefix;
 }
