@@ -170,3 +170,13 @@ def test_long_run_many_tailors(bits, every_step):
     sb = _run(wl, rho=0.5, check_every=37, every_step=every_step)
     oc = sb.oracles[(0, 0)]
     assert oc.n_tailors >= (600 if every_step else 20)
+
+
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (16, 2), (2, 2)])
+def test_many_splits_per_unit(hq, hkv):
+    """Two units with 17K live tokens each: the launch uses 128 splits per unit, so the merging workgroup
+    reduces the splits' maxima and sums over two keys per lane and fetches the partials in several batches."""
+    wl = synth.C1.scaled(name=f"splits_g{hq // hkv}", n_q_heads=hq, n_kv_heads=hkv, head_dim=128, prefill=17000,
+                         budget_frac=1.1, decode_steps=10)
+    sb = _run(wl, check_every=3)
+    assert sb.oracles[(0, 0)].n_tailors == 0
