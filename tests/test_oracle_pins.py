@@ -253,11 +253,89 @@ def test_quantiser_constant_group_and_directed_rounding():
     assert (c == 0).all() and s[0] == 0 and z[0] == np.float16(1.5)
     assert O.dequantize_row(c[0], s, z).tolist() == [1.5] * 32
     # a minimum that fp16 would round upwards must be stepped down
-    mn = np.float32(-(1 + 2.0 ** -11 + 2.0 ** -13))     # rounds to -1.0 in fp16 (towards zero = up)
+    mn = np.float32(-(1 + 2.0 ** -11 - 2.0 ** -13))     # rounds to -1.0 in fp16 (towards zero = up)
+    assert np.float32(np.float16(mn)) > mn
     x = np.linspace(mn, 1.0, 32).astype(np.float32); x[0] = mn
     c, s, z = O.quantize_groups(x[None], 4)
     assert np.float32(z[0]) <= mn and np.float32(z[0]) + 15 * np.float32(s[0]) >= 1.0
     assert c[0, 0] == 0 and c[0, -1] == 15
+
+
+@pytest.mark.parametrize("bits", [4, 2])
+def test_quantiser_grid_covers_arbitrary_fp32_groups(bits):
+    """Inputs that fp16 cannot hold exactly (the quantiser takes any fp32 row): the zero point must still sit
+    at or below the minimum and the grid must still reach the maximum, which is what the directed adjustments of
+    zero and scale are for; then every element is within half a step."""
+    rng = np.random.default_rng(11)
+    qmax = (1 << bits) - 1
+    x = (rng.standard_normal((4000, 32)) * rng.choice([1e-6, 1e-3, 1.0, 300.0], (4000, 1))).astype(np.float32)
+    codes, sc, zr = O.quantize_groups(x, bits)
+    scf = sc.astype(np.float64); zf = zr.astype(np.float64)
+    xd = x.astype(np.float64)
+    assert (zf <= xd.min(1)).all()
+    assert (zf + qmax * scf >= xd.max(1)).all()
+    stepped = zr != x.min(1).astype(np.float16)
+    assert stepped.sum() > 100                       # the case is really exercised
+    deq = codes * scf[:, None] + zf[:, None]
+    assert (np.abs(deq - xd) <= scf[:, None] / 2 * (1 + 1e-6) + 1e-30).all()
+    # the scale is no larger than needed: one fp16 step less would leave the maximum outside the grid
+    prev = np.nextafter(sc, np.float16(-np.inf)).astype(np.float64)
+    tight = (sc > 0) & np.isfinite(prev)
+    r32 = (x.max(1) - zr.astype(np.float32)).astype(np.float32)
+    assert ((prev * qmax).astype(np.float32)[tight] <= r32[tight] * (1 + 2e-3)).all()
+
+
+def test_budget_counts_worked_examples():
+    """Alg. 1 "Assign origin budget" by hand: floors, the window on top, the cap at b."""
+    # N = 128, W = 32, alpha = 0.75: b = floor(0.75 * 96) = 72
+    assert O.budget_counts(0.3, 128, 32) == (28, 44, 72)        # floor(28.8) = 28
+    assert O.budget_counts(0.99, 128, 32) == (72, 0, 72)        # floor(95.04) = 95, capped at b
+    assert O.budget_counts(0.7499, 128, 32) == (71, 1, 72)      # floor(71.99)
+    # N = 2048: b = floor(0.75 * 2016) = 1512; rho = 1/3 -> floor(672.0) = 672
+    assert O.budget_counts(1.0 / 3.0, 2048, 32)[0] in (671, 672)
+    assert O.budget_counts(0.3337, 2048, 32) == (672, 840, 1512)   # floor(672.74)
+    # alpha = 0.5, N = 40, W = 8: b = 16; rho = 0.2 -> floor(6.4) = 6
+    assert O.budget_counts(0.2, 40, 8, alpha=0.5) == (6, 10, 16)
+
+
+def _round_to_fp32(x):
+    """Nearest IEEE binary32 value of the rational x, ties to even, as a Fraction (normal range only)."""
+    from fractions import Fraction
+    if x == 0:
+        return Fraction(0)
+    sgn = -1 if x < 0 else 1
+    x = abs(Fraction(x))
+    e = 0
+    while x >= Fraction(2) ** (e + 1):
+        e += 1
+    while x < Fraction(2) ** e:
+        e -= 1
+    assert -126 <= e <= 127
+    ulp = Fraction(2) ** (e - 23)
+    q, r = divmod(x, ulp)
+    if r * 2 > ulp or (r * 2 == ulp and q % 2 == 1):
+        q += 1
+    return sgn * q * ulp
+
+
+def test_hh_score_fp32_mode_rounds_once_per_operation_in_the_stated_order():
+    """exact32: div, div, mul, sub, max, mul, add, each rounded to binary32 (the precision in which selection
+    keys are built).  The expected bits come from exact rational arithmetic with an explicit rounding step."""
+    from fractions import Fraction as Fr
+    rng = np.random.default_rng(12)
+    s1 = rng.random(200).astype(np.float32) * np.float32(0.3)
+    s2 = (rng.random(200).astype(np.float32) * np.float32(0.01)).astype(np.float32)
+    n = rng.integers(1, 5000, 200) * 4
+    gamma = np.float32(263.81)
+    got = O.hh_score(s1, s2, n, gamma=263.81, exact32=True)
+    assert got.dtype == np.float32
+    R = _round_to_fp32
+    for j in range(200):
+        a, b2, nn = Fr(float(s1[j])), Fr(float(s2[j])), Fr(int(n[j]))
+        mu = R(a / nn); ex2 = R(b2 / nn)
+        var = max(R(ex2 - R(mu * mu)), Fr(0))
+        want = R(mu + R(Fr(float(gamma)) * var))
+        assert Fr(float(got[j])) == want, j
 
 
 def test_pack_unpack_layout():

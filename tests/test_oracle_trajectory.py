@@ -126,6 +126,12 @@ def test_invariants_on_c1(rho, bits):
             for pj in qs:                       # stored codes reproduce the value attention sees
                 e = u.q[pj]; j = int(np.nonzero(u.pos == pj)[0][0])
                 assert np.array_equal(u.kv[j, 0], O.dequantize_row(e["k_codes"], e["k_scale"], e["k_zero"]))
+                assert np.array_equal(u.kv[j, 1], O.dequantize_row(e["v_codes"], e["v_scale"], e["v_zero"]))
+                # both rows went through the quantiser of the bf16 row (K and V alike)
+                for r, nm in ((0, "k"), (1, "v")):
+                    c, sc, zr = O.quantize_row(u.raw[j, r], bits)
+                    assert np.array_equal(c, e[nm + "_codes"]) and np.array_equal(sc, e[nm + "_scale"])
+                    assert np.array_equal(zr, e[nm + "_zero"])
         if t == -1:
             assert all(len(u.pos) == b + W for u in cache.units)
     assert cache.n_tailors == 1 + (wl.decode_steps // (N - b - W))
@@ -145,3 +151,24 @@ def test_lockstep_override_is_used():
         keep = set(order[:b]) | set(range(T - 4, T))
         assert set(u.pos.tolist()) == keep
         assert set(u.pos[u.state == O.STATE_O].tolist()) == set(order[:n_o]) | set(range(T - 4, T))
+
+
+@pytest.mark.parametrize("delta", [-1, 0, 1])
+def test_prompt_that_exactly_fills_the_cache(delta):
+    """T = N - 1: the prompt fits and nothing is removed until the first decode step fills the cache; T = N and
+    T = N + 1: the first tailor runs at commit, so that the first append has room (Sec. IV-F: the tailor is
+    triggered when the cache reaches the limit)."""
+    wl = synth.C1.scaled(name="exact", prefill=128 + delta, budget_frac=1.0, decode_steps=2)
+    N, W = 128, wl.window
+    k, v, a, s1, s2, scale = _prefill(wl)
+    cache = O.SequenceCacheOracle(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, N)
+    cache.commit(k, v, s1, s2, rho=0.5)
+    b = O.budget_counts(0.5, N, W)[2]
+    if delta < 0:
+        assert cache.n_tailors == 0 and all(len(u.pos) == N - 1 for u in cache.units)
+    else:
+        assert cache.n_tailors == 1 and all(len(u.pos) == b + W for u in cache.units)
+    q, kn, vn = _decode(wl)
+    _, fired = cache.decode_step(q[0], kn[0], vn[0], scale)
+    assert fired == (delta < 0)                 # N - 1 + 1 = N live tokens: now it is full
+    assert all(len(u.pos) <= N - 1 for u in cache.units)
