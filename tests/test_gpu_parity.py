@@ -180,3 +180,14 @@ def test_many_splits_per_unit(hq, hkv):
                          budget_frac=1.1, decode_steps=10)
     sb = _run(wl, check_every=3)
     assert sb.oracles[(0, 0)].n_tailors == 0
+
+
+@pytest.mark.parametrize("delta", [-1, 0, 1])
+def test_prompt_that_exactly_fills_the_cache(delta):
+    """T = N - 1 (no tailor at commit, the first decode step fills the cache), T = N and T = N + 1 (tailor at
+    commit): the first append always has room."""
+    T = 128 + delta
+    wl = synth.C1.scaled(name=f"exact{delta:+d}", prefill=T, budget_frac=128.5 / T, decode_steps=30)
+    assert wl.capacity == 128
+    sb = _run(wl, check_every=1)
+    assert sb.oracles[(0, 0)].n_tailors == 2
