@@ -694,24 +694,26 @@ int arkv_debug_stream_read(void* buf, uint64_t buf_bytes, uint64_t bytes_per_lau
     return ARKV_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   unsigned* sink = nullptr;
-  HIP_TRY(hipMalloc(reinterpret_cast<void**>(&sink), 2048 * sizeof(unsigned)));
-  hipEvent_t e0, e1;
-  HIP_TRY(hipEventCreate(&e0));
-  HIP_TRY(hipEventCreate(&e1));
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&sink), 2048 * sizeof(unsigned));
+  if (e == hipSuccess) e = hipEventCreate(&e0);
+  if (e == hipSuccess) e = hipEventCreate(&e1);
   const uint64_t windows = buf_bytes / bytes_per_launch;
-  for (int pass = 0; pass < 2; ++pass) {          // pass 0 warms up
-    if (pass == 1) HIP_TRY(hipEventRecord(e0, st));
+  for (int pass = 0; pass < 2 && e == hipSuccess; ++pass) {          // pass 0 warms up
+    if (pass == 1) e = hipEventRecord(e0, st);
     const int n = pass == 0 ? std::min(launches, 8) : launches;
-    for (int i = 0; i < n; ++i)
-      HIP_TRY(launch_stream_read(buf, (size_t)((uint64_t)i % windows) * bytes_per_launch, (size_t)bytes_per_launch, pattern, sink, st));
-    if (pass == 1) HIP_TRY(hipEventRecord(e1, st));
+    for (int i = 0; i < n && e == hipSuccess; ++i)
+      e = launch_stream_read(buf, (size_t)((uint64_t)i % windows) * bytes_per_launch, (size_t)bytes_per_launch, pattern, sink, st);
+    if (pass == 1 && e == hipSuccess) e = hipEventRecord(e1, st);
   }
-  HIP_TRY(hipEventSynchronize(e1));
+  if (e == hipSuccess) e = hipEventSynchronize(e1);
   float ms = 0.f;
-  HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
-  *avg_us = ms * 1000.0f / (float)launches;
-  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); (void)hipFree(sink);
-  return ARKV_OK;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  if (e == hipSuccess) *avg_us = ms * 1000.0f / (float)launches;
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (sink) (void)hipFree(sink);
+  return e == hipSuccess ? ARKV_OK : hip_fail(e, "arkv_debug_stream_read");
 }
 
 const char* arkv_strerror(int code) {
