@@ -557,7 +557,11 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
 
   __shared__ __align__(16) float pbuf[4][16][G < 4 ? 4 : G];
   __shared__ __align__(16) float pspare[4][16][4];
-  __shared__ float sm_a[4][G][D];
+  // accumulators of the 4 waves; where LDS allows (kParkRows) every value-row group of a wave parks its own share
+  // and the readers add them up, which replaces 8 * G cross-lane exchanges per reduction stage
+  constexpr bool kParkRows = R * G * D <= 2048;
+  constexpr int RP = kParkRows ? R : 1;
+  __shared__ __align__(16) float sm_a[4][RP][G][D];
   __shared__ float sm_m[4][G], sm_l[4][G];
   __shared__ int sm_last;
   __shared__ PendingLds<D, G> sm_pend;   // only touched when FOLD
@@ -819,17 +823,26 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   // ---------------- reduce within the wave, across the 4 waves ----------------
 #pragma unroll
   for (int i = 0; i < HPL; ++i) lsum[i] = row_sum16(lsum[i]);
+  if constexpr (kParkRows) {
 #pragma unroll
-  for (int stride = LPR; stride < 64; stride <<= 1)
+    for (int h = 0; h < G; ++h) {
+      float4* dst = reinterpret_cast<float4*>(&sm_a[w][vrow][h][sub * 8]);
+      dst[0] = make_float4(acc[h][0], acc[h][1], acc[h][2], acc[h][3]);
+      dst[1] = make_float4(acc[h][4], acc[h][5], acc[h][6], acc[h][7]);
+    }
+  } else {
 #pragma unroll
-    for (int h = 0; h < G; ++h)
+    for (int stride = LPR; stride < 64; stride <<= 1)
 #pragma unroll
-      for (int c = 0; c < 8; ++c) acc[h][c] += __shfl_xor(acc[h][c], stride);
-  if (vrow == 0) {
+      for (int h = 0; h < G; ++h)
 #pragma unroll
-    for (int h = 0; h < G; ++h)
+        for (int c = 0; c < 8; ++c) acc[h][c] += __shfl_xor(acc[h][c], stride);
+    if (vrow == 0) {
 #pragma unroll
-      for (int c = 0; c < 8; ++c) sm_a[w][h][sub * 8 + c] = acc[h][c];
+      for (int h = 0; h < G; ++h)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) sm_a[w][0][h][sub * 8 + c] = acc[h][c];
+    }
   }
   if (tok == 0 && active) {
 #pragma unroll
@@ -848,8 +861,16 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const float cw_ = fexp2(sm_m[i][h] - M);
-      a0 = fmaf(sm_a[i][h][c], cw_, a0);
-      a1 = fmaf(sm_a[i][h][c + 1], cw_, a1);
+      // the wave's value-row groups, added pairwise in the order a butterfly over the lanes would take
+      float2 t[RP];
+#pragma unroll
+      for (int v = 0; v < RP; ++v) t[v] = *reinterpret_cast<const float2*>(&sm_a[i][v][h][c]);
+#pragma unroll
+      for (int st = 1; st < RP; st <<= 1)
+#pragma unroll
+        for (int v = 0; v < RP; v += 2 * st) { t[v].x += t[v + st].x; t[v].y += t[v + st].y; }
+      a0 = fmaf(t[0].x, cw_, a0);
+      a1 = fmaf(t[0].y, cw_, a1);
       l = fmaf(sm_l[i][h], cw_, l);
     }
     st_dev2(part + h * (D + 2) + c, a0, a1);
