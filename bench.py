@@ -515,7 +515,7 @@ def main():
                   "amortised_us_per_step": round((tailor_ms * 1e3 / nl - call_us) / max(cadence, 1), 3)}
 
     result = {
-        "metric": "decode steps/sec per layer-batch at 32K ctx", "value": round(value, 1), "unit": "steps/s",
+        "metric": "decode steps/sec per layer-batch at 32K ctx; achieved HBM GB/s vs peak", "value": round(value, 1), "unit": "steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32 accumulate over bf16 / %s rows" % ("fp8" if wl.bits == 8 else "int%d" % wl.bits), "data": "synthetic",
