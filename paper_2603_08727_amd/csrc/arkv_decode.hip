@@ -761,7 +761,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
       P.opos[(size_t)gu * P.capO + cO] = L.position;
       P.qscale[(size_t)L.slot * (P.fin_stride / G) + gu] = scale2;
     }
-    // this step's query, for the next step's score update
+    // this step's query, for the later launch that adds this step to the scores
     if (tok < G) {
       uint16_t* dq = P.qprev + ((size_t)L.slot * P.fin_stride + (size_t)gu * G + tok) * D + 8 * blk;
 #pragma unroll
