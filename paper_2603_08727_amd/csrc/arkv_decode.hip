@@ -308,7 +308,7 @@ __device__ __forceinline__ float2 prob_moments(const float (&x)[HPL], const floa
 // same bits as in the step itself), turned into probabilities and their moments added in step order.
 template <int D, int G>
 struct PendingLds {
-  uint16_t q[kRing - 1][G][D];       // query rows of waiting step j (0 = oldest)
+  uint16_t q[kRing][G][D];           // query rows of waiting step j (0 = oldest); row block kRing - 1 is all zero
   float2 fin[kRing - 1][G];          // its final (max, 1/sum) per head
   float scale[kRing - 1];            // its softmax scale * log2(e)
 };
@@ -323,6 +323,8 @@ __device__ __forceinline__ void stage_pending(const Pools& P, int gu, int n, int
     reinterpret_cast<uint4*>(&sm.q[j][0][0])[c] =
         reinterpret_cast<const uint4*>(P.qprev + ((size_t)sl * P.fin_stride + (size_t)gu * G) * D)[c];
   }
+  for (int i = tid; i < G * D / 8; i += nthreads)       // operand rows no waiting step fills read zeros from here
+    reinterpret_cast<uint4*>(&sm.q[kRing - 1][0][0])[i] = make_uint4(0, 0, 0, 0);
   for (int i = tid; i < n * G; i += nthreads) {
     const int j = i / G, h = i % G;
     const int sl = (slot - n + j + kRing) % kRing;
@@ -350,12 +352,9 @@ __device__ __forceinline__ float2 fold_pending(const PendingLds<D, G>& sm, int n
     {
       const int rstep = j0 + tok / RPS, rhead = tok % RPS;
       const bool rvalid = rhead < G && rstep < n;
-      const uint16_t* src = &sm.q[rvalid ? rstep : 0][rvalid ? rhead : 0][8 * blk];
+      const uint16_t* src = &sm.q[rvalid ? rstep : kRing - 1][rvalid ? rhead : 0][8 * blk];
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        const uint4 v = *reinterpret_cast<const uint4*>(src + 32 * kk);
-        qop[kk] = rvalid ? v : make_uint4(0, 0, 0, 0);
-      }
+      for (int kk = 0; kk < KK; ++kk) qop[kk] = *reinterpret_cast<const uint4*>(src + 32 * kk);
     }
     float x[HPL], pm[HPL], pinv[HPL];
     dots(qop, x);
