@@ -90,6 +90,14 @@ int arkv_cache_reset(arkv_cache* cache, int32_t layer);
 int arkv_prefill_stats(arkv_cache* cache, int32_t layer, const void* q_win, const void* k, int32_t T,
                        float softmax_scale, float* stats, void* hip_stream);
 
+/* The same scorer for callers whose own attention kernel already produced the softmax normalisers of the window
+ * rows: lse DEVICE float [B][H_q][W] = natural logarithm of the sum over the visible keys j <= T-W+i of
+ * exp(softmax_scale * q.k), for window query i of every head (the per-row log-sum-exp that attention kernels
+ * return).  The scorer then reads the keys once instead of twice (Sec. IV-C: eq. 2's rows are rows of the
+ * prompt's attention).  Everything else as arkv_prefill_stats. */
+int arkv_prefill_stats_lse(arkv_cache* cache, int32_t layer, const void* q_win, const void* k, int32_t T,
+                           float softmax_scale, const float* lse, float* stats, void* hip_stream);
+
 /* Causal self-attention of prompt queries with the scorer fused (Sec. IV-C: eq. 2's rows are the last W
  * rows of the prompt's causal attention).  ASYNC on hip_stream.
  * q [B][H_q][T_q][d] DEVICE bf16: the queries of positions [T - T_q, T); k, v [B][H_kv][T][d] DEVICE bf16: keys

@@ -84,6 +84,24 @@ def window_attention(q_win, k, scale, group):
     return a
 
 
+def window_lse(q_win, k, scale, group):
+    """Natural-log normaliser of every window row of eq. 2: ln sum_{j <= T-W+i} exp(scale q_i.k_j), the
+    per-row log-sum-exp that attention kernels return next to their output.  q_win [Hq, W, d], k [Hkv, T, d];
+    returns [Hq, W] fp64."""
+    q_win = np.asarray(q_win, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    Hq, W, _ = q_win.shape
+    T = k.shape[1]
+    out = np.empty((Hq, W), dtype=np.float64)
+    for h in range(Hq):
+        logits = scale * (q_win[h] @ k[h // group].T)
+        for i in range(W):
+            row = logits[i, :T - W + i + 1]
+            m = row.max()
+            out[h, i] = m + np.log(np.exp(row - m).sum())
+    return out
+
+
 def layer_statistics(a, W):
     """Entropy, variance, kurtosis of the aggregated key distribution (eqs. 3-5).
 

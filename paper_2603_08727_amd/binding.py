@@ -19,7 +19,7 @@ STATE_ORIGINAL, STATE_QUANTIZED, STATE_EVICTED = 0, 1, 2
 
 EXPORTED = [
     "arkv_config_default", "arkv_cache_create", "arkv_cache_destroy", "arkv_cache_reset",
-    "arkv_prefill_stats", "arkv_prefill_attention", "arkv_oq_ratio", "arkv_budget_counts", "arkv_prefill_commit",
+    "arkv_prefill_stats", "arkv_prefill_stats_lse", "arkv_prefill_attention", "arkv_oq_ratio", "arkv_budget_counts", "arkv_prefill_commit",
     "arkv_decode_step", "arkv_decode_step_layers", "arkv_cache_counters", "arkv_cache_export",
     "arkv_debug_last_tailor_scores", "arkv_debug_last_out_f32", "arkv_cache_progress",
     "arkv_debug_time_attend", "arkv_debug_attend_time", "arkv_debug_stream_read", "arkv_debug_split_range",
@@ -67,6 +67,7 @@ def load():
         "arkv_cache_destroy": (C.c_int, [vp]),
         "arkv_cache_reset": (C.c_int, [vp, i32]),
         "arkv_prefill_stats": (C.c_int, [vp, i32, vp, vp, i32, f32, vp, vp]),
+        "arkv_prefill_stats_lse": (C.c_int, [vp, i32, vp, vp, i32, f32, vp, vp, vp]),
         "arkv_oq_ratio": (C.c_int, [vp, i32, i32, vp, vp]),
         "arkv_budget_counts": (C.c_int, [P(arkv_config), f32, P(i32), P(i32), P(i32)]),
         "arkv_prefill_commit": (C.c_int, [vp, i32, vp, vp, i32, vp, vp]),
@@ -152,6 +153,14 @@ def arkv_prefill_stats(cache, layer, q_win, k, T, softmax_scale, stats):
     _check(load().arkv_prefill_stats(cache, layer, _dev_ptr(q_win, torch.bfloat16), _dev_ptr(k, torch.bfloat16),
                                      T, softmax_scale, _dev_ptr(stats, torch.float32), _stream()),
            "arkv_prefill_stats")
+
+
+def arkv_prefill_stats_lse(cache, layer, q_win, k, T, softmax_scale, lse, stats):
+    import torch
+    _check(load().arkv_prefill_stats_lse(cache, layer, _dev_ptr(q_win, torch.bfloat16), _dev_ptr(k, torch.bfloat16),
+                                         T, softmax_scale, _dev_ptr(lse, torch.float32),
+                                         _dev_ptr(stats, torch.float32), _stream()),
+           "arkv_prefill_stats_lse")
 
 
 def arkv_prefill_attention(cache, layer, q, k, v, T_q, T, softmax_scale, out, stats=None):

@@ -142,5 +142,6 @@ struct AttnLaunch {
 };
 hipError_t launch_prefill_attn(const AttnLaunch& a, hipStream_t s);
 hipError_t launch_prefill_stats(const PrefillLaunch& a, float* rowc /*[U][MP] scratch*/, hipStream_t s);
+hipError_t launch_lse_to_rowc(const float* lse /*[U][G][W]*/, float* rowc /*[U][MP]*/, int U, int G, int W, int MP, hipStream_t s);
 
 }  // namespace arkv

@@ -291,9 +291,11 @@ int arkv_cache_reset(arkv_cache* c, int32_t layer) {
 
 // Scorer of one layer (eqs. 2-5 + the window sums kept for the commit).  q_win: window query rows, heads
 // q_head_stride elements apart.  attn != nullptr: run the causal attention pass first; it leaves the window
-// rows' softmax constants in the scratch, so the scorer's own first pass over the keys is skipped.
+// rows' softmax constants in the scratch, so the scorer's own first pass over the keys is skipped.  lse != nullptr:
+// the caller's attention produced those constants.
 static int run_scorer(arkv_cache* c, int32_t layer, const uint16_t* q_win, size_t q_head_stride, const uint16_t* k,
-                      int32_t T, float softmax_scale, float* stats, hipStream_t s, AttnLaunch* attn) {
+                      int32_t T, float softmax_scale, float* stats, hipStream_t s, AttnLaunch* attn,
+                      const float* lse = nullptr) {
   LayerState& ls = c->layers[(size_t)layer];
   const int U = c->U, G = c->P.G, W = c->cfg.window;
   int rc;
@@ -312,10 +314,11 @@ static int run_scorer(arkv_cache* c, int32_t layer, const uint16_t* q_win, size_
     attn->rowc = c->rowc; attn->MP = MP; attn->W = W;
     HIP_TRY(launch_prefill_attn(*attn, s));
   }
+  if (lse) HIP_TRY(launch_lse_to_rowc(lse, c->rowc, U, G, W, MP, s));
   PrefillLaunch a;
   a.q_win = q_win;
   a.q_head_stride = q_head_stride;
-  a.have_rowc = attn ? 1 : 0;
+  a.have_rowc = (attn || lse) ? 1 : 0;
   a.k = k;
   a.pre = ls.pre; a.rowstat = c->rowstat; a.stats = stats; a.stat_ticket = c->stat_ticket;
   a.B = c->cfg.batch; a.Hkv = c->cfg.n_kv_heads; a.G = G; a.W = W; a.D = c->P.D; a.T = T;
@@ -335,6 +338,16 @@ int arkv_prefill_stats(arkv_cache* c, int32_t layer, const void* q_win, const vo
   return run_scorer(c, layer, static_cast<const uint16_t*>(q_win), (size_t)c->cfg.window * c->P.D,
                     static_cast<const uint16_t*>(k), T, softmax_scale, stats, static_cast<hipStream_t>(hip_stream),
                     nullptr);
+}
+
+int arkv_prefill_stats_lse(arkv_cache* c, int32_t layer, const void* q_win, const void* k, int32_t T,
+                           float softmax_scale, const float* lse, float* stats, void* hip_stream) {
+  if (!c || !q_win || !k || !lse || !stats || layer < 0 || layer >= c->L) return ARKV_EINVAL;
+  if (T <= c->cfg.window || !(softmax_scale > 0.0f)) return ARKV_EINVAL;
+  if (c->layers[(size_t)layer].committed) return ARKV_ESTATE;
+  return run_scorer(c, layer, static_cast<const uint16_t*>(q_win), (size_t)c->cfg.window * c->P.D,
+                    static_cast<const uint16_t*>(k), T, softmax_scale, stats, static_cast<hipStream_t>(hip_stream),
+                    nullptr, lse);
 }
 
 int arkv_prefill_attention(arkv_cache* c, int32_t layer, const void* q, const void* k, const void* v, int32_t T_q,

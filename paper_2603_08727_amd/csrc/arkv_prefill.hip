@@ -338,6 +338,22 @@ static hipError_t launch_prefill_t(const PrefillLaunch& a, float* rowc, hipStrea
   return hipGetLastError();
 }
 
+// Row constants from a caller's log-sum-exp (natural log of the sum over visible keys of exp(scale q.k), what
+// attention kernels commonly return per query row): the same quantity in base-2 units, in the scratch layout
+// [U][MP] with row r = (head inside the group) * W + (window query).
+__global__ __launch_bounds__(256) void k_lse_to_rowc(const float* __restrict__ lse, float* __restrict__ rowc, int U, int G,
+                                                     int W, int MP) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= U * MP) return;
+  const int u = i / MP, r = i % MP;
+  rowc[i] = r < G * W ? lse[((size_t)u * G + r / W) * W + r % W] * 1.4426950408889634f : 0.f;
+}
+
+hipError_t launch_lse_to_rowc(const float* lse, float* rowc, int U, int G, int W, int MP, hipStream_t s) {
+  hipLaunchKernelGGL(k_lse_to_rowc, dim3((U * MP + 255) / 256), dim3(256), 0, s, lse, rowc, U, G, W, MP);
+  return hipGetLastError();
+}
+
 // rowc: scratch [U][MP] floats followed by U*n_chunks + 3*B*ceil((T-W)/512) doubles for the statistics partials
 hipError_t launch_prefill_stats(const PrefillLaunch& a, float* rowc, hipStream_t s) {
   const int M = a.G * a.W;

@@ -141,8 +141,16 @@ def test_prefill_attention_argument_errors():
             with pytest.raises(A.ArkvError) as e:
                 A.arkv_prefill_attention(c, layer, q[:, :, :max(Tq, 1)].contiguous(), k, v, Tq, Tk, scale, out, st)
             assert e.value.code == A.EINVAL, args
+        lse = torch.zeros((wl.batch, wl.n_q_heads, W), dtype=torch.float32, device="cuda")
+        for layer, Tk, scale in [(3, T, 0.1), (0, W, 0.1), (0, T, -1.0)]:   # the log-sum-exp variant checks the same
+            with pytest.raises(A.ArkvError) as e:
+                A.arkv_prefill_stats_lse(c, layer, qw, k, Tk, scale, lse, stats)
+            assert e.value.code == A.EINVAL
         A.arkv_prefill_attention(c, 0, q, k, v, T, T, 0.1, out, stats)      # scores the layer
         A.arkv_prefill_commit(c, 0, k, v, T, np.full(wl.batch, 0.5, np.float32))
+        with pytest.raises(A.ArkvError) as e:
+            A.arkv_prefill_stats_lse(c, 0, qw, k, T, 0.1, lse, stats)
+        assert e.value.code == A.ESTATE
         with pytest.raises(A.ArkvError) as e:                               # scoring a committed layer again
             A.arkv_prefill_attention(c, 0, q, k, v, T, T, 0.1, out, stats)
         assert e.value.code == A.ESTATE

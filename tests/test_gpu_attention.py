@@ -249,3 +249,40 @@ def test_fused_scorer_on_the_last_chunk_of_a_chunked_prompt():
         assert A.arkv_cache_progress(cache, 0)[0] == 1
     finally:
         A.arkv_cache_destroy(cache)
+
+
+@pytest.mark.parametrize("hq,hkv,d,T", [(8, 2, 64, 700), (8, 1, 128, 333), (4, 4, 128, 1500)])
+def test_scorer_with_the_callers_log_sum_exp(hq, hkv, d, T):
+    """arkv_prefill_stats_lse: the window rows' normalisers come from the caller (here: the oracle's, rounded to
+    fp32), the scorer reads the keys once.  Statistics against the oracle; the per-token sums it leaves behind
+    against the stand-alone scorer's through the commit and a few decode steps."""
+    wl = synth.C1.scaled(name="lse", n_q_heads=hq, n_kv_heads=hkv, head_dim=d, prefill=T, batch=2, n_layers=2,
+                         decode_steps=12)
+
+    class WithLse(SideBySide):
+        def prefill(self):
+            super().prefill()                     # stand-alone scorer + oracle reference
+            A.arkv_cache_reset(self.cache, -1)
+            wl_ = self.wl
+            stats = torch.zeros((wl_.n_layers, wl_.batch, 3), dtype=torch.float32, device=self.dev)
+            for l in range(wl_.n_layers):
+                k, v, qw = self.inputs[l]
+                lse = np.stack([O.window_lse(synth.to_numpy_f32(qw[b]), synth.to_numpy_f32(k[b]), self.scales[l], wl_.group)
+                                for b in range(wl_.batch)])
+                lse_d = torch.tensor(lse, dtype=torch.float32, device=self.dev)
+                A.arkv_prefill_stats_lse(self.cache, l, qw.to(self.dev), k.to(self.dev), wl_.prefill, self.scales[l],
+                                         lse_d, stats[l])
+            torch.cuda.synchronize()
+            self.stats_gpu = stats.cpu().numpy()
+            err = np.abs(self.stats_gpu - self.stats_ref) / np.maximum(np.abs(self.stats_ref), 1e-300)
+            self.max_err["stats"] = float(err.max())
+            self.rho_gpu = A.arkv_oq_ratio(self.stats_gpu, wl_.tau)
+
+    sb = WithLse(wl)
+    try:
+        sb.prefill()
+        sb.commit()
+        sb.decode(check_every=4)
+        sb.assert_within_tol()
+    finally:
+        sb.close()

@@ -56,6 +56,25 @@ def test_window_attention_matches_library_sdpa():
 
 
 # ------------------------------------------------------------ eqs. 3-5 ----
+def test_window_lse_against_library_and_the_attention_it_normalises():
+    """exp(logit - lse) must be the attention of eq. 2 row by row, and the values must be torch.logsumexp's."""
+    rng = np.random.default_rng(21)
+    Hq, Hkv, W, T, d = 4, 2, 5, 19, 8
+    q = bf16(rng.standard_normal((Hq, W, d))); k = bf16(rng.standard_normal((Hkv, T, d)))
+    scale = 0.31
+    lse = O.window_lse(q, k, scale, Hq // Hkv)
+    a = O.window_attention(q, k, scale, Hq // Hkv)
+    for h in range(Hq):
+        lg = torch.tensor(scale * (q[h].astype(np.float64) @ k[h // 2].astype(np.float64).T))
+        for i in range(W):
+            n = T - W + i + 1
+            assert lse[h, i] == pytest.approx(float(torch.logsumexp(lg[i, :n], 0)), rel=1e-12)
+            assert np.allclose(np.exp(lg[i, :n].numpy() - lse[h, i]), a[h, i, :n], rtol=1e-12, atol=0)
+    # uniform logits: lse = ln(number of visible keys)
+    z = O.window_lse(np.zeros((1, 3, 4)), np.ones((1, 10, 4)), 1.0, 1)
+    assert np.allclose(z[0], np.log([8, 9, 10]))
+
+
 def test_statistics_uniform_closed_form():
     """q = 0 makes every visible row uniform: H = ln n, V = 0, Kurt := 0."""
     Hq, Hkv, W, T, d = 4, 2, 4, 36, 8
