@@ -139,3 +139,22 @@ def test_c3_natural_tailor_cadence_invariants():
                 assert (nq > 1000).all()
     finally:
         A.arkv_cache_destroy(cache)
+
+
+def test_c4_shape_whole_prompt_kept():
+    """The largest cache of the benchmark: configuration 4's 131072-token prompt with a limit above its length,
+    so every token stays Original (131K rows per unit, 32 splits of 4K rows each); three decode steps, every unit's
+    outputs, scores and rows against the oracle."""
+    T = synth.C4.prefill
+    wl = synth.C4.scaled(name="c4_full_cache", n_layers=1, budget_frac=(T + 64) / T, decode_steps=3)
+    sb = SideBySide(wl)
+    try:
+        sb.prefill()
+        sb.commit()
+        sb.decode(3, check_every=3)
+        print(wl.name, {k: f"{v:.2e}" for k, v in sb.max_err.items()}, flush=True)
+        sb.assert_within_tol()
+        for oc in sb.oracles.values():
+            assert oc.n_tailors == 0 and all(len(u.pos) == T + 3 for u in oc.units)
+    finally:
+        sb.close()
