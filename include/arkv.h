@@ -67,7 +67,7 @@ int arkv_config_default(arkv_config* cfg);
  * rows, per-slot position / score accumulators, the latest queries per unit) and returns the cache in *out.
  * Synchronous.  ARKV_EINVAL: null pointers, non-positive shapes, W >= N - 1, alpha outside (0,1],
  * gamma < 0, group_size != 32.  ARKV_EUNSUPPORTED: head_dim not in {64,128}, G not in {1,2,4,8}, G*W > 512,
- * quant_bits not in {2,4,8}. */
+ * quant_bits not in {2,4,8}, N > 2^20 - 64 tokens. */
 int arkv_cache_create(const arkv_config* cfg, arkv_cache** out);
 
 /* Frees everything.  Synchronises the device first.  NULL is accepted. */

@@ -86,6 +86,9 @@ static int validate(const arkv_config* c) {
   if (G != 1 && G != 2 && G != 4 && G != 8) return ARKV_EUNSUPPORTED;
   if (c->quant_bits != 2 && c->quant_bits != 4 && c->quant_bits != 8) return ARKV_EUNSUPPORTED;
   if (G * c->window > 512) return ARKV_EUNSUPPORTED;
+  // the decode kernel's split cut points are 32-bit products of a unit's weighted row count (<= 32 N) and the split
+  // count (<= 128)
+  if (c->capacity_tokens > (1 << 20) - 64) return ARKV_EUNSUPPORTED;
   return ARKV_OK;
 }
 

@@ -41,6 +41,7 @@ def _cfg(**kw):
     (dict(group_size=64), A.EINVAL), (dict(head_dim=96), A.EUNSUPPORTED),
     (dict(quant_bits=3), A.EUNSUPPORTED), (dict(n_q_heads=6, n_kv_heads=2), A.EUNSUPPORTED),
     (dict(tau=(1.0, 0.0, 1.0)), A.EINVAL), (dict(tailor_policy=2), A.EINVAL), (dict(budget_mode=3), A.EINVAL),
+    (dict(capacity_tokens=1 << 20), A.EUNSUPPORTED),
 ])
 def test_create_rejects_bad_config_without_gpu(kw, code):
     with pytest.raises(A.ArkvError) as e:
