@@ -15,6 +15,7 @@ in the same precision:
 What follows the paper, by passage:
   window_attention        Sec. IV-C, eq. 2   (observation window, causal softmax)
   causal_attention_rows   the causal prefill attention eq. 2 is a slice of (Sec. IV-C, first paragraph)
+  window_lse              the normalisers of eq. 2's rows (log of the softmax denominators)
   layer_statistics        Sec. IV-C, eqs. 3-5 (entropy, variance, kurtosis)
   prefill_accumulators    Sec. IV-E, eq. 9   (first samples of the per-token moments)
   oq_score / oq_ratio     Sec. IV-D, eqs. 6-7
