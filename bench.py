@@ -543,10 +543,11 @@ def main():
         "metric": "decode steps/sec per layer-batch at 32K ctx; achieved HBM GB/s vs peak", "value": round(value, 1), "unit": "steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32 accumulate over bf16 / %s rows" % ("fp8" if wl.bits == 8 else "int%d" % wl.bits), "data": "synthetic",
+        "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "n_layers": L, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": d, "context": T, "capacity_tokens": wl.capacity, "quant_bits": wl.bits,
-                   "window": W, "launch": "one arkv_decode_step per layer"},
+                   "window": W, "launch": "one arkv_decode_step per layer",
+                   "rows": "bf16 Original, %s Quantized; logits on bf16 MFMA, softmax and PV in f32" % ("fp8" if wl.bits == 8 else "int%d" % wl.bits)},
         "roofline": roofline,
         "step": {"us_per_layer_batch_call": round(call_us, 2),
                  "achieved_GBps_whole_call": round(step_bytes / (call_us * 1e-6) / 1e9, 1),
