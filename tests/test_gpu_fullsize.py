@@ -158,3 +158,21 @@ def test_c4_shape_whole_prompt_kept():
             assert oc.n_tailors == 0 and all(len(u.pos) == T + 3 for u in oc.units)
     finally:
         sb.close()
+
+
+@pytest.mark.parametrize("rho", [None, 0.5])
+def test_c3_full_size_tailor_at_every_step(rho):
+    """Config 3's shape under tailor_policy 1 (no slack: the cache stays full, one token leaves per unit and
+    step): commit plus four decode steps, each followed by a tailor over 8160 eligible tokens per unit."""
+    wl = synth.C3.scaled(name="c3_every_step", n_layers=1, decode_steps=4)
+    sb = SideBySide(wl, rho_override=rho, every_step=True)
+    try:
+        sb.prefill()
+        sb.commit()
+        sb.decode(4, check_every=1)
+        print(wl.name, rho, {k: f"{v:.2e}" for k, v in sb.max_err.items()}, flush=True)
+        sb.assert_within_tol()
+        for oc in sb.oracles.values():
+            assert oc.n_tailors == 5 and all(len(u.pos) == wl.capacity - 1 for u in oc.units)
+    finally:
+        sb.close()
