@@ -176,3 +176,25 @@ def test_c3_full_size_tailor_at_every_step(rho):
             assert oc.n_tailors == 5 and all(len(u.pos) == wl.capacity - 1 for u in oc.units)
     finally:
         sb.close()
+
+
+def test_c3_full_size_fp8_rows_byte_budget_decode_time_tailor():
+    """The paper's own Quantized format (fp8 codes, one scale per row) under the byte reading of the budget
+    (eq. 1, eq. 8), at config 3's size with a mixed cache: commit, the steps up to the first decode-time tailor
+    and a few more; live bytes stay within the limit on both sides."""
+    wl = synth.C3.scaled(name="c3_fp8_bytes", n_layers=1, alpha=0.99, bits=8)
+    sb = SideBySide(wl, rho_override=0.5, byte_budget=True)
+    try:
+        sb.prefill()
+        sb.commit()
+        steps = wl.capacity - int(wl.alpha * (wl.capacity - wl.window)) - wl.window + 6
+        sb.decode(steps, check_every=steps)
+        print(wl.name, steps, {k: f"{v:.2e}" for k, v in sb.max_err.items()}, flush=True)
+        sb.assert_within_tol()
+        for oc in sb.oracles.values():
+            assert oc.n_tailors == 2
+            for g in range(wl.n_kv_heads):
+                assert oc.counts(g)[1] > 1000
+                assert oc.live_bytes(g) <= wl.capacity * 4 * wl.head_dim
+    finally:
+        sb.close()
