@@ -191,3 +191,33 @@ def test_prompt_that_exactly_fills_the_cache(delta):
     assert wl.capacity == 128
     sb = _run(wl, check_every=1)
     assert sb.oracles[(0, 0)].n_tailors == 2
+
+
+@pytest.mark.parametrize("which", ["zero_queries", "identical_keys"])
+def test_uniform_attention_statistics(which):
+    """Closed form (eqs. 3-5): when every window row attends uniformly the aggregated key distribution is uniform,
+    the entropy is ln(T - W), the variance exactly 0 and the kurtosis 0 by the degenerate-case reading; with every
+    layer like that every OQ ratio is 1."""
+    import math
+    import torch
+    from paper_2603_08727_amd import binding as A
+    from helpers import make_cfg
+    wl = synth.C1.scaled(name="uniform", prefill=300, n_layers=2, batch=2)
+    cache = A.arkv_cache_create(make_cfg(wl))
+    try:
+        stats = torch.zeros((wl.n_layers, wl.batch, 3), dtype=torch.float32, device="cuda")
+        for l in range(wl.n_layers):
+            k, v, qw = synth.prefill_inputs(wl, l)
+            if which == "zero_queries":
+                qw = torch.zeros_like(qw)
+            else:
+                k = k[:, :, :1, :].expand_as(k).contiguous()
+            A.arkv_prefill_stats(cache, l, qw.cuda(), k.cuda(), wl.prefill, synth.softmax_scale(wl, l), stats[l])
+        torch.cuda.synchronize()
+        s = stats.cpu().numpy()
+        n = wl.prefill - wl.window
+        assert np.allclose(s[..., 0], math.log(n), rtol=1e-6)
+        assert (s[..., 1] == 0).all() and (s[..., 2] == 0).all()
+        assert (A.arkv_oq_ratio(s, wl.tau) == 1.0).all()
+    finally:
+        A.arkv_cache_destroy(cache)
