@@ -221,3 +221,31 @@ def test_uniform_attention_statistics(which):
         assert (A.arkv_oq_ratio(s, wl.tau) == 1.0).all()
     finally:
         A.arkv_cache_destroy(cache)
+
+
+def test_one_hot_attention_statistics():
+    """Closed form (eqs. 3-5): when every window row puts all its weight on one prompt key, the aggregated
+    distribution is one-hot: entropy 0, variance (n - 1) / n^2, kurtosis m4 / m2^2 with
+    m4 = ((1 - 1/n)^4 + (n - 1) / n^4) / n, n = T - W."""
+    import torch
+    from paper_2603_08727_amd import binding as A
+    from helpers import make_cfg
+    wl = synth.C1.scaled(name="one_hot", prefill=400, n_layers=1, batch=2)
+    cache = A.arkv_cache_create(make_cfg(wl))
+    try:
+        k, v, qw = synth.prefill_inputs(wl, 0)
+        k = torch.zeros_like(k); qw = torch.zeros_like(qw)
+        qw[..., 0] = 64.0                                    # logit 64 * 64 / sqrt(d) on the chosen key, 0 elsewhere
+        k[0, :, 137, 0] = 64.0                               # sequence 0: key 137; sequence 1: key 5
+        k[1, :, 5, 0] = 64.0
+        stats = torch.zeros((wl.batch, 3), dtype=torch.float32, device="cuda")
+        A.arkv_prefill_stats(cache, 0, qw.cuda(), k.cuda(), wl.prefill, synth.softmax_scale(wl, 0), stats)
+        torch.cuda.synchronize()
+        s = stats.cpu().numpy().astype(np.float64)
+        n = wl.prefill - wl.window
+        m2 = (n - 1) / n ** 2
+        m4 = ((1 - 1 / n) ** 4 + (n - 1) / n ** 4) / n
+        assert (s[:, 0] == 0).all()
+        assert np.allclose(s[:, 1], m2, rtol=1e-6) and np.allclose(s[:, 2], m4 / m2 ** 2, rtol=1e-6)
+    finally:
+        A.arkv_cache_destroy(cache)
