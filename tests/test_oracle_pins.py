@@ -317,6 +317,25 @@ def test_budget_counts_worked_examples():
     assert O.budget_counts(0.2, 40, 8, alpha=0.5) == (6, 10, 16)
 
 
+@pytest.mark.parametrize("N,W", [(128, 32), (40, 8), (2048, 32), (8192, 32), (10, 3)])
+def test_budget_counts_every_step_closed_form(N, W):
+    """Sec. IV-F first sentence read literally (a tailor at each step, no slack): the cache is kept full, so of
+    the N - W tokens outside the window all but one survive, whatever the slack factor says; the Original share
+    is Alg. 1's floor(rho (N - W)) capped at that."""
+    for alpha in (0.25, 0.75, 1.0):
+        for rho in (0.0, 0.2, 0.5, 0.9, 1.0):
+            n_o, n_q, b = O.budget_counts(rho, N, W, alpha=alpha, every_step=True)
+            assert b == N - W - 1                                   # exactly one slot is freed
+            assert n_o == min(math.floor(rho * (N - W)), N - W - 1)
+            assert n_q == b - n_o and n_o + n_q + W == N - 1
+    # worked by hand: N = 128, W = 32: b = 95; rho = 0.3 -> floor(28.8) = 28 Original, 67 Quantized
+    assert O.budget_counts(0.3, 128, 32, every_step=True) == (28, 67, 95)
+    assert O.budget_counts(1.0, 128, 32, every_step=True) == (95, 0, 95)
+    assert O.budget_counts(0.0, 40, 8, alpha=0.5, every_step=True) == (0, 31, 31)
+    # the slack reading differs from it for every alpha < 1
+    assert O.budget_counts(0.3, 128, 32, every_step=False)[2] == 72
+
+
 def _round_to_fp32(x):
     """Nearest IEEE binary32 value of the rational x, ties to even, as a Fraction (normal range only)."""
     from fractions import Fraction

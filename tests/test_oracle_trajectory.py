@@ -172,3 +172,55 @@ def test_prompt_that_exactly_fills_the_cache(delta):
     _, fired = cache.decode_step(q[0], kn[0], vn[0], scale)
     assert fired == (delta < 0)                 # N - 1 + 1 = N live tokens: now it is full
     assert all(len(u.pos) <= N - 1 for u in cache.units)
+
+
+@pytest.mark.parametrize("rho,bits,window", [(0.4, 4, 32), (0.0, 2, 8), (1.0, 4, 16), (0.6, 8, 32)])
+def test_every_step_reading_trajectory(rho, bits, window):
+    """Sec. IV-F first sentence read literally ("at each step"): no slack, the cache stays full.  What that
+    reading fixes without running anything: after the commit and after every decode step a kv-head holds N - 1
+    tokens; every step runs one tailor (n_tailors = 1 + steps); each tailor of a decode step evicts exactly one
+    token per kv-head, and that token is the one a full sort of the eligible tokens by (score descending,
+    position ascending) puts last; the window stays Original; eq. 1 holds."""
+    d = 128 if bits == 8 else 64
+    wl = synth.C1.scaled(name="every", prefill=200, budget_frac=0.3, decode_steps=20, window=window, bits=bits,
+                         head_dim=d)
+    N, W = wl.capacity, wl.window
+    k, v, a, s1, s2, scale = _prefill(wl)
+    q, kn, vn = _decode(wl)
+    cache = O.SequenceCacheOracle(wl.n_q_heads, wl.n_kv_heads, d, N, W=W, bits=bits, every_step=True)
+    cache.commit(k, v, s1, s2, rho=rho)
+    assert cache.b == N - W - 1 and cache.n_o == min(int(np.floor(rho * (N - W))), N - W - 1)
+    assert cache.n_tailors == 1 and all(len(u.pos) == N - 1 for u in cache.units)
+    for t in range(wl.decode_steps):
+        before = [set(u.pos.tolist()) for u in cache.units]
+        # scores the tailor of this step will rank on, replayed by hand from the cache's own rows
+        P = cache.P + 1
+        last = []
+        for g, u in enumerate(cache.units):
+            keys = np.concatenate([u.kv[:, 0], kn[t][g][None].astype(np.float64)])
+            poss = np.append(u.pos, P)
+            c1 = np.append(u.s1, 0.0); c2 = np.append(u.s2, 0.0)
+            for hh in range(wl.group):
+                lg = scale * keys @ q[t][g * wl.group + hh].astype(np.float64)
+                e = np.exp(lg - lg.max()); p = e / e.sum()
+                c1 += p; c2 += p * p
+            n = wl.group * (P - np.maximum(poss, wl.prefill - W) + 1)
+            mu = c1 / n
+            S = mu + cache.gamma * np.maximum(c2 / n - mu * mu, 0.0)
+            el = poss < P + 1 - W
+            ranked = sorted(zip(-S[el], poss[el]))                  # score descending, position ascending
+            last.append(int(ranked[-1][1]))
+        _, fired = cache.decode_step(q[t], kn[t], vn[t], scale)
+        assert fired and cache.n_tailors == 2 + t
+        for g, u in enumerate(cache.units):
+            now = set(u.pos.tolist())
+            assert len(u.pos) == N - 1
+            gone = (before[g] | {P}) - now
+            assert gone == {last[g]}                                # one eviction, the lowest-ranked eligible token
+            win = u.pos > cache.P - W
+            assert win.sum() == W and (u.state[win] == O.STATE_O).all()
+            no, nq = cache.counts(g)
+            assert no + nq == N - 1 and no <= cache.n_o + W
+            if rho == 1.0:
+                assert nq == 0
+            assert cache.live_bytes(g) <= N * 4 * d
