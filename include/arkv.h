@@ -67,7 +67,8 @@ int arkv_config_default(arkv_config* cfg);
  * rows, per-slot position / score accumulators, the latest queries per unit) and returns the cache in *out.
  * Synchronous.  ARKV_EINVAL: null pointers, non-positive shapes, W >= N - 1, alpha outside (0,1],
  * gamma < 0, group_size != 32.  ARKV_EUNSUPPORTED: head_dim not in {64,128}, G not in {1,2,4,8}, G*W > 512,
- * quant_bits not in {2,4,8}, N > 2^20 - 64 tokens. */
+ * quant_bits not in {2,4,8}, N > 2^20 - 64 tokens, or pools of more than 2^21 - 32 rows per unit (byte budgets
+ * keep up to C_orig / C_quant Quantized rows per Original row they replace). */
 int arkv_cache_create(const arkv_config* cfg, arkv_cache** out);
 
 /* Frees everything.  Synchronises the device first.  NULL is accepted. */
@@ -85,7 +86,12 @@ int arkv_cache_reset(arkv_cache* cache, int32_t layer);
  * Window query i (position T-W+i) attends causally to keys 0..T-W+i with
  * softmax(softmax_scale * q.k); the layer statistics use keys < T-W only.  As a side effect the
  * per-(kv-head, token) sums of attention and squared attention over the window are kept inside the
- * cache for arkv_prefill_commit.  May allocate scratch on first use or when T grows.
+ * cache for arkv_prefill_commit.  Asynchronous, except that scratch is allocated on first use and when T grows
+ * (an allocation may synchronise the device).
+ * A prompt must be longer than the window: T <= W returns ARKV_EINVAL, because eqs. 3-5 are taken over the
+ * keys outside the window and there are none.  Such a prompt needs no cache management until it has grown (below
+ * the cache limit the method is plain attention, Sec. V-E); a caller can keep it outside the library and hand
+ * over the first W + 1 or more tokens as the prompt.
  * ARKV_EINVAL: T <= W, bad layer.  ARKV_ESTATE: layer already committed. */
 int arkv_prefill_stats(arkv_cache* cache, int32_t layer, const void* q_win, const void* k, int32_t T,
                        float softmax_scale, float* stats, void* hip_stream);
@@ -128,8 +134,11 @@ int arkv_budget_counts(const arkv_config* cfg, float rho, int32_t* n_o, int32_t*
  *   k, v  DEVICE bf16 [B][H_kv][T][d]  (the same k that was scored)
  *   rho   HOST float [B]               OQ ratio of this layer for every sequence
  * If T >= N the first tailor runs here on the window scores (Top-b, Top-B_o, quantise, evict).
- * The caller's k, v are not referenced after the stream has passed this call.
- * ARKV_ESTATE: arkv_prefill_stats has not run for this layer with the same T, or already committed. */
+ * Asynchronous on hip_stream (rho is read before the call returns; the budgets travel as launch arguments),
+ * except that the first tailor's key scratch is allocated on first use and when T grows (an allocation may
+ * synchronise the device).  The caller's k, v are not referenced after the stream has passed this call.
+ * ARKV_ESTATE: the scorer (arkv_prefill_stats, _lse or arkv_prefill_attention with stats) has not run for this
+ * layer with the same T, or the layer is already committed. */
 int arkv_prefill_commit(arkv_cache* cache, int32_t layer, const void* k, const void* v, int32_t T,
                         const float* rho, void* hip_stream);
 
@@ -142,7 +151,9 @@ int arkv_prefill_commit(arkv_cache* cache, int32_t layer, const void* k, const v
  * probabilities to its running sums (eq. 9), and when the number of live tokens has reached N
  * runs the tailor (eq. 10): ranks tokens older than the W most recent by S = mean + gamma*variance,
  * keeps the top b, the top n_o of them in bf16 (a Quantized token is never promoted), quantises the
- * others in place, evicts the rest.  Never allocates, never synchronises. */
+ * others in place, evicts the rest.  Never allocates, never synchronises.
+ * ARKV_ESTATE: layer not committed, or an earlier step of it failed half way (ARKV_EHIP from a tailor launch):
+ * such a layer refuses further steps until arkv_cache_reset. */
 int arkv_decode_step(arkv_cache* cache, int32_t layer, const void* q, const void* k_new,
                      const void* v_new, float softmax_scale, void* out, void* hip_stream);
 
@@ -163,8 +174,10 @@ int arkv_decode_step_layers(arkv_cache* cache, int32_t layer_begin, int32_t n, c
 int arkv_cache_counters(arkv_cache* cache, int32_t layer, int32_t* n_original, int32_t* n_quantized,
                         int32_t* n_evicted, int64_t* live_bytes);
 
-/* Contents of one layer, per unit, tokens sorted by position.  max_tokens >= N.  Any output pointer
- * may be NULL.  n_live [U]; pos, state [U][max_tokens]; s1, s2 [U][max_tokens] running sums of
+/* Contents of one layer, per unit, tokens sorted by position.  max_tokens >= N, and at least the largest
+ * number of live tokens of a unit (under budget_mode 1 a unit can hold more than N tokens: up to
+ * W + n_o + n_q of arkv_budget_counts plus the steps since the last tailor; arkv_cache_counters gives the
+ * counts); ARKV_EINVAL if a unit holds more.  Any output pointer may be NULL.  n_live [U]; pos, state [U][max_tokens]; s1, s2 [U][max_tokens] running sums of
  * attention and squared attention; rows_k, rows_v bf16 [U][max_tokens][d] (Original tokens, else 0);
  * codes_k, codes_v uint8 [U][max_tokens][d*bits/8] in canonical packing (channel c of a 4-bit row in
  * byte c/2 bits 4(c%2)..; of a 2-bit row in byte c/4 bits 2(c%4)..; of an fp8 row in byte c); scale_*,
@@ -183,7 +196,15 @@ int arkv_debug_last_tailor_scores(arkv_cache* cache, int32_t layer, int32_t max_
 /* fp32 attention output of the latest decode step of this layer, before rounding to bf16. [B][H_q][d] */
 int arkv_debug_last_out_f32(arkv_cache* cache, int32_t layer, float* out);
 
-/* Number of tailors run so far on this layer and the current number of live tokens per unit. */
+/* Parity hook.  out_f32 DEVICE float [B][H_q][T_q][d] (caller-owned) or NULL: while set, every
+ * arkv_prefill_attention on this cache also writes its output there before the rounding to bf16 (the bf16 output
+ * is the round-to-nearest-even of these values); the buffer must be large enough for the T_q of those calls. */
+int arkv_debug_prefill_attention_f32(arkv_cache* cache, float* out_f32);
+
+/* Number of tailors run so far on this layer, the occupancy the trigger of the tailor counts (tokens per unit;
+ * under budget_mode 1 the booked rows, i.e. every survivor counted as Original, which is an upper bound of the
+ * live bytes / C_orig and not the number of live tokens: use arkv_cache_counters for those), and the position of
+ * the latest token. */
 int arkv_cache_progress(arkv_cache* cache, int32_t layer, int32_t* n_tailors, int32_t* n_live,
                         int32_t* position);
 
@@ -193,6 +214,13 @@ int arkv_cache_progress(arkv_cache* cache, int32_t layer, int32_t* n_tailors, in
  * attention-kernel launches since the hook was enabled, and clears both. */
 int arkv_debug_time_attend(arkv_cache* cache, int32_t enable);
 int arkv_debug_attend_time(arkv_cache* cache, double* total_ms, int64_t* launches);
+
+/* Measurement hook: launch shape of the kernels, for sweeps.  wg_target: workgroups a decode launch aims at
+ * when it picks its split-K factor (default 512 = two per compute unit); packed_weight: cost of a packed row in
+ * sixteenths of a bf16 row when rows are dealt to the splits (default 14); prefill_chunk: keys per workgroup of
+ * the prefill scorer (multiple of 128, default 1024).  A value <= 0 leaves that setting as it is.  Results do
+ * not depend on these beyond the order of floating-point additions. */
+int arkv_debug_set_launch_shape(arkv_cache* cache, int32_t wg_target, int32_t packed_weight, int32_t prefill_chunk);
 
 /* Parity hook, HOST, pure: the rows split `split` of `n_splits` owns in a decode launch over a unit with
  * n_original bf16 rows and n_quantized packed rows (a packed row weighs packed_weight sixteenths of a bf16

@@ -21,8 +21,8 @@ EXPORTED = [
     "arkv_config_default", "arkv_cache_create", "arkv_cache_destroy", "arkv_cache_reset",
     "arkv_prefill_stats", "arkv_prefill_stats_lse", "arkv_prefill_attention", "arkv_oq_ratio", "arkv_budget_counts", "arkv_prefill_commit",
     "arkv_decode_step", "arkv_decode_step_layers", "arkv_cache_counters", "arkv_cache_export",
-    "arkv_debug_last_tailor_scores", "arkv_debug_last_out_f32", "arkv_cache_progress",
-    "arkv_debug_time_attend", "arkv_debug_attend_time", "arkv_debug_stream_read", "arkv_debug_split_range",
+    "arkv_debug_last_tailor_scores", "arkv_debug_last_out_f32", "arkv_debug_prefill_attention_f32", "arkv_cache_progress",
+    "arkv_debug_time_attend", "arkv_debug_attend_time", "arkv_debug_set_launch_shape", "arkv_debug_stream_read", "arkv_debug_split_range",
     "arkv_strerror",
     "arkv_last_hip_error",
 ]
@@ -77,7 +77,9 @@ def load():
         "arkv_cache_export": (C.c_int, [vp, i32, i32] + [vp] * 13),
         "arkv_debug_last_tailor_scores": (C.c_int, [vp, i32, i32, vp, vp, vp]),
         "arkv_debug_last_out_f32": (C.c_int, [vp, i32, vp]),
+        "arkv_debug_prefill_attention_f32": (C.c_int, [vp, vp]),
         "arkv_cache_progress": (C.c_int, [vp, i32, P(i32), P(i32), P(i32)]),
+        "arkv_debug_set_launch_shape": (C.c_int, [vp, i32, i32, i32]),
         "arkv_debug_time_attend": (C.c_int, [vp, i32]),
         "arkv_debug_attend_time": (C.c_int, [vp, P(C.c_double), P(C.c_int64)]),
         "arkv_debug_stream_read": (C.c_int, [vp, C.c_uint64, C.c_uint64, i32, i32, vp, P(C.c_float)]),
@@ -268,6 +270,18 @@ def arkv_debug_last_out_f32(cache, layer, shape):
     out = np.empty(shape, np.float32)
     _check(load().arkv_debug_last_out_f32(cache, layer, _np_ptr(out)), "arkv_debug_last_out_f32")
     return out
+
+
+def arkv_debug_prefill_attention_f32(cache, out_f32=None):
+    """out_f32: GPU fp32 tensor that later arkv_prefill_attention calls also fill, or None to switch it off."""
+    import torch
+    _check(load().arkv_debug_prefill_attention_f32(cache, None if out_f32 is None else _dev_ptr(out_f32, torch.float32)),
+           "arkv_debug_prefill_attention_f32")
+
+
+def arkv_debug_set_launch_shape(cache, wg_target=0, packed_weight=0, prefill_chunk=0):
+    _check(load().arkv_debug_set_launch_shape(cache, wg_target, packed_weight, prefill_chunk),
+           "arkv_debug_set_launch_shape")
 
 
 def arkv_debug_time_attend(cache, enable: bool):

@@ -300,18 +300,22 @@ __global__ __launch_bounds__(64 * G, G >= 4 ? 2 : 1) void k_prefill_attn(AttnLau
   const float inv = 1.0f / l_tot;
   if (row < Tq) {
     uint16_t* op = L.out + ((size_t)(b * L.Hq + g * G + w) * Tq + row) * D;
+    float* opf = L.outf ? L.outf + ((size_t)(b * L.Hq + g * G + w) * Tq + row) * D : nullptr;   // parity hook
 #pragma unroll
     for (int cb = 0; cb < CBN; ++cb)
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
         uint16_t o[4];
+        float of[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const float val = acc[cb][4 * i4 + e] * inv;
+          of[e] = val;
           uint32_t bits = __float_as_uint(val);
           bits += 0x7fffu + ((bits >> 16) & 1u);      // round to nearest even (finite values)
           o[e] = (uint16_t)(bits >> 16);
         }
+        if (opf) *reinterpret_cast<float4*>(opf + 32 * cb + 8 * i4 + 4 * hh) = make_float4(of[0], of[1], of[2], of[3]);
         *reinterpret_cast<uint2*>(op + 32 * cb + 8 * i4 + 4 * hh) =
             make_uint2((uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16));
       }

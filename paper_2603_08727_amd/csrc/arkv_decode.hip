@@ -101,7 +101,7 @@ __host__ __device__ inline unsigned mulhi_u32(unsigned a, unsigned b) {
 }
 __host__ __device__ inline void split_range(int cO, int cQ, int wq, int S, int s, SplitRecip rc, int& ao, int& bo,
                                             int& aq, int& bq) {
-  // 16 cO + wq cQ < 2^19 and S <= 128: tot * S < 2^26, every product below fits 64 bits, every result 32
+  // tot * S fits 32 bits: the library only creates caches with 16 (capO + capQ + 32) * 128 < 2^32
   const unsigned tot = 16u * (unsigned)cO + (unsigned)wq * (unsigned)cQ + 16u * kNewTokenRows;
   auto cut = [&](int i) {
     if (i <= 0) return 0u;
@@ -1091,7 +1091,8 @@ hipError_t launch_flush_scores(const Pools& P, int unit_begin, int n_units, int 
 extern "C" int arkv_debug_split_range(int32_t n_original, int32_t n_quantized, int32_t packed_weight, int32_t n_splits,
                                       int32_t split, int32_t* range) {
   if (!range || n_original < 0 || n_quantized < 0 || n_splits < 1 || n_splits > arkv::kMaxSplits || split < 0 ||
-      split >= n_splits || packed_weight < 1 || packed_weight > 16)
+      split >= n_splits || packed_weight < 1 || packed_weight > 16 ||
+      (16ull * (uint64_t)n_original + (uint64_t)packed_weight * (uint64_t)n_quantized + 512ull) * (uint64_t)n_splits > 0xFFFFFFFFull)
     return ARKV_EINVAL;
   int ao, bo, aq, bq;
   arkv::split_range(n_original, n_quantized, packed_weight, n_splits, split, arkv::split_recip(n_splits, packed_weight), ao, bo,

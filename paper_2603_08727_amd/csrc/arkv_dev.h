@@ -130,12 +130,16 @@ hipError_t launch_stream_read(const void* buf, size_t offset_bytes, size_t bytes
 hipError_t launch_flush_scores(const Pools& P, int unit_begin, int n_units, int n_pending, int slot, hipStream_t s);
 hipError_t launch_tailor(const Pools& P, const TailorLaunch& a, hipStream_t s);
 hipError_t launch_commit(const Pools& P, const CommitLaunch& a, uint64_t* commit_keys /*[U][T]*/, hipStream_t s);
+// n_o_seq, nb_seq: HOST [batch]; written to the units of one layer (unit_begin = layer * U) on the stream
+hipError_t launch_set_budgets(const Pools& P, int unit_begin, int hkv, int batch, const int32_t* n_o_seq,
+                              const int32_t* nb_seq, hipStream_t s);
 // Causal prefill attention of T_q queries (positions [T - T_q, T)) over T keys.
 struct AttnLaunch {
   const uint16_t* q;      // [B][Hq][Tq][D]
   const uint16_t* k;      // [B][Hkv][T][D]
   const uint16_t* v;
   uint16_t* out;          // [B][Hq][Tq][D]
+  float* outf;            // [B][Hq][Tq][D] the same output before its rounding to bf16 (parity hook), or null
   float* rowc;            // [U][MP] max + log2(sum) of the last W rows per head, or null
   int B, Hq, Hkv, D, T, Tq, W, MP;
   float scale2;

@@ -31,6 +31,7 @@ static int hip_fail(hipError_t e, const char* what) {
 
 struct LayerState {
   bool scored = false, committed = false;
+  bool failed = false;          // a launch of a decode step failed half way: the layer must be reset
   int scored_T = 0, T = 0, P = -1, live = 0, n_pending = 0, slot = 0, n_tailors = 0;
   int last_tailor = 0;          // 0 none, 1 at commit (keys in commit scratch), 2 during decode
   float2* pre = nullptr;        // [U][T] window sums from the prefill scorer
@@ -62,8 +63,10 @@ struct arkv_cache {
   int ckeys_layer = -1, ckeys_T = 0;
   hipStream_t last_stream = nullptr;
   // measurement hook: events around the attention kernel
+  int prefill_chunk = 1024; // keys per workgroup of the prefill scorer (halved while the grid would be small)
   int wg_target = 512;      // workgroups per decode launch the split-K factor aims at
   int wq = 14;              // measured: a packed row costs nearly as much time as a bf16 row in the attention kernel
+  float* attn_outf = nullptr;   // parity hook: fp32 copy of the prefill attention's output (caller's device buffer)
   bool timing = false;
   std::vector<hipEvent_t> ev_pool;   // pairs, reused after every read
   size_t ev_used = 0;
@@ -86,8 +89,8 @@ static int validate(const arkv_config* c) {
   if (G != 1 && G != 2 && G != 4 && G != 8) return ARKV_EUNSUPPORTED;
   if (c->quant_bits != 2 && c->quant_bits != 4 && c->quant_bits != 8) return ARKV_EUNSUPPORTED;
   if (G * c->window > 512) return ARKV_EUNSUPPORTED;
-  // the decode kernel's split cut points are 32-bit products of a unit's weighted row count (<= 32 N) and the split
-  // count (<= 128)
+  // the decode kernel's split cut points are 32-bit products of a unit's weighted row count and the split count
+  // (<= 128); arkv_cache_create repeats the check with the real size of the Quantized pool
   if (c->capacity_tokens > (1 << 20) - 64) return ARKV_EUNSUPPORTED;
   return ARKV_OK;
 }
@@ -225,6 +228,9 @@ int arkv_cache_create(const arkv_config* cfg, arkv_cache** out) {
     if (arkv_budget_counts(cfg, 0.0f, &no0, &nq0, &b0) != ARKV_OK) { delete c; return ARKV_EINVAL; }
     P.capQ = std::max(b0, 1);             // every survivor may be Quantized
   }
+  // split cut points: (16 capO + 16 capQ + 16 * 32) * 128 must fit 32 bits (byte budgets keep up to
+  // C_orig / C_quant times more Quantized rows than the token rule)
+  if (((uint64_t)P.capO + (uint64_t)P.capQ + 32u) * 16u * (uint64_t)kMaxSplits > 0xFFFFFFFFull) { delete c; return ARKV_EUNSUPPORTED; }
   P.D = cfg->head_dim;
   P.G = cfg->n_q_heads / cfg->n_kv_heads;
   P.bits = cfg->quant_bits;
@@ -232,9 +238,7 @@ int arkv_cache_create(const arkv_config* cfg, arkv_cache** out) {
   const size_t CB = D * P.bits / 8, NG = (size_t)metas_per_row(P.D, P.bits);
   P.fin_stride = LU * G;
   P.plan_stride = kPlanHdr + 3 * P.capO + 2 * P.capQ;
-  if (const char* e = getenv("ARKV_WG_TARGET")) c->wg_target = std::max(1, atoi(e));
-  if (const char* e = getenv("ARKV_WQ")) c->wq = std::max(1, std::min(16, atoi(e)));
-  P.max_splits = std::max(1, std::min(kMaxSplits, (c->wg_target + c->U - 1) / c->U));
+  P.max_splits = std::max(1, std::min(kMaxSplits, (1024 + c->U - 1) / c->U));   // room for launch-shape sweeps
 #define A(field, count) if ((rc = dev_alloc(c, &P.field, (count))) != ARKV_OK) { arkv_cache_destroy(c); return rc; }
   A(ok, LU * P.capO * D) A(ov, LU * P.capO * D)
   A(opos, LU * P.capO) A(oacc, LU * P.capO)
@@ -285,7 +289,7 @@ int arkv_cache_reset(arkv_cache* c, int32_t layer) {
   for (int l = 0; l < c->L; ++l) {
     if (layer >= 0 && l != layer) continue;
     LayerState& s = c->layers[(size_t)l];
-    s.scored = s.committed = s.cnt_valid = s.cnt_refresh = false;
+    s.scored = s.committed = s.cnt_valid = s.cnt_refresh = s.failed = false;
     s.scored_T = s.T = s.live = s.n_pending = s.slot = s.n_tailors = s.last_tailor = 0;
     s.P = -1;
   }
@@ -303,8 +307,7 @@ static int run_scorer(arkv_cache* c, int32_t layer, const uint16_t* q_win, size_
   const int U = c->U, G = c->P.G, W = c->cfg.window;
   int rc;
   if ((rc = grow(&ls.pre, &ls.pre_cap, (size_t)U * T)) != ARKV_OK) return rc;
-  int chunk = 1024;
-  if (const char* e = getenv("ARKV_PREFILL_CHUNK")) chunk = std::max(128, atoi(e) / 128 * 128);
+  int chunk = c->prefill_chunk;
   while (chunk > 128 && (size_t)((T + chunk - 1) / chunk) * U < 1024) chunk >>= 1;
   const int n_chunks = (T + chunk - 1) / chunk;
   int MP = 32;
@@ -363,6 +366,7 @@ int arkv_prefill_attention(arkv_cache* c, int32_t layer, const void* q, const vo
   a.k = static_cast<const uint16_t*>(k);
   a.v = static_cast<const uint16_t*>(v);
   a.out = static_cast<uint16_t*>(out);
+  a.outf = c->attn_outf;
   a.rowc = nullptr;
   a.B = c->cfg.batch; a.Hq = c->cfg.n_q_heads; a.Hkv = c->cfg.n_kv_heads; a.D = c->P.D;
   a.T = T; a.Tq = T_q; a.W = c->cfg.window; a.MP = 0;
@@ -385,21 +389,24 @@ int arkv_prefill_commit(arkv_cache* c, int32_t layer, const void* k, const void*
   if (ls.committed || !ls.scored || ls.scored_T != T) return ARKV_ESTATE;
   const arkv_config& cfg = c->cfg;
   const int N = cfg.capacity_tokens, W = cfg.window, U = c->U;
-  std::vector<int32_t> no_units((size_t)U), nb_units((size_t)U);
+  std::vector<int32_t> no_units((size_t)U), nb_units((size_t)U), no_seq((size_t)cfg.batch), nb_seq((size_t)cfg.batch);
   for (int s = 0; s < cfg.batch; ++s) {
     int32_t no, nq, bb;
     int rc = arkv_budget_counts(&cfg, rho[s], &no, &nq, &bb);
     if (rc != ARKV_OK) return rc;
-    ls.n_o[(size_t)s] = no;
+    no_seq[(size_t)s] = no; nb_seq[(size_t)s] = bb;
     for (int g = 0; g < cfg.n_kv_heads; ++g) {
       no_units[(size_t)s * cfg.n_kv_heads + g] = no;
       nb_units[(size_t)s * cfg.n_kv_heads + g] = bb;
     }
   }
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  HIP_TRY(hipStreamSynchronize(st));
-  HIP_TRY(hipMemcpy(c->P.n_o + (size_t)layer * U, no_units.data(), (size_t)U * sizeof(int32_t), hipMemcpyHostToDevice));
-  HIP_TRY(hipMemcpy(c->P.nb + (size_t)layer * U, nb_units.data(), (size_t)U * sizeof(int32_t), hipMemcpyHostToDevice));
+  if (T >= N) {      // the key scratch of the first tailor; sized before anything is launched or recorded
+    int rc = grow(&c->ckeys, &c->ckeys_cap, (size_t)U * T);
+    if (rc != ARKV_OK) return rc;
+  }
+  for (int s = 0; s < cfg.batch; ++s) ls.n_o[(size_t)s] = no_seq[(size_t)s];
+  HIP_TRY(launch_set_budgets(c->P, layer * U, cfg.n_kv_heads, cfg.batch, no_seq.data(), nb_seq.data(), st));
   CommitLaunch a;
   a.k = static_cast<const uint16_t*>(k);
   a.v = static_cast<const uint16_t*>(v);
@@ -407,11 +414,7 @@ int arkv_prefill_commit(arkv_cache* c, int32_t layer, const void* k, const void*
   a.unit_begin = layer * U; a.n_units = U;
   a.T = T; a.window = W; a.gamma = cfg.gamma;
   a.select = T >= N ? 1 : 0;
-  if (a.select) {
-    int rc = grow(&c->ckeys, &c->ckeys_cap, (size_t)U * T);
-    if (rc != ARKV_OK) return rc;
-    c->ckeys_layer = layer; c->ckeys_T = T;
-  }
+  if (a.select) { c->ckeys_layer = layer; c->ckeys_T = T; }
   HIP_TRY(launch_commit(c->P, a, c->ckeys, st));
   ls.committed = true; ls.T = T; ls.P = T - 1; ls.n_pending = 0; ls.slot = 0;
   if (a.select) {
@@ -443,7 +446,7 @@ int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const
   LayerState& l0 = c->layers[(size_t)layer_begin];
   for (int i = 0; i < n; ++i) {
     const LayerState& li = c->layers[(size_t)(layer_begin + i)];
-    if (!li.committed) return ARKV_ESTATE;
+    if (!li.committed || li.failed) return ARKV_ESTATE;
     if (li.T != l0.T || li.P != l0.P || li.live != l0.live || li.n_pending != l0.n_pending || li.slot != l0.slot)
       return ARKV_ESTATE;
     if (!(softmax_scale[i] > 0.0f)) return ARKV_EINVAL;
@@ -515,7 +518,13 @@ int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const
     t.unit_begin = a.unit_begin; t.n_units = a.n_units;
     t.position = P; t.t_prefill = l0.T; t.window = W; t.gamma = cfg.gamma;
     t.n_pending = n_pending; t.slot = slot;
-    HIP_TRY(launch_tailor(c->P, t, st));
+    const hipError_t te = launch_tailor(c->P, t, st);
+    if (te != hipSuccess) {
+      // the attention of this step is on the stream, the tailor is not (or only partly): the device-side state of
+      // these layers is no longer what the host would book, so they refuse further steps until they are reset
+      for (int i = 0; i < n; ++i) c->layers[(size_t)(layer_begin + i)].failed = true;
+      return hip_fail(te, "launch_tailor");
+    }
     const int wcount = std::min(W, P + 1);
     live_after = std::min(c->b, live - wcount) + wcount;
   }
@@ -678,6 +687,20 @@ int arkv_debug_last_out_f32(arkv_cache* c, int32_t layer, float* out) {
   HIP_TRY(hipStreamSynchronize(c->last_stream));
   const size_t n = (size_t)c->U * c->P.G * c->P.D;
   HIP_TRY(hipMemcpy(out, c->P.outf + (size_t)layer * n, n * sizeof(float), hipMemcpyDeviceToHost));
+  return ARKV_OK;
+}
+
+int arkv_debug_prefill_attention_f32(arkv_cache* c, float* out_f32) {
+  if (!c) return ARKV_EINVAL;
+  c->attn_outf = out_f32;
+  return ARKV_OK;
+}
+
+int arkv_debug_set_launch_shape(arkv_cache* c, int32_t wg_target, int32_t packed_weight, int32_t prefill_chunk) {
+  if (!c || packed_weight > 16 || (prefill_chunk > 0 && (prefill_chunk % 128 != 0 || prefill_chunk > 8192))) return ARKV_EINVAL;
+  if (wg_target > 0) c->wg_target = wg_target;
+  if (packed_weight > 0) c->wq = packed_weight;
+  if (prefill_chunk > 0) c->prefill_chunk = prefill_chunk;
   return ARKV_OK;
 }
 

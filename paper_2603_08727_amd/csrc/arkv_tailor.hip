@@ -595,6 +595,29 @@ static void launch_commit_scatter(const Pools& P, const CommitLaunch& a, hipStre
   hipLaunchKernelGGL((k_commit_scatter<D, BITS>), g, dim3(256), 0, s, P, a);
 }
 
+// The layer's budgets (per sequence: Original target and survivor count) reach the device as launch
+// arguments, so that the commit stays ordered on the caller's stream without a staging buffer.
+struct BudgetArgs { int n_o[64], nb[64]; };
+__global__ void k_set_budgets(int32_t* n_o, int32_t* nb, int unit_begin, int hkv, int seq0, int n_seq, BudgetArgs a) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_seq * hkv) return;
+  const int u = unit_begin + seq0 * hkv + i;
+  n_o[u] = a.n_o[i / hkv];
+  nb[u] = a.nb[i / hkv];
+}
+
+hipError_t launch_set_budgets(const Pools& P, int unit_begin, int hkv, int batch, const int32_t* n_o_seq,
+                              const int32_t* nb_seq, hipStream_t s) {
+  for (int s0 = 0; s0 < batch; s0 += 64) {
+    const int n = batch - s0 < 64 ? batch - s0 : 64;
+    BudgetArgs a;
+    for (int i = 0; i < n; ++i) { a.n_o[i] = n_o_seq[s0 + i]; a.nb[i] = nb_seq[s0 + i]; }
+    for (int i = n; i < 64; ++i) { a.n_o[i] = 0; a.nb[i] = 0; }
+    hipLaunchKernelGGL(k_set_budgets, dim3((n * hkv + 255) / 256), dim3(256), 0, s, P.n_o, P.nb, unit_begin, hkv, s0, n, a);
+  }
+  return hipGetLastError();
+}
+
 hipError_t launch_commit(const Pools& P, const CommitLaunch& a, uint64_t* ckeys, hipStream_t s) {
   if (a.select) {
     hipLaunchKernelGGL(k_commit_keys, dim3((a.T + 255) / 256, a.n_units), dim3(256), 0, s, ckeys, a, P.G);

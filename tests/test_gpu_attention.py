@@ -22,13 +22,29 @@ def _full_queries(wl, layer, qw):
     return q
 
 
+def _attention(cache, layer, q, k, v, Tq, T, scale, out, stats=None):
+    """arkv_prefill_attention with the fp32 parity hook switched on for this call: fills `out` (bf16), checks that it
+    is the round-to-nearest-even of the fp32 result, and returns the fp32 result (also kept as out.f32)."""
+    f32 = torch.zeros(out.shape, dtype=torch.float32, device="cuda")
+    A.arkv_debug_prefill_attention_f32(cache, f32)
+    try:
+        A.arkv_prefill_attention(cache, layer, q, k, v, Tq, T, scale, out, stats)
+        torch.cuda.synchronize()
+    finally:
+        A.arkv_debug_prefill_attention_f32(cache, None)
+    assert torch.equal(out.view(torch.int16), f32.to(torch.bfloat16).view(torch.int16))   # torch rounds to nearest even
+    out.f32 = f32
+    return f32
+
+
 def _check_rows(out, q, k, v, scale, group, positions, q0):
-    """out [B][Hq][Tq][d] (GPU, bf16) rows at absolute `positions` against the oracle."""
+    """Rows at absolute `positions` of the GPU's fp32 output (out.f32, [B][Hq][Tq][d], before the rounding to bf16)
+    against the oracle: max |x - ref| / max |ref| per head row."""
     worst = 0.0
     for b in range(q.shape[0]):
         ref = O.causal_attention_rows(synth.to_numpy_f32(q[b][:, positions - q0]), positions, synth.to_numpy_f32(k[b]),
                                       synth.to_numpy_f32(v[b]), scale, group)
-        got = out[b][:, positions - q0].float().cpu().numpy()
+        got = out.f32[b][:, positions - q0].cpu().numpy()
         for h in range(ref.shape[0]):
             for r in range(ref.shape[1]):
                 worst = max(worst, rel_err(got[h, r], ref[h, r]))
@@ -45,10 +61,8 @@ def test_attention_small_all_rows(hq, hkv, d, T):
         q = _full_queries(wl, 0, qw)
         scale = synth.softmax_scale(wl, 0)
         out = torch.zeros_like(q, device="cuda")
-        A.arkv_prefill_attention(cache, 0, q.cuda(), k.cuda(), v.cuda(), T, T, scale, out)
-        torch.cuda.synchronize()
-        # bf16 output rounding adds up to 2^-9 relative per element
-        assert _check_rows(out, q, k, v, scale, hq // hkv, np.arange(T), 0) <= TOL + 2.0 ** -8
+        _attention(cache, 0, q.cuda(), k.cuda(), v.cuda(), T, T, scale, out)
+        assert _check_rows(out, q, k, v, scale, hq // hkv, np.arange(T), 0) <= TOL
         # the same prompt in three ragged chunks: keys so far, queries of the chunk
         out2 = torch.zeros_like(out)
         edges = sorted({0, min(40, T), min(41 + T // 3, T), T})
@@ -81,10 +95,10 @@ def test_fused_scorer_equals_standalone_and_oracle():
                 k, v, qw = self.inputs[l]
                 q = _full_queries(wl_, l, qw)
                 out = torch.zeros_like(q, device=self.dev)
-                A.arkv_prefill_attention(self.cache, l, q.to(self.dev), k.to(self.dev), v.to(self.dev), wl_.prefill,
-                                         wl_.prefill, self.scales[l], out, stats[l])
+                _attention(self.cache, l, q.to(self.dev), k.to(self.dev), v.to(self.dev), wl_.prefill,
+                           wl_.prefill, self.scales[l], out, stats[l])
                 pos = np.array([0, 1, 31, 32, 333, wl_.prefill - wl_.window - 1, wl_.prefill - 2, wl_.prefill - 1])
-                assert _check_rows(out, q, k, v, self.scales[l], wl_.group, pos, 0) <= TOL + 2.0 ** -8
+                assert _check_rows(out, q, k, v, self.scales[l], wl_.group, pos, 0) <= TOL
             torch.cuda.synchronize()
             self.stats_gpu = stats.cpu().numpy()
             assert np.all(np.abs(self.stats_gpu - stats_alone) <= TOL * np.abs(stats_alone))
@@ -115,10 +129,9 @@ def test_attention_32k_sampled_rows():
         scale = synth.softmax_scale(wl, 0)
         out = torch.zeros_like(q, device="cuda")
         stats = torch.zeros((wl.batch, 3), dtype=torch.float32, device="cuda")
-        A.arkv_prefill_attention(cache, 0, q.cuda(), k.cuda(), v.cuda(), T, T, scale, out, stats)
-        torch.cuda.synchronize()
+        _attention(cache, 0, q.cuda(), k.cuda(), v.cuda(), T, T, scale, out, stats)
         pos = np.array([0, 31, 32, 4097, 20000, T - wl.window, T - 1])
-        assert _check_rows(out, q, k, v, scale, wl.group, pos, 0) <= TOL + 2.0 ** -8
+        assert _check_rows(out, q, k, v, scale, wl.group, pos, 0) <= TOL
         ref = []
         for b in range(wl.batch):
             a = O.window_attention(synth.to_numpy_f32(qw[b]), synth.to_numpy_f32(k[b]), scale, wl.group)
@@ -134,9 +147,8 @@ def _run_attention(wl, q, k, v, scale, Tq, T):
     cache = A.arkv_cache_create(cfg)
     try:
         out = torch.zeros((wl.batch, wl.n_q_heads, Tq, wl.head_dim), dtype=torch.bfloat16, device="cuda")
-        A.arkv_prefill_attention(cache, 0, q.contiguous().cuda(), k[:, :, :T].contiguous().cuda(),
-                                 v[:, :, :T].contiguous().cuda(), Tq, T, scale, out)
-        torch.cuda.synchronize()
+        _attention(cache, 0, q.contiguous().cuda(), k[:, :, :T].contiguous().cuda(),
+                   v[:, :, :T].contiguous().cuda(), Tq, T, scale, out)
         return out
     finally:
         A.arkv_cache_destroy(cache)
@@ -157,7 +169,7 @@ def test_attention_drifting_logits(direction):
     k = (k.float() + direction * 6.0 * ramp[None, None, :, None] * u).to(torch.bfloat16)
     q = (q.float() + (60.0 / (6.0 * scale * 1.4427)) * u).to(torch.bfloat16)   # q.u * scale * log2(e) * 6 = 60
     out = _run_attention(wl, q, k, v, scale, T, T)
-    assert _check_rows(out, q, k, v, scale, 4, np.arange(T), 0) <= TOL + 2.0 ** -8
+    assert _check_rows(out, q, k, v, scale, 4, np.arange(T), 0) <= TOL
     out2 = torch.zeros_like(out)
     for a, e in [(0, 7), (7, 100), (100, 101), (101, 263), (263, T)]:
         out2[:, :, a:e] = _run_attention(wl, q[:, :, a:e], k, v, scale, e - a, e)
@@ -174,7 +186,7 @@ def test_attention_short_and_single_rows(Tq, T):
     scale = synth.softmax_scale(wl, 0)
     out = _run_attention(wl, q[:, :, T - Tq:T], k, v, scale, Tq, T)
     kk, vv = k[:, :, :T], v[:, :, :T]
-    assert _check_rows(out, q[:, :, T - Tq:T], kk, vv, scale, 4, np.arange(T - Tq, T), T - Tq) <= TOL + 2.0 ** -8
+    assert _check_rows(out, q[:, :, T - Tq:T], kk, vv, scale, 4, np.arange(T - Tq, T), T - Tq) <= TOL
 
 
 def test_attention_whole_prompt_and_chunks_agree_bitwise_600():
@@ -187,7 +199,7 @@ def test_attention_whole_prompt_and_chunks_agree_bitwise_600():
     scale = synth.softmax_scale(wl, 0)
     out = _run_attention(wl, q, k, v, scale, T, T)
     pos = np.array([0, 31, 32, 255, 256, 300, 599, 600])
-    assert _check_rows(out, q, k, v, scale, 4, pos, 0) <= TOL + 2.0 ** -8
+    assert _check_rows(out, q, k, v, scale, 4, pos, 0) <= TOL
     out2 = torch.zeros_like(out)
     for a, e in [(0, 50), (50, 290), (290, 330), (330, T)]:
         out2[:, :, a:e] = _run_attention(wl, q[:, :, a:e], k, v, scale, e - a, e)
@@ -210,7 +222,7 @@ def test_attention_drawn_shapes_and_chunks(seed):
     scale = synth.softmax_scale(wl, 0) * float(r.choice([0.5, 1.0, 3.0]))
     out = _run_attention(wl, q, k, v, scale, T, T)
     pos = np.unique(np.concatenate([[0, T - 1, T // 2], r.integers(0, T, 6)]))
-    assert _check_rows(out, q, k, v, scale, g, pos, 0) <= TOL + 2.0 ** -8
+    assert _check_rows(out, q, k, v, scale, g, pos, 0) <= TOL
     cuts = np.unique(np.concatenate([[0, T], r.integers(1, T, 3)]))
     out2 = torch.zeros_like(out)
     for a, e in zip(cuts[:-1], cuts[1:]):
@@ -235,16 +247,17 @@ def test_fused_scorer_on_the_last_chunk_of_a_chunked_prompt():
         A.arkv_cache_reset(cache, 0)
         fused = torch.zeros_like(alone)
         out = torch.zeros_like(qd)
+        out.f32 = torch.zeros(qd.shape, dtype=torch.float32, device="cuda")
         for a, e in [(0, 190), (190, 431), (431, T)]:
             oc = torch.zeros((wl.batch, wl.n_q_heads, e - a, wl.head_dim), dtype=torch.bfloat16, device="cuda")
-            A.arkv_prefill_attention(cache, 0, qd[:, :, a:e].contiguous(), kd[:, :, :e].contiguous(), vd[:, :, :e].contiguous(),
-                                     e - a, e, scale, oc, fused if e == T else None)
+            out.f32[:, :, a:e] = _attention(cache, 0, qd[:, :, a:e].contiguous(), kd[:, :, :e].contiguous(),
+                                            vd[:, :, :e].contiguous(), e - a, e, scale, oc, fused if e == T else None)
             out[:, :, a:e] = oc
         torch.cuda.synchronize()
         sa, sf = alone.cpu().numpy(), fused.cpu().numpy()
         assert np.all(np.abs(sf - sa) <= TOL * np.abs(sa))
         pos = np.array([0, 189, 190, 430, 431, T - 1])
-        assert _check_rows(out, q, k, v, scale, wl.group, pos, 0) <= TOL + 2.0 ** -8
+        assert _check_rows(out, q, k, v, scale, wl.group, pos, 0) <= TOL
         A.arkv_prefill_commit(cache, 0, kd, vd, T, A.arkv_oq_ratio(sf[None], wl.tau)[0])
         assert A.arkv_cache_progress(cache, 0)[0] == 1
     finally:

@@ -11,8 +11,8 @@ from helpers import SideBySide
 pytestmark = pytest.mark.gpu
 
 
-def _run(wl, steps):
-    sb = SideBySide(wl)
+def _run(wl, steps, lockstep=True):
+    sb = SideBySide(wl, lockstep=lockstep)
     try:
         sb.prefill()
         sb.commit()
@@ -39,14 +39,21 @@ def test_c4_128k_2bit_one_layer():
     _run(synth.C4.scaled(n_layers=1), steps=3)
 
 
-@pytest.mark.parametrize("rho", [None, 0.5])
-def test_c3_full_size_decode_time_tailor(rho):
+def test_c3_qwen3_32k_batch4_one_layer_free_running():
+    """The same layer without the score hand-over: the first tailor ranks 32736 prompt tokens per kv-head on each
+    side's own scores; choices are compared under the score-band rule (2e-3 around the two cuts)."""
+    _run(synth.C3.scaled(n_layers=1), steps=3, lockstep=False)
+
+
+@pytest.mark.parametrize("rho,lockstep", [(None, True), (0.5, True), (0.5, False)])
+def test_c3_full_size_decode_time_tailor(rho, lockstep):
     """Config 3's shape with almost no slack (alpha = 0.99: b = 8078 of N = 8192, a tailor every 82 decode steps) so
     that a decode-time tailor over the full-size cache (eq. 10 on 8.2K tokens per unit, 32 units: select,
     demotion with in-place quantisation, compaction) is compared with the oracle, then a few steps more.  rho = 0.5 forces a mixed cache, so that
-    rows are demoted and quantised in place; None takes the scored ratio of this layer."""
+    rows are demoted and quantised in place; None takes the scored ratio of this layer.  lockstep False: no score
+    hand-over, both tailors compared under the score-band rule."""
     wl = synth.C3.scaled(name="c3_tight", n_layers=1, alpha=0.99)
-    sb = SideBySide(wl, rho_override=rho)
+    sb = SideBySide(wl, rho_override=rho, lockstep=lockstep)
     try:
         sb.prefill()
         sb.commit()
