@@ -26,6 +26,7 @@ extern "C" {
 #define ARKV_ENOMEM       -3   /* device or host allocation failed */
 #define ARKV_EHIP         -4   /* a HIP runtime call failed; arkv_last_hip_error() has its text */
 #define ARKV_EUNSUPPORTED -5   /* valid but not built (head_dim, group size, bit width) */
+#define ARKV_ESCRATCH     -6   /* arkv_decode_step_static: the launch does not fit the static scratch array */
 
 /* Token states (Sec. IV-B "Problem Formulation": full precision, quantized, evicted). */
 #define ARKV_STATE_ORIGINAL  0
@@ -156,6 +157,20 @@ int arkv_prefill_commit(arkv_cache* cache, int32_t layer, const void* k, const v
  * such a layer refuses further steps until arkv_cache_reset. */
 int arkv_decode_step(arkv_cache* cache, int32_t layer, const void* q, const void* k_new,
                      const void* v_new, float softmax_scale, void* out, void* hip_stream);
+
+/* arkv_decode_step for callers that must not allocate device memory while they run (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, same result bit for bit when the
+ * split-K factor is the same.  The split-K partials and the units' tickets of the launch live in a 4 MiB array in
+ * the library's static device memory (one per GPU, held until the process ends; its address is looked up by
+ * arkv_cache_create on that GPU) instead of the cache's own buffers, and the call makes no hipMalloc / hipFree and
+ * records no timing events.  Limits: B * H_kv <= 4096 units and B * H_kv * G * (d + 2) * 4 bytes <= 4 MiB - 16 KiB
+ * (one split per unit must fit), else ARKV_ESCRATCH; the split-K factor is lowered to what fits (config of 32
+ * units, G = 4, d = 128: up to 62 splits per unit).  Every call on a GPU shares that GPU's array: calls on
+ * different streams (or different caches) that overlap in time on one GPU race; calls ordered on one stream do
+ * not.  The tickets are zero between launches (the last workgroup of a unit clears its ticket); partials need
+ * no clearing. */
+int arkv_decode_step_static(arkv_cache* cache, int32_t layer, const void* q, const void* k_new,
+                            const void* v_new, float softmax_scale, void* out, void* hip_stream);
 
 /* The same for n consecutive, independent layers in one set of launches (benchmarks, graph capture).
  *   q [n][B][H_q][d], k_new/v_new [n][B][H_kv][d], out [n][B][H_q][d]  DEVICE bf16

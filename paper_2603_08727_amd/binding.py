@@ -14,13 +14,13 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("ARKV_LIBRARY") or os.path.join(_HERE, "libarkv.so")
 
-OK, EINVAL, ESTATE, ENOMEM, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+OK, EINVAL, ESTATE, ENOMEM, EHIP, EUNSUPPORTED, ESCRATCH = 0, -1, -2, -3, -4, -5, -6
 STATE_ORIGINAL, STATE_QUANTIZED, STATE_EVICTED = 0, 1, 2
 
 EXPORTED = [
     "arkv_config_default", "arkv_cache_create", "arkv_cache_destroy", "arkv_cache_reset",
     "arkv_prefill_stats", "arkv_prefill_stats_lse", "arkv_prefill_attention", "arkv_oq_ratio", "arkv_budget_counts", "arkv_prefill_commit",
-    "arkv_decode_step", "arkv_decode_step_layers", "arkv_cache_counters", "arkv_cache_export",
+    "arkv_decode_step", "arkv_decode_step_static", "arkv_decode_step_layers", "arkv_cache_counters", "arkv_cache_export",
     "arkv_debug_last_tailor_scores", "arkv_debug_last_out_f32", "arkv_debug_prefill_attention_f32", "arkv_cache_progress",
     "arkv_debug_time_attend", "arkv_debug_attend_time", "arkv_debug_set_launch_shape", "arkv_debug_stream_read", "arkv_debug_split_range",
     "arkv_strerror",
@@ -72,6 +72,7 @@ def load():
         "arkv_budget_counts": (C.c_int, [P(arkv_config), f32, P(i32), P(i32), P(i32)]),
         "arkv_prefill_commit": (C.c_int, [vp, i32, vp, vp, i32, vp, vp]),
         "arkv_decode_step": (C.c_int, [vp, i32, vp, vp, vp, f32, vp, vp]),
+        "arkv_decode_step_static": (C.c_int, [vp, i32, vp, vp, vp, f32, vp, vp]),
         "arkv_decode_step_layers": (C.c_int, [vp, i32, i32, vp, vp, vp, vp, vp, vp]),
         "arkv_cache_counters": (C.c_int, [vp, i32, vp, vp, vp, vp]),
         "arkv_cache_export": (C.c_int, [vp, i32, i32] + [vp] * 13),
@@ -206,6 +207,13 @@ def arkv_decode_step(cache, layer, q, k_new, v_new, softmax_scale, out):
     bf = torch.bfloat16
     _check(load().arkv_decode_step(cache, layer, _dev_ptr(q, bf), _dev_ptr(k_new, bf), _dev_ptr(v_new, bf),
                                    softmax_scale, _dev_ptr(out, bf), _stream()), "arkv_decode_step")
+
+
+def arkv_decode_step_static(cache, layer, q, k_new, v_new, softmax_scale, out):
+    import torch
+    bf = torch.bfloat16
+    _check(load().arkv_decode_step_static(cache, layer, _dev_ptr(q, bf), _dev_ptr(k_new, bf), _dev_ptr(v_new, bf),
+                                          softmax_scale, _dev_ptr(out, bf), _stream()), "arkv_decode_step_static")
 
 
 def arkv_decode_step_layers(cache, layer_begin, n, q, k_new, v_new, softmax_scale, out):

@@ -424,7 +424,7 @@ __device__ __forceinline__ void combine_splits(const Pools& P, const DecodeLaunc
   constexpr int NI = (NP + 255) / 256;             // pairs per thread
   constexpr int NB = (G <= 2 ? 32 : 64) / NI;      // splits per batch of loads (NI * NB * 2 registers)
   TRACE_M(0);
-  const float* part = P.part + (size_t)gu * P.max_splits * RS;
+  const float* part = P.part + (size_t)(gu - L.part_unit0) * P.max_splits * RS;
   const int S = L.splits;
   int hh[NI], off[NI];
 #pragma unroll
@@ -850,7 +850,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   __syncthreads();
 
   // ---------------- this split's partial ----------------
-  float* part = P.part + ((size_t)gu * P.max_splits + s) * G * (D + 2);
+  float* part = P.part + ((size_t)(gu - L.part_unit0) * P.max_splits + s) * G * (D + 2);
   for (int idx = tid; idx < G * D / 2; idx += 256) {
     const int h = idx / (D / 2), c = 2 * (idx % (D / 2));
     float M = sm_m[0][h];
@@ -883,9 +883,10 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
   if (tid == 0) {
-    const int old = __hip_atomic_fetch_add(P.ticket + gu, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    int* const ticket = P.ticket + (gu - L.part_unit0);
+    const int old = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const int last = old == L.splits - 1;
-    if (last) __hip_atomic_store(P.ticket + gu, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
+    if (last) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
     sm_last = last;
   }
   __syncthreads();
@@ -985,6 +986,50 @@ hipError_t launch_decode(const Pools& P, const DecodeLaunch& a, hipStream_t s, h
   if (P.D == 128) return launch_decode_g<128>(P, a, s, e0, e1);
   if (P.D == 64) return launch_decode_g<64>(P, a, s, e0, e1);
   return hipErrorInvalidValue;
+}
+
+// ---- split-K scratch for callers that cannot allocate ---------------------------------------------
+// One file-scope array per GPU: the units' tickets first (zero between launches: the workgroup that draws a
+// unit's last ticket clears it), the splits' partials behind them.  The array's name is only a handle in host
+// code; its device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
+__global__ void k_clear_words(unsigned* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
+hipError_t static_scratch_setup() {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  if (g_scratch_ptr[dev]) return hipSuccess;
+  unsigned char* ptr = nullptr;
+  e = hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch));
+  if (e != hipSuccess) return e;
+  if (!ptr) return hipErrorInvalidSymbol;
+  hipLaunchKernelGGL(k_clear_words, dim3((kStaticUnits + 255) / 256), dim3(256), 0, nullptr,
+                     reinterpret_cast<unsigned*>(ptr), kStaticUnits);
+  e = hipGetLastError();
+  if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+  if (e != hipSuccess) return e;
+  g_scratch_ptr[dev] = ptr;
+  return hipSuccess;
+}
+
+hipError_t static_scratch_get(float** part, int** ticket, size_t* part_floats) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices || !g_scratch_ptr[dev]) return hipErrorNotInitialized;
+  unsigned char* ptr = g_scratch_ptr[dev];
+  *ticket = reinterpret_cast<int*>(ptr);
+  *part = reinterpret_cast<float*>(ptr + (size_t)kStaticUnits * sizeof(int));
+  *part_floats = (kStaticScratchBytes - (size_t)kStaticUnits * sizeof(int)) / sizeof(float);
+  return hipSuccess;
 }
 
 // Plain streaming read: each workgroup reads a contiguous share, 8 x 16 bytes per lane in flight.

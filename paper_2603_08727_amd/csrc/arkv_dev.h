@@ -85,6 +85,8 @@ struct DecodeLaunch {
   int fold;               // 1: this launch adds the pending steps to (s1,s2)
   int wq;                 // cost of a packed row in sixteenths of a bf16 row (split balancing)
   unsigned inv_splits, inv_wq;   // ceil(2^32 / splits), ceil(2^32 / wq): the split cut points without divisions
+  int part_unit0;         // global unit whose partials and ticket come first in Pools::part / ticket (0: arrays of the
+                          // whole cache; unit_begin: a buffer that holds this launch only)
   int cnt_known;          // 1: cnt_o / cnt_q below are the units' token counts (saves a dependent load)
   int cnt_o[kMaxUnitsKnown], cnt_q[kMaxUnitsKnown];
   float scale2[kMaxLayersPerLaunch];  // softmax scale * log2(e), per launched layer
@@ -126,6 +128,11 @@ struct PrefillLaunch {
 
 hipError_t launch_decode(const Pools& P, const DecodeLaunch& a, hipStream_t s, hipEvent_t ev0 = nullptr,
                          hipEvent_t ev1 = nullptr);  // ev0/ev1: recorded around the attention kernel
+// Split-K scratch in static device memory (for the entry point that must not allocate): one array per GPU.
+constexpr size_t kStaticScratchBytes = 4u << 20;   // tickets of up to kStaticUnits units, then partials
+constexpr int kStaticUnits = 4096;
+hipError_t static_scratch_setup();                  // once per device, with that device current (synchronous)
+hipError_t static_scratch_get(float** part, int** ticket, size_t* part_floats);   // pointers for the current device
 hipError_t launch_stream_read(const void* buf, size_t offset_bytes, size_t bytes, int pattern, unsigned* sink /*[2048]*/, hipStream_t s);
 hipError_t launch_flush_scores(const Pools& P, int unit_begin, int n_units, int n_pending, int slot, hipStream_t s);
 hipError_t launch_tailor(const Pools& P, const TailorLaunch& a, hipStream_t s);

@@ -260,6 +260,7 @@ int arkv_cache_create(const arkv_config* cfg, arkv_cache** out) {
   if (e == hipSuccess) e = hipMemset(P.fin, 0, kRing * LU * G * sizeof(float2));
   if (e == hipSuccess) e = hipMemset(P.qprev, 0, kRing * LU * G * D * sizeof(uint16_t));
   if (e == hipSuccess) e = hipMemset(P.qscale, 0, kRing * LU * sizeof(float));
+  if (e == hipSuccess) e = static_scratch_setup();      // device address of the static split-K scratch
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) { arkv_cache_destroy(c); return hip_fail(e, "cache set-up"); }
   *out = c;
@@ -439,8 +440,11 @@ int arkv_prefill_commit(arkv_cache* c, int32_t layer, const void* k, const void*
   return ARKV_OK;
 }
 
-int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const void* q, const void* k_new,
-                            const void* v_new, const float* softmax_scale, void* out, void* hip_stream) {
+// One decode step of n layers in the same state.  static_scratch: the split-K partials and tickets of this launch
+// live in the library's static device array instead of the cache's own buffers.
+static int decode_impl(arkv_cache* c, int32_t layer_begin, int32_t n, const void* q, const void* k_new,
+                       const void* v_new, const float* softmax_scale, void* out, void* hip_stream,
+                       bool static_scratch) {
   if (!c || !q || !k_new || !v_new || !softmax_scale || !out) return ARKV_EINVAL;
   if (n < 1 || n > kMaxLayersPerLaunch || layer_begin < 0 || layer_begin + n > c->L) return ARKV_EINVAL;
   LayerState& l0 = c->layers[(size_t)layer_begin];
@@ -470,6 +474,18 @@ int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const
   splits = std::min(splits, std::max(1, l0.live / 128));
   a.splits = std::max(1, std::min(splits, c->P.max_splits));
   a.wq = c->wq;
+  a.part_unit0 = 0;
+  Pools pools = c->P;                 // by value: the launch may point the split-K scratch elsewhere
+  if (static_scratch) {
+    float* sp = nullptr; int* stk = nullptr; size_t cap = 0;
+    HIP_TRY(static_scratch_get(&sp, &stk, &cap));
+    const size_t row = (size_t)pools.G * ((size_t)pools.D + 2);
+    if (a.n_units > kStaticUnits || (size_t)a.n_units * row > cap) return ARKV_ESCRATCH;
+    // as many splits as fit (never more than the cache's own buffers would get)
+    a.splits = (int)std::min<size_t>((size_t)a.splits, cap / ((size_t)a.n_units * row));
+    pools.part = sp; pools.ticket = stk; pools.max_splits = a.splits;
+    a.part_unit0 = a.unit_begin;
+  }
   { const SplitRecip rc = split_recip(a.splits, a.wq); a.inv_splits = rc.inv_s; a.inv_wq = rc.inv_wq; }
   for (int i = 0; i < n; ++i) {
     LayerState& li = c->layers[(size_t)(layer_begin + i)];
@@ -497,7 +513,7 @@ int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const
   a.fold = l0.n_pending == kRing - 1 ? 1 : 0;   // the ring is full: add the waiting steps now
   for (int i = 0; i < n; ++i) a.scale2[i] = softmax_scale[i] * 1.4426950408889634f;
   hipEvent_t e0 = nullptr, e1 = nullptr;
-  if (c->timing) {
+  if (c->timing && !static_scratch) {        // the event pool grows by allocation
     if (c->ev_used + 2 > c->ev_pool.size()) {
       for (int i = 0; i < 2; ++i) {
         hipEvent_t e;
@@ -508,7 +524,7 @@ int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const
     e0 = c->ev_pool[c->ev_used]; e1 = c->ev_pool[c->ev_used + 1];
     c->ev_used += 2;
   }
-  HIP_TRY(launch_decode(c->P, a, st, e0, e1));
+  HIP_TRY(launch_decode(pools, a, st, e0, e1));
   const int P = l0.P + 1, live = l0.live + 1;
   const int n_pending = (a.fold ? 0 : l0.n_pending) + 1, slot = (l0.slot + 1) % kRing;
   bool tailor = live >= N;
@@ -546,9 +562,19 @@ int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const
   return ARKV_OK;
 }
 
+int arkv_decode_step_layers(arkv_cache* c, int32_t layer_begin, int32_t n, const void* q, const void* k_new,
+                            const void* v_new, const float* softmax_scale, void* out, void* hip_stream) {
+  return decode_impl(c, layer_begin, n, q, k_new, v_new, softmax_scale, out, hip_stream, false);
+}
+
 int arkv_decode_step(arkv_cache* c, int32_t layer, const void* q, const void* k_new, const void* v_new,
                      float softmax_scale, void* out, void* hip_stream) {
-  return arkv_decode_step_layers(c, layer, 1, q, k_new, v_new, &softmax_scale, out, hip_stream);
+  return decode_impl(c, layer, 1, q, k_new, v_new, &softmax_scale, out, hip_stream, false);
+}
+
+int arkv_decode_step_static(arkv_cache* c, int32_t layer, const void* q, const void* k_new, const void* v_new,
+                            float softmax_scale, void* out, void* hip_stream) {
+  return decode_impl(c, layer, 1, q, k_new, v_new, &softmax_scale, out, hip_stream, true);
 }
 
 // ---- observability ---------------------------------------------------------------------------
@@ -763,6 +789,7 @@ const char* arkv_strerror(int code) {
     case ARKV_ENOMEM: return "out of memory";
     case ARKV_EHIP: return "HIP runtime error (see arkv_last_hip_error)";
     case ARKV_EUNSUPPORTED: return "configuration not supported by this build";
+    case ARKV_ESCRATCH: return "the launch needs more static scratch memory than the library holds";
   }
   return "unknown error code";
 }
