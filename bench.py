@@ -103,7 +103,8 @@ def cpu_baseline(wl, k, v, qw, dq, scale, rho, seconds_budget=12.0):
     }, stats
 
 
-def quick_measure(wl, rho_force=None, steps=24, warmup=4, every_step=False, byte_budget=False):
+def quick_measure(wl, rho_force=None, steps=24, warmup=4, every_step=False, byte_budget=False, packed_weight=0,
+                  wg_target=0):
     """Prefill + commit + a short timed decode run of one workload (all its layers); returns steps/s per
     layer-batch, the attention kernel's average duration and its algorithmic bytes.  Used for the policy
     and workload variants; the headline run in main() is more thorough."""
@@ -120,6 +121,8 @@ def quick_measure(wl, rho_force=None, steps=24, warmup=4, every_step=False, byte
                                 budget_mode=1 if byte_budget else 0)
     cache = A.arkv_cache_create(cfg)
     try:
+        if packed_weight or wg_target:
+            A.arkv_debug_set_launch_shape(cache, wg_target, packed_weight, 0)
         scales = [synth.softmax_scale(wl, l) for l in range(L)]
         stats = torch.zeros((L, B, 3), dtype=torch.float32, device=dev)
         for l in range(L):

@@ -74,15 +74,6 @@ __device__ __forceinline__ float half_bits_to_float(uint32_t h) {
   return __half2float(__ushort_as_half((unsigned short)(h & 0xffffu)));
 }
 
-// 8 consecutive channels of a packed row -> fp32 values code*scale + zero.
-template <int BITS>
-__device__ __forceinline__ void dequant8(uint32_t codes, uint32_t meta, float (&f)[8]) {
-  const float sc = half_bits_to_float(meta), z = half_bits_to_float(meta >> 16);
-  constexpr uint32_t mask = (1u << BITS) - 1u;
-#pragma unroll
-  for (int c = 0; c < 8; ++c) f[c] = fmaf((float)((codes >> (BITS * c)) & mask), sc, z);
-}
-
 __device__ __forceinline__ uint16_t float_to_bf16_rne(float x) {
   uint32_t u = __float_as_uint(x);
   u += 0x7fffu + ((u >> 16) & 1u);
@@ -114,7 +105,8 @@ __host__ __device__ inline void split_range(int cO, int cQ, int wq, int S, int s
   auto mapQ = [&](unsigned v) {
     if (v <= 16u * (unsigned)cO) return 0;
     const unsigned x = v - 16u * (unsigned)cO + (unsigned)wq - 1u;
-    const int r = (int)(wq > 1 ? mulhi_u32(x, rc.inv_wq) : x);
+    int r = (int)(wq > 1 ? mulhi_u32(x, rc.inv_wq) : x);
+    r = (r + kVBlock - 1) & ~(kVBlock - 1);      // packed rows are dealt in whole value blocks
     return r < cQ ? r : cQ;
   };
   ao = mapO(v0); bo = mapO(v1); aq = mapQ(v0); bq = mapQ(v1);
@@ -192,7 +184,6 @@ struct PackedFmt {
   static constexpr int KK = D / 32, CB = D * BITS / 8, NG = D / kGroup, CW = BITS;
   struct Query { uint4 qp[KK]; float qs[KK][HPL]; };
   struct Keys { uint32_t cw[KK], meta[KK]; };
-  struct Vals { uint32_t cw, meta; };
   static __device__ __forceinline__ void prep(const uint4 (&qa)[KK], Query& q) {
     const uint4 ones = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
 #pragma unroll
@@ -219,17 +210,13 @@ struct PackedFmt {
     for (int kk = 0; kk < KK; ++kk) {
       f32x4 C = {0.f, 0.f, 0.f, 0.f};
       C = mfma16(q.qp[kk], codes_to_bf16_biased<BITS>(k.cw[kk]), C);
+      // sum_c q_c (sc code_c + z) = sc (C - 128 qs) + z qs = sc C + (z - 128 sc) qs
       const float sc = half_bits_to_float(k.meta[kk]), z = half_bits_to_float(k.meta[kk] >> 16);
+      const float zz = fmaf(-128.0f, sc, z);
 #pragma unroll
-      for (int i = 0; i < HPL; ++i) x[i] += fmaf(sc, C[i] - 128.0f * q.qs[kk][i], z * q.qs[kk][i]);
+      for (int i = 0; i < HPL; ++i) x[i] = fmaf(sc, C[i], fmaf(zz, q.qs[kk][i], x[i]));
     }
   }
-  static __device__ __forceinline__ void load_vals(const uint8_t* vc, const uint32_t* vm, int rv, int sub, Vals& v) {
-    const uint8_t* p = vc + (unsigned)rv * CB + sub * CW;
-    v.cw = BITS == 4 ? *reinterpret_cast<const uint32_t*>(p) : (uint32_t)*reinterpret_cast<const uint16_t*>(p);
-    v.meta = vm[(unsigned)rv * NG + sub / 4];
-  }
-  static __device__ __forceinline__ void value_row(const Vals& v, float (&f)[8]) { dequant8<BITS>(v.cw, v.meta, f); }
 };
 
 // BITS = 8: the paper's own format (Alg. 1 "Reconstruction Before Attention", x~ = q^ * s): one fp8 E4M3
@@ -256,7 +243,6 @@ struct PackedFmt<D, HPL, 8> {
   static constexpr int KK = D / 32, CB = D, NG = 1;
   struct Query { uint4 q[KK]; };
   struct Keys { uint2 cw[KK]; uint32_t meta; };
-  struct Vals { uint2 cw; uint32_t meta; };
   static __device__ __forceinline__ void prep(const uint4 (&qa)[KK], Query& q) {
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) q.q[kk] = qa[kk];
@@ -274,16 +260,128 @@ struct PackedFmt<D, HPL, 8> {
 #pragma unroll
     for (int i = 0; i < HPL; ++i) x[i] = C[i] * sc;
   }
-  static __device__ __forceinline__ void load_vals(const uint8_t* vc, const uint32_t* vm, int rv, int sub, Vals& v) {
-    v.cw = *reinterpret_cast<const uint2*>(vc + (unsigned)rv * CB + 8 * sub);
-    v.meta = vm[rv];
-  }
-  static __device__ __forceinline__ void value_row(const Vals& v, float (&f)[8]) {
-    fp8x8_to_f32(v.cw, f);
-    const float sc = half_bits_to_float(v.meta);
+};
+
+// ---- packed value rows on the matrix cores --------------------------------------------------------
+// PV contracts over tokens, so the value codes are stored token-minor (Pools::qvc): lane (n = lane%16,
+// kb = lane/16) of a 16x16x32 fp16 MFMA reads 8 bytes = one byte column of tokens 8kb..8kb+7 of a 32-token
+// block and turns them into the B operand of output channel(s) of that column.  The A operand is the
+// probabilities of the block times the tokens' scales of the channel group, rounded to fp16
+// (lane = head lane%16, tokens 8kb..+7).  Codes enter as fp16 "1024 + code * 2^s" (0x6400 OR-ed with the
+// masked byte: exact, no shift, no conversion); the offset is taken out again with the sum of the A operand
+// (an MFMA against all ones), the factor 2^s at the end, and the zero points come from one more MFMA of
+// the plain probabilities against the tokens' zero points (one column per group; a column of ones gives
+// the probabilities' sum, i.e. the softmax denominator, in the same rounding as the numerator).
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ f32x4 mfma16h(const uint4& a, const uint4& b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+__device__ __forceinline__ uint4 mul_f16x8(const uint4& a, const uint4& b) {
+  return __builtin_bit_cast(uint4, __builtin_bit_cast(f16x8, a) * __builtin_bit_cast(f16x8, b));
+}
+// bytes (b0, b1, b2, b3) of x -> fp16 pairs (0x6400 | b0, 0x6400 | b1), (0x6400 | b2, 0x6400 | b3)
+__device__ __forceinline__ void bytes_to_f16_biased(uint32_t x, uint32_t& lo, uint32_t& hi) {
+  lo = __builtin_amdgcn_perm(0x64646464u, x, 0x04010400u);
+  hi = __builtin_amdgcn_perm(0x64646464u, x, 0x04030402u);
+}
+constexpr uint32_t kOnesF16 = 0x3C003C00u;
+
+template <int D, int BITS>
+struct ValueFmt {
+  static constexpr int CB = D * BITS / 8;            // byte columns of a row
+  static constexpr int NG = D / kGroup;              // scale groups
+  static constexpr int MH = vmeta_per_row(D, BITS);
+  static constexpr int NACC = D / 16;                // PV MFMAs (accumulators of 16 channels) per block
+  static constexpr int APG = NACC / NG;              // accumulators per group (2)
+  static constexpr int NLD = BITS == 4 ? CB / 16 : NG;   // 8-byte code loads per lane and block
+  static constexpr int ZCOLS = NG;                   // columns of the correction MFMA that hold zero points
+  static constexpr bool kBiased = true;
+  // The A operand has 16 rows and a unit only G heads, so one operand carries several groups: rows
+  // [r * RPG, r * RPG + G) hold the probabilities times the scales of the operand's r-th group, and the PV
+  // MFMAs of that group find their results in those rows.
+  template <int G> static constexpr int rpg() { return G <= 4 ? 4 : 8; }          // operand rows per group
+  template <int G> static constexpr int gpa() { return 16 / rpg<G>(); }           // groups per A operand
+  template <int G> static constexpr int na() { return (NG + gpa<G>() - 1) / gpa<G>(); }   // A operands per block
+  static constexpr int NSC = 2;                      // >= na<G>() for every G
+  struct Blk { uint2 cw[NLD]; uint4 sc[NSC]; uint4 z; };
+  // gs[j]: the group whose scales this lane's row of A operand j needs
+  static __device__ __forceinline__ void load(const uint8_t* vc, const uint16_t* vm, int b32, int n, int kb,
+                                              const int (&gs)[NSC], int nsc, Blk& b) {
+    const uint8_t* base = vc + (size_t)b32 * (CB * kVBlock) + 8 * kb;
 #pragma unroll
-    for (int c = 0; c < 8; ++c) f[c] *= sc;
+    for (int i = 0; i < NLD; ++i) {
+      const int col = BITS == 4 ? 16 * i + n : 8 * i + (n & 7);
+      b.cw[i] = *reinterpret_cast<const uint2*>(base + col * kVBlock);
+    }
+    const uint16_t* mb = vm + (size_t)b32 * (MH * kVBlock) + 8 * kb;
+#pragma unroll
+    for (int j = 0; j < NSC; ++j)
+      if (j < nsc) b.sc[j] = *reinterpret_cast<const uint4*>(mb + gs[j] * kVBlock);
+    const uint4 zl = *reinterpret_cast<const uint4*>(mb + (NG + (n < NG ? n : NG - 1)) * kVBlock);
+    const uint32_t fill = n == NG ? kOnesF16 : 0u;
+    b.z = n < NG ? zl : make_uint4(fill, fill, fill, fill);
   }
+  static __device__ __forceinline__ int group_of(int a) { return a / APG; }
+  // B operand of accumulator a
+  static __device__ __forceinline__ uint4 operand(const Blk& b, int a, int n) {
+    uint32_t mask;
+    uint2 w;
+    if constexpr (BITS == 4) {
+      w = b.cw[a >> 1];
+      mask = (a & 1) ? 0xF0F0F0F0u : 0x0F0F0F0Fu;
+    } else {
+      w = b.cw[a >> 1];
+      const uint32_t m0 = n < 8 ? 0x03030303u : 0x0C0C0C0Cu;
+      mask = (a & 1) ? m0 << 4 : m0;
+    }
+    uint4 r;
+    bytes_to_f16_biased(w.x & mask, r.x, r.y);
+    bytes_to_f16_biased(w.y & mask, r.z, r.w);
+    return r;
+  }
+  // what the accumulator holds is 2^s times the channel's sum: its reciprocal
+  static __device__ __forceinline__ float unscale(int a, int n) {
+    if constexpr (BITS == 4) return (a & 1) ? 0.0625f : 1.0f;
+    else return (a & 1) ? (n < 8 ? 0.0625f : 0.015625f) : (n < 8 ? 1.0f : 0.25f);
+  }
+  static __device__ __forceinline__ int channel(int a, int n) {
+    if constexpr (BITS == 4) return 2 * (16 * (a >> 1) + n) + (a & 1);
+    else return 4 * (8 * (a >> 1) + (n & 7)) + 2 * (a & 1) + (n >> 3);
+  }
+};
+
+// fp8 rows: one byte per channel, one scale per row; E4M3 values are fp16 values, so no offset and no zero point.
+template <int D>
+struct ValueFmt<D, 8> {
+  static constexpr int CB = D, NG = 1, MH = 1, NACC = D / 16, APG = NACC, NLD = D / 16, ZCOLS = 0;
+  static constexpr bool kBiased = false;
+  template <int G> static constexpr int rpg() { return 16; }     // one scale per row: the operand's rows are the heads
+  template <int G> static constexpr int gpa() { return 1; }
+  template <int G> static constexpr int na() { return 1; }
+  static constexpr int NSC = 1;
+  struct Blk { uint2 cw[NLD]; uint4 sc[1]; uint4 z; };
+  static __device__ __forceinline__ void load(const uint8_t* vc, const uint16_t* vm, int b32, int n, int kb,
+                                              const int (&)[NSC], int, Blk& b) {
+    const uint8_t* base = vc + (size_t)b32 * (CB * kVBlock) + 8 * kb;
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) b.cw[i] = *reinterpret_cast<const uint2*>(base + (16 * i + n) * kVBlock);
+    b.sc[0] = *reinterpret_cast<const uint4*>(vm + (size_t)b32 * kVBlock + 8 * kb);
+    const uint32_t fill = n == 0 ? kOnesF16 : 0u;
+    b.z = make_uint4(fill, fill, fill, fill);
+  }
+  static __device__ __forceinline__ int group_of(int) { return 0; }
+  static __device__ __forceinline__ uint4 operand(const Blk& b, int a, int) {
+    typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+    const uint2 w = b.cw[a];
+    uint4 r;
+    r.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8((int)w.x, 1.0f, false));
+    r.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8((int)w.x, 1.0f, true));
+    r.z = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8((int)w.y, 1.0f, false));
+    r.w = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8((int)w.y, 1.0f, true));
+    return r;
+  }
+  static __device__ __forceinline__ float unscale(int, int) { return 1.0f; }
+  static __device__ __forceinline__ int channel(int a, int n) { return 16 * a + n; }
 };
 
 // Eq. 9 running moments: the lane's HPL logits of one token (base-2 units) -> probabilities with the
@@ -536,9 +634,9 @@ __device__ __forceinline__ void combine_splits(const Pools& P, const DecodeLaunc
 // b = lane/16) then owns the logits of token t for heads 4b..4b+3.  FOLD launches multiply the same key
 // tile with the waiting steps' queries as well (fold_pending) and update the tokens' (s1, s2).  This
 // step's probabilities go through a small LDS buffer to the value layout (lane = 8 channels of one of
-// 64/(D/8) rows), where PV runs on the vector ALU.  The softmax reference maximum is only moved when a
-// logit exceeds it by more than 8 (base-2 units), which is rare, so the accumulators are almost never
-// rescaled.
+// 64/(D/8) rows), where PV of the bf16 rows runs on the vector ALU (HBM-bound as it is); packed rows take
+// PV to the matrix cores (ValueFmt).  The softmax reference maximum is only moved when a logit of a bf16
+// row exceeds it by more than 8 (base-2 units), which is rare, so the accumulators are almost never rescaled.
 template <int D, int G, int BITS, bool FOLD>
 __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch L) {
   constexpr int KK = D / 32;           // MFMA k-steps = quantisation groups per row
@@ -562,6 +660,10 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   constexpr int RP = kParkRows ? R : 1;
   __shared__ __align__(16) float sm_a[4][RP][G][D];
   __shared__ float sm_m[4][G], sm_l[4][G];
+  __shared__ float sm_fo[4][G];                        // factor the parked Original-row sums still have to take
+  __shared__ __align__(16) float sm_q[4][G][D];        // the waves' sums over packed rows
+  __shared__ __align__(16) _Float16 sm_p[4][16][kVBlock];   // a block's probabilities, [head][token], rows >= G zero
+  __shared__ _Float16 sm_pdump[4][16][8];
   __shared__ int sm_last;
   __shared__ PendingLds<D, G> sm_pend;   // only touched when FOLD
 
@@ -769,59 +871,8 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   }
 
   TRACE(3);
-  // ---------------- Quantized rows ----------------
-  if (aq < bq) {
-    using Fmt = PackedFmt<D, HPL, BITS>;
-    const uint8_t* kc = P.qkc + (size_t)gu * P.capQ * Fmt::CB;
-    const uint8_t* vc = P.qvc + (size_t)gu * P.capQ * Fmt::CB;
-    const uint32_t* km = P.qkm + (size_t)gu * P.capQ * Fmt::NG;
-    const uint32_t* vm = P.qvm + (size_t)gu * P.capQ * Fmt::NG;
-    typename Fmt::Query pqa;
-    Fmt::prep(qa, pqa);
-    struct QTile { typename Fmt::Keys k; typename Fmt::Vals v[NV]; float2 ac; };
-    auto load_q = [&](QTile& t, int row0) {
-      const int rk = min(row0 + tok, bq - 1);
-      Fmt::load_keys(kc, km, rk, blk, t.k);
-#pragma unroll
-      for (int j = 0; j < NV; ++j) Fmt::load_vals(vc, vm, min(row0 + R * j + vrow, bq - 1), sub, t.v[j]);
-      if constexpr (FOLD) t.ac = qacc_[rk];
-    };
-    auto compute_q = [&](const QTile& t, int row0) {
-      const bool own = (row0 + tok < bq) && active;
-      float x[HPL];
-      Fmt::dots(pqa, t.k, x);
-#pragma unroll
-      for (int i = 0; i < HPL; ++i) x[i] = own ? x[i] * scale2 : kNegBig;
-      if constexpr (FOLD) {
-        const float2 ac = fold_pending<D, G>(sm_pend, npend, 0, t.ac, lane, [&](const uint4 (&qop)[KK], float (&xp)[HPL]) {
-          typename Fmt::Query pq_;
-          Fmt::prep(qop, pq_);
-          Fmt::dots(pq_, t.k, xp);
-        });
-        store_acc(ac, own, qacc_, min(row0 + tok, bq - 1));
-      }
-      softmax_pv(own, x, [&](int j, float (&f)[8]) { Fmt::value_row(t.v[j], f); });
-    };
-    QTile ta, tb;
-    int row0 = aq + 16 * w;
-    load_q(ta, row0);
-    for (; row0 + 128 < bq; row0 += 128) {
-      load_q(tb, row0 + 64);
-      compute_q(ta, row0);
-      load_q(ta, row0 + 128);
-      compute_q(tb, row0 + 64);
-    }
-    if (row0 < bq) {
-      load_q(tb, row0 + 64);
-      compute_q(ta, row0);
-      if (row0 + 64 < bq) compute_q(tb, row0 + 64);
-    }
-  }
-
-  TRACE(4);
-  // ---------------- reduce within the wave, across the 4 waves ----------------
-#pragma unroll
-  for (int i = 0; i < HPL; ++i) lsum[i] = row_sum16(lsum[i]);
+  // ---------------- the wave's sums over Original rows go to LDS ----------------
+  // (where LDS allows, kParkRows, every value-row group parks its own share and the readers add them up)
   if constexpr (kParkRows) {
 #pragma unroll
     for (int h = 0; h < G; ++h) {
@@ -843,9 +894,159 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
         for (int c = 0; c < 8; ++c) sm_a[w][0][h][sub * 8 + c] = acc[h][c];
     }
   }
+#pragma unroll
+  for (int i = 0; i < HPL; ++i) lsum[i] = row_sum16(lsum[i]);
+  float fo[HPL];                 // rescaling of the reference after the sums above were parked
+#pragma unroll
+  for (int i = 0; i < HPL; ++i) fo[i] = 1.0f;
+
+  // ---------------- Quantized rows ----------------
+  // Blocks of 32 tokens: logits of two 16-token tiles as above (codes -> bf16 MFMA operands), then PV on the
+  // matrix cores from the token-minor value blocks (ValueFmt).  Probabilities are at most 1 here (the reference
+  // maximum follows every new maximum), so that probability * scale cannot overflow fp16.
+  const bool hasq = aq < bq;                 // uniform over the workgroup
+  if (hasq) {
+    using Fmt = PackedFmt<D, HPL, BITS>;
+    using VF = ValueFmt<D, BITS>;
+    const uint8_t* kc = P.qkc + (size_t)gu * P.capQ * Fmt::CB;
+    const uint32_t* km = P.qkm + (size_t)gu * P.capQ * Fmt::NG;
+    const uint8_t* vc = P.qvc + (size_t)gu * P.capQv * VF::CB;
+    const uint16_t* vm = P.qvm + (size_t)gu * P.capQv * VF::MH;
+    typename Fmt::Query pqa;
+    Fmt::prep(qa, pqa);
+    // rows of the probability buffer that no head fills stay zero
+    *reinterpret_cast<uint4*>(&sm_p[w][lane >> 2][8 * (lane & 3)]) = make_uint4(0, 0, 0, 0);
+    constexpr int RPG = VF::template rpg<G>(), GPA = VF::template gpa<G>(), NA = VF::template na<G>();
+    // row tok of A operand j: head tok % RPG, group j * GPA + tok / RPG (rows beyond the groups repeat the last)
+    const int arow_head = tok % RPG;
+    int gs[VF::NSC];
+#pragma unroll
+    for (int j = 0; j < VF::NSC; ++j) gs[j] = min(j * GPA + tok / RPG, VF::NG - 1);
+    f32x4 pacc[VF::NACC], sacc[NA], zacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int a = 0; a < VF::NACC; ++a) pacc[a] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < NA; ++j) sacc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const uint4 ones = make_uint4(kOnesF16, kOnesF16, kOnesF16, kOnesF16);
+    struct QBlk { typename Fmt::Keys k[2]; typename VF::Blk v; float2 ac[2]; };
+    const int blast = (bq - 1) / kVBlock;      // last block of the range (loads are clamped to it)
+    auto load_q = [&](QBlk& t, int b32) {
+      b32 = min(b32, blast);
+#pragma unroll
+      for (int tl = 0; tl < 2; ++tl) {
+        const int rk = min(kVBlock * b32 + 16 * tl + tok, bq - 1);
+        Fmt::load_keys(kc, km, rk, blk, t.k[tl]);
+        if constexpr (FOLD) t.ac[tl] = qacc_[rk];
+      }
+      VF::load(vc, vm, b32, tok, blk, gs, NA, t.v);
+    };
+    auto compute_q = [&](const QBlk& t, int b32) {
+      float x[2][HPL];
+      bool own[2];
+#pragma unroll
+      for (int tl = 0; tl < 2; ++tl) {
+        const int row = kVBlock * b32 + 16 * tl + tok;
+        own[tl] = (row < bq) && active;
+        Fmt::dots(pqa, t.k[tl], x[tl]);
+#pragma unroll
+        for (int i = 0; i < HPL; ++i) x[tl][i] = own[tl] ? x[tl][i] * scale2 : kNegBig;
+        if constexpr (FOLD) {
+          const float2 ac = fold_pending<D, G>(sm_pend, npend, 0, t.ac[tl], lane, [&](const uint4 (&qop)[KK], float (&xp)[HPL]) {
+            typename Fmt::Query pq_;
+            Fmt::prep(qop, pq_);
+            Fmt::dots(pq_, t.k[tl], xp);
+          });
+          store_acc(ac, own[tl], qacc_, min(row, bq - 1));
+        }
+      }
+      bool need = false;
+#pragma unroll
+      for (int i = 0; i < HPL; ++i) need |= active && (fmaxf(x[0][i], x[1][i]) > Mreg[i]);
+      if (__any(need)) {
+#pragma unroll
+        for (int i = 0; i < HPL; ++i) {
+          const float nm = fmaxf(Mreg[i], row_max16(fmaxf(x[0][i], x[1][i])));
+          const float f = fexp2(Mreg[i] - nm);      // the same in the 16 lanes of a block; 1 in blocks without heads
+          Mreg[i] = nm;
+          lsum[i] *= f;
+          fo[i] *= f;
+          zacc[i] *= f;                             // rows of the correction MFMA are the heads, as in this layout
+          // rows of the PV accumulators: head (4 blk + i) % RPG, whose factor lives in lane block that head / 4
+          float fr;
+          if constexpr (RPG == 16) fr = f;
+          else if constexpr (RPG == 4) fr = lane_value(f, 0);
+          else fr = (blk & 1) ? lane_value(f, 16) : lane_value(f, 0);
+#pragma unroll
+          for (int a = 0; a < VF::NACC; ++a) pacc[a][i] *= fr;
+#pragma unroll
+          for (int j = 0; j < NA; ++j) sacc[j][i] *= fr;
+        }
+      }
+      // probabilities as fp16, [head][token] (blocks without heads write a dump: no branch round the LDS op)
+#pragma unroll
+      for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+        for (int i = 0; i < HPL; ++i) {
+          const float p = own[tl] ? fexp2(x[tl][i] - Mreg[i]) : 0.f;
+          _Float16* dst = active ? &sm_p[w][4 * blk + i][16 * tl + tok] : &sm_pdump[w][tok][4 * tl + i];
+          *dst = (_Float16)p;
+        }
+      __builtin_amdgcn_wave_barrier();
+      const uint4 pz = *reinterpret_cast<const uint4*>(&sm_p[w][tok][8 * blk]);        // row = head lane%16, tokens 8 (lane/16) ..+7
+      uint4 pg = pz;
+      if constexpr (RPG != 16) pg = *reinterpret_cast<const uint4*>(&sm_p[w][arow_head][8 * blk]);   // row = head of a group's row
+      __builtin_amdgcn_wave_barrier();
+      zacc = mfma16h(pz, t.v.z, zacc);
+#pragma unroll
+      for (int j = 0; j < NA; ++j) {
+        const uint4 aj = mul_f16x8(pg, t.v.sc[j]);
+        if constexpr (VF::kBiased) sacc[j] = mfma16h(aj, ones, sacc[j]);
+#pragma unroll
+        for (int a = j * GPA * VF::APG; a < (j + 1) * GPA * VF::APG && a < VF::NACC; ++a)
+          pacc[a] = mfma16h(aj, VF::operand(t.v, a, tok), pacc[a]);
+      }
+    };
+    QBlk qa_, qb_;
+    int b32 = aq / kVBlock + w;                // aq is a multiple of the block size
+    load_q(qa_, b32);
+    for (; b32 + 8 <= blast; b32 += 8) {
+      load_q(qb_, b32 + 4);
+      compute_q(qa_, b32);
+      load_q(qa_, b32 + 8);
+      compute_q(qb_, b32 + 4);
+    }
+    if (b32 <= blast) {
+      load_q(qb_, b32 + 4);
+      compute_q(qa_, b32);
+      if (b32 + 4 <= blast) compute_q(qb_, b32 + 4);
+    }
+    // accumulators -> channel sums: take the code offset out (1024 * sum of the A operand), undo the code's
+    // position in its byte, add the zero points' share (column g of the correction MFMA, whose rows are the heads)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float lq = __shfl(zacc[i], (lane & 48) | VF::ZCOLS);
+      if (i < HPL) lsum[i] += lq;
+#pragma unroll
+      for (int a = 0; a < VF::NACC; ++a) {
+        const int g = VF::group_of(a), j = g / GPA;
+        const int r0 = RPG == 16 ? 0 : (g % GPA) * RPG;          // first operand row of this group
+        const int head = 4 * blk + i - r0;
+        const bool useful = head >= 0 && head < G;
+        float v = pacc[a][i];
+        if constexpr (VF::kBiased) v = fmaf(-1024.0f, sacc[j][i], v);
+        float zg = 0.f;
+        if constexpr (VF::ZCOLS > 0) zg = __shfl(zacc[i], (16 * max(blk - r0 / 4, 0)) | g);
+        v = fmaf(v, VF::unscale(a, tok), zg);
+        if (useful) sm_q[w][head][VF::channel(a, tok)] = v;
+      }
+    }
+  }
+
+  TRACE(4);
+  // ---------------- across the 4 waves ----------------
   if (tok == 0 && active) {
 #pragma unroll
-    for (int i = 0; i < HPL; ++i) { sm_m[w][4 * blk + i] = Mreg[i]; sm_l[w][4 * blk + i] = lsum[i]; }
+    for (int i = 0; i < HPL; ++i) { sm_m[w][4 * blk + i] = Mreg[i]; sm_l[w][4 * blk + i] = lsum[i]; sm_fo[w][4 * blk + i] = fo[i]; }
   }
   __syncthreads();
 
@@ -868,6 +1069,12 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
       for (int st = 1; st < RP; st <<= 1)
 #pragma unroll
         for (int v = 0; v < RP; v += 2 * st) { t[v].x += t[v + st].x; t[v].y += t[v + st].y; }
+      if (hasq) {
+        const float2 tq = *reinterpret_cast<const float2*>(&sm_q[i][h][c]);
+        const float f = sm_fo[i][h];
+        t[0].x = fmaf(t[0].x, f, tq.x);
+        t[0].y = fmaf(t[0].y, f, tq.y);
+      }
       a0 = fmaf(t[0].x, cw_, a0);
       a1 = fmaf(t[0].y, cw_, a1);
       l = fmaf(sm_l[i][h], cw_, l);

@@ -18,12 +18,24 @@ constexpr int kMaxUnitsKnown = 64;     // launches with at most this many units 
 // wait for their score update, one slot is written by the step in flight.
 constexpr int kRing = 9;
 
-// 32-bit metadata words of one packed K (or V) row
+// 32-bit metadata words of one packed K row
 __host__ __device__ constexpr int metas_per_row(int D, int bits) { return bits == 8 ? 1 : D / kGroup; }
+// tokens per block of the value rows' token-minor layout, and fp16 metadata words of one packed V row
+constexpr int kVBlock = 32;
+__host__ __device__ constexpr int vmeta_per_row(int D, int bits) { return bits == 8 ? 1 : 2 * (D / kGroup); }
+// where byte `col` of the value row in slot `slot` of a unit sits, relative to the unit's qvc (CB = bytes per row)
+__host__ __device__ inline size_t vcode_index(int slot, int col, int CB) {
+  return ((size_t)(slot / kVBlock) * CB + col) * kVBlock + slot % kVBlock;
+}
+// the same for fp16 metadata word m of the row (grouped formats: m = g for the scale, D/32 + g for the zero point)
+__host__ __device__ inline size_t vmeta_index(int slot, int m, int MH) {
+  return ((size_t)(slot / kVBlock) * MH + m) * kVBlock + slot % kVBlock;
+}
 
 struct Pools {
   int U;                // units per layer
   int capO, capQ;       // slots per unit: N and b
+  int capQv;            // capQ rounded up to whole value blocks (kVBlock tokens): rows per unit of qvc / qvm
   int D, G, bits;
   // O pool
   uint16_t* ok;         // [LU][capO][D] bf16 keys
@@ -32,9 +44,14 @@ struct Pools {
   float2*   oacc;       // [LU][capO] (s1, s2): running sums of attention and attention^2 (eq. 9)
   // Q pool
   uint8_t*  qkc;        // [LU][capQ][D*bits/8] key codes, canonical packing (bits = 8: one fp8 E4M3 byte per channel)
-  uint8_t*  qvc;        // [LU][capQ][D*bits/8]
   uint32_t* qkm;        // [LU][capQ][metas_per_row] (fp16 scale | fp16 zero << 16) per group; bits = 8: one fp16 scale per row
-  uint32_t* qvm;        // [LU][capQ][metas_per_row]
+  // Value rows are stored token-minor in blocks of kVBlock tokens, because PV contracts over tokens and a matrix-core
+  // operand holds 8 consecutive contraction indices per lane: byte b of a token's canonical row (the same bytes as
+  // in qkc: two 4-bit, four 2-bit or one fp8 code) sits at [block][b][token % kVBlock].
+  uint8_t*  qvc;        // [LU][capQv / kVBlock][D*bits/8][kVBlock]
+  // fp16 words: grouped formats [block][2][D/32][kVBlock] (scales of group g, then zero points of group g, one per
+  // token); fp8 rows [block][kVBlock] (the row scales)
+  uint16_t* qvm;        // [LU][capQv / kVBlock][vmeta_per_row][kVBlock]
   int32_t*  qpos;       // [LU][capQ]
   float2*   qacc;       // [LU][capQ]
   // per unit

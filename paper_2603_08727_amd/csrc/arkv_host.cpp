@@ -227,6 +227,7 @@ int arkv_cache_create(const arkv_config* cfg, arkv_cache** out) {
     int32_t no0, nq0, b0;
     if (arkv_budget_counts(cfg, 0.0f, &no0, &nq0, &b0) != ARKV_OK) { delete c; return ARKV_EINVAL; }
     P.capQ = std::max(b0, 1);             // every survivor may be Quantized
+    P.capQv = (P.capQ + kVBlock - 1) / kVBlock * kVBlock;
   }
   // split cut points: (16 capO + 16 capQ + 16 * 32) * 128 must fit 32 bits (byte budgets keep up to
   // C_orig / C_quant times more Quantized rows than the token rule)
@@ -242,8 +243,9 @@ int arkv_cache_create(const arkv_config* cfg, arkv_cache** out) {
 #define A(field, count) if ((rc = dev_alloc(c, &P.field, (count))) != ARKV_OK) { arkv_cache_destroy(c); return rc; }
   A(ok, LU * P.capO * D) A(ov, LU * P.capO * D)
   A(opos, LU * P.capO) A(oacc, LU * P.capO)
-  A(qkc, LU * P.capQ * CB) A(qvc, LU * P.capQ * CB)
-  A(qkm, LU * P.capQ * NG) A(qvm, LU * P.capQ * NG)
+  const size_t MH = (size_t)vmeta_per_row(P.D, P.bits);
+  A(qkc, LU * P.capQ * CB) A(qvc, LU * P.capQv * CB)
+  A(qkm, LU * P.capQ * NG) A(qvm, LU * P.capQv * MH)
   A(qpos, LU * P.capQ) A(qacc, LU * P.capQ)
   A(cnt, LU) A(fin, kRing * LU * G) A(qprev, kRing * LU * G * D) A(qscale, kRing * LU) A(part, LU * (size_t)P.max_splits * G * (D + 2)) A(outf, LU * G * D) A(n_o, LU) A(nb, LU) A(ticket, LU)
   A(keys, LU * (size_t)(P.capO + P.capQ)) A(thr, LU * 2) A(plan, LU * (size_t)P.plan_stride)
@@ -253,6 +255,9 @@ int arkv_cache_create(const arkv_config* cfg, arkv_cache** out) {
     if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&ls.cnt_host), (size_t)c->U * sizeof(int2), hipHostMallocDefault);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&ls.cnt_ev, hipEventDisableTiming);
   }
+  // value blocks are read whole, stale slots included (their probabilities are zero): what they hold must be finite
+  if (e == hipSuccess) e = hipMemset(P.qvc, 0, LU * P.capQv * CB);
+  if (e == hipSuccess) e = hipMemset(P.qvm, 0, LU * P.capQv * MH * sizeof(uint16_t));
   if (e == hipSuccess) e = hipMemset(P.cnt, 0, LU * sizeof(int2));
   if (e == hipSuccess) e = hipMemset(P.ticket, 0, LU * sizeof(int));
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->stat_ticket), (size_t)c->cfg.batch * sizeof(int));
@@ -623,7 +628,9 @@ int arkv_cache_export(arkv_cache* c, int32_t layer, int32_t max_tokens, int32_t*
   std::vector<float2> oacc, qacc;
   std::vector<uint16_t> ok, ov;
   std::vector<uint8_t> qkc, qvc;
-  std::vector<uint32_t> qkm, qvm;
+  std::vector<uint32_t> qkm;
+  std::vector<uint16_t> qvm;
+  const size_t cQv = (size_t)P.capQv, MH = (size_t)vmeta_per_row(P.D, P.bits);
   if ((rc = fetch(cnt, P.cnt + off, U)) || (rc = fetch(opos, P.opos + off * cO, U * cO)) ||
       (rc = fetch(qpos, P.qpos + off * cQ, U * cQ)) || (rc = fetch(oacc, P.oacc + off * cO, U * cO)) ||
       (rc = fetch(qacc, P.qacc + off * cQ, U * cQ)))
@@ -631,9 +638,9 @@ int arkv_cache_export(arkv_cache* c, int32_t layer, int32_t max_tokens, int32_t*
   if (rows_k && (rc = fetch(ok, P.ok + off * cO * D, U * cO * D))) return rc;
   if (rows_v && (rc = fetch(ov, P.ov + off * cO * D, U * cO * D))) return rc;
   if (codes_k && (rc = fetch(qkc, P.qkc + off * cQ * CB, U * cQ * CB))) return rc;
-  if (codes_v && (rc = fetch(qvc, P.qvc + off * cQ * CB, U * cQ * CB))) return rc;
+  if (codes_v && (rc = fetch(qvc, P.qvc + off * cQv * CB, U * cQv * CB))) return rc;
   if ((scale_k || zero_k) && (rc = fetch(qkm, P.qkm + off * cQ * NG, U * cQ * NG))) return rc;
-  if ((scale_v || zero_v) && (rc = fetch(qvm, P.qvm + off * cQ * NG, U * cQ * NG))) return rc;
+  if ((scale_v || zero_v) && (rc = fetch(qvm, P.qvm + off * cQv * MH, U * cQv * MH))) return rc;
   const size_t MT = (size_t)max_tokens;
   struct Ent { int32_t pos; int32_t slot; uint8_t st; };
   std::vector<Ent> ents;
@@ -656,12 +663,15 @@ int arkv_cache_export(arkv_cache* c, int32_t layer, int32_t max_tokens, int32_t*
       if (rows_k) { if (isq) memset(rows_k + o * D, 0, D * 2); else memcpy(rows_k + o * D, &ok[so * D], D * 2); }
       if (rows_v) { if (isq) memset(rows_v + o * D, 0, D * 2); else memcpy(rows_v + o * D, &ov[so * D], D * 2); }
       if (codes_k) { if (isq) memcpy(codes_k + o * CB, &qkc[sq * CB], CB); else memset(codes_k + o * CB, 0, CB); }
-      if (codes_v) { if (isq) memcpy(codes_v + o * CB, &qvc[sq * CB], CB); else memset(codes_v + o * CB, 0, CB); }
+      if (codes_v) {      // gather the row's bytes out of the token-minor value blocks
+        for (size_t bcol = 0; bcol < CB; ++bcol)
+          codes_v[o * CB + bcol] = isq ? qvc[u * cQv * CB + vcode_index(e.slot, (int)bcol, (int)CB)] : (uint8_t)0;
+      }
       for (size_t g = 0; g < NG; ++g) {
         if (scale_k) scale_k[o * NG + g] = isq ? (uint16_t)(qkm[sq * NG + g] & 0xffffu) : 0;
         if (zero_k) zero_k[o * NG + g] = isq ? (uint16_t)(qkm[sq * NG + g] >> 16) : 0;
-        if (scale_v) scale_v[o * NG + g] = isq ? (uint16_t)(qvm[sq * NG + g] & 0xffffu) : 0;
-        if (zero_v) zero_v[o * NG + g] = isq ? (uint16_t)(qvm[sq * NG + g] >> 16) : 0;
+        if (scale_v) scale_v[o * NG + g] = isq ? qvm[u * cQv * MH + vmeta_index(e.slot, (int)g, (int)MH)] : (uint16_t)0;
+        if (zero_v) zero_v[o * NG + g] = (isq && MH > 1) ? qvm[u * cQv * MH + vmeta_index(e.slot, (int)(NG + g), (int)MH)] : (uint16_t)0;
       }
     }
   }

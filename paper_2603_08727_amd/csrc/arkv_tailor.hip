@@ -403,23 +403,39 @@ __device__ __forceinline__ void quantize_into(const Pools& P, int gu, int dst, c
   const uint4 raw = *reinterpret_cast<const uint4*>(src);
   float x[8];
   unpack8(raw, x);
-  uint8_t* cdst = (isv ? P.qvc : P.qkc) + ((size_t)gu * P.capQ + dst) * CB;
-  uint32_t* mdst = (isv ? P.qvm : P.qkm) + ((size_t)gu * P.capQ + dst) * NG;
+  // K: canonical row-major packing.  V: the same bytes, token-minor in blocks of kVBlock tokens (see Pools).
+  uint8_t* cdst = P.qkc + ((size_t)gu * P.capQ + dst) * CB;
+  uint32_t* mdst = P.qkm + ((size_t)gu * P.capQ + dst) * NG;
+  uint8_t* vcu = P.qvc + (size_t)gu * P.capQv * CB;
+  constexpr int MH = vmeta_per_row(D, BITS);
+  uint16_t* vmu = P.qvm + (size_t)gu * P.capQv * MH;
   if constexpr (BITS == 8) {
     uint2 codes;
     uint32_t meta;
     quantize8_fp8<LPR>(x, codes, meta);
-    if (lane < 2 * LPR) {
+    if (lane < LPR) {
       *reinterpret_cast<uint2*>(cdst + sub * 8) = codes;
       if (sub == 0) mdst[0] = meta;
+    } else if (lane < 2 * LPR) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        vcu[vcode_index(dst, 8 * sub + i, CB)] = (uint8_t)((i < 4 ? codes.x >> (8 * i) : codes.y >> (8 * (i - 4))) & 0xffu);
+      if (sub == 0) vmu[vmeta_index(dst, 0, MH)] = (uint16_t)meta;
     }
   } else {
     uint32_t codes, meta;
     quantize8<BITS>(x, codes, meta);
-    if (lane < 2 * LPR) {
+    if (lane < LPR) {
       if (BITS == 4) *reinterpret_cast<uint32_t*>(cdst + sub * 4) = codes;
       else *reinterpret_cast<uint16_t*>(cdst + sub * 2) = (uint16_t)codes;
       if ((sub & 3) == 0) mdst[sub >> 2] = meta;
+    } else if (lane < 2 * LPR) {
+#pragma unroll
+      for (int i = 0; i < BITS; ++i) vcu[vcode_index(dst, BITS * sub + i, CB)] = (uint8_t)((codes >> (8 * i)) & 0xffu);
+      if ((sub & 3) == 0) {
+        vmu[vmeta_index(dst, sub >> 2, MH)] = (uint16_t)(meta & 0xffffu);              // scale
+        vmu[vmeta_index(dst, D / kGroup + (sub >> 2), MH)] = (uint16_t)(meta >> 16);   // zero point
+      }
     }
   }
 }
@@ -446,12 +462,15 @@ __global__ __launch_bounds__(256) void k_tailor_move_q(Pools P, TailorLaunch L) 
     } else {
       const int src = qmov[item - nD];
       const size_t so = (size_t)gu * P.capQ + src, d_ = (size_t)gu * P.capQ + dst;
-      // code bytes of K then V, 4 bytes per lane
-      for (int b = lane * 4; b < CB; b += 256) {
+      // K: code bytes, 4 per lane; V: one byte column per lane (token-minor blocks)
+      for (int b = lane * 4; b < CB; b += 256)
         *reinterpret_cast<uint32_t*>(P.qkc + d_ * CB + b) = *reinterpret_cast<const uint32_t*>(P.qkc + so * CB + b);
-        *reinterpret_cast<uint32_t*>(P.qvc + d_ * CB + b) = *reinterpret_cast<const uint32_t*>(P.qvc + so * CB + b);
-      }
-      if (lane < NG) { P.qkm[d_ * NG + lane] = P.qkm[so * NG + lane]; P.qvm[d_ * NG + lane] = P.qvm[so * NG + lane]; }
+      uint8_t* vcu = P.qvc + (size_t)gu * P.capQv * CB;
+      for (int b = lane; b < CB; b += 64) vcu[vcode_index(dst, b, CB)] = vcu[vcode_index(src, b, CB)];
+      constexpr int MH = vmeta_per_row(D, BITS);
+      uint16_t* vmu = P.qvm + (size_t)gu * P.capQv * MH;
+      if (lane < MH) vmu[vmeta_index(dst, lane, MH)] = vmu[vmeta_index(src, lane, MH)];
+      if (lane < NG) P.qkm[d_ * NG + lane] = P.qkm[so * NG + lane];
       if (lane == 0) { P.qpos[d_] = P.qpos[so]; P.qacc[d_] = P.qacc[so]; }
     }
   }

@@ -96,7 +96,7 @@ def test_oq_ratio_matches_oracle():
 def test_split_ranges_partition_the_pools():
     """Host logic of the split-K decomposition: for any counts the splits' row ranges are contiguous, ordered,
     cover both pools exactly once, and carry about equal weight (a packed row weighs w/16 of a bf16 row; the
-    last split is charged 32 rows for the appended token)."""
+    last split is charged 32 rows for the appended token; packed rows are dealt in blocks of 32)."""
     rng = np.random.default_rng(1)
     cases = [(0, 0, 14, 1), (1, 0, 14, 1), (0, 5, 14, 4), (6180, 0, 14, 16), (60, 6120, 14, 16), (4140, 2040, 14, 16),
              (8209, 19584, 16, 128), (33, 1, 1, 7)]
@@ -109,8 +109,9 @@ def test_split_ranges_partition_the_pools():
             assert ao == ends_o and aq == ends_q and ao <= bo <= cO and aq <= bq <= cQ, (cO, cQ, w, S, s)
             ends_o, ends_q = bo, bq
             weights.append(16 * (bo - ao) + w * (bq - aq) + (16 * 32 if s == S - 1 else 0))
+            assert aq % 32 == 0 and (bq % 32 == 0 or bq == cQ)      # packed rows are dealt in whole value blocks
         assert ends_o == cO and ends_q == cQ
-        assert max(weights) - min(weights) <= 2 * 16 + 16 * 32, (cO, cQ, w, S, weights)
+        assert max(weights) - min(weights) <= 2 * 16 + 16 * 32 + 2 * 32 * w, (cO, cQ, w, S, weights)
     for bad in [(-1, 0, 14, 4, 0), (0, 0, 0, 4, 0), (0, 0, 14, 0, 0), (0, 0, 14, 129, 0), (0, 0, 14, 4, 4)]:
         with pytest.raises(A.ArkvError):
             A.arkv_debug_split_range(*bad)
