@@ -196,12 +196,19 @@ struct PackedFmt {
     }
   }
   static __device__ __forceinline__ void load_keys(const uint8_t* kc, const uint32_t* km, int rk, int blk, Keys& k) {
+    // the KK chunks this lane block needs of the row are contiguous (kcode_index): one load; so are the row's
+    // KK metadata words
+    const uint8_t* p = kc + (unsigned)rk * CB + blk * (KK * CW);
+    uint32_t raw[4] = {0, 0, 0, 0};
+    if constexpr (KK * CW == 16) { const uint4 v = *reinterpret_cast<const uint4*>(p); raw[0] = v.x; raw[1] = v.y; raw[2] = v.z; raw[3] = v.w; }
+    else if constexpr (KK * CW == 8) { const uint2 v = *reinterpret_cast<const uint2*>(p); raw[0] = v.x; raw[1] = v.y; }
+    else raw[0] = *reinterpret_cast<const uint32_t*>(p);
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      const uint8_t* p = kc + (unsigned)rk * CB + kk * (4 * CW) + blk * CW;
-      k.cw[kk] = BITS == 4 ? *reinterpret_cast<const uint32_t*>(p) : (uint32_t)*reinterpret_cast<const uint16_t*>(p);
-      k.meta[kk] = km[(unsigned)rk * NG + kk];
-    }
+    for (int kk = 0; kk < KK; ++kk)
+      k.cw[kk] = BITS == 4 ? raw[kk] : ((raw[kk >> 1] >> (16 * (kk & 1))) & 0xFFFFu);
+    const uint32_t* m = km + (unsigned)rk * NG;
+    if constexpr (KK == 4) { const uint4 v = *reinterpret_cast<const uint4*>(m); k.meta[0] = v.x; k.meta[1] = v.y; k.meta[2] = v.z; k.meta[3] = v.w; }
+    else { const uint2 v = *reinterpret_cast<const uint2*>(m); k.meta[0] = v.x; k.meta[1] = v.y; }
   }
   static __device__ __forceinline__ void dots(const Query& q, const Keys& k, float (&x)[HPL]) {
 #pragma unroll
@@ -215,6 +222,24 @@ struct PackedFmt {
       const float zz = fmaf(-128.0f, sc, z);
 #pragma unroll
       for (int i = 0; i < HPL; ++i) x[i] = fmaf(sc, C[i], fmaf(zz, q.qs[kk][i], x[i]));
+    }
+  }
+  // the same against a round of waiting steps, whose prepared operand rows (qp) and channel sums (qs) sit in LDS
+  static __device__ __forceinline__ void dots_pending(const uint16_t (*qp)[D], const float (*qs)[16], const Keys& k, int tok,
+                                                      int blk, float (&x)[HPL]) {
+#pragma unroll
+    for (int i = 0; i < HPL; ++i) x[i] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const uint4 q = *reinterpret_cast<const uint4*>(&qp[tok][32 * kk + 8 * blk]);
+      const float4 s4 = *reinterpret_cast<const float4*>(&qs[kk][4 * blk]);
+      const float s[4] = {s4.x, s4.y, s4.z, s4.w};
+      f32x4 C = {0.f, 0.f, 0.f, 0.f};
+      C = mfma16(q, codes_to_bf16_biased<BITS>(k.cw[kk]), C);
+      const float sc = half_bits_to_float(k.meta[kk]), z = half_bits_to_float(k.meta[kk] >> 16);
+      const float zz = fmaf(-128.0f, sc, z);
+#pragma unroll
+      for (int i = 0; i < HPL; ++i) x[i] = fmaf(sc, C[i], fmaf(zz, s[i], x[i]));
     }
   }
 };
@@ -248,8 +273,13 @@ struct PackedFmt<D, HPL, 8> {
     for (int kk = 0; kk < KK; ++kk) q.q[kk] = qa[kk];
   }
   static __device__ __forceinline__ void load_keys(const uint8_t* kc, const uint32_t* km, int rk, int blk, Keys& k) {
+    const uint4* p = reinterpret_cast<const uint4*>(kc + (unsigned)rk * CB + blk * (KK * 8));   // see kcode_index
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) k.cw[kk] = *reinterpret_cast<const uint2*>(kc + (unsigned)rk * CB + 32 * kk + 8 * blk);
+    for (int h = 0; h < KK / 2; ++h) {
+      const uint4 v = p[h];
+      k.cw[2 * h] = make_uint2(v.x, v.y);
+      k.cw[2 * h + 1] = make_uint2(v.z, v.w);
+    }
     k.meta = km[rk];
   }
   static __device__ __forceinline__ void dots(const Query& q, const Keys& k, float (&x)[HPL]) {
@@ -307,11 +337,14 @@ struct ValueFmt {
   // gs[j]: the group whose scales this lane's row of A operand j needs
   static __device__ __forceinline__ void load(const uint8_t* vc, const uint16_t* vm, int b32, int n, int kb,
                                               const int (&gs)[NSC], int nsc, Blk& b) {
-    const uint8_t* base = vc + (size_t)b32 * (CB * kVBlock) + 8 * kb;
+    // the lane's NLD byte columns x 8 tokens are contiguous (vcode_index)
+    constexpr int NL = BITS == 2 ? 8 : 16;
+    const uint4* base = reinterpret_cast<const uint4*>(vc + (size_t)b32 * (CB * kVBlock) + (size_t)((kb * NL + (n & (NL - 1))) * NLD) * 8);
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int col = BITS == 4 ? 16 * i + n : 8 * i + (n & 7);
-      b.cw[i] = *reinterpret_cast<const uint2*>(base + col * kVBlock);
+    for (int i = 0; i < NLD / 2; ++i) {
+      const uint4 v = base[i];
+      b.cw[2 * i] = make_uint2(v.x, v.y);
+      b.cw[2 * i + 1] = make_uint2(v.z, v.w);
     }
     const uint16_t* mb = vm + (size_t)b32 * (MH * kVBlock) + 8 * kb;
 #pragma unroll
@@ -362,9 +395,13 @@ struct ValueFmt<D, 8> {
   struct Blk { uint2 cw[NLD]; uint4 sc[1]; uint4 z; };
   static __device__ __forceinline__ void load(const uint8_t* vc, const uint16_t* vm, int b32, int n, int kb,
                                               const int (&)[NSC], int, Blk& b) {
-    const uint8_t* base = vc + (size_t)b32 * (CB * kVBlock) + 8 * kb;
+    const uint4* base = reinterpret_cast<const uint4*>(vc + (size_t)b32 * (CB * kVBlock) + (size_t)((kb * 16 + n) * NLD) * 8);
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) b.cw[i] = *reinterpret_cast<const uint2*>(base + (16 * i + n) * kVBlock);
+    for (int i = 0; i < NLD / 2; ++i) {
+      const uint4 v = base[i];
+      b.cw[2 * i] = make_uint2(v.x, v.y);
+      b.cw[2 * i + 1] = make_uint2(v.z, v.w);
+    }
     b.sc[0] = *reinterpret_cast<const uint4*>(vm + (size_t)b32 * kVBlock + 8 * kb);
     const uint32_t fill = n == 0 ? kOnesF16 : 0u;
     b.z = make_uint4(fill, fill, fill, fill);
@@ -404,58 +441,81 @@ __device__ __forceinline__ float2 prob_moments(const float (&x)[HPL], const floa
 // qscale, fin).  A workgroup that is to add n waiting steps to (s1, s2) first copies their state to LDS;
 // then, per 16-token key tile, the logits of every waiting step are recomputed (same MFMA sequence on the
 // same bits as in the step itself), turned into probabilities and their moments added in step order.
+// The MFMA has 16 query rows and a step only needs G of them, so several waiting steps share one operand
+// ("round"): step r * SPR + b occupies rows [b * RPS, b * RPS + G) of round r's operand; rows nothing fills are zero.
+template <int G> struct PendingShape {
+  static constexpr int RPS = G <= 4 ? 4 : 8;                       // operand rows per step
+  static constexpr int SPR = 16 / RPS;                             // steps per round
+  static constexpr int ROUNDS = (kRing - 1 + SPR - 1) / SPR;       // 2 (G <= 4) or 4 (G = 8)
+};
 template <int D, int G>
 struct PendingLds {
-  uint16_t q[kRing][G][D];           // query rows of waiting step j (0 = oldest); row block kRing - 1 is all zero
-  float2 fin[kRing - 1][G];          // its final (max, 1/sum) per head
-  float scale[kRing - 1];            // its softmax scale * log2(e)
+  uint16_t q[PendingShape<G>::ROUNDS][16][D];    // round r's operand rows (bf16)
+  uint16_t qp[PendingShape<G>::ROUNDS][16][D];   // the same rows as the grouped packed formats want them (permute_for_codes)
+  float qs[PendingShape<G>::ROUNDS][D / 32][16]; // ... and each row's channel sums per group of 32
+  float2 fin[kRing - 1][G];                      // a waiting step's final (max, 1/sum) per head
+  float scale[kRing - 1];                        // its softmax scale * log2(e)
 };
 
+// All threads of the workgroup; ends with a barrier.  packed: also prepare qp / qs (waves 0 .. ROUNDS-1, one round each).
 template <int D, int G>
 __device__ __forceinline__ void stage_pending(const Pools& P, int gu, int n, int slot, PendingLds<D, G>& sm, int tid,
-                                              int nthreads) {
+                                              int nthreads, bool packed) {
+  using PS = PendingShape<G>;
+  constexpr int KK = D / 32;
   const size_t LU = P.fin_stride / G;
-  for (int i = tid; i < n * (G * D / 8); i += nthreads) {
-    const int j = i / (G * D / 8), c = i % (G * D / 8);
-    const int sl = (slot - n + j + kRing) % kRing;
-    reinterpret_cast<uint4*>(&sm.q[j][0][0])[c] =
-        reinterpret_cast<const uint4*>(P.qprev + ((size_t)sl * P.fin_stride + (size_t)gu * G) * D)[c];
+  for (int i = tid; i < PS::ROUNDS * 16 * (D / 8); i += nthreads) {
+    const int row = i / (D / 8), c = i % (D / 8);            // row = 16 r + operand row
+    const int step = (row / 16) * PS::SPR + (row % 16) / PS::RPS, head = (row % 16) % PS::RPS;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (head < G && step < n) {
+      const int sl = (slot - n + step + kRing) % kRing;
+      v = reinterpret_cast<const uint4*>(P.qprev + ((size_t)sl * P.fin_stride + (size_t)gu * G + head) * D)[c];
+    }
+    reinterpret_cast<uint4*>(&sm.q[0][0][0])[i] = v;
   }
-  for (int i = tid; i < G * D / 8; i += nthreads)       // operand rows no waiting step fills read zeros from here
-    reinterpret_cast<uint4*>(&sm.q[kRing - 1][0][0])[i] = make_uint4(0, 0, 0, 0);
   for (int i = tid; i < n * G; i += nthreads) {
     const int j = i / G, h = i % G;
     const int sl = (slot - n + j + kRing) % kRing;
     sm.fin[j][h] = P.fin[(size_t)sl * P.fin_stride + (size_t)gu * G + h];
     if (h == 0) sm.scale[j] = P.qscale[(size_t)sl * LU + gu];
   }
+  __syncthreads();
+  if (packed) {
+    const int lane = tid & 63, r = tid >> 6, tok = lane & 15, blk = lane >> 4;
+    if (r < PS::ROUNDS) {
+      const uint4 ones = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const uint4 qo = *reinterpret_cast<const uint4*>(&sm.q[r][tok][32 * kk + 8 * blk]);
+        f32x4 C = {0.f, 0.f, 0.f, 0.f};
+        C = mfma16(qo, ones, C);                      // every column: the rows' sums over this group's channels
+        *reinterpret_cast<uint4*>(&sm.qp[r][tok][32 * kk + 8 * blk]) = permute_for_codes(qo);
+        if (tok == 0) *reinterpret_cast<float4*>(&sm.qs[r][kk][4 * blk]) = make_float4(C[0], C[1], C[2], C[3]);
+      }
+    }
+    __syncthreads();
+  }
 }
 
-// Adds the moments of the n waiting steps to (s1, s2) of the lane's token.  dots(qop, x) must fill x with
-// the token's raw dot products against query operand qop; a token takes part from waiting step `first` on
-// (it did not exist before).  The result is valid in lanes of block 0.
+// Adds the moments of the n waiting steps to (s1, s2) of the lane's token.  dots(r, qop, x) must fill x with
+// the token's raw dot products against round r's query operand (qop: the plain bf16 rows); a token takes part
+// from waiting step `first` on (it did not exist before).  The result is valid in lanes of block 0.
 //
-// The MFMA has 16 query rows and a step only needs G of them, so several waiting steps share one operand:
-// step j0 + b occupies rows [b*RPS, b*RPS + G).  Their logits land in different lane blocks, where the
-// probabilities and moments of up to four steps are computed by the same instructions; block 0 then
-// collects them and adds them in step order (the same fp32 additions as one step at a time).
+// The logits of the steps of a round land in different lane blocks, where the probabilities and moments of up
+// to four steps are computed by the same instructions; block 0 then collects them and adds them in step
+// order (the same fp32 additions as one step at a time).
 template <int D, int G, typename Dots>
 __device__ __forceinline__ float2 fold_pending(const PendingLds<D, G>& sm, int n, int first, float2 ac, int lane, Dots&& dots) {
   constexpr int KK = D / 32, HB = (G + 3) / 4, HPL = G < 4 ? G : 4;
-  constexpr int RPS = G <= 4 ? 4 : 8;        // operand rows per step
-  constexpr int SPR = 16 / RPS;              // steps per round
+  constexpr int RPS = PendingShape<G>::RPS, SPR = PendingShape<G>::SPR;
   const int tok = lane & 15, blk = lane >> 4;
   for (int j0 = 0; j0 < n; j0 += SPR) {
     uint4 qop[KK];
-    {
-      const int rstep = j0 + tok / RPS, rhead = tok % RPS;
-      const bool rvalid = rhead < G && rstep < n;
-      const uint16_t* src = &sm.q[rvalid ? rstep : kRing - 1][rvalid ? rhead : 0][8 * blk];
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) qop[kk] = *reinterpret_cast<const uint4*>(src + 32 * kk);
-    }
+    for (int kk = 0; kk < KK; ++kk) qop[kk] = *reinterpret_cast<const uint4*>(&sm.q[j0 / SPR][tok][32 * kk + 8 * blk]);
     float x[HPL], pm[HPL], pinv[HPL];
-    dots(qop, x);
+    dots(j0 / SPR, qop, x);
     // this lane's results are rows 4*blk .. +3 of the operand: step js, heads h0 .. h0+3
     const int js = min(j0 + (4 * blk) / RPS, n - 1), h0 = (4 * blk) % RPS;
     const float sc = sm.scale[js];
@@ -728,10 +788,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   // this step's query; on a launch that also updates the scores, the waiting steps' state goes to LDS
   uint4 qa[KK];
   load_query<D, G>(pq + (size_t)lu * G * D, lane, qa);
-  if constexpr (FOLD) {
-    stage_pending<D, G>(P, gu, npend, L.slot, sm_pend, tid, 256);
-    __syncthreads();
-  }
+  if constexpr (FOLD) stage_pending<D, G>(P, gu, npend, L.slot, sm_pend, tid, 256, BITS != 8 && cQ > 0);
 
   float Mreg[HPL], lsum[HPL], acc[G][8];
 #pragma unroll
@@ -808,7 +865,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
     if constexpr (FOLD) {
       // the token appended by waiting step j sits at row cO - npend + j: older steps did not see it
       const int row = min(row0 + tok, bo - 1);
-      const float2 ac = fold_pending<D, G>(sm_pend, npend, row - (cO - npend), t.ac, lane, [&](const uint4 (&qop)[KK], float (&xp)[HPL]) {
+      const float2 ac = fold_pending<D, G>(sm_pend, npend, row - (cO - npend), t.ac, lane, [&](int, const uint4 (&qop)[KK], float (&xp)[HPL]) {
         const f32x4 Cp = dots_bf16<KK>(qop, t.kb);
 #pragma unroll
         for (int i = 0; i < HPL; ++i) xp[i] = Cp[i];
@@ -928,6 +985,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
 #pragma unroll
     for (int j = 0; j < NA; ++j) sacc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
     const uint4 ones = make_uint4(kOnesF16, kOnesF16, kOnesF16, kOnesF16);
+    constexpr bool kLateV = FOLD && BITS != 8;
     struct QBlk { typename Fmt::Keys k[2]; typename VF::Blk v; float2 ac[2]; };
     const int blast = (bq - 1) / kVBlock;      // last block of the range (loads are clamped to it)
     auto load_q = [&](QBlk& t, int b32) {
@@ -938,9 +996,15 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
         Fmt::load_keys(kc, km, rk, blk, t.k[tl]);
         if constexpr (FOLD) t.ac[tl] = qacc_[rk];
       }
-      VF::load(vc, vm, b32, tok, blk, gs, NA, t.v);
+      // launches that also update the scores spend several times longer on a block's logits (grouped formats):
+      // there the value block is requested at the start of the block's work instead of one block ahead, which
+      // saves a buffer's worth of registers
+      if constexpr (!kLateV) VF::load(vc, vm, b32, tok, blk, gs, NA, t.v);
     };
     auto compute_q = [&](const QBlk& t, int b32) {
+      typename VF::Blk vnow;
+      if constexpr (kLateV) VF::load(vc, vm, b32, tok, blk, gs, NA, vnow);
+      const typename VF::Blk& tv = kLateV ? vnow : t.v;
       float x[2][HPL];
       bool own[2];
 #pragma unroll
@@ -951,10 +1015,14 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
 #pragma unroll
         for (int i = 0; i < HPL; ++i) x[tl][i] = own[tl] ? x[tl][i] * scale2 : kNegBig;
         if constexpr (FOLD) {
-          const float2 ac = fold_pending<D, G>(sm_pend, npend, 0, t.ac[tl], lane, [&](const uint4 (&qop)[KK], float (&xp)[HPL]) {
-            typename Fmt::Query pq_;
-            Fmt::prep(qop, pq_);
-            Fmt::dots(pq_, t.k[tl], xp);
+          const float2 ac = fold_pending<D, G>(sm_pend, npend, 0, t.ac[tl], lane, [&](int r, const uint4 (&qop)[KK], float (&xp)[HPL]) {
+            if constexpr (BITS == 8) {
+              typename Fmt::Query pq_;
+              Fmt::prep(qop, pq_);
+              Fmt::dots(pq_, t.k[tl], xp);
+            } else {
+              Fmt::dots_pending(sm_pend.qp[r], sm_pend.qs[r], t.k[tl], tok, blk, xp);
+            }
           });
           store_acc(ac, own[tl], qacc_, min(row, bq - 1));
         }
@@ -996,14 +1064,14 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
       uint4 pg = pz;
       if constexpr (RPG != 16) pg = *reinterpret_cast<const uint4*>(&sm_p[w][arow_head][8 * blk]);   // row = head of a group's row
       __builtin_amdgcn_wave_barrier();
-      zacc = mfma16h(pz, t.v.z, zacc);
+      zacc = mfma16h(pz, tv.z, zacc);
 #pragma unroll
       for (int j = 0; j < NA; ++j) {
-        const uint4 aj = mul_f16x8(pg, t.v.sc[j]);
+        const uint4 aj = mul_f16x8(pg, tv.sc[j]);
         if constexpr (VF::kBiased) sacc[j] = mfma16h(aj, ones, sacc[j]);
 #pragma unroll
         for (int a = j * GPA * VF::APG; a < (j + 1) * GPA * VF::APG && a < VF::NACC; ++a)
-          pacc[a] = mfma16h(aj, VF::operand(t.v, a, tok), pacc[a]);
+          pacc[a] = mfma16h(aj, VF::operand(tv, a, tok), pacc[a]);
       }
     };
     QBlk qa_, qb_;
@@ -1113,8 +1181,7 @@ __global__ __launch_bounds__(256) void k_flush_scores(Pools P, int unit_begin, i
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int tok = lane & 15, blk = lane >> 4;
   const int2 cnt = P.cnt[gu];
-  stage_pending<D, G>(P, gu, n_pending, slot, sm_pend, threadIdx.x, 256);
-  __syncthreads();
+  stage_pending<D, G>(P, gu, n_pending, slot, sm_pend, threadIdx.x, 256, BITS != 8 && cnt.y > 0);
   const int wave = blockIdx.x * 4 + w, step = gridDim.x * 64;
   {
     const uint16_t* ok_ = P.ok + (size_t)gu * P.capO * D;
@@ -1128,7 +1195,7 @@ __global__ __launch_bounds__(256) void k_flush_scores(Pools P, int unit_begin, i
         kb[kk] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(ok_) + off + 64 * kk);
       // the token appended by waiting step j sits at row cnt.x - n_pending + j
       const float2 ac = fold_pending<D, G>(sm_pend, n_pending, rk - (cnt.x - n_pending), acc[rk], lane,
-                                           [&](const uint4 (&qop)[KK], float (&xp)[HPL]) {
+                                           [&](int, const uint4 (&qop)[KK], float (&xp)[HPL]) {
         const f32x4 Cp = dots_bf16<KK>(qop, kb);
 #pragma unroll
         for (int i = 0; i < HPL; ++i) xp[i] = Cp[i];
@@ -1145,10 +1212,14 @@ __global__ __launch_bounds__(256) void k_flush_scores(Pools P, int unit_begin, i
       const int rk = min(row0 + tok, cnt.y - 1);
       typename Fmt::Keys k;
       Fmt::load_keys(kc, km, rk, blk, k);
-      const float2 ac = fold_pending<D, G>(sm_pend, n_pending, 0, acc[rk], lane, [&](const uint4 (&qop)[KK], float (&xp)[HPL]) {
-        typename Fmt::Query pq_;
-        Fmt::prep(qop, pq_);
-        Fmt::dots(pq_, k, xp);
+      const float2 ac = fold_pending<D, G>(sm_pend, n_pending, 0, acc[rk], lane, [&](int r, const uint4 (&qop)[KK], float (&xp)[HPL]) {
+        if constexpr (BITS == 8) {
+          typename Fmt::Query pq_;
+          Fmt::prep(qop, pq_);
+          Fmt::dots(pq_, k, xp);
+        } else {
+          Fmt::dots_pending(sm_pend.qp[r], sm_pend.qs[r], k, tok, blk, xp);
+        }
       });
       if (row0 + tok < cnt.y && blk == 0) acc[rk] = ac;
     }

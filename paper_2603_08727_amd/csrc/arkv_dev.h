@@ -23,9 +23,22 @@ __host__ __device__ constexpr int metas_per_row(int D, int bits) { return bits =
 // tokens per block of the value rows' token-minor layout, and fp16 metadata words of one packed V row
 constexpr int kVBlock = 32;
 __host__ __device__ constexpr int vmeta_per_row(int D, int bits) { return bits == 8 ? 1 : 2 * (D / kGroup); }
-// where byte `col` of the value row in slot `slot` of a unit sits, relative to the unit's qvc (CB = bytes per row)
-__host__ __device__ inline size_t vcode_index(int slot, int col, int CB) {
-  return ((size_t)(slot / kVBlock) * CB + col) * kVBlock + slot % kVBlock;
+// Where byte `col` of the value row in slot `slot` of a unit sits, relative to the unit's qvc (CB = bytes per
+// row).  Within a block the bytes are ordered [8-token octet kb][lane n][column group i][token % 8], with
+// n = col % NL, i = col / NL and NL = 16 lanes (8 for 2-bit rows, where lanes n and n + 8 read the same bytes): the 8
+// tokens of ALL the columns a lane needs are contiguous, so a lane fetches them with 16-byte loads.
+__host__ __device__ inline size_t vcode_index(int slot, int col, int CB, int bits) {
+  const int NL = bits == 2 ? 8 : 16, NLD = CB / NL;
+  const int t = slot % kVBlock;
+  return ((((size_t)(slot / kVBlock) * 4 + t / 8) * NL + col % NL) * NLD + col / NL) * 8 + t % 8;
+}
+// Key codes of a row: the row's chunks (k-step kk, lane block blk) of CW = bits bytes (4 for 4-bit, 2 for 2-bit, 8
+// for fp8 rows) are stored [blk][kk] instead of the canonical [kk][blk], so that everything lane block blk needs
+// of a row is contiguous (one wide load per lane instead of one narrow load per k-step).  Canonical byte c -> stored.
+__host__ __device__ inline int kcode_index(int c, int D, int bits) {
+  const int KK = D / 32, CW = bits;
+  const int kk = c / (4 * CW), blk = (c / CW) % 4;
+  return (blk * KK + kk) * CW + c % CW;
 }
 // the same for fp16 metadata word m of the row (grouped formats: m = g for the scale, D/32 + g for the zero point)
 __host__ __device__ inline size_t vmeta_index(int slot, int m, int MH) {
@@ -43,12 +56,13 @@ struct Pools {
   int32_t*  opos;       // [LU][capO] position of the token in the sequence
   float2*   oacc;       // [LU][capO] (s1, s2): running sums of attention and attention^2 (eq. 9)
   // Q pool
-  uint8_t*  qkc;        // [LU][capQ][D*bits/8] key codes, canonical packing (bits = 8: one fp8 E4M3 byte per channel)
+  uint8_t*  qkc;        // [LU][capQ][D*bits/8] key codes: canonical packing (bits = 8: one fp8 E4M3 byte per channel), bytes in
+                        // the order of kcode_index
   uint32_t* qkm;        // [LU][capQ][metas_per_row] (fp16 scale | fp16 zero << 16) per group; bits = 8: one fp16 scale per row
   // Value rows are stored token-minor in blocks of kVBlock tokens, because PV contracts over tokens and a matrix-core
   // operand holds 8 consecutive contraction indices per lane: byte b of a token's canonical row (the same bytes as
-  // in qkc: two 4-bit, four 2-bit or one fp8 code) sits at [block][b][token % kVBlock].
-  uint8_t*  qvc;        // [LU][capQv / kVBlock][D*bits/8][kVBlock]
+  // in a canonical row: two 4-bit, four 2-bit or one fp8 code) sits at vcode_index within the unit's blocks.
+  uint8_t*  qvc;        // [LU][capQv / kVBlock][D*bits/8 * kVBlock]
   // fp16 words: grouped formats [block][2][D/32][kVBlock] (scales of group g, then zero points of group g, one per
   // token); fp8 rows [block][kVBlock] (the row scales)
   uint16_t* qvm;        // [LU][capQv / kVBlock][vmeta_per_row][kVBlock]

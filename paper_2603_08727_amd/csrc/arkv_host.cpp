@@ -662,10 +662,13 @@ int arkv_cache_export(arkv_cache* c, int32_t layer, int32_t max_tokens, int32_t*
       if (s2) s2[o] = isq ? qacc[sq].y : oacc[so].y;
       if (rows_k) { if (isq) memset(rows_k + o * D, 0, D * 2); else memcpy(rows_k + o * D, &ok[so * D], D * 2); }
       if (rows_v) { if (isq) memset(rows_v + o * D, 0, D * 2); else memcpy(rows_v + o * D, &ov[so * D], D * 2); }
-      if (codes_k) { if (isq) memcpy(codes_k + o * CB, &qkc[sq * CB], CB); else memset(codes_k + o * CB, 0, CB); }
+      if (codes_k) {      // the row's bytes back into canonical order
+        for (size_t bcol = 0; bcol < CB; ++bcol)
+          codes_k[o * CB + bcol] = isq ? qkc[sq * CB + (size_t)kcode_index((int)bcol, P.D, P.bits)] : (uint8_t)0;
+      }
       if (codes_v) {      // gather the row's bytes out of the token-minor value blocks
         for (size_t bcol = 0; bcol < CB; ++bcol)
-          codes_v[o * CB + bcol] = isq ? qvc[u * cQv * CB + vcode_index(e.slot, (int)bcol, (int)CB)] : (uint8_t)0;
+          codes_v[o * CB + bcol] = isq ? qvc[u * cQv * CB + vcode_index(e.slot, (int)bcol, (int)CB, P.bits)] : (uint8_t)0;
       }
       for (size_t g = 0; g < NG; ++g) {
         if (scale_k) scale_k[o * NG + g] = isq ? (uint16_t)(qkm[sq * NG + g] & 0xffffu) : 0;

@@ -414,24 +414,25 @@ __device__ __forceinline__ void quantize_into(const Pools& P, int gu, int dst, c
     uint32_t meta;
     quantize8_fp8<LPR>(x, codes, meta);
     if (lane < LPR) {
-      *reinterpret_cast<uint2*>(cdst + sub * 8) = codes;
+      *reinterpret_cast<uint2*>(cdst + ((sub & 3) * (D / 32) + (sub >> 2)) * 8) = codes;     // see kcode_index
       if (sub == 0) mdst[0] = meta;
     } else if (lane < 2 * LPR) {
 #pragma unroll
       for (int i = 0; i < 8; ++i)
-        vcu[vcode_index(dst, 8 * sub + i, CB)] = (uint8_t)((i < 4 ? codes.x >> (8 * i) : codes.y >> (8 * (i - 4))) & 0xffu);
+        vcu[vcode_index(dst, 8 * sub + i, CB, BITS)] = (uint8_t)((i < 4 ? codes.x >> (8 * i) : codes.y >> (8 * (i - 4))) & 0xffu);
       if (sub == 0) vmu[vmeta_index(dst, 0, MH)] = (uint16_t)meta;
     }
   } else {
     uint32_t codes, meta;
     quantize8<BITS>(x, codes, meta);
     if (lane < LPR) {
-      if (BITS == 4) *reinterpret_cast<uint32_t*>(cdst + sub * 4) = codes;
-      else *reinterpret_cast<uint16_t*>(cdst + sub * 2) = (uint16_t)codes;
+      const int chunk = (sub & 3) * (D / 32) + (sub >> 2);                                   // see kcode_index
+      if (BITS == 4) *reinterpret_cast<uint32_t*>(cdst + chunk * 4) = codes;
+      else *reinterpret_cast<uint16_t*>(cdst + chunk * 2) = (uint16_t)codes;
       if ((sub & 3) == 0) mdst[sub >> 2] = meta;
     } else if (lane < 2 * LPR) {
 #pragma unroll
-      for (int i = 0; i < BITS; ++i) vcu[vcode_index(dst, BITS * sub + i, CB)] = (uint8_t)((codes >> (8 * i)) & 0xffu);
+      for (int i = 0; i < BITS; ++i) vcu[vcode_index(dst, BITS * sub + i, CB, BITS)] = (uint8_t)((codes >> (8 * i)) & 0xffu);
       if ((sub & 3) == 0) {
         vmu[vmeta_index(dst, sub >> 2, MH)] = (uint16_t)(meta & 0xffffu);              // scale
         vmu[vmeta_index(dst, D / kGroup + (sub >> 2), MH)] = (uint16_t)(meta >> 16);   // zero point
@@ -466,7 +467,7 @@ __global__ __launch_bounds__(256) void k_tailor_move_q(Pools P, TailorLaunch L) 
       for (int b = lane * 4; b < CB; b += 256)
         *reinterpret_cast<uint32_t*>(P.qkc + d_ * CB + b) = *reinterpret_cast<const uint32_t*>(P.qkc + so * CB + b);
       uint8_t* vcu = P.qvc + (size_t)gu * P.capQv * CB;
-      for (int b = lane; b < CB; b += 64) vcu[vcode_index(dst, b, CB)] = vcu[vcode_index(src, b, CB)];
+      for (int b = lane; b < CB; b += 64) vcu[vcode_index(dst, b, CB, BITS)] = vcu[vcode_index(src, b, CB, BITS)];
       constexpr int MH = vmeta_per_row(D, BITS);
       uint16_t* vmu = P.qvm + (size_t)gu * P.capQv * MH;
       if (lane < MH) vmu[vmeta_index(dst, lane, MH)] = vmu[vmeta_index(src, lane, MH)];

@@ -109,7 +109,7 @@ def test_split_ranges_partition_the_pools():
             assert ao == ends_o and aq == ends_q and ao <= bo <= cO and aq <= bq <= cQ, (cO, cQ, w, S, s)
             ends_o, ends_q = bo, bq
             weights.append(16 * (bo - ao) + w * (bq - aq) + (16 * 32 if s == S - 1 else 0))
-            assert aq % 32 == 0 and (bq % 32 == 0 or bq == cQ)      # packed rows are dealt in whole value blocks
+            assert (aq % 32 == 0 or aq == bq == cQ) and (bq % 32 == 0 or bq == cQ)   # packed rows are dealt in whole value blocks
         assert ends_o == cO and ends_q == cQ
         assert max(weights) - min(weights) <= 2 * 16 + 16 * 32 + 2 * 32 * w, (cO, cQ, w, S, weights)
     for bad in [(-1, 0, 14, 4, 0), (0, 0, 0, 4, 0), (0, 0, 14, 0, 0), (0, 0, 14, 129, 0), (0, 0, 14, 4, 4)]:
