@@ -37,16 +37,14 @@ def kv_bytes_per_token(d, bits):
     return c_o, c_q
 
 
-SCORE_UPDATE_EVERY = 8   # steps whose score update is done in one pass (kRing - 1 in csrc/arkv_dev.h)
-
-
 def algorithmic_bytes_attend(n_o, n_q, d, G, bits):
-    """Bytes the path must move for one unit in one decode step: every live K and V row once, each
-    token's (s1, s2) read and written once per SCORE_UPDATE_EVERY steps, the unit's queries and outputs,
-    the appended row."""
+    """Bytes the method itself must move for one unit in one decode step: every live K and V row once, each live
+    token's (s1, s2) read and written (16 bytes), its position and state (4 + 1 bytes), the unit's queries and
+    outputs, the appended row.  (The kernels move less than this: the score update is batched over 8 steps and
+    positions / states are not read during decode; the hardware counters under profiles/ show the real traffic.)"""
     c_o, c_q = kv_bytes_per_token(d, bits)
     n_live = n_o + n_q
-    return n_o * c_o + n_q * c_q + 16.0 * n_live / SCORE_UPDATE_EVERY + 2 * G * d * 2 + c_o
+    return n_o * c_o + n_q * c_q + 21.0 * n_live + 2 * G * d * 2 + c_o
 
 
 def stored_traffic(workload):
@@ -104,10 +102,11 @@ def cpu_baseline(wl, k, v, qw, dq, scale, rho, seconds_budget=12.0):
 
 
 def quick_measure(wl, rho_force=None, steps=24, warmup=4, every_step=False, byte_budget=False, packed_weight=0,
-                  wg_target=0):
+                  wg_target=0, fill=False):
     """Prefill + commit + a short timed decode run of one workload (all its layers); returns steps/s per
     layer-batch, the attention kernel's average duration and its algorithmic bytes.  Used for the policy
-    and workload variants; the headline run in main() is more thorough."""
+    and workload variants; the headline run in main() is more thorough.  fill: first step the caches (untimed)
+    up to just before their next tailor, so that the timed steps see a cache at capacity."""
     import numpy as np
     import torch
     from paper_2603_08727_amd import binding as A
@@ -137,6 +136,10 @@ def quick_measure(wl, rho_force=None, steps=24, warmup=4, every_step=False, byte
             A.arkv_prefill_commit(cache, l, k, v, T, rho[l])
             del k, v, qw
         total = warmup + 2 * steps
+        n_fill = 0
+        if fill:
+            live = A.arkv_cache_progress(cache, 0)[1]
+            n_fill = max(0, wl.capacity - 2 - live - total)          # the timed steps end one step short of the tailor
         per_layer = [synth.decode_inputs(wl, l, total, device=dev) for l in range(L)]
         q_all = torch.stack([p[0] for p in per_layer], dim=1).contiguous()
         kn_all = torch.stack([p[1] for p in per_layer], dim=1).contiguous()
@@ -152,13 +155,15 @@ def quick_measure(wl, rho_force=None, steps=24, warmup=4, every_step=False, byte
         def run(n):
             nonlocal t_i
             for _ in range(n):
+                t = t_i % total                       # (the filling steps reuse the drawn inputs)
                 for l in range(L):
-                    rc = lib.arkv_decode_step(cache, l, qp + (t_i * L + l) * qs_, kp + (t_i * L + l) * ks_,
-                                              vp + (t_i * L + l) * ks_, float(scales[l]), op + l * os_, stream)
+                    rc = lib.arkv_decode_step(cache, l, qp + (t * L + l) * qs_, kp + (t * L + l) * ks_,
+                                              vp + (t * L + l) * ks_, float(scales[l]), op + l * os_, stream)
                     if rc != 0:
                         raise A.ArkvError(rc, "arkv_decode_step")
                 t_i += 1
 
+        run(n_fill)
         run(warmup)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -181,7 +186,8 @@ def quick_measure(wl, rho_force=None, steps=24, warmup=4, every_step=False, byte
                 "frac_of_hbm_peak": round(bpl / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
                 "tokens_per_unit": {"original": round(float(no), 1), "quantized": round(float(nq), 1)},
                 "capacity_tokens": wl.capacity, "context": T, "n_layers": L, "batch": B, "quant_bits": wl.bits,
-                "us_per_call": round(dt / (L * steps) * 1e6, 2), "tailor_every_step": bool(every_step)}
+                "us_per_call": round(dt / (L * steps) * 1e6, 2), "tailor_every_step": bool(every_step),
+                "tailors_so_far_layer0": A.arkv_cache_progress(cache, 0)[0]}
     finally:
         A.arkv_cache_destroy(cache)
 
@@ -288,6 +294,8 @@ def main():
     ap.add_argument("--prefill", type=int, default=None, help="override the prompt length (debug)")
     ap.add_argument("--budget", type=float, default=None, help="override the budget fraction (debug)")
     ap.add_argument("--rho", type=float, default=None, help="force every layer's OQ ratio (variant runs)")
+    ap.add_argument("--alpha", type=float, default=None, help="override the slack factor (debug, ceiling runs)")
+    ap.add_argument("--bits", type=int, default=None, help="override the Quantized format: 2, 4 or 8 (variant runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=8)
     ap.add_argument("--no-tailor-run", action="store_true", help="skip stepping 4 layers up to their next tailor")
@@ -314,6 +322,10 @@ def main():
         wl = wl.scaled(prefill=args.prefill)
     if args.budget:
         wl = wl.scaled(budget_frac=args.budget)
+    if args.alpha:
+        wl = wl.scaled(alpha=args.alpha)
+    if args.bits:
+        wl = wl.scaled(bits=args.bits)
     if args.attention_only:
         print(json.dumps({"prefill_attention": attention_measure(wl), "workload": wl.name}))
         return
@@ -457,6 +469,11 @@ def main():
     roofline = {"bound": "hbm", "kernel": "k_decode_attend", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": stored_traffic(wl.name),
                 "avg_kernel_us": round(att_us, 2), "launches_timed": int(att_n),
+                "avg_kernel_us_clock": "HIP event pair around every launch of the kernel on the launch stream "
+                                       "(arkv_debug_time_attend); agrees with rocprofv3's kernel trace.  It may exceed "
+                                       "step.us_per_layer_batch_call (stream time per call without events): an event "
+                                       "pair costs ~2 us that back-to-back launches do not pay, and consecutive "
+                                       "launches overlap their start-up with the previous launch's tail",
                 "algorithmic_bytes_per_launch": int(bytes_per_launch),
                 "tokens_per_unit": {"original": round(float(mean_no), 1), "quantized": round(float(mean_nq), 1)}}
     # whole-step view: algorithmic bytes of a layer-batch call over its wall time in the timed region
@@ -589,8 +606,15 @@ def main():
             "arkv_mixed_rho0.5_fp8_rows": quick_measure(base12.scaled(bits=8), rho_force=0.5),
             "arkv_mixed_rho0.5_byte_budget": quick_measure(base12, rho_force=0.5, byte_budget=True),
             "arkv_scored_rho_tailor_every_step": quick_measure(base12.scaled(n_layers=4), every_step=True),
-            # ceiling run of the packed-row stream: almost the whole 32K prompt kept, all of it Quantized
+            # the paper's composition (Table VII: Quantized tokens = 14.4 % of the budget): n_q = 0.144 N = 1180 of
+            # the b = 6120 survivors, i.e. rho = (6120 - 1180) / 8160
+            "arkv_paper_like_composition_rho0.605": quick_measure(base12, rho_force=0.6054),
+            # cache at capacity (just before a tailor) at rho = 0.5: 8190 tokens per unit, 2040 of them Quantized
+            "arkv_mixed_rho0.5_at_capacity": quick_measure(base12, rho_force=0.5, fill=True),
+            # ceiling runs of the packed-row stream: almost the whole 32K prompt kept, all of it Quantized
             "ceiling_all_quantized_32k": quick_measure(base12.scaled(n_layers=6, budget_frac=0.99, alpha=0.99), rho_force=0.0),
+            "ceiling_all_quantized_32k_fp8_rows": quick_measure(base12.scaled(n_layers=6, budget_frac=0.99, alpha=0.99, bits=8), rho_force=0.0),
+            "ceiling_all_quantized_32k_2bit_rows": quick_measure(base12.scaled(n_layers=6, budget_frac=0.99, alpha=0.99, bits=2), rho_force=0.0),
         }
         ref = pol["base_full_cache"]["steps_per_s_per_layer_batch"]
         for v_ in pol.values():
@@ -599,7 +623,8 @@ def main():
         # the other decode configurations (8 layers each), same measurement
         result["other_workloads"] = {
             "c2_llama3_8b_8k": quick_measure(synth.C2.scaled(n_layers=8)),
-            "c4_llama3_8b_128k_2bit": quick_measure(synth.C4.scaled(n_layers=8)),
+            "c4_llama3_8b_128k_2bit": quick_measure(synth.C4),          # all 32 layers (the first 8 hold no Quantized rows)
+            "c4_llama3_8b_128k_2bit_rho0.5": quick_measure(synth.C4.scaled(n_layers=8), rho_force=0.5),
             "c4_shape_all_original_100pct": quick_measure(synth.C4.scaled(n_layers=4, budget_frac=(synth.C4.prefill + 128) / synth.C4.prefill)),
         }
     if not args.no_variants:

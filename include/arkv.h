@@ -232,7 +232,7 @@ int arkv_debug_attend_time(arkv_cache* cache, double* total_ms, int64_t* launche
 
 /* Measurement hook: launch shape of the kernels, for sweeps.  wg_target: workgroups a decode launch aims at
  * when it picks its split-K factor (default 512 = two per compute unit); packed_weight: cost of a packed row in
- * sixteenths of a bf16 row when rows are dealt to the splits (default 14); prefill_chunk: keys per workgroup of
+ * sixteenths of a bf16 row when rows are dealt to the splits (default 10); prefill_chunk: keys per workgroup of
  * the prefill scorer (multiple of 128, default 1024).  A value <= 0 leaves that setting as it is.  Results do
  * not depend on these beyond the order of floating-point additions. */
 int arkv_debug_set_launch_shape(arkv_cache* cache, int32_t wg_target, int32_t packed_weight, int32_t prefill_chunk);

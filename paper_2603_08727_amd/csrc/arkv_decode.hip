@@ -450,17 +450,20 @@ template <int G> struct PendingShape {
 };
 template <int D, int G>
 struct PendingLds {
-  uint16_t q[PendingShape<G>::ROUNDS][16][D];    // round r's operand rows (bf16)
-  uint16_t qp[PendingShape<G>::ROUNDS][16][D];   // the same rows as the grouped packed formats want them (permute_for_codes)
-  float qs[PendingShape<G>::ROUNDS][D / 32][16]; // ... and each row's channel sums per group of 32
+  // index ROUNDS of qp / qs: the query of the step in flight (rows 0 .. G-1), so that launches that update the
+  // scores need not hold its packed-format operands in registers
+  uint16_t q[PendingShape<G>::ROUNDS][16][D];        // round r's operand rows (bf16)
+  uint16_t qp[PendingShape<G>::ROUNDS + 1][16][D];   // the same rows as the grouped packed formats want them (permute_for_codes)
+  float qs[PendingShape<G>::ROUNDS + 1][D / 32][16]; // ... and each row's channel sums per group of 32
   float2 fin[kRing - 1][G];                      // a waiting step's final (max, 1/sum) per head
   float scale[kRing - 1];                        // its softmax scale * log2(e)
 };
 
-// All threads of the workgroup; ends with a barrier.  packed: also prepare qp / qs (waves 0 .. ROUNDS-1, one round each).
+// All threads of the workgroup; ends with a barrier.  packed: also prepare qp / qs, a round per wave; q_now (may be
+// null): this step's query rows [G][D], prepared as index ROUNDS.
 template <int D, int G>
 __device__ __forceinline__ void stage_pending(const Pools& P, int gu, int n, int slot, PendingLds<D, G>& sm, int tid,
-                                              int nthreads, bool packed) {
+                                              int nthreads, bool packed, const uint16_t* q_now = nullptr) {
   using PS = PendingShape<G>;
   constexpr int KK = D / 32;
   const size_t LU = P.fin_stride / G;
@@ -482,12 +485,18 @@ __device__ __forceinline__ void stage_pending(const Pools& P, int gu, int n, int
   }
   __syncthreads();
   if (packed) {
-    const int lane = tid & 63, r = tid >> 6, tok = lane & 15, blk = lane >> 4;
-    if (r < PS::ROUNDS) {
-      const uint4 ones = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
+    const int lane = tid & 63, tok = lane & 15, blk = lane >> 4;
+    const uint4 ones = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
+    for (int r = tid >> 6; r < PS::ROUNDS + (q_now ? 1 : 0); r += nthreads >> 6) {
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) {
-        const uint4 qo = *reinterpret_cast<const uint4*>(&sm.q[r][tok][32 * kk + 8 * blk]);
+        uint4 qo;
+        if (r < PS::ROUNDS) {
+          qo = *reinterpret_cast<const uint4*>(&sm.q[r][tok][32 * kk + 8 * blk]);
+        } else {
+          const uint4 v = *reinterpret_cast<const uint4*>(q_now + (size_t)(tok < G ? tok : 0) * D + 32 * kk + 8 * blk);
+          qo = tok < G ? v : make_uint4(0, 0, 0, 0);
+        }
         f32x4 C = {0.f, 0.f, 0.f, 0.f};
         C = mfma16(qo, ones, C);                      // every column: the rows' sums over this group's channels
         *reinterpret_cast<uint4*>(&sm.qp[r][tok][32 * kk + 8 * blk]) = permute_for_codes(qo);
@@ -697,8 +706,17 @@ __device__ __forceinline__ void combine_splits(const Pools& P, const DecodeLaunc
 // 64/(D/8) rows), where PV of the bf16 rows runs on the vector ALU (HBM-bound as it is); packed rows take
 // PV to the matrix cores (ValueFmt).  The softmax reference maximum is only moved when a logit of a bf16
 // row exceeds it by more than 8 (base-2 units), which is rare, so the accumulators are almost never rescaled.
+// What a workgroup needs before it can request its first tile, packed together at the front of the launch
+// arguments so that it arrives in one round trip of the scalar cache (copies of fields of Pools / DecodeLaunch).
+struct DecodeHot {
+  const uint16_t* ok; const uint16_t* ov; float2* oacc; float2* qacc; const uint16_t* q;
+  size_t fin_stride;
+  int capO, capQ, splits, wq, known, npend, upl, ubeg;
+  unsigned inv_s, inv_wq;
+};
+
 template <int D, int G, int BITS, bool FOLD>
-__global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch L) {
+__global__ __launch_bounds__(256, 2) void k_decode_attend(DecodeHot H, Pools P, DecodeLaunch L) {
   constexpr int KK = D / 32;           // MFMA k-steps = quantisation groups per row
   constexpr int LPR = D / 8;           // lanes per value row
   constexpr int R = 64 / LPR;          // value rows per wave load
@@ -721,11 +739,15 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   __shared__ __align__(16) float sm_a[4][RP][G][D];
   __shared__ float sm_m[4][G], sm_l[4][G];
   __shared__ float sm_fo[4][G];                        // factor the parked Original-row sums still have to take
-  __shared__ __align__(16) float sm_q[4][G][D];        // the waves' sums over packed rows
+  // the waves' sums over packed rows; launches that update the scores put them where the waiting steps' state was
+  // (sm_pend: dead by then, a barrier separates the two uses), which keeps two workgroups per compute unit
+  __shared__ __align__(16) float sm_q_own[FOLD ? 1 : 4][FOLD ? 1 : G][FOLD ? 4 : D];
   __shared__ __align__(16) _Float16 sm_p[4][16][kVBlock];   // a block's probabilities, [head][token], rows >= G zero
   __shared__ _Float16 sm_pdump[4][16][8];
   __shared__ int sm_last;
-  __shared__ PendingLds<D, G> sm_pend;   // only touched when FOLD
+  __shared__ __align__(16) PendingLds<D, G> sm_pend;   // only touched when FOLD (16-byte alignment: its rows are read as 16-byte vectors)
+  static_assert(!FOLD || sizeof(PendingLds<D, G>) >= sizeof(float) * 4 * G * D, "the packed rows' sums must fit the waiting steps' state");
+  float (*sm_q)[G][D] = FOLD ? reinterpret_cast<float (*)[G][D]>(&sm_pend) : reinterpret_cast<float (*)[G][D]>(&sm_q_own[0][0][0]);
 
   // Everything the first tile request depends on is read from the launch arguments in ONE batch of scalar
   // loads (the empty asm pins the values here); left to itself the compiler fetches each where it is first
@@ -734,16 +756,16 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   // wait for units_per_layer, and every launch argument is requested in the same batch)
   const int lk = blockIdx.y < (unsigned)kMaxUnitsKnown ? (int)blockIdx.y : 0;
   int cO = L.cnt_o[lk], cQ = L.cnt_q[lk];
-  const int known = L.cnt_known, wq = L.wq, splits = L.splits, npend = L.n_pending;
-  const int capO = P.capO, capQ = P.capQ;
-  const size_t fin_stride = P.fin_stride;
-  const uint16_t* const pok = P.ok;
-  const uint16_t* const pov = P.ov;
-  float2* const poacc = P.oacc;
-  float2* const pqacc = P.qacc;
-  const uint16_t* const pq = L.q;
-  const int upl = L.units_per_layer, ubeg = L.unit_begin;
-  const unsigned inv_s = L.inv_splits, inv_wq = L.inv_wq;
+  const int known = H.known, wq = H.wq, splits = H.splits, npend = H.npend;
+  const int capO = H.capO, capQ = H.capQ;
+  const size_t fin_stride = H.fin_stride;
+  const uint16_t* const pok = H.ok;
+  const uint16_t* const pov = H.ov;
+  float2* const poacc = H.oacc;
+  float2* const pqacc = H.qacc;
+  const uint16_t* const pq = H.q;
+  const int upl = H.upl, ubeg = H.ubeg;
+  const unsigned inv_s = H.inv_s, inv_wq = H.inv_wq;
   const float scale2 = L.scale2[blockIdx.z];
   asm volatile("" ::"s"(cO), "s"(cQ), "s"(known), "s"(wq), "s"(splits), "s"(npend), "s"(capO), "s"(capQ),
                "s"(fin_stride), "s"(pok), "s"(pov), "s"(poacc), "s"(pqacc), "s"(pq), "s"(upl), "s"(ubeg), "s"(inv_s),
@@ -788,7 +810,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   // this step's query; on a launch that also updates the scores, the waiting steps' state goes to LDS
   uint4 qa[KK];
   load_query<D, G>(pq + (size_t)lu * G * D, lane, qa);
-  if constexpr (FOLD) stage_pending<D, G>(P, gu, npend, L.slot, sm_pend, tid, 256, BITS != 8 && cQ > 0);
+  if constexpr (FOLD) stage_pending<D, G>(P, gu, npend, L.slot, sm_pend, tid, 256, BITS != 8 && cQ > 0, pq + (size_t)lu * G * D);
 
   float Mreg[HPL], lsum[HPL], acc[G][8];
 #pragma unroll
@@ -894,7 +916,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
 
   TRACE(2);
   // ---------------- the token being generated (last split; wave 3 has the fewest tiles) ----------------
-  if (s == L.splits - 1 && w == 3) {
+  if (s == splits - 1 && w == 3) {
     const uint16_t* kn = L.k_new + (size_t)lu * D;
     const uint16_t* vn = L.v_new + (size_t)lu * D;
     uint4 kb[KK];
@@ -962,15 +984,18 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   // matrix cores from the token-minor value blocks (ValueFmt).  Probabilities are at most 1 here (the reference
   // maximum follows every new maximum), so that probability * scale cannot overflow fp16.
   const bool hasq = aq < bq;                 // uniform over the workgroup
-  if (hasq) {
+  if (__builtin_expect(hasq, 0)) {           // (out of line: most workgroups of a mixed cache hold bf16 rows only)
     using Fmt = PackedFmt<D, HPL, BITS>;
     using VF = ValueFmt<D, BITS>;
     const uint8_t* kc = P.qkc + (size_t)gu * P.capQ * Fmt::CB;
     const uint32_t* km = P.qkm + (size_t)gu * P.capQ * Fmt::NG;
     const uint8_t* vc = P.qvc + (size_t)gu * P.capQv * VF::CB;
     const uint16_t* vm = P.qvm + (size_t)gu * P.capQv * VF::MH;
+    // launches that also update the scores (grouped formats) read this step's prepared query from LDS, next to the
+    // waiting steps' (PendingLds index ROUNDS); the others keep it in registers
+    constexpr bool kQueryInLds = FOLD && BITS != 8;
     typename Fmt::Query pqa;
-    Fmt::prep(qa, pqa);
+    if constexpr (!kQueryInLds) Fmt::prep(qa, pqa);
     // rows of the probability buffer that no head fills stay zero
     *reinterpret_cast<uint4*>(&sm_p[w][lane >> 2][8 * (lane & 3)]) = make_uint4(0, 0, 0, 0);
     constexpr int RPG = VF::template rpg<G>(), GPA = VF::template gpa<G>(), NA = VF::template na<G>();
@@ -1011,7 +1036,10 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
       for (int tl = 0; tl < 2; ++tl) {
         const int row = kVBlock * b32 + 16 * tl + tok;
         own[tl] = (row < bq) && active;
-        Fmt::dots(pqa, t.k[tl], x[tl]);
+        if constexpr (kQueryInLds)
+          Fmt::dots_pending(sm_pend.qp[PendingShape<G>::ROUNDS], sm_pend.qs[PendingShape<G>::ROUNDS], t.k[tl], tok, blk, x[tl]);
+        else
+          Fmt::dots(pqa, t.k[tl], x[tl]);
 #pragma unroll
         for (int i = 0; i < HPL; ++i) x[tl][i] = own[tl] ? x[tl][i] * scale2 : kNegBig;
         if constexpr (FOLD) {
@@ -1088,6 +1116,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
       compute_q(qa_, b32);
       if (b32 + 4 <= blast) compute_q(qb_, b32 + 4);
     }
+    if constexpr (FOLD) __syncthreads();      // every wave is done with the waiting steps' state (hasq is uniform)
     // accumulators -> channel sums: take the code offset out (1024 * sum of the A operand), undo the code's
     // position in its byte, add the zero points' share (column g of the correction MFMA, whose rows are the heads)
 #pragma unroll
@@ -1160,7 +1189,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(Pools P, DecodeLaunch 
   if (tid == 0) {
     int* const ticket = P.ticket + (gu - L.part_unit0);
     const int old = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const int last = old == L.splits - 1;
+    const int last = old == splits - 1;
     if (last) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
     sm_last = last;
   }
@@ -1176,7 +1205,7 @@ template <int D, int G, int BITS>
 __global__ __launch_bounds__(256) void k_flush_scores(Pools P, int unit_begin, int n_pending, int slot) {
   constexpr int KK = D / 32;
   constexpr int HPL = G < 4 ? G : 4;
-  __shared__ PendingLds<D, G> sm_pend;
+  __shared__ __align__(16) PendingLds<D, G> sm_pend;
   const int gu = unit_begin + blockIdx.y;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int tok = lane & 15, blk = lane >> 4;
@@ -1234,8 +1263,13 @@ static hipError_t launch_decode_t(const Pools& P, const DecodeLaunch& a, hipStre
 #ifdef ARKV_PHASE_TRACE
   hipLaunchKernelGGL(k_trace_mark, dim3(1), dim3(64), 0, s, 0);
 #endif
-  if (a.fold) hipLaunchKernelGGL((k_decode_attend<D, G, BITS, true>), grid, dim3(256), 0, s, P, a);
-  else hipLaunchKernelGGL((k_decode_attend<D, G, BITS, false>), grid, dim3(256), 0, s, P, a);
+  DecodeHot h;
+  h.ok = P.ok; h.ov = P.ov; h.oacc = P.oacc; h.qacc = P.qacc; h.q = a.q;
+  h.fin_stride = P.fin_stride;
+  h.capO = P.capO; h.capQ = P.capQ; h.splits = a.splits; h.wq = a.wq; h.known = a.cnt_known; h.npend = a.n_pending;
+  h.upl = a.units_per_layer; h.ubeg = a.unit_begin; h.inv_s = a.inv_splits; h.inv_wq = a.inv_wq;
+  if (a.fold) hipLaunchKernelGGL((k_decode_attend<D, G, BITS, true>), grid, dim3(256), 0, s, h, P, a);
+  else hipLaunchKernelGGL((k_decode_attend<D, G, BITS, false>), grid, dim3(256), 0, s, h, P, a);
 #ifdef ARKV_PHASE_TRACE
   hipLaunchKernelGGL(k_trace_mark, dim3(1), dim3(64), 0, s, 1);
 #endif

@@ -65,7 +65,7 @@ struct arkv_cache {
   // measurement hook: events around the attention kernel
   int prefill_chunk = 1024; // keys per workgroup of the prefill scorer (halved while the grid would be small)
   int wg_target = 512;      // workgroups per decode launch the split-K factor aims at
-  int wq = 14;              // measured: a packed row costs nearly as much time as a bf16 row in the attention kernel
+  int wq = 10;              // measured cost of a packed row in sixteenths of a bf16 row (mixed caches: 8 to 14 within 1 %)
   float* attn_outf = nullptr;   // parity hook: fp32 copy of the prefill attention's output (caller's device buffer)
   bool timing = false;
   std::vector<hipEvent_t> ev_pool;   // pairs, reused after every read
