@@ -300,6 +300,9 @@ def main():
     ap.add_argument("--profile-steps", type=int, default=8)
     ap.add_argument("--no-tailor-run", action="store_true", help="skip stepping 4 layers up to their next tailor")
     ap.add_argument("--no-variants", action="store_true", help="skip the policy / other-workload variant runs")
+    ap.add_argument("--scorer-only", type=int, default=0, metavar="W",
+                    help="time only the prefill scorer of the scorer-stress configuration with an observation window of W "
+                         "tokens and print that entry (profiling runs)")
     ap.add_argument("--attention-only", action="store_true",
                     help="time only the causal prefill attention of the workload's prompt and print that entry")
     args = ap.parse_args()
@@ -326,6 +329,9 @@ def main():
         wl = wl.scaled(alpha=args.alpha)
     if args.bits:
         wl = wl.scaled(bits=args.bits)
+    if args.scorer_only:
+        print(json.dumps({"scorer_stress": scorer_measure(synth.C5, args.scorer_only), "workload": synth.C5.name}))
+        return
     if args.attention_only:
         print(json.dumps({"prefill_attention": attention_measure(wl), "workload": wl.name}))
         return
