@@ -2,8 +2,9 @@
 //   k_decode_attend : append + split-K attention of one query per head over the bf16 pool and the
 //                     packed pool (dequantisation inside the QK and PV loops)
 //                     + the merge of the split-K partials by the unit's last workgroup (partials
-//                     move through device-scope atomics; a device-scope fence per workgroup instead
-//                     was measured 3-6x slower, a second kernel costs a launch gap per step)
+//                     move through device-scope atomics, see st_dev2; a device-scope fence per
+//                     workgroup instead was measured 3-6x slower, a second kernel costs a launch gap
+//                     per step)
 //                     + on every (kRing-1)-th launch the score update (Eq. 9) of the steps since the
 //                     last one: a step's probabilities need its final softmax denominator, which
 //                     only exists after the merge, so they are formed later, from the step's stored
@@ -174,7 +175,8 @@ __device__ __forceinline__ f32x4 dots_bf16(const uint4 (&qa)[KK], const uint4 (&
 // ---- packed row formats -------------------------------------------------------------------------
 // PackedFmt<D, HPL, BITS> gives the attention loop what it needs of a Quantized row: what to keep of a
 // query, how lane (token lane%16, block lane/16) loads the key codes of row rk and turns them into the
-// token's HPL dot products, and how lane (row, 8-channel chunk `sub`) loads and decodes values.
+// token's HPL dot products (one 16-byte load per lane: a row's key chunks are stored [lane block][k-step]).
+// Values are ValueFmt's business, further down.
 //
 // BITS = 2, 4: uniform codes, groups of 32 channels, fp16 scale and zero per group.  Codes are OR-ed into
 // bf16 "128 + code" operands, one MFMA per group; scale, zero and the 128 offset are applied to the
@@ -568,6 +570,14 @@ extern "C" int arkv_debug_trace_dump_m(unsigned long long* host, int n_wg) {
 // Split-K partials cross workgroups that may sit on different XCDs, whose L2 caches are not coherent
 // with each other for ordinary accesses.  They are therefore written and read with device-scope relaxed
 // atomics (write-through stores, loads that do not hit a stale L2 line); no cache-wide flush is needed.
+// What this rests on is the AMDGPU backend's documented memory model for the gfx942 family, which gfx950
+// belongs to: an agent-scope atomic store or load is a global access with sc1 set, which writes through to /
+// is served from the level at which the whole device is coherent, and an agent-scope read-modify-write is
+// performed at that level.  A release at agent scope is, by the same table, an L2 write-back followed by
+// s_waitcnt vmcnt(0), and an acquire an L2 invalidate; the write-back and the invalidate exist for data that
+// ordinary stores left dirty in, or ordinary loads pulled into, an XCD's L2.  Nothing the merge consumes is
+// written or read by ordinary accesses, so only the wait remains: a wave's partial stores are acknowledged
+// (s_waitcnt 0) before the workgroup's barrier, and the ticket is taken after the barrier.
 // (two adjacent floats, 8-byte aligned, per access)
 __device__ __forceinline__ void st_dev2(float* p, float a, float b) {
   __hip_atomic_store(reinterpret_cast<unsigned long long*>(p),
