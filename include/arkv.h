@@ -232,7 +232,8 @@ int arkv_debug_attend_time(arkv_cache* cache, double* total_ms, int64_t* launche
 
 /* Measurement hook: launch shape of the kernels, for sweeps.  wg_target: workgroups a decode launch aims at
  * when it picks its split-K factor (default 512 = two per compute unit); packed_weight: cost of a packed row in
- * sixteenths of a bf16 row when rows are dealt to the splits (default 10); prefill_chunk: keys per workgroup of
+ * sixteenths of a bf16 row when rows are dealt to the splits (default: 10, or 16 for launches of at most 256
+ * workgroups); prefill_chunk: keys per workgroup of
  * the prefill scorer (multiple of 128, default 1024).  A value <= 0 leaves that setting as it is.  Results do
  * not depend on these beyond the order of floating-point additions. */
 int arkv_debug_set_launch_shape(arkv_cache* cache, int32_t wg_target, int32_t packed_weight, int32_t prefill_chunk);
@@ -244,6 +245,20 @@ int arkv_debug_set_launch_shape(arkv_cache* cache, int32_t wg_target, int32_t pa
  * [1, 128], split outside [0, n_splits), packed_weight outside [1, 16]. */
 int arkv_debug_split_range(int32_t n_original, int32_t n_quantized, int32_t packed_weight, int32_t n_splits,
                            int32_t split, int32_t* range);
+
+/* Measurement hook of profiling builds (the library compiled with -DARKV_PHASE_TRACE, see the package's build
+ * script; the product build returns ARKV_EUNSUPPORTED and its kernels carry none of this).  In such a build
+ * thread 0 of every workgroup of the decode kernel stores the 100 MHz wall clock at its phase boundaries, and a
+ * one-wave marker kernel is launched before and after the decode kernel.  Copies to HOST memory (synchronous):
+ * which = 0: n_rows rows of 8 words, row = workgroup (unit-major, split-minor) of the latest decode launch:
+ *   start, first tile requested, bf16 rows done, new token done, packed rows done, partial stored, end, and the
+ *   XCC_ID hardware register (the XCD number is its low 4 bits); row 8190 holds the two markers' times in words 0 and 1;
+ * which = 1: the same rows for the merge inside the unit's last workgroup: entered, loads issued, weights
+ *   reduced, barrier passed, accumulated, stored (words 0..5; rows of other workgroups keep older values);
+ * which = 2: 4 words of the latest prefill-attention launch: shader clock and wall clock at the start and at the
+ *   end of workgroup (0, 0) (n_rows is ignored, pass 1).
+ * ARKV_EINVAL: null pointer, which outside 0..2, n_rows outside 1..8192. */
+int arkv_debug_phase_trace(int32_t which, unsigned long long* host_words, int32_t n_rows);
 
 /* Measurement hook: a plain streaming read (16 bytes per lane, nothing else) of bytes_per_launch bytes
  * per kernel launch, `launches` launches back to back on the stream, walking through the DEVICE buffer

@@ -22,7 +22,7 @@ EXPORTED = [
     "arkv_prefill_stats", "arkv_prefill_stats_lse", "arkv_prefill_attention", "arkv_oq_ratio", "arkv_budget_counts", "arkv_prefill_commit",
     "arkv_decode_step", "arkv_decode_step_static", "arkv_decode_step_layers", "arkv_cache_counters", "arkv_cache_export",
     "arkv_debug_last_tailor_scores", "arkv_debug_last_out_f32", "arkv_debug_prefill_attention_f32", "arkv_cache_progress",
-    "arkv_debug_time_attend", "arkv_debug_attend_time", "arkv_debug_set_launch_shape", "arkv_debug_stream_read", "arkv_debug_split_range",
+    "arkv_debug_time_attend", "arkv_debug_attend_time", "arkv_debug_set_launch_shape", "arkv_debug_stream_read", "arkv_debug_split_range", "arkv_debug_phase_trace",
     "arkv_strerror",
     "arkv_last_hip_error",
 ]
@@ -83,6 +83,7 @@ def load():
         "arkv_debug_set_launch_shape": (C.c_int, [vp, i32, i32, i32]),
         "arkv_debug_time_attend": (C.c_int, [vp, i32]),
         "arkv_debug_attend_time": (C.c_int, [vp, P(C.c_double), P(C.c_int64)]),
+        "arkv_debug_phase_trace": (C.c_int, [i32, vp, i32]),
         "arkv_debug_stream_read": (C.c_int, [vp, C.c_uint64, C.c_uint64, i32, i32, vp, P(C.c_float)]),
         "arkv_strerror": (C.c_char_p, [C.c_int]),
         "arkv_last_hip_error": (C.c_char_p, []),
@@ -300,6 +301,15 @@ def arkv_debug_attend_time(cache):
     ms, n = C.c_double(), C.c_int64()
     _check(load().arkv_debug_attend_time(cache, C.byref(ms), C.byref(n)), "arkv_debug_attend_time")
     return ms.value, n.value
+
+
+def arkv_debug_phase_trace(which: int, n_rows: int = 1):
+    """In-kernel timestamps of the latest launches (profiling builds only; ARKV_EUNSUPPORTED otherwise):
+    a uint64 array [n_rows][8] for which = 0 (decode phases) or 1 (merge phases), [4] for which = 2."""
+    import numpy as np
+    buf = np.zeros((max(n_rows, 1), 8), dtype=np.uint64)
+    _check(load().arkv_debug_phase_trace(which, buf.ctypes.data_as(C.c_void_p), n_rows), "arkv_debug_phase_trace")
+    return buf.reshape(-1)[:4] if which == 2 else buf
 
 
 def arkv_debug_stream_read(buf, bytes_per_launch: int, launches: int, pattern: int = 0) -> float:

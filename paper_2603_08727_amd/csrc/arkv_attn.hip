@@ -337,8 +337,16 @@ hipError_t launch_prefill_attn(const AttnLaunch& a, hipStream_t s) {
 
 }  // namespace arkv
 
+namespace arkv {
+// the prefill attention's four clock words (shader clock and 100 MHz counter at the start and the end of workgroup 0)
+hipError_t phase_trace_attn(unsigned long long* host, bool* built) {
 #ifdef ARKV_PHASE_TRACE
-extern "C" int arkv_debug_attn_clock(unsigned long long* host) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(arkv::g_attn_clock), 4 * sizeof(unsigned long long));
-}
+  *built = true;
+  return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_attn_clock), 4 * sizeof(unsigned long long));
+#else
+  (void)host;
+  *built = false;
+  return hipSuccess;
 #endif
+}
+}  // namespace arkv

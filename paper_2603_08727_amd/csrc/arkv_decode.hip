@@ -548,21 +548,24 @@ __device__ __forceinline__ float2 fold_pending(const PendingLds<D, G>& sm, int n
   return ac;
 }
 
-// Profiling builds (-DARKV_PHASE_TRACE) record a 100 MHz timestamp per workgroup at the phase boundaries
-// marked TRACE(i); arkv_debug_trace_dump copies them out.  Product builds compile none of it.
+// Profiling builds (-DARKV_PHASE_TRACE, which also turns on the merge's own marks) record a 100 MHz timestamp
+// per workgroup at the phase boundaries marked TRACE(i) / TRACE_M(i); arkv_debug_phase_trace copies them out.
+// Product builds compile none of it.
 #ifdef ARKV_PHASE_TRACE
+#define ARKV_PHASE_TRACE_MERGE
 __device__ unsigned long long g_trace[8192][8];
 #define TRACE(i) do { if (threadIdx.x == 0) g_trace[blockIdx.y * gridDim.x + blockIdx.x][i] = wall_clock64(); } while (0)
+// word 7 of a workgroup's row: the XCC_ID hardware register (id 20, all 32 bits; the XCD number is its low 4 bits)
+#define TRACE_XCD() do { if (threadIdx.x == 0) g_trace[blockIdx.y * gridDim.x + blockIdx.x][7] = \
+    (unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 20); } while (0)
 __global__ void k_trace_mark(int slot) { if (threadIdx.x == 0) g_trace[8190][slot] = wall_clock64(); }
 #else
 #define TRACE(i)
+#define TRACE_XCD()
 #endif
 #ifdef ARKV_PHASE_TRACE_MERGE
 __device__ unsigned long long g_trace_m[8192][8];
 #define TRACE_M(i) do { if (threadIdx.x == 0) g_trace_m[blockIdx.y * gridDim.x + blockIdx.x][i] = wall_clock64(); } while (0)
-extern "C" int arkv_debug_trace_dump_m(unsigned long long* host, int n_wg) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace_m), (size_t)n_wg * 8 * sizeof(unsigned long long));
-}
 #else
 #define TRACE_M(i)
 #endif
@@ -739,6 +742,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(DecodeHot H, Pools P, 
   const int vrow = lane / LPR, sub = lane % LPR;
   const bool active = blk < HB;
   TRACE(0);
+  TRACE_XCD();
 
   __shared__ __align__(16) float pbuf[4][16][G < 4 ? 4 : G];
   __shared__ __align__(16) float pspare[4][16][4];
@@ -1401,11 +1405,20 @@ __global__ __launch_bounds__(256) void k_stream_copy(uint4* __restrict__ buf, un
   }
 }
 
+// which: 0 = the decode kernel's phase marks, 1 = its merge marks; n_wg rows of 8 words each
+hipError_t phase_trace_decode(int which, unsigned long long* host, int n_wg, bool* built) {
 #ifdef ARKV_PHASE_TRACE
-extern "C" int arkv_debug_trace_dump(unsigned long long* host, int n_wg) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), (size_t)n_wg * 8 * sizeof(unsigned long long));
-}
+  *built = true;
+  if (n_wg < 0 || n_wg > 8192) return hipErrorInvalidValue;
+  const size_t bytes = (size_t)n_wg * 8 * sizeof(unsigned long long);
+  return which == 0 ? hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), bytes)
+                    : hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace_m), bytes);
+#else
+  (void)which; (void)host; (void)n_wg;
+  *built = false;
+  return hipSuccess;
 #endif
+}
 
 hipError_t launch_stream_read(const void* buf, size_t offset_bytes, size_t bytes, int pattern, unsigned* sink, hipStream_t s) {
   if (pattern == 2) {

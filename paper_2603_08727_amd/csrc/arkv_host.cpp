@@ -65,7 +65,7 @@ struct arkv_cache {
   // measurement hook: events around the attention kernel
   int prefill_chunk = 1024; // keys per workgroup of the prefill scorer (halved while the grid would be small)
   int wg_target = 512;      // workgroups per decode launch the split-K factor aims at
-  int wq = 10;              // measured cost of a packed row in sixteenths of a bf16 row (mixed caches: 8 to 14 within 1 %)
+  int wq = 0;               // cost of a packed row in sixteenths of a bf16 row; 0 = by launch shape (decode_impl)
   float* attn_outf = nullptr;   // parity hook: fp32 copy of the prefill attention's output (caller's device buffer)
   bool timing = false;
   std::vector<hipEvent_t> ev_pool;   // pairs, reused after every read
@@ -478,7 +478,6 @@ static int decode_impl(arkv_cache* c, int32_t layer_begin, int32_t n, const void
   if (splits > 32) splits = (splits + 1) / 2;
   splits = std::min(splits, std::max(1, l0.live / 128));
   a.splits = std::max(1, std::min(splits, c->P.max_splits));
-  a.wq = c->wq;
   a.part_unit0 = 0;
   Pools pools = c->P;                 // by value: the launch may point the split-K scratch elsewhere
   if (static_scratch) {
@@ -491,6 +490,11 @@ static int decode_impl(arkv_cache* c, int32_t layer_begin, int32_t n, const void
     pools.part = sp; pools.ticket = stk; pools.max_splits = a.splits;
     a.part_unit0 = a.unit_begin;
   }
+  // Measured cost of a packed row in sixteenths of a bf16 row.  With two workgroups per CU the bf16 rows stream
+  // at the HBM limit and a packed row costs about 10/16 of one (8 to 14 measure within 1 %); with one workgroup
+  // per CU (few units) the bf16 rows are not bandwidth-bound and a packed row costs as much as a bf16 row
+  // (128K-context shape, 8 units: 18.1 us per launch at 16 against 19.4 at 10).
+  a.wq = c->wq > 0 ? c->wq : (a.splits * a.n_units <= 256 ? 16 : 10);
   { const SplitRecip rc = split_recip(a.splits, a.wq); a.inv_splits = rc.inv_s; a.inv_wq = rc.inv_wq; }
   for (int i = 0; i < n; ++i) {
     LayerState& li = c->layers[(size_t)(layer_begin + i)];
@@ -792,6 +796,15 @@ int arkv_debug_stream_read(void* buf, uint64_t buf_bytes, uint64_t bytes_per_lau
   if (e1) (void)hipEventDestroy(e1);
   if (sink) (void)hipFree(sink);
   return e == hipSuccess ? ARKV_OK : hip_fail(e, "arkv_debug_stream_read");
+}
+
+int arkv_debug_phase_trace(int32_t which, unsigned long long* host_words, int32_t n_rows) {
+  if (!host_words || which < 0 || which > 2 || n_rows < 1 || n_rows > 8192) return ARKV_EINVAL;
+  bool built = false;
+  const hipError_t e = which == 2 ? phase_trace_attn(host_words, &built)
+                                  : phase_trace_decode(which, host_words, n_rows, &built);
+  if (!built) return ARKV_EUNSUPPORTED;
+  return e == hipSuccess ? ARKV_OK : hip_fail(e, "arkv_debug_phase_trace");
 }
 
 const char* arkv_strerror(int code) {

@@ -22,6 +22,15 @@ def test_library_exports_every_declared_symbol():
     assert declared == set(A.EXPORTED)
 
 
+def test_phase_trace_hook_is_off_in_the_product_build():
+    import ctypes as C
+    buf = (C.c_uint64 * 8)()
+    lib = A.load()
+    assert lib.arkv_debug_phase_trace(0, buf, 1) == A.EUNSUPPORTED
+    assert lib.arkv_debug_phase_trace(3, buf, 1) == A.EINVAL and lib.arkv_debug_phase_trace(0, None, 1) == A.EINVAL
+    assert lib.arkv_debug_phase_trace(0, buf, 0) == A.EINVAL and lib.arkv_debug_phase_trace(0, buf, 8193) == A.EINVAL
+
+
 def test_strerror_and_defaults():
     assert A.strerror(0) == "ok" and "invalid" in A.strerror(A.EINVAL)
     cfg = A.arkv_config_default()
