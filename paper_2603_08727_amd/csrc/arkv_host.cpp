@@ -64,6 +64,7 @@ struct arkv_cache {
   hipStream_t last_stream = nullptr;
   // measurement hook: events around the attention kernel
   int prefill_chunk = 1024; // keys per workgroup of the prefill scorer (halved while the grid would be small)
+  bool prefill_chunk_fixed = false;   // set through the launch-shape hook: taken as it is
   int wg_target = 512;      // workgroups per decode launch the split-K factor aims at
   int wq = 0;               // cost of a packed row in sixteenths of a bf16 row; 0 = by launch shape (decode_impl)
   float* attn_outf = nullptr;   // parity hook: fp32 copy of the prefill attention's output (caller's device buffer)
@@ -314,7 +315,7 @@ static int run_scorer(arkv_cache* c, int32_t layer, const uint16_t* q_win, size_
   int rc;
   if ((rc = grow(&ls.pre, &ls.pre_cap, (size_t)U * T)) != ARKV_OK) return rc;
   int chunk = c->prefill_chunk;
-  while (chunk > 128 && (size_t)((T + chunk - 1) / chunk) * U < 1024) chunk >>= 1;
+  while (!c->prefill_chunk_fixed && chunk > 128 && (size_t)((T + chunk - 1) / chunk) * U < 1024) chunk >>= 1;
   const int n_chunks = (T + chunk - 1) / chunk;
   int MP = 32;
   while (MP < G * W) MP *= 2;
@@ -743,7 +744,7 @@ int arkv_debug_set_launch_shape(arkv_cache* c, int32_t wg_target, int32_t packed
   if (!c || packed_weight > 16 || (prefill_chunk > 0 && (prefill_chunk % 128 != 0 || prefill_chunk > 8192))) return ARKV_EINVAL;
   if (wg_target > 0) c->wg_target = wg_target;
   if (packed_weight > 0) c->wq = packed_weight;
-  if (prefill_chunk > 0) c->prefill_chunk = prefill_chunk;
+  if (prefill_chunk > 0) { c->prefill_chunk = prefill_chunk; c->prefill_chunk_fixed = true; }
   return ARKV_OK;
 }
 

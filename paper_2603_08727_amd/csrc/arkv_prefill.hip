@@ -11,12 +11,15 @@
 //   k_prefill_stats    per sequence: p_k over keys < T-W aggregated over all heads, entropy,
 //                      variance, kurtosis (fp64 reductions; the normaliser's partial sums come from
 //                      k_prefill_cols, the last workgroup of a sequence finishes)
+#include <type_traits>
+
 #include "arkv_dev.h"
 
 namespace arkv {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float kNegBigP = -1.0e30f;
 
@@ -40,95 +43,172 @@ __device__ __forceinline__ float sum32(float x) {
 
 // Stage the unit's query rows in LDS: row r = (head r / W, window query r % W) at byte r*(2D+16), rows >= M
 // zero.  q points at the unit's first head; heads are head_stride elements apart.
-template <int D>
+template <int D, int NT>
 __device__ __forceinline__ void stage_q(unsigned char* sm, const uint16_t* q, size_t head_stride, int W, int M, int MP) {
   constexpr int RB = 2 * D + 16;
   constexpr int VPR = D / 8;  // uint4 per row
-  for (int i = threadIdx.x; i < MP * VPR; i += 256) {
-    const int r = i / VPR, c = i % VPR;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (r < M) v = *reinterpret_cast<const uint4*>(q + (size_t)(r / W) * head_stride + (size_t)(r % W) * D + c * 8);
-    *reinterpret_cast<uint4*>(sm + (size_t)r * RB + c * 16) = v;
-  }
-}
-
-// Logits of one 32-key tile against row tile rt: C[i] at key j0 + 8(i/4) + 4(lane/32) + i%4, row rt*32 + lane%32.
-template <int D>
-__device__ __forceinline__ f32x16 tile_logits(const uint4 (&kf)[D / 16], const unsigned char* sm, int rt, int lane) {
-  constexpr int RB = 2 * D + 16;
-  f32x16 C = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-  const unsigned char* qrow = sm + (size_t)(rt * 32 + (lane & 31)) * RB + (lane >> 5) * 16;
+  constexpr int BATCH = 8;    // loads in flight per thread (one at a time, every load costs a memory round trip)
+  for (int i0 = threadIdx.x; i0 < MP * VPR; i0 += NT * BATCH) {
+    uint4 v[BATCH];
 #pragma unroll
-  for (int kk = 0; kk < D / 16; ++kk) {
-    const uint4 qb = *reinterpret_cast<const uint4*>(qrow + kk * 32);
-    C = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[kk]), __builtin_bit_cast(bf16x8, qb), C, 0, 0, 0);
+    for (int b = 0; b < BATCH; ++b) {
+      const int i = i0 + b * NT, r = i / VPR, c = i % VPR;
+      v[b] = make_uint4(0, 0, 0, 0);
+      if (r < M) v[b] = *reinterpret_cast<const uint4*>(q + (size_t)(r / W) * head_stride + (size_t)(r % W) * D + c * 8);
+    }
+#pragma unroll
+    for (int b = 0; b < BATCH; ++b) {
+      const int i = i0 + b * NT, r = i / VPR, c = i % VPR;
+      if (i < MP * VPR) *reinterpret_cast<uint4*>(sm + (size_t)r * RB + c * 16) = v[b];
+    }
   }
-  return C;
 }
 
 template <int D>
-__device__ __forceinline__ void load_keys(uint4 (&kf)[D / 16], const uint16_t* k, int j0, int T, int lane) {
+__device__ __forceinline__ void load_keys(u32x4 (&kf)[D / 16], const uint16_t* k, int j0, int T, int lane) {
   int key = j0 + (lane & 31);
   if (key > T - 1) key = T - 1;
   const uint16_t* p = k + (size_t)key * D + (lane >> 5) * 8;
 #pragma unroll
-  for (int kk = 0; kk < D / 16; ++kk) kf[kk] = *reinterpret_cast<const uint4*>(p + kk * 16);
+  for (int kk = 0; kk < D / 16; ++kk) kf[kk] = *reinterpret_cast<const u32x4*>(p + kk * 16);
 }
 
-template <int D, int RT>
-__global__ __launch_bounds__(256) void k_prefill_rows(PrefillLaunch L) {
+// One step of the two passes' software pipeline: the D/16 MFMAs that form the NEXT step's 32x32 logits tile
+// (key operands kx, query operands of row tile rt_next read from LDS two MFMAs ahead), with the vector work on
+// THIS step's tile dealt out between them by `work(kk)`.  A wave's MFMAs only run in the background of its own
+// vector instructions if the two alternate in the instruction stream, and left to itself the compiler groups
+// them apart (scheduling barriers do not help: the instruction selector has already grouped them).  The order is
+// therefore pinned by data: after slot kk an empty volatile asm takes the two running sums of the vector work
+// (p0, p1: every slot's work must read and write them) together with the key operand of MFMA kk + 1, so that
+// work(kk) lies before it and MFMA kk + 1 after it.
+// KEYS_ON_M: the keys are the MFMA's M side (a lane owns one query row), else its N side (a lane owns one key).
+// qoff: the lane's byte offset inside a row tile, (lane % 32) * row pitch + (lane / 32) * 16; it goes through an
+// empty asm so that the optimiser cannot hoist the LDS reads (the same for every key tile) out of the key loop,
+// where they would take 32 RT registers.
+constexpr int kQAhead = 3;                      // LDS operands are requested this many MFMAs ahead, across steps
+
+// The first kQAhead operands of row tile rt: what a step expects to be in flight when it starts.
+template <int D>
+__device__ __forceinline__ void prime_operands(uint4 (&qb)[kQAhead + 1], const unsigned char* sm, int rt, int qoff) {
+  constexpr int RB = 2 * D + 16;
+  asm volatile("" : "+v"(qoff));
+#pragma unroll
+  for (int i = 0; i < kQAhead; ++i) qb[i] = *reinterpret_cast<const uint4*>(sm + rt * 32 * RB + qoff + i * 32);
+}
+
+// rt_next: the row tile whose logits this step's MFMAs form; rt_after: the row tile of the step after it, whose
+// first kQAhead operands are requested in this step's last slots (ring qb, slot = operand index % (kQAhead + 1);
+// D/16 is a multiple of the ring size, so the slots line up from step to step).
+template <int D, bool KEYS_ON_M, typename Work>
+__device__ __forceinline__ f32x16 pipeline_step(u32x4 (&kx)[D / 16], uint4 (&qb)[kQAhead + 1], const unsigned char* sm,
+                                                int rt_next, int rt_after, int qoff, float& p0, float& p1, Work work) {
+  constexpr int RB = 2 * D + 16;
+  constexpr int KK = D / 16;
+  static_assert(KK % (kQAhead + 1) == 0 && KK > kQAhead, "ring slots must line up across steps");
+  asm volatile("" : "+v"(qoff));
+  const unsigned char* qrow = sm + rt_next * 32 * RB + qoff;
+  const unsigned char* qrow2 = sm + rt_after * 32 * RB + qoff;
+  f32x16 C = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) {
+    const int ahead = kk + kQAhead;
+    qb[ahead % (kQAhead + 1)] = *reinterpret_cast<const uint4*>(ahead < KK ? qrow + ahead * 32 : qrow2 + (ahead - KK) * 32);
+    const uint4 qc = qb[kk % (kQAhead + 1)];
+    if constexpr (KEYS_ON_M)
+      C = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kx[kk]), __builtin_bit_cast(bf16x8, qc), C, 0, 0, 0);
+    else
+      C = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, qc), __builtin_bit_cast(bf16x8, kx[kk]), C, 0, 0, 0);
+    work(kk);
+    if (kk + 1 < KK) {
+      // (resident since the previous key tile: pinning it waits for nothing)
+      asm volatile("" : "+v"(p0), "+v"(p1), "+v"(kx[kk + 1]));
+    }
+  }
+  return C;
+}
+
+// NW waves per workgroup: 4, or 8 where the staged queries leave room for only one workgroup per CU (more than
+// 256 query rows), so that a SIMD still has two waves.
+// Logits tile of the first pass: C[i] at key j0 + 8(i/4) + 4(lane/32) + i%4, row rt*32 + lane%32.
+template <int D, int RT, int NW>
+__global__ __launch_bounds__(64 * NW, (NW == 4 && RT < 8) ? 3 : 2) void k_prefill_rows(PrefillLaunch L) {
   extern __shared__ __align__(16) unsigned char sm[];
+  constexpr int NT = 64 * NW;
+  constexpr int KK = D / 16;
   const int chunk = blockIdx.x, u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int M = L.G * L.W, MP = RT * 32, T = L.T;
-  stage_q<D>(sm, L.q_win + (size_t)u * L.G * L.q_head_stride, L.q_head_stride, L.W, M, MP);
+  stage_q<D, NT>(sm, L.q_win + (size_t)u * L.G * L.q_head_stride, L.q_head_stride, L.W, M, MP);
   __syncthreads();
   const uint16_t* k = L.k + (size_t)u * T * D;
   float m[RT], l[RT];
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) { m[rt] = kNegBigP; l[rt] = 0.f; }
   const int jbeg = chunk * L.chunk, jend = min(jbeg + L.chunk, T);
-  int lastv[RT];
-#pragma unroll
-  for (int rt = 0; rt < RT; ++rt) {
-    const int r = rt * 32 + (lane & 31);
-    lastv[rt] = r < M ? T - L.W + (r % L.W) : -1;   // last visible key of this row
-  }
-  uint4 kf[D / 16], kn[D / 16];
+  const int qoff = (lane & 31) * (2 * D + 16) + (lane >> 5) * 16;
+  const float scale2 = L.scale2;
+  u32x4 kf[KK], kn[KK];
   if (jbeg + w * 32 < jend) load_keys<D>(kf, k, jbeg + w * 32, T, lane);
-  for (int j0 = jbeg + w * 32; j0 < jend; j0 += 128) {
-    load_keys<D>(kn, k, j0 + 128, T, lane);            // next tile of this wave (clamped past the end)
-    const bool full = (j0 + 32 <= T - L.W) && (RT * 32 == M);   // no causal mask, no padded rows
+  float pin0 = 0.f, pin1 = 0.f;
+  uint4 qb[kQAhead + 1];
+  prime_operands<D>(qb, sm, 0, qoff);
+  f32x16 C = pipeline_step<D, true>(kf, qb, sm, 0, RT > 1 ? 1 : 0, qoff, pin0, pin1, [](int) {});
+  // One key tile against all row tiles; every step also issues the next step's MFMAs.  FULL: no key of the tile
+  // is masked for any row (padded rows are rows of zeros whose statistics nobody reads), and then nothing in the
+  // body branches.
+  auto key_tile = [&](int j0, auto full_c) {
+    constexpr bool FULL = decltype(full_c)::value;
+    load_keys<D>(kn, k, j0 + 32 * NW, T, lane);        // next tile of this wave (clamped past the end)
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-      const f32x16 C = tile_logits<D>(kf, sm, rt, lane);
       float x[16];
-      float mt = kNegBigP;
-      if (full) {
+      float mn = 0.f, s = 0.f;
+      auto work = [&](int kk) {
+        if (kk == 0) {
+          if constexpr (FULL) {
+            // the scale is positive, so the maximum is taken on the raw dot products
 #pragma unroll
-        for (int i = 0; i < 16; ++i) { x[i] = C[i] * L.scale2; mt = fmaxf(mt, x[i]); }
-      } else {
+            for (int i = 0; i < 16; ++i) x[i] = C[i];
+            float mt = fmaxf(x[0], x[1]);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int j = j0 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-          x[i] = j <= lastv[rt] ? C[i] * L.scale2 : kNegBigP;
-          mt = fmaxf(mt, x[i]);
+            for (int i = 2; i < 16; i += 2) mt = fmaxf(fmaxf(mt, x[i]), x[i + 1]);
+            mn = fmaxf(m[rt], mt * scale2);
+          } else {
+            const int r = rt * 32 + (lane & 31);
+            const int lastv = r < M ? T - L.W + (r % L.W) : -1;   // last visible key of this row
+            float mt = kNegBigP;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int j = j0 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+              x[i] = j <= lastv ? C[i] * scale2 : kNegBigP;       // scaled here: the sentinel stays the sentinel
+              mt = fmaxf(mt, x[i]);
+            }
+            mn = fmaxf(m[rt], mt);
+          }
+          s = l[rt] * pexp2(m[rt] - mn);
+        } else {
+          // the 16 logits are dealt over the remaining KK - 1 slots; FULL: 2^(scale x - max) is one fma and one exp
+          const int i0 = (kk - 1) * 16 / (KK - 1), i1 = kk * 16 / (KK - 1);
+#pragma unroll
+          for (int i = i0; i < i1; ++i) {
+            if constexpr (FULL) s += pexp2(fmaf(x[i], scale2, -mn));
+            else s += pexp2(x[i] - mn);                           // masked entries: 2^(-1e30 - mn) = 0
+          }
         }
-      }
-      const float mn = fmaxf(m[rt], mt);
-      float s = l[rt] * pexp2(m[rt] - mn);
-      if (mn > 0.5f * kNegBigP) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) s += pexp2(x[i] - mn);   // masked entries: 2^(-1e30 - mn) = 0
-      }
+      };
+      constexpr int RT2 = RT > 1 ? 1 : 0;          // the row tile after row tile 0
+      const f32x16 Cn = rt + 1 < RT ? pipeline_step<D, true>(kf, qb, sm, rt + 1, rt + 2 < RT ? rt + 2 : 0, qoff, mn, s, work)
+                                    : pipeline_step<D, true>(kn, qb, sm, 0, RT2, qoff, mn, s, work);
+      if constexpr (!FULL) { if (!(mn > 0.5f * kNegBigP)) s = 0.f; }      // nothing visible yet: 16 * 2^0 dropped
       m[rt] = mn; l[rt] = s;
-      // one row tile at a time: without this the compiler interleaves all RT tiles and the kernel drops
-      // to one wave per SIMD; other waves fill the MFMA -> VALU gaps instead
-      __builtin_amdgcn_sched_barrier(0);
+      C = Cn;
     }
 #pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk) kf[kk] = kn[kk];
-  }
-  // merge the two lane halves, then the four waves
+    for (int kk = 0; kk < KK; ++kk) kf[kk] = kn[kk];
+  };
+  int j0 = jbeg + w * 32;
+  for (; j0 < jend && j0 + 32 <= T - L.W; j0 += 32 * NW) key_tile(j0, std::true_type{});
+  for (; j0 < jend; j0 += 32 * NW) key_tile(j0, std::false_type{});
+  // merge the two lane halves, then the waves
   float* red = reinterpret_cast<float*>(sm);   // reuse after everyone is done with the queries
   __syncthreads();
 #pragma unroll
@@ -140,11 +220,11 @@ __global__ __launch_bounds__(256) void k_prefill_rows(PrefillLaunch L) {
     if (lane < 32) { red[(w * MP + rt * 32 + lane) * 2] = m[rt]; red[(w * MP + rt * 32 + lane) * 2 + 1] = l[rt]; }
   }
   __syncthreads();
-  for (int r = tid; r < MP; r += 256) {
+  for (int r = tid; r < MP; r += NT) {
     float mn = kNegBigP;
-    for (int i = 0; i < 4; ++i) mn = fmaxf(mn, red[(i * MP + r) * 2]);
+    for (int i = 0; i < NW; ++i) mn = fmaxf(mn, red[(i * MP + r) * 2]);
     float s = 0.f;
-    for (int i = 0; i < 4; ++i) s += red[(i * MP + r) * 2 + 1] * exp2f(red[(i * MP + r) * 2] - mn);
+    for (int i = 0; i < NW; ++i) s += red[(i * MP + r) * 2 + 1] * exp2f(red[(i * MP + r) * 2] - mn);
     L.rowstat[((size_t)u * L.n_chunks + chunk) * MP + r] = make_float2(mn, s);
   }
 }
@@ -188,16 +268,18 @@ __device__ __forceinline__ double block_sum_d(double v, double* sm) {
 // Second pass.  Here the MFMA is turned round (query rows on the M side, keys on the N side) so that a
 // lane owns ONE key and the sums over the M = G*W query rows are in-register additions: C[i] is row
 // rt*32 + 8(i/4) + 4(lane/32) + i%4 against key j0 + lane%32.  The row constants c_r come from LDS.
-template <int D, int RT>
-__global__ __launch_bounds__(256) void k_prefill_cols(PrefillLaunch L, const float* rowc, double* zpart) {
+template <int D, int RT, int NW>
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_prefill_cols(PrefillLaunch L, const float* rowc, double* zpart) {
   extern __shared__ __align__(16) unsigned char sm[];
   constexpr int RB = 2 * D + 16;
+  constexpr int NT = 64 * NW;
+  constexpr int KK = D / 16;
   const int chunk = blockIdx.x, u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int M = L.G * L.W, MP = RT * 32, T = L.T;
-  stage_q<D>(sm, L.q_win + (size_t)u * L.G * L.q_head_stride, L.q_head_stride, L.W, M, MP);
-  float* crow = reinterpret_cast<float*>(sm + (size_t)MP * RB);   // [MP] -c_r (padded rows: +1e30 -> p = 0)
+  stage_q<D, NT>(sm, L.q_win + (size_t)u * L.G * L.q_head_stride, L.q_head_stride, L.W, M, MP);
+  float* crow = reinterpret_cast<float*>(sm + (size_t)MP * RB);   // [MP] -c_r (padded rows: -1e30 -> p = 0)
   int* lastk = reinterpret_cast<int*>(crow + MP);                 // [MP] last visible key of the row
-  for (int r = tid; r < MP; r += 256) {
+  for (int r = tid; r < MP; r += NT) {
     crow[r] = r < M ? -rowc[(size_t)u * MP + r] : kNegBigP;
     lastk[r] = r < M ? T - L.W + (r % L.W) : -1;
   }
@@ -206,55 +288,63 @@ __global__ __launch_bounds__(256) void k_prefill_cols(PrefillLaunch L, const flo
   const int jbeg = chunk * L.chunk, jend = min(jbeg + L.chunk, T);
   float2* pre = L.pre + (size_t)u * T;
   const int hl = lane >> 5, kl = lane & 31;
+  const int qoff = kl * RB + hl * 16;
+  const float scale2 = L.scale2;
   double zacc = 0.0;                                              // this workgroup's share of eq. 3's normaliser
-  uint4 kf[D / 16], kn[D / 16];
+  u32x4 kf[KK], kn[KK];
   if (jbeg + w * 32 < jend) load_keys<D>(kf, k, jbeg + w * 32, T, lane);
-  for (int j0 = jbeg + w * 32; j0 < jend; j0 += 128) {
-    load_keys<D>(kn, k, j0 + 128, T, lane);
-    const bool full = (j0 + 32 <= T - L.W) && (RT * 32 == M);   // no causal mask, no padded rows
+  float pin0 = 0.f, pin1 = 0.f;
+  uint4 qb[kQAhead + 1];
+  prime_operands<D>(qb, sm, 0, qoff);
+  f32x16 C = pipeline_step<D, false>(kf, qb, sm, 0, RT > 1 ? 1 : 0, qoff, pin0, pin1, [](int) {});
+  // FULL: no key of the tile is masked for any row (padded rows have c_r = -1e30, so p = 0 without a test)
+  auto key_tile = [&](int j0, auto full_c) {
+    constexpr bool FULL = decltype(full_c)::value;
+    load_keys<D>(kn, k, j0 + 32 * NW, T, lane);
     const int j = j0 + kl;
     float a1 = 0.f, a2 = 0.f;
+    // the row constants are the same for every key tile too: opaque offset, see pipeline_step
+    int c0 = 4 * hl;
+    asm volatile("" : "+v"(c0));
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-      f32x16 C = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-      const unsigned char* qrow = sm + (size_t)(rt * 32 + kl) * RB + hl * 16;
-#pragma unroll
-      for (int kk = 0; kk < D / 16; ++kk) {
-        const uint4 qa = *reinterpret_cast<const uint4*>(qrow + kk * 32);
-        C = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, qa), __builtin_bit_cast(bf16x8, kf[kk]), C, 0, 0, 0);
-      }
-#pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        const int r0 = rt * 32 + 8 * g4 + 4 * hl;
-        const float4 nc = *reinterpret_cast<const float4*>(crow + r0);
-        const float ncv[4] = {nc.x, nc.y, nc.z, nc.w};
-        if (full) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const float p = pexp2(fmaf(C[4 * g4 + i], L.scale2, ncv[i]));
-            a1 += p;
-            a2 = fmaf(p, p, a2);
-          }
-        } else {
-          const int4 lk = *reinterpret_cast<const int4*>(lastk + r0);
-          const int lkv[4] = {lk.x, lk.y, lk.z, lk.w};
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const float p = j <= lkv[i] ? pexp2(fmaf(C[4 * g4 + i], L.scale2, ncv[i])) : 0.f;
-            a1 += p;
-            a2 = fmaf(p, p, a2);
-          }
+      // slot kk handles the 4 rows 8 g4 + 4 hl .. + 3 of the tile for g4 = kk / 2 (two logits per slot)
+      float4 nc;
+      int4 lk;
+      auto work = [&](int kk) {
+        static_assert(KK == 8 || KK == 4, "two or four logits per slot");
+        constexpr int PER = 16 / KK;                      // logits per slot
+        const int i0 = kk * PER;
+        if (i0 % 4 == 0) {
+          const int r0 = rt * 32 + 8 * (i0 / 4) + c0;
+          nc = *reinterpret_cast<const float4*>(crow + r0);
+          if constexpr (!FULL) lk = *reinterpret_cast<const int4*>(lastk + r0);
         }
-      }
-      __builtin_amdgcn_sched_barrier(0);     // one row tile at a time (register pressure, see k_prefill_rows)
+        const float ncv[4] = {nc.x, nc.y, nc.z, nc.w};
+        const int lkv[4] = {lk.x, lk.y, lk.z, lk.w};
+#pragma unroll
+        for (int i = i0; i < i0 + PER; ++i) {
+          float p = pexp2(fmaf(C[i], scale2, ncv[i % 4]));
+          if constexpr (!FULL) p = j <= lkv[i % 4] ? p : 0.f;
+          a1 += p;
+          a2 = fmaf(p, p, a2);
+        }
+      };
+      constexpr int RT2 = RT > 1 ? 1 : 0;          // the row tile after row tile 0
+      const f32x16 Cn = rt + 1 < RT ? pipeline_step<D, false>(kf, qb, sm, rt + 1, rt + 2 < RT ? rt + 2 : 0, qoff, a1, a2, work)
+                                    : pipeline_step<D, false>(kn, qb, sm, 0, RT2, qoff, a1, a2, work);
+      C = Cn;
     }
     a1 += __shfl_xor(a1, 32);
     a2 += __shfl_xor(a2, 32);
     if (hl == 0 && j < T) pre[j] = make_float2(a1, a2);
     if (hl == 0 && j < T - L.W) zacc += (double)a1;
 #pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk) kf[kk] = kn[kk];
-  }
+    for (int kk = 0; kk < KK; ++kk) kf[kk] = kn[kk];
+  };
+  int j0 = jbeg + w * 32;
+  for (; j0 < jend && j0 + 32 <= T - L.W; j0 += 32 * NW) key_tile(j0, std::true_type{});
+  for (; j0 < jend; j0 += 32 * NW) key_tile(j0, std::false_type{});
   // sum over the chunk's keys before the window of the attention they received, in a fixed order
   zacc = block_sum_d(zacc, reinterpret_cast<double*>(sm));       // (its first barrier ends the use of the queries)
   if (tid == 0) zpart[(size_t)u * L.n_chunks + chunk] = zacc;
@@ -316,24 +406,25 @@ __global__ __launch_bounds__(256) void k_prefill_stats(PrefillLaunch L, const do
 template <int D, int RT>
 static hipError_t launch_prefill_t(const PrefillLaunch& a, float* rowc, hipStream_t s) {
   const int U = a.B * a.Hkv, MP = RT * 32;
+  constexpr int NW = RT > 8 ? 8 : 4;
   const size_t shm = (size_t)MP * (2 * D + 16);
   if (shm + (size_t)MP * 8 > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_prefill_rows<D, RT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_prefill_rows<D, RT, NW>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_prefill_cols<D, RT>),
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_prefill_cols<D, RT, NW>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)(shm + (size_t)MP * 8));
     if (e != hipSuccess) return e;
   }
   dim3 grid(a.n_chunks, U);
   if (!a.have_rowc) {
-    hipLaunchKernelGGL((k_prefill_rows<D, RT>), grid, dim3(256), shm, s, a);
+    hipLaunchKernelGGL((k_prefill_rows<D, RT, NW>), grid, dim3(64 * NW), shm, s, a);
     hipLaunchKernelGGL(k_prefill_rowfinal, dim3(MP / 32, U), dim3(256), 0, s, a, MP, rowc);
   }
   const int nch = (a.T - a.W + kStatChunk - 1) / kStatChunk;
   double* zpart = reinterpret_cast<double*>(rowc + (size_t)U * MP);      // [U][n_chunks], then [B][nch][3]
   double* mpart = zpart + (size_t)U * a.n_chunks;
-  hipLaunchKernelGGL((k_prefill_cols<D, RT>), grid, dim3(256), shm + (size_t)MP * 8, s, a, (const float*)rowc, zpart);
+  hipLaunchKernelGGL((k_prefill_cols<D, RT, NW>), grid, dim3(64 * NW), shm + (size_t)MP * 8, s, a, (const float*)rowc, zpart);
   hipLaunchKernelGGL(k_prefill_stats, dim3(nch, a.B), dim3(256), 0, s, a, (const double*)zpart, mpart);
   return hipGetLastError();
 }
