@@ -314,11 +314,20 @@ static int run_scorer(arkv_cache* c, int32_t layer, const uint16_t* q_win, size_
   const int U = c->U, G = c->P.G, W = c->cfg.window;
   int rc;
   if ((rc = grow(&ls.pre, &ls.pre_cap, (size_t)U * T)) != ARKV_OK) return rc;
-  int chunk = c->prefill_chunk;
-  while (!c->prefill_chunk_fixed && chunk > 128 && (size_t)((T + chunk - 1) / chunk) * U < 1024) chunk >>= 1;
-  const int n_chunks = (T + chunk - 1) / chunk;
   int MP = 32;
   while (MP < G * W) MP *= 2;
+  int chunk = c->prefill_chunk;
+  if (!c->prefill_chunk_fixed) {
+    if (MP > 256) {
+      // more than 256 query rows: the staged queries fill a CU's LDS, one workgroup (of 8 waves) per CU, and every
+      // workgroup stages them again, so the grid is one round of the chip where the prompt allows it
+      // (16K keys x 64 units at 512 rows: 173 us per pass with 4096 keys per workgroup, 185 us with 1024)
+      const size_t per_wg = ((size_t)T * U + 255) / 256;
+      chunk = (int)std::min<size_t>(8192, std::max<size_t>(1024, (per_wg + 127) / 128 * 128));
+    }
+    while (chunk > 128 && (size_t)((T + chunk - 1) / chunk) * U < (MP > 256 ? 256u : 1024u)) chunk >>= 1;
+  }
+  const int n_chunks = (T + chunk - 1) / chunk;
   if ((rc = grow(&c->rowstat, &c->rowstat_cap, (size_t)U * n_chunks * MP)) != ARKV_OK) return rc;
   // row constants [U][MP] floats (MP even, so what follows is 8-byte aligned) + statistics partials
   const size_t stat_doubles = (size_t)U * n_chunks + 3 * (size_t)c->cfg.batch * ((size_t)(T - W + 511) / 512);

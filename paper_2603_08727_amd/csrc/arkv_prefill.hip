@@ -85,12 +85,15 @@ __device__ __forceinline__ void load_keys(u32x4 (&kf)[D / 16], const uint16_t* k
 // qoff: the lane's byte offset inside a row tile, (lane % 32) * row pitch + (lane / 32) * 16; it goes through an
 // empty asm so that the optimiser cannot hoist the LDS reads (the same for every key tile) out of the key loop,
 // where they would take 32 RT registers.
-constexpr int kQAhead = 3;                      // LDS operands are requested this many MFMAs ahead, across steps
+// LDS operands are requested this many MFMAs ahead, across steps (a whole step ahead measured the same and costs
+// 16 registers more)
+template <int D> constexpr int kQAheadOf = 3;
 
 // The first kQAhead operands of row tile rt: what a step expects to be in flight when it starts.
 template <int D>
-__device__ __forceinline__ void prime_operands(uint4 (&qb)[kQAhead + 1], const unsigned char* sm, int rt, int qoff) {
+__device__ __forceinline__ void prime_operands(uint4 (&qb)[kQAheadOf<D> + 1], const unsigned char* sm, int rt, int qoff) {
   constexpr int RB = 2 * D + 16;
+  constexpr int kQAhead = kQAheadOf<D>;
   asm volatile("" : "+v"(qoff));
 #pragma unroll
   for (int i = 0; i < kQAhead; ++i) qb[i] = *reinterpret_cast<const uint4*>(sm + rt * 32 * RB + qoff + i * 32);
@@ -100,10 +103,11 @@ __device__ __forceinline__ void prime_operands(uint4 (&qb)[kQAhead + 1], const u
 // first kQAhead operands are requested in this step's last slots (ring qb, slot = operand index % (kQAhead + 1);
 // D/16 is a multiple of the ring size, so the slots line up from step to step).
 template <int D, bool KEYS_ON_M, typename Work>
-__device__ __forceinline__ f32x16 pipeline_step(u32x4 (&kx)[D / 16], uint4 (&qb)[kQAhead + 1], const unsigned char* sm,
+__device__ __forceinline__ f32x16 pipeline_step(u32x4 (&kx)[D / 16], uint4 (&qb)[kQAheadOf<D> + 1], const unsigned char* sm,
                                                 int rt_next, int rt_after, int qoff, float& p0, float& p1, Work work) {
   constexpr int RB = 2 * D + 16;
   constexpr int KK = D / 16;
+  constexpr int kQAhead = kQAheadOf<D>;
   static_assert(KK % (kQAhead + 1) == 0 && KK > kQAhead, "ring slots must line up across steps");
   asm volatile("" : "+v"(qoff));
   const unsigned char* qrow = sm + rt_next * 32 * RB + qoff;
@@ -149,7 +153,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && RT < 8) ? 3 : 2) void k_prefil
   u32x4 kf[KK], kn[KK];
   if (jbeg + w * 32 < jend) load_keys<D>(kf, k, jbeg + w * 32, T, lane);
   float pin0 = 0.f, pin1 = 0.f;
-  uint4 qb[kQAhead + 1];
+  uint4 qb[kQAheadOf<D> + 1];
   prime_operands<D>(qb, sm, 0, qoff);
   f32x16 C = pipeline_step<D, true>(kf, qb, sm, 0, RT > 1 ? 1 : 0, qoff, pin0, pin1, [](int) {});
   // One key tile against all row tiles; every step also issues the next step's MFMAs.  FULL: no key of the tile
@@ -294,9 +298,10 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_prefill_cols(Prefi
   u32x4 kf[KK], kn[KK];
   if (jbeg + w * 32 < jend) load_keys<D>(kf, k, jbeg + w * 32, T, lane);
   float pin0 = 0.f, pin1 = 0.f;
-  uint4 qb[kQAhead + 1];
+  uint4 qb[kQAheadOf<D> + 1];
   prime_operands<D>(qb, sm, 0, qoff);
   f32x16 C = pipeline_step<D, false>(kf, qb, sm, 0, RT > 1 ? 1 : 0, qoff, pin0, pin1, [](int) {});
+  float4 nc_nxt = *reinterpret_cast<const float4*>(crow + 4 * hl);      // row tile 0, first group
   // FULL: no key of the tile is masked for any row (padded rows have c_r = -1e30, so p = 0 without a test)
   auto key_tile = [&](int j0, auto full_c) {
     constexpr bool FULL = decltype(full_c)::value;
@@ -308,7 +313,10 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_prefill_cols(Prefi
     asm volatile("" : "+v"(c0));
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-      // slot kk handles the 4 rows 8 g4 + 4 hl .. + 3 of the tile for g4 = kk / 2 (two logits per slot)
+      // a slot handles PER logits: rows 8 g4 + 4 hl .. + 3 of the tile for g4 = first logit / 4.  The four row
+      // constants of a group are requested from LDS one group ahead (nc_nxt; across steps and key tiles as well:
+      // used right after the request, every group would wait for an LDS round trip)
+      const int rt_n = rt + 1 < RT ? rt + 1 : 0;        // the tile the next step works on
       float4 nc;
       int4 lk;
       auto work = [&](int kk) {
@@ -316,9 +324,10 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_prefill_cols(Prefi
         constexpr int PER = 16 / KK;                      // logits per slot
         const int i0 = kk * PER;
         if (i0 % 4 == 0) {
-          const int r0 = rt * 32 + 8 * (i0 / 4) + c0;
-          nc = *reinterpret_cast<const float4*>(crow + r0);
-          if constexpr (!FULL) lk = *reinterpret_cast<const int4*>(lastk + r0);
+          const int g4 = i0 / 4;
+          nc = nc_nxt;
+          nc_nxt = *reinterpret_cast<const float4*>(crow + (g4 + 1 < 4 ? rt * 32 + 8 * (g4 + 1) : rt_n * 32) + c0);
+          if constexpr (!FULL) lk = *reinterpret_cast<const int4*>(lastk + rt * 32 + 8 * g4 + c0);
         }
         const float ncv[4] = {nc.x, nc.y, nc.z, nc.w};
         const int lkv[4] = {lk.x, lk.y, lk.z, lk.w};
