@@ -509,9 +509,9 @@ def main():
     try:
         big = torch.empty(3 << 30, dtype=torch.uint8, device=dev)
         bpl = max(524288, int(bytes_per_launch) // 524288 * 524288)
-        us = A.arkv_debug_stream_read(big, bpl, 200, 0)
-        us1 = A.arkv_debug_stream_read(big, bpl, 200, 1)
-        A.arkv_debug_stream_read(big, bpl, 20, 2)      # known-size copy: calibrates the write counter under rocprofv3
+        us = A.arkv_measure_stream_read(big, bpl, 200, 0)
+        us1 = A.arkv_measure_stream_read(big, bpl, 200, 1)
+        A.arkv_measure_stream_read(big, bpl, 20, 2)      # known-size copy: calibrates the write counter under rocprofv3
         ceiling = {"us_per_launch": round(us, 2), "GBps": round(bpl / (us * 1e-6) / 1e9, 1), "bytes_per_launch": bpl,
                    "operand_layout_GBps": round(bpl / (us1 * 1e-6) / 1e9, 1)}
         roofline["frac_of_stream_read_ceiling"] = round(achieved / ceiling["GBps"], 4)

@@ -260,19 +260,6 @@ int arkv_debug_split_range(int32_t n_original, int32_t n_quantized, int32_t pack
  * ARKV_EINVAL: null pointer, which outside 0..2, n_rows outside 1..8192. */
 int arkv_debug_phase_trace(int32_t which, unsigned long long* host_words, int32_t n_rows);
 
-/* Measurement hook: a plain streaming read (16 bytes per lane, nothing else) of bytes_per_launch bytes
- * per kernel launch, `launches` launches back to back on the stream, walking through the DEVICE buffer
- * buf of buf_bytes bytes and wrapping around.  pattern 0: fully coalesced (a wave reads 1 KB contiguous
- * per instruction; kernel k_stream_read); pattern 1: the MFMA-operand layout the attention kernel uses
- * for keys (rows of 256 bytes, lane = row lane%16, 16-byte chunk lane/16 of each 64 bytes; kernel
- * k_stream_read_operand); pattern 2: plain copy that reads the first half of each window and WRITES the
- * second half (kernel k_stream_copy; buf is modified).  Returns the average time of one launch in microseconds (HIP events;
- * synchronises).  This is the practical bandwidth ceiling of the box for a launch of that size, and a
- * kernel of known traffic for calibrating hardware counters.  bytes_per_launch must be a multiple of
- * 524288 and <= buf_bytes. */
-int arkv_debug_stream_read(void* buf, uint64_t buf_bytes, uint64_t bytes_per_launch, int32_t launches,
-                           int32_t pattern, void* hip_stream, float* avg_us);
-
 const char* arkv_strerror(int code);        /* static text for an ARKV_E* code */
 const char* arkv_last_hip_error(void);      /* text of the HIP error behind the latest ARKV_EHIP */
 

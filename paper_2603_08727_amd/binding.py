@@ -22,7 +22,7 @@ EXPORTED = [
     "arkv_prefill_stats", "arkv_prefill_stats_lse", "arkv_prefill_attention", "arkv_oq_ratio", "arkv_budget_counts", "arkv_prefill_commit",
     "arkv_decode_step", "arkv_decode_step_static", "arkv_decode_step_layers", "arkv_cache_counters", "arkv_cache_export",
     "arkv_debug_last_tailor_scores", "arkv_debug_last_out_f32", "arkv_debug_prefill_attention_f32", "arkv_cache_progress",
-    "arkv_debug_time_attend", "arkv_debug_attend_time", "arkv_debug_set_launch_shape", "arkv_debug_stream_read", "arkv_debug_split_range", "arkv_debug_phase_trace",
+    "arkv_debug_time_attend", "arkv_debug_attend_time", "arkv_debug_set_launch_shape", "arkv_debug_split_range", "arkv_debug_phase_trace",
     "arkv_strerror",
     "arkv_last_hip_error",
 ]
@@ -84,7 +84,6 @@ def load():
         "arkv_debug_time_attend": (C.c_int, [vp, i32]),
         "arkv_debug_attend_time": (C.c_int, [vp, P(C.c_double), P(C.c_int64)]),
         "arkv_debug_phase_trace": (C.c_int, [i32, vp, i32]),
-        "arkv_debug_stream_read": (C.c_int, [vp, C.c_uint64, C.c_uint64, i32, i32, vp, P(C.c_float)]),
         "arkv_strerror": (C.c_char_p, [C.c_int]),
         "arkv_last_hip_error": (C.c_char_p, []),
     }
@@ -312,14 +311,33 @@ def arkv_debug_phase_trace(which: int, n_rows: int = 1):
     return buf.reshape(-1)[:4] if which == 2 else buf
 
 
-def arkv_debug_stream_read(buf, bytes_per_launch: int, launches: int, pattern: int = 0) -> float:
+MEASURE_LIB_PATH = os.environ.get("ARKV_MEASURE_LIBRARY") or os.path.join(_HERE, "libarkv_measure.so")
+MEASURE_EXPORTED = ["arkv_measure_stream_read"]
+_mlib = None
+
+
+def load_measure():
+    """libarkv_measure.so (include/arkv_measure.h): bandwidth measurement kernels, separate from the product."""
+    global _mlib
+    if _mlib is None:
+        if not os.path.exists(MEASURE_LIB_PATH):
+            raise RuntimeError(f"{MEASURE_LIB_PATH} is missing: build it with `python -m paper_2603_08727_amd.build`")
+        _mlib = C.CDLL(MEASURE_LIB_PATH)
+        _mlib.arkv_measure_stream_read.restype = C.c_int
+        _mlib.arkv_measure_stream_read.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_int32, C.c_int32, C.c_void_p,
+                                                   C.POINTER(C.c_float)]
+    return _mlib
+
+
+def arkv_measure_stream_read(buf, bytes_per_launch: int, launches: int, pattern: int = 0) -> float:
     """Average microseconds per launch of a plain streaming read over the GPU tensor `buf`
-    (pattern 0: coalesced; 1: the attention kernel's key-operand layout)."""
+    (pattern 0: coalesced; 1: the attention kernel's key-operand layout; 2: plain copy, buf is modified)."""
     us = C.c_float()
     nbytes = buf.numel() * buf.element_size()
-    _check(load().arkv_debug_stream_read(_dev_ptr(buf), nbytes, bytes_per_launch, launches, pattern, _stream(),
-                                         C.byref(us)),
-           "arkv_debug_stream_read")
+    rc = load_measure().arkv_measure_stream_read(_dev_ptr(buf), nbytes, bytes_per_launch, launches, pattern, _stream(),
+                                                 C.byref(us))
+    if rc != 0:
+        raise RuntimeError(f"arkv_measure_stream_read failed with code {rc}")
     return us.value
 
 

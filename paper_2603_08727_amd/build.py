@@ -13,6 +13,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libarkv.so")
 LIB_TRACE = os.path.join(HERE, "libarkv_trace.so")
+LIB_MEASURE = os.path.join(HERE, "libarkv_measure.so")   # bandwidth measurement kernels, not part of the product
+MEASURE_SOURCES = ["arkv_measure.hip"]
 SOURCES = ["arkv_host.cpp", "arkv_decode.hip", "arkv_tailor.hip", "arkv_prefill.hip", "arkv_attn.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
@@ -30,6 +32,10 @@ def build(verbose: bool = True, phase_trace: bool = False) -> str:
     os.makedirs(objdir, exist_ok=True)
     procs = []
     objs = []
+    mobjs = [os.path.join(objdir, src + ".o") for src in MEASURE_SOURCES]
+    for src, obj in zip(MEASURE_SOURCES, mobjs):
+        cmd = [hipcc, *flags, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+        procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     for src in SOURCES:
         obj = os.path.join(objdir, src + ".o")
         objs.append(obj)
@@ -44,6 +50,7 @@ def build(verbose: bool = True, phase_trace: bool = False) -> str:
             print(out, file=sys.stderr)
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", lib]
     subprocess.run(cmd, check=True)
+    subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *mobjs, "-o", LIB_MEASURE], check=True)
     return lib
 
 

@@ -1358,53 +1358,6 @@ hipError_t static_scratch_get(float** part, int** ticket, size_t* part_floats) {
   return hipSuccess;
 }
 
-// Plain streaming read: each workgroup reads a contiguous share, 8 x 16 bytes per lane in flight.
-__global__ __launch_bounds__(256) void k_stream_read(const uint4* __restrict__ src, unsigned n_per_wg, unsigned* sink) {
-  const uint4* p = src + (size_t)blockIdx.x * n_per_wg;
-  unsigned acc = 0;
-  for (unsigned i = threadIdx.x; i < n_per_wg; i += 256 * 8) {
-    uint4 v[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) { const unsigned j = i + u * 256; v[u] = p[j < n_per_wg ? j : n_per_wg - 1]; }
-#pragma unroll
-    for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
-  }
-  if (acc == 0x9E3779B9u) sink[blockIdx.x] = acc;   // practically never: keeps the loads alive
-}
-
-// The same bytes in the key-operand layout of k_decode_attend: rows of 256 bytes, a wave covers 16
-// rows per tile with 4 instructions, lane = row lane%16, chunk lane/16 of each 64 bytes.
-__global__ __launch_bounds__(256) void k_stream_read_operand(const uint4* __restrict__ src, unsigned rows_per_wg, unsigned* sink) {
-  const uint4* p = src + (size_t)blockIdx.x * rows_per_wg * 16;
-  const unsigned lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  unsigned acc = 0;
-  for (unsigned r0 = w * 16; r0 < rows_per_wg; r0 += 128) {
-    uint4 v[8];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      unsigned row = r0 + t * 64 + (lane & 15);
-      if (row >= rows_per_wg) row = rows_per_wg - 1;
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) v[t * 4 + kk] = p[row * 16 + kk * 4 + (lane >> 4)];
-    }
-#pragma unroll
-    for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
-  }
-  if (acc == 0x9E3779B9u) sink[blockIdx.x] = acc;
-}
-
-// Plain copy: reads bytes/2 and writes bytes/2 (the second half of the window), coalesced.
-__global__ __launch_bounds__(256) void k_stream_copy(uint4* __restrict__ buf, unsigned n_per_wg, unsigned half) {
-  uint4* p = buf + (size_t)blockIdx.x * n_per_wg;
-  for (unsigned i = threadIdx.x; i < n_per_wg; i += 256 * 4) {
-    uint4 v[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) { const unsigned j = i + u * 256; v[u] = p[j < n_per_wg ? j : n_per_wg - 1]; }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) { const unsigned j = i + u * 256; if (j < n_per_wg) p[(size_t)half + j] = v[u]; }
-  }
-}
-
 // which: 0 = the decode kernel's phase marks, 1 = its merge marks; n_wg rows of 8 words each
 hipError_t phase_trace_decode(int which, unsigned long long* host, int n_wg, bool* built) {
 #ifdef ARKV_PHASE_TRACE
@@ -1418,23 +1371,6 @@ hipError_t phase_trace_decode(int which, unsigned long long* host, int n_wg, boo
   *built = false;
   return hipSuccess;
 #endif
-}
-
-hipError_t launch_stream_read(const void* buf, size_t offset_bytes, size_t bytes, int pattern, unsigned* sink, hipStream_t s) {
-  if (pattern == 2) {
-    const unsigned wgs = 2048;
-    uint4* b = reinterpret_cast<uint4*>(const_cast<char*>(static_cast<const char*>(buf)) + offset_bytes);
-    hipLaunchKernelGGL(k_stream_copy, dim3(wgs), dim3(256), 0, s, b, (unsigned)(bytes / 2 / 16 / wgs), (unsigned)(bytes / 2 / 16));
-    return hipGetLastError();
-  }
-  const unsigned wgs = 2048;
-  const uint4* src = reinterpret_cast<const uint4*>(static_cast<const char*>(buf) + offset_bytes);
-  if (pattern == 0) {
-    hipLaunchKernelGGL(k_stream_read, dim3(wgs), dim3(256), 0, s, src, (unsigned)(bytes / 16 / wgs), sink);
-  } else {
-    hipLaunchKernelGGL(k_stream_read_operand, dim3(wgs), dim3(256), 0, s, src, (unsigned)(bytes / 256 / wgs), sink);
-  }
-  return hipGetLastError();
 }
 
 template <int D, int G>

@@ -167,7 +167,6 @@ hipError_t static_scratch_get(float** part, int** ticket, size_t* part_floats); 
 // Profiling builds only (built = false otherwise): in-kernel timestamps of the latest launches.
 hipError_t phase_trace_decode(int which, unsigned long long* host, int n_wg, bool* built);
 hipError_t phase_trace_attn(unsigned long long* host, bool* built);
-hipError_t launch_stream_read(const void* buf, size_t offset_bytes, size_t bytes, int pattern, unsigned* sink /*[2048]*/, hipStream_t s);
 hipError_t launch_flush_scores(const Pools& P, int unit_begin, int n_units, int n_pending, int slot, hipStream_t s);
 hipError_t launch_tailor(const Pools& P, const TailorLaunch& a, hipStream_t s);
 hipError_t launch_commit(const Pools& P, const CommitLaunch& a, uint64_t* commit_keys /*[U][T]*/, hipStream_t s);

@@ -779,35 +779,6 @@ int arkv_debug_attend_time(arkv_cache* c, double* total_ms, int64_t* launches) {
   return ARKV_OK;
 }
 
-int arkv_debug_stream_read(void* buf, uint64_t buf_bytes, uint64_t bytes_per_launch, int32_t launches,
-                           int32_t pattern, void* hip_stream, float* avg_us) {
-  if (!buf || !avg_us || launches < 1 || bytes_per_launch == 0 || bytes_per_launch % 524288 != 0 ||
-      bytes_per_launch > buf_bytes || pattern < 0 || pattern > 2)
-    return ARKV_EINVAL;
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  unsigned* sink = nullptr;
-  hipEvent_t e0 = nullptr, e1 = nullptr;
-  hipError_t e = hipMalloc(reinterpret_cast<void**>(&sink), 2048 * sizeof(unsigned));
-  if (e == hipSuccess) e = hipEventCreate(&e0);
-  if (e == hipSuccess) e = hipEventCreate(&e1);
-  const uint64_t windows = buf_bytes / bytes_per_launch;
-  for (int pass = 0; pass < 2 && e == hipSuccess; ++pass) {          // pass 0 warms up
-    if (pass == 1) e = hipEventRecord(e0, st);
-    const int n = pass == 0 ? std::min(launches, 8) : launches;
-    for (int i = 0; i < n && e == hipSuccess; ++i)
-      e = launch_stream_read(buf, (size_t)((uint64_t)i % windows) * bytes_per_launch, (size_t)bytes_per_launch, pattern, sink, st);
-    if (pass == 1 && e == hipSuccess) e = hipEventRecord(e1, st);
-  }
-  if (e == hipSuccess) e = hipEventSynchronize(e1);
-  float ms = 0.f;
-  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
-  if (e == hipSuccess) *avg_us = ms * 1000.0f / (float)launches;
-  if (e0) (void)hipEventDestroy(e0);
-  if (e1) (void)hipEventDestroy(e1);
-  if (sink) (void)hipFree(sink);
-  return e == hipSuccess ? ARKV_OK : hip_fail(e, "arkv_debug_stream_read");
-}
-
 int arkv_debug_phase_trace(int32_t which, unsigned long long* host_words, int32_t n_rows) {
   if (!host_words || which < 0 || which > 2 || n_rows < 1 || n_rows > 8192) return ARKV_EINVAL;
   bool built = false;

@@ -22,6 +22,19 @@ def test_library_exports_every_declared_symbol():
     assert declared == set(A.EXPORTED)
 
 
+def test_measurement_library_exports_what_its_header_declares_and_is_not_in_the_product():
+    hdr = open(os.path.join(ROOT, "include", "arkv_measure.h")).read()
+    declared = set(re.findall(r"\b(arkv_measure_[a-z0-9_]+)\s*\(", hdr))
+    assert declared == set(A.MEASURE_EXPORTED)
+    mlib = A.load_measure()
+    for name in declared:
+        assert hasattr(mlib, name), f"{name} declared in arkv_measure.h but not exported"
+        assert not hasattr(A.load(), name), f"{name} must not be part of libarkv.so"
+    import ctypes as C
+    us = C.c_float()
+    assert mlib.arkv_measure_stream_read(None, 0, 0, 1, 0, None, C.byref(us)) == -1      # argument check, no GPU
+
+
 def test_phase_trace_hook_is_off_in_the_product_build():
     import ctypes as C
     buf = (C.c_uint64 * 8)()

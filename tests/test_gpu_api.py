@@ -174,7 +174,7 @@ def test_measurement_hooks():
         A.arkv_debug_time_attend(c, False)
         buf = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
         for pattern in (0, 1, 2):
-            us = A.arkv_debug_stream_read(buf, 16 << 20, 20, pattern)
+            us = A.arkv_measure_stream_read(buf, 16 << 20, 20, pattern)
             assert 0 < us < 1e4
     finally:
         A.arkv_cache_destroy(c)
