@@ -469,21 +469,39 @@ __device__ __forceinline__ void stage_pending(const Pools& P, int gu, int n, int
   using PS = PendingShape<G>;
   constexpr int KK = D / 32;
   const size_t LU = P.fin_stride / G;
-  for (int i = tid; i < PS::ROUNDS * 16 * (D / 8); i += nthreads) {
+  // every load is requested before the first store: one at a time, each would cost a memory round trip in front
+  // of the tile loop (the loop below has at most kStageBatch iterations per thread for 256 threads)
+  constexpr int NQ = PS::ROUNDS * 16 * (D / 8);
+  constexpr int kStageBatch = (NQ + 255) / 256;
+  uint4 qv[kStageBatch];
+#pragma unroll
+  for (int b = 0; b < kStageBatch; ++b) {
+    const int i = tid + b * nthreads;
     const int row = i / (D / 8), c = i % (D / 8);            // row = 16 r + operand row
     const int step = (row / 16) * PS::SPR + (row % 16) / PS::RPS, head = (row % 16) % PS::RPS;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (head < G && step < n) {
+    qv[b] = make_uint4(0, 0, 0, 0);
+    if (i < NQ && head < G && step < n) {
       const int sl = (slot - n + step + kRing) % kRing;
-      v = reinterpret_cast<const uint4*>(P.qprev + ((size_t)sl * P.fin_stride + (size_t)gu * G + head) * D)[c];
+      qv[b] = reinterpret_cast<const uint4*>(P.qprev + ((size_t)sl * P.fin_stride + (size_t)gu * G + head) * D)[c];
     }
-    reinterpret_cast<uint4*>(&sm.q[0][0][0])[i] = v;
   }
-  for (int i = tid; i < n * G; i += nthreads) {
-    const int j = i / G, h = i % G;
+  float2 fv = make_float2(0.f, 0.f);
+  float sv = 0.f;
+  if (tid < n * G) {                                            // n * G <= 8 * 8 < 256
+    const int j = tid / G, h = tid % G;
     const int sl = (slot - n + j + kRing) % kRing;
-    sm.fin[j][h] = P.fin[(size_t)sl * P.fin_stride + (size_t)gu * G + h];
-    if (h == 0) sm.scale[j] = P.qscale[(size_t)sl * LU + gu];
+    fv = P.fin[(size_t)sl * P.fin_stride + (size_t)gu * G + h];
+    if (h == 0) sv = P.qscale[(size_t)sl * LU + gu];
+  }
+#pragma unroll
+  for (int b = 0; b < kStageBatch; ++b) {
+    const int i = tid + b * nthreads;
+    if (i < NQ) reinterpret_cast<uint4*>(&sm.q[0][0][0])[i] = qv[b];
+  }
+  if (tid < n * G) {
+    const int j = tid / G, h = tid % G;
+    sm.fin[j][h] = fv;
+    if (h == 0) sm.scale[j] = sv;
   }
   __syncthreads();
   if (packed) {
