@@ -227,7 +227,7 @@ struct PackedFmt {
     }
   }
   // the same against a round of waiting steps, whose prepared operand rows (qp) and channel sums (qs) sit in LDS
-  static __device__ __forceinline__ void dots_pending(const uint16_t (*qp)[D], const float (*qs)[16], const Keys& k, int tok,
+  static __device__ __forceinline__ void dots_pending(const uint16_t (*qp)[D + 8], const float (*qs)[16], const Keys& k, int tok,
                                                       int blk, float (&x)[HPL]) {
 #pragma unroll
     for (int i = 0; i < HPL; ++i) x[i] = 0.f;
@@ -454,8 +454,11 @@ template <int D, int G>
 struct PendingLds {
   // index ROUNDS of qp / qs: the query of the step in flight (rows 0 .. G-1), so that launches that update the
   // scores need not hold its packed-format operands in registers
-  uint16_t q[PendingShape<G>::ROUNDS][16][D];        // round r's operand rows (bf16)
-  uint16_t qp[PendingShape<G>::ROUNDS + 1][16][D];   // the same rows as the grouped packed formats want them (permute_for_codes)
+  // Row pitch D + 8 elements (2D + 16 bytes): the 16 rows that the lanes of a quarter wave read as 16-byte
+  // vectors then fall into 16 different bank groups; at a pitch of 2D bytes they all fall into the same one
+  static constexpr int PITCH = D + 8;
+  uint16_t q[PendingShape<G>::ROUNDS][16][PITCH];        // round r's operand rows (bf16)
+  uint16_t qp[PendingShape<G>::ROUNDS + 1][16][PITCH];   // the same rows as the grouped packed formats want them (permute_for_codes)
   float qs[PendingShape<G>::ROUNDS + 1][D / 32][16]; // ... and each row's channel sums per group of 32
   float2 fin[kRing - 1][G];                      // a waiting step's final (max, 1/sum) per head
   float scale[kRing - 1];                        // its softmax scale * log2(e)
@@ -496,7 +499,7 @@ __device__ __forceinline__ void stage_pending(const Pools& P, int gu, int n, int
 #pragma unroll
   for (int b = 0; b < kStageBatch; ++b) {
     const int i = tid + b * nthreads;
-    if (i < NQ) reinterpret_cast<uint4*>(&sm.q[0][0][0])[i] = qv[b];
+    if (i < NQ) *reinterpret_cast<uint4*>(&sm.q[i / (16 * (D / 8))][(i / (D / 8)) % 16][8 * (i % (D / 8))]) = qv[b];
   }
   if (tid < n * G) {
     const int j = tid / G, h = tid % G;
