@@ -777,7 +777,9 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(DecodeHot H, Pools P, 
   // the waves' sums over packed rows; launches that update the scores put them where the waiting steps' state was
   // (sm_pend: dead by then, a barrier separates the two uses), which keeps two workgroups per compute unit
   __shared__ __align__(16) float sm_q_own[FOLD ? 1 : 4][FOLD ? 1 : G][FOLD ? 4 : D];
-  __shared__ __align__(16) _Float16 sm_p[4][16][kVBlock];   // a block's probabilities, [head][token], rows >= G zero
+  // a block's probabilities, [head][token], rows >= G zero (pitch 80 bytes: the 16 rows a quarter wave reads as
+  // 16-byte vectors fall into different bank groups)
+  __shared__ __align__(16) _Float16 sm_p[4][16][kVBlock + 8];
   __shared__ _Float16 sm_pdump[4][16][8];
   __shared__ int sm_last;
   __shared__ __align__(16) PendingLds<D, G> sm_pend;   // only touched when FOLD (16-byte alignment: its rows are read as 16-byte vectors)
