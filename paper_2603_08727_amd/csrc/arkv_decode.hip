@@ -823,7 +823,19 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(DecodeHot H, Pools P, 
   float2* oacc_ = poacc + (size_t)gu * capO;
   float2* qacc_ = pqacc + (size_t)gu * capQ;
 
-  struct OTile { uint4 kb[KK]; uint4 vr[NV]; float2 ac; };
+  // Launches that update the scores at group size 8 work through four rounds of waiting steps per tile and have
+  // no registers for a second tile's value rows: those are requested when the tile's turn comes, in front of
+  // the score update (which covers their latency), and live in one shared set of registers.
+  constexpr bool kLateVO = FOLD && G > 4;
+  struct OTile { uint4 kb[KK]; uint4 vr[kLateVO ? 1 : NV]; float2 ac; };
+  uint4 vlate[kLateVO ? NV : 1];
+  auto load_v = [&](uint4 (&vr)[NV], int row0) {
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int rv = min(row0 + R * j + vrow, bo - 1);
+      vr[j] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(ov_) + (unsigned)rv * (2 * D) + 16 * sub);
+    }
+  };
   auto load_o = [&](OTile& t, int row0) {
     const int rk = min(row0 + tok, bo - 1);
     {
@@ -832,11 +844,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(DecodeHot H, Pools P, 
       for (int kk = 0; kk < KK; ++kk)
         t.kb[kk] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(ok_) + off + 64 * kk);
     }
-#pragma unroll
-    for (int j = 0; j < NV; ++j) {
-      const int rv = min(row0 + R * j + vrow, bo - 1);
-      t.vr[j] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(ov_) + (unsigned)rv * (2 * D) + 16 * sub);
-    }
+    if constexpr (!kLateVO) load_v(t.vr, row0);
     if constexpr (FOLD) t.ac = oacc_[rk];
   };
   // the first tile is requested before anything else touches memory
@@ -916,6 +924,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(DecodeHot H, Pools P, 
 
   // ---------------- Original rows ----------------
   auto compute_o = [&](const OTile& t, int row0) {
+    if constexpr (kLateVO) load_v(vlate, row0);
     const f32x4 C = dots_bf16<KK>(qa, t.kb);
     const bool own = (row0 + tok < bo) && active;
     float x[HPL];
@@ -931,7 +940,10 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(DecodeHot H, Pools P, 
       });
       store_acc(ac, own, oacc_, row);
     }
-    softmax_pv(own, x, [&](int j, float (&f)[8]) { unpack_bf16x8(t.vr[j], f); });
+    softmax_pv(own, x, [&](int j, float (&f)[8]) {
+      if constexpr (kLateVO) unpack_bf16x8(vlate[j], f);
+      else unpack_bf16x8(t.vr[j], f);
+    });
   };
   if (ao < bo) {
     // two tiles in registers: while one is consumed the other is in flight.  Loads past the end of the
