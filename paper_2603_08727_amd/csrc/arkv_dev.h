@@ -152,6 +152,8 @@ struct PrefillLaunch {
   int B, Hkv, G, W, D, T;
   size_t q_head_stride;   // elements between heads (W*D for a packed [B][Hq][W][D] tensor)
   int have_rowc;          // 1: the row constants are already in the scratch (attention pass), skip the first pass
+  const float* lse;       // not null: the caller's log-sum-exp [U][G][W] (natural log), from which the column pass
+                          // takes its row constants itself (have_rowc is 1 then, and the scratch rows are not read)
   int chunk;              // keys per workgroup
   int n_chunks;
   float scale2;
@@ -186,6 +188,5 @@ struct AttnLaunch {
 };
 hipError_t launch_prefill_attn(const AttnLaunch& a, hipStream_t s);
 hipError_t launch_prefill_stats(const PrefillLaunch& a, float* rowc /*[U][MP] scratch*/, hipStream_t s);
-hipError_t launch_lse_to_rowc(const float* lse /*[U][G][W]*/, float* rowc /*[U][MP]*/, int U, int G, int W, int MP, hipStream_t s);
 
 }  // namespace arkv

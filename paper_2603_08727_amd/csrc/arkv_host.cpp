@@ -336,11 +336,11 @@ static int run_scorer(arkv_cache* c, int32_t layer, const uint16_t* q_win, size_
     attn->rowc = c->rowc; attn->MP = MP; attn->W = W;
     HIP_TRY(launch_prefill_attn(*attn, s));
   }
-  if (lse) HIP_TRY(launch_lse_to_rowc(lse, c->rowc, U, G, W, MP, s));
   PrefillLaunch a;
   a.q_win = q_win;
   a.q_head_stride = q_head_stride;
   a.have_rowc = (attn || lse) ? 1 : 0;
+  a.lse = lse;
   a.k = k;
   a.pre = ls.pre; a.rowstat = c->rowstat; a.stats = stats; a.stat_ticket = c->stat_ticket;
   a.B = c->cfg.batch; a.Hkv = c->cfg.n_kv_heads; a.G = G; a.W = W; a.D = c->P.D; a.T = T;

@@ -284,7 +284,12 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_prefill_cols(Prefi
   float* crow = reinterpret_cast<float*>(sm + (size_t)MP * RB);   // [MP] -c_r (padded rows: -1e30 -> p = 0)
   int* lastk = reinterpret_cast<int*>(crow + MP);                 // [MP] last visible key of the row
   for (int r = tid; r < MP; r += NT) {
-    crow[r] = r < M ? -rowc[(size_t)u * MP + r] : kNegBigP;
+    // the row constant in base-2 units: from the first pass / the attention pass, or from the caller's
+    // log-sum-exp (natural log of the sum over visible keys of exp(scale q.k), what attention kernels commonly
+    // return per query row; row r = (head inside the group) * W + (window query))
+    float cr = 0.f;
+    if (r < M) cr = L.lse ? L.lse[((size_t)u * L.G + r / L.W) * L.W + r % L.W] * 1.4426950408889634f : rowc[(size_t)u * MP + r];
+    crow[r] = r < M ? -cr : kNegBigP;
     lastk[r] = r < M ? T - L.W + (r % L.W) : -1;
   }
   __syncthreads();
@@ -435,22 +440,6 @@ static hipError_t launch_prefill_t(const PrefillLaunch& a, float* rowc, hipStrea
   double* mpart = zpart + (size_t)U * a.n_chunks;
   hipLaunchKernelGGL((k_prefill_cols<D, RT, NW>), grid, dim3(64 * NW), shm + (size_t)MP * 8, s, a, (const float*)rowc, zpart);
   hipLaunchKernelGGL(k_prefill_stats, dim3(nch, a.B), dim3(256), 0, s, a, (const double*)zpart, mpart);
-  return hipGetLastError();
-}
-
-// Row constants from a caller's log-sum-exp (natural log of the sum over visible keys of exp(scale q.k), what
-// attention kernels commonly return per query row): the same quantity in base-2 units, in the scratch layout
-// [U][MP] with row r = (head inside the group) * W + (window query).
-__global__ __launch_bounds__(256) void k_lse_to_rowc(const float* __restrict__ lse, float* __restrict__ rowc, int U, int G,
-                                                     int W, int MP) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= U * MP) return;
-  const int u = i / MP, r = i % MP;
-  rowc[i] = r < G * W ? lse[((size_t)u * G + r / W) * W + r % W] * 1.4426950408889634f : 0.f;
-}
-
-hipError_t launch_lse_to_rowc(const float* lse, float* rowc, int U, int G, int W, int MP, hipStream_t s) {
-  hipLaunchKernelGGL(k_lse_to_rowc, dim3((U * MP + 255) / 256), dim3(256), 0, s, lse, rowc, U, G, W, MP);
   return hipGetLastError();
 }
 
