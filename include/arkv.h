@@ -233,9 +233,11 @@ int arkv_debug_attend_time(arkv_cache* cache, double* total_ms, int64_t* launche
 /* Measurement hook: launch shape of the kernels, for sweeps.  wg_target: workgroups a decode launch aims at
  * when it picks its split-K factor (default 512 = two per compute unit); packed_weight: cost of a packed row in
  * sixteenths of a bf16 row when rows are dealt to the splits (default: 10, or 16 for launches of at most 256
- * workgroups); prefill_chunk: keys per workgroup of
- * the prefill scorer (multiple of 128, default 1024).  A value <= 0 leaves that setting as it is.  Results do
- * not depend on these beyond the order of floating-point additions. */
+ * workgroups); prefill_chunk: keys per workgroup of the prefill scorer (multiple of 128, at most 8192; default:
+ * 1024, halved while the grid would be small, or, with more than 256 query rows per kv-head, what makes the
+ * grid one round of the chip; a value given here is taken as it is).  A value <= 0 leaves that setting as it
+ * is.  Results do not depend on these beyond the order of floating-point additions.  ARKV_EINVAL: null cache,
+ * packed_weight above 16, prefill_chunk not a multiple of 128 or above 8192. */
 int arkv_debug_set_launch_shape(arkv_cache* cache, int32_t wg_target, int32_t packed_weight, int32_t prefill_chunk);
 
 /* Parity hook, HOST, pure: the rows split `split` of `n_splits` owns in a decode launch over a unit with
