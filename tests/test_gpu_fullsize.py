@@ -90,6 +90,14 @@ def test_c5_prefill_scorer_window_128():
     _run_scorer(synth.C5.scaled(n_layers=1, batch=2, window=128))
 
 
+@pytest.mark.parametrize("window,hq,hkv", [(64, 32, 8), (16, 32, 8), (64, 16, 8), (128, 16, 8), (32, 64, 8)])
+def test_prefill_scorer_row_tile_counts(window, hq, hkv):
+    """Every number of 32-row tiles the scorer instantiates (2, 4, 8, 16; 4 and 8 waves per workgroup) on a prompt
+    long enough for several unmasked key tiles per wave, one sequence."""
+    _run_scorer(synth.C5.scaled(name=f"scorer_w{window}_g{hq // hkv}", n_layers=1, batch=1, window=window,
+                                n_q_heads=hq, n_kv_heads=hkv, prefill=4096 + 77))
+
+
 def test_c3_natural_tailor_cadence_invariants():
     """Config 3 at full size, two layers, stepped past the first decode-time tailor at its natural cadence
     (N - b - W = 2040 steps) without the oracle: what must hold at any size.  Every unit holds b + W + (steps since
