@@ -464,11 +464,12 @@ struct PendingLds {
   float scale[kRing - 1];                        // its softmax scale * log2(e)
 };
 
-// All threads of the workgroup; ends with a barrier.  packed: also prepare qp / qs, a round per wave; q_now (may be
+// All 256 threads of the workgroup; ends with a barrier.  packed: also prepare qp / qs, a round per wave; q_now (may be
 // null): this step's query rows [G][D], prepared as index ROUNDS.
 template <int D, int G>
 __device__ __forceinline__ void stage_pending(const Pools& P, int gu, int n, int slot, PendingLds<D, G>& sm, int tid,
-                                              int nthreads, bool packed, const uint16_t* q_now = nullptr) {
+                                              bool packed, const uint16_t* q_now = nullptr) {
+  constexpr int nthreads = 256;                  // both callers run 256-thread workgroups
   using PS = PendingShape<G>;
   constexpr int KK = D / 32;
   const size_t LU = P.fin_stride / G;
@@ -855,7 +856,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_attend(DecodeHot H, Pools P, 
   // this step's query; on a launch that also updates the scores, the waiting steps' state goes to LDS
   uint4 qa[KK];
   load_query<D, G>(pq + (size_t)lu * G * D, lane, qa);
-  if constexpr (FOLD) stage_pending<D, G>(P, gu, npend, L.slot, sm_pend, tid, 256, BITS != 8 && cQ > 0, pq + (size_t)lu * G * D);
+  if constexpr (FOLD) stage_pending<D, G>(P, gu, npend, L.slot, sm_pend, tid, BITS != 8 && cQ > 0, pq + (size_t)lu * G * D);
 
   float Mreg[HPL], lsum[HPL], acc[G][8];
 #pragma unroll
@@ -1259,7 +1260,7 @@ __global__ __launch_bounds__(256) void k_flush_scores(Pools P, int unit_begin, i
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int tok = lane & 15, blk = lane >> 4;
   const int2 cnt = P.cnt[gu];
-  stage_pending<D, G>(P, gu, n_pending, slot, sm_pend, threadIdx.x, 256, BITS != 8 && cnt.y > 0);
+  stage_pending<D, G>(P, gu, n_pending, slot, sm_pend, threadIdx.x, BITS != 8 && cnt.y > 0);
   const int wave = blockIdx.x * 4 + w, step = gridDim.x * 64;
   {
     const uint16_t* ok_ = P.ok + (size_t)gu * P.capO * D;
