@@ -45,6 +45,16 @@ def test_c3_qwen3_32k_batch4_one_layer_free_running():
     _run(synth.C3.scaled(n_layers=1), steps=3, lockstep=False)
 
 
+def test_c4_128k_2bit_one_layer_free_running():
+    """The 128K-context configuration without the score hand-over: 131040 prompt tokens per kv-head ranked on each
+    side's own scores, 2-bit rows."""
+    _run(synth.C4.scaled(n_layers=1), steps=3, lockstep=False)
+
+
+def test_c2_llama3_8k_one_layer_free_running():
+    _run(synth.C2.scaled(n_layers=1), steps=4, lockstep=False)
+
+
 @pytest.mark.parametrize("rho,lockstep", [(None, True), (0.5, True), (0.5, False)])
 def test_c3_full_size_decode_time_tailor(rho, lockstep):
     """Config 3's shape with almost no slack (alpha = 0.99: b = 8078 of N = 8192, a tailor every 82 decode steps) so
